@@ -1,0 +1,197 @@
+"""ctypes front end of the CPU oracle (oracle/nvq_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, the smoke check and the
+benchmark's cpu_baseline leg.  It never imports the GPU package, and the GPU
+package never imports it.  Arrays are numpy; bf16 and fp16 values travel as
+uint16 bit patterns.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+
+class OracleError(RuntimeError):
+    pass
+
+
+class _Linear(C.Structure):
+    _fields_ = [("qweight", C.c_void_p), ("scales", C.c_void_p),
+                ("N", C.c_int64), ("K", C.c_int64),
+                ("x", C.c_void_p), ("y", C.c_void_p), ("precision", C.c_int)]
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.build()
+        L = C.CDLL(path)
+        L.orc_bf16_to_float.restype = C.c_float
+        L.orc_bf16_to_float.argtypes = [C.c_uint16]
+        L.orc_float_to_bf16.restype = C.c_uint16
+        L.orc_float_to_bf16.argtypes = [C.c_float]
+        L.orc_half_to_float.restype = C.c_float
+        L.orc_half_to_float.argtypes = [C.c_uint16]
+        L.orc_float_to_half.restype = C.c_uint16
+        L.orc_float_to_half.argtypes = [C.c_float]
+        vp, i64, ci = C.c_void_p, C.c_int64, C.c_int
+        L.orc_pack_int4.argtypes = [vp, i64, i64, vp, vp]
+        L.orc_dequant_int4.argtypes = [vp, vp, i64, i64, vp]
+        L.orc_quant_act_i8.argtypes = [vp, i64, i64, ci, vp, vp, vp]
+        L.orc_gemv_w4a8.argtypes = [vp, vp, i64, i64, vp, vp, ci, i64, vp, vp]
+        L.orc_w4a8_acc_deferred.argtypes = [vp, i64, i64, vp, vp, i64, vp]
+        L.orc_gemv_w4a16.argtypes = [vp, vp, i64, i64, vp, i64, vp]
+        L.orc_decode_linears.argtypes = [vp, i64, i64, ci, vp, vp]
+        L.orc_precision_from_scores.argtypes = [vp, i64, C.c_double, C.c_double, vp, vp]
+        for f in ("orc_pack_int4", "orc_dequant_int4", "orc_quant_act_i8", "orc_gemv_w4a8",
+                  "orc_w4a8_acc_deferred", "orc_gemv_w4a16", "orc_decode_linears",
+                  "orc_precision_from_scores"):
+            getattr(L, f).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _p(a):
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def _chk(rc, what):
+    if rc != 0:
+        raise OracleError("%s failed with oracle status %d" % (what, rc))
+
+
+def _arr(a, dtype, ndim=None):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    if ndim is not None and a.ndim != ndim:
+        raise ValueError("expected %d-d array" % ndim)
+    return a
+
+
+# ---- number formats --------------------------------------------------------
+def half_to_float(bits):
+    return lib().orc_half_to_float(int(bits))
+
+
+def float_to_half(f):
+    return lib().orc_float_to_half(float(np.float32(f)))
+
+
+def bf16_to_float(bits):
+    return lib().orc_bf16_to_float(int(bits))
+
+
+def float_to_bf16(f):
+    return lib().orc_float_to_bf16(float(np.float32(f)))
+
+
+# ---- the path ---------------------------------------------------------------
+def pack_int4(W, allow_range_error=False):
+    """W fp32 [N,K] -> (qweight u8 [N,K/2], scales u16 [N,K/32])."""
+    W = _arr(W, np.float32, 2)
+    N, K = W.shape
+    q = np.empty((N, K // 2), np.uint8)
+    s = np.empty((N, K // 32), np.uint16)
+    rc = lib().orc_pack_int4(_p(W), N, K, _p(q), _p(s))
+    if not (allow_range_error and rc == 3):
+        _chk(rc, "pack_int4")
+    return q, s
+
+
+def dequant_int4(qweight, scales):
+    """-> float64 [N,K] with Wd = code * scale."""
+    q = _arr(qweight, np.uint8, 2)
+    s = _arr(scales, np.uint16, 2)
+    N, K = q.shape[0], q.shape[1] * 2
+    Wd = np.empty((N, K), np.float64)
+    _chk(lib().orc_dequant_int4(_p(q), _p(s), N, K, _p(Wd)), "dequant_int4")
+    return Wd
+
+
+def quant_act_i8(x_bf16, act_group=0):
+    """x u16(bf16 bits) [M,K] -> (xq i8 [M,K], xscale f32 [M] or [M,K/32], xgsum i32 [M,K/32])."""
+    x = _arr(x_bf16, np.uint16, 2)
+    M, K = x.shape
+    xq = np.empty((M, K), np.int8)
+    xs = np.empty((M,) if act_group == 0 else (M, K // 32), np.float32)
+    gs = np.empty((M, K // 32), np.int32)
+    _chk(lib().orc_quant_act_i8(_p(x), M, K, act_group, _p(xq), _p(xs), _p(gs)), "quant_act_i8")
+    return xq, xs, gs
+
+
+def gemv_w4a8(qweight, scales, xq, xscale, act_group=0, want_acc=False):
+    """-> y float64 [M,N] (and acc int32 [M,N,K/32])."""
+    q = _arr(qweight, np.uint8, 2)
+    s = _arr(scales, np.uint16, 2)
+    xq = _arr(xq, np.int8, 2)
+    xs = _arr(xscale, np.float32)
+    N, K = q.shape[0], q.shape[1] * 2
+    M = xq.shape[0]
+    assert xq.shape[1] == K and s.shape == (N, K // 32)
+    y = np.empty((M, N), np.float64)
+    acc = np.empty((M, N, K // 32), np.int32) if want_acc else None
+    _chk(lib().orc_gemv_w4a8(_p(q), _p(s), N, K, _p(xq), _p(xs), act_group, M, _p(y),
+                             _p(acc) if want_acc else None), "gemv_w4a8")
+    return (y, acc) if want_acc else y
+
+
+def w4a8_acc_deferred(qweight, xq, xgsum):
+    q = _arr(qweight, np.uint8, 2)
+    xq = _arr(xq, np.int8, 2)
+    gs = _arr(xgsum, np.int32, 2)
+    N, K = q.shape[0], q.shape[1] * 2
+    M = xq.shape[0]
+    acc = np.empty((M, N, K // 32), np.int32)
+    _chk(lib().orc_w4a8_acc_deferred(_p(q), N, K, _p(xq), _p(gs), M, _p(acc)), "w4a8_acc_deferred")
+    return acc
+
+
+def gemv_w4a16(qweight, scales, x_bf16):
+    """-> y float64 [M,N]."""
+    q = _arr(qweight, np.uint8, 2)
+    s = _arr(scales, np.uint16, 2)
+    x = _arr(x_bf16, np.uint16, 2)
+    N, K = q.shape[0], q.shape[1] * 2
+    M = x.shape[0]
+    assert x.shape[1] == K and s.shape == (N, K // 32)
+    y = np.empty((M, N), np.float64)
+    _chk(lib().orc_gemv_w4a16(_p(q), _p(s), N, K, _p(x), M, _p(y)), "gemv_w4a16")
+    return y
+
+
+def decode_linears(layers, M, act_group=0):
+    """layers: list of dicts {qweight, scales, x, precision}; returns list of y float64 [M,N]."""
+    n = len(layers)
+    arr = (_Linear * max(n, 1))()
+    keep = []
+    ys = []
+    maxK = 32
+    for i, L in enumerate(layers):
+        q = _arr(L["qweight"], np.uint8, 2)
+        s = _arr(L["scales"], np.uint16, 2)
+        x = _arr(L["x"], np.uint16, 2)
+        N, K = q.shape[0], q.shape[1] * 2
+        assert x.shape == (M, K)
+        y = np.empty((M, N), np.float64)
+        keep += [q, s, x]
+        ys.append(y)
+        maxK = max(maxK, K)
+        arr[i] = _Linear(q.ctypes.data, s.ctypes.data, N, K, x.ctypes.data, y.ctypes.data,
+                         int(L["precision"]))
+    sq = np.empty(M * maxK, np.int8)
+    ss = np.empty(M * maxK // 32, np.float32)
+    _chk(lib().orc_decode_linears(C.byref(arr), n, M, act_group, _p(sq), _p(ss)), "decode_linears")
+    return ys
+
+
+def precision_from_scores(scores, tau=0.7, eps=1e-12):
+    """-> (uint8 [L]: 1 = W4A16, 0 = W4A8; normalised scores float64 [L])."""
+    s = _arr(scores, np.float64, 1)
+    out = np.empty(s.shape[0], np.uint8)
+    shat = np.empty(s.shape[0], np.float64)
+    _chk(lib().orc_precision_from_scores(_p(s), s.shape[0], tau, eps, _p(out), _p(shat)),
+         "precision_from_scores")
+    return out, shat
