@@ -1,0 +1,181 @@
+/*
+ * nvq.h -- C ABI of libnvq: decode-time linear layers over int4
+ * group-quantised weights on AMD MI355X (gfx950), each layer run as W4A16
+ * or W4A8 under a per-layer precision map.
+ *
+ * The operations are the ones the paper's section "Per-Layer Precision
+ * Dispatch and the W4A8 Path" and its appendix "CUDA Kernel Implementation
+ * Details" describe; citations below name the passage that defines each one.
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers unless marked "host".  The caller
+ *     owns every buffer; the library allocates nothing.
+ *   - Work is enqueued on the HIP stream passed as `stream` (a hipStream_t
+ *     cast to void*, NULL = the default stream).  No call synchronises.
+ *   - Return value: NVQ_OK or an error code; on error nothing was enqueued.
+ *     Arguments are validated on the host before any launch.  Inputs are
+ *     assumed finite; NaN/Inf are not checked.
+ *   - Shapes: a linear layer has K inputs and N outputs, weights are [N][K]
+ *     with K contiguous, K % 32 == 0, G = K / 32 groups per row, M tokens.
+ *   - Device pointers must be 16-byte aligned (4-byte for fp32/int32 vectors
+ *     and outputs, 2-byte for fp16 scales).
+ *
+ * Packed weight layout (shared by every entry point)
+ *   qweight[n][g*16 + j], j < 16 : low nibble  = element k = 32 g + j,
+ *                                  high nibble = element k = 32 g + 16 + j,
+ *   stored nibble = signed code + 8 (code in [-8, 7]; the paper's block
+ *   format centres the unsigned nibble at 8).  scales[n][g] holds IEEE
+ *   binary16 bits.  18 bytes per 32 weights = 4.5 bits per weight, as in the
+ *   paper, but nibbles and scales are two planes so that one 128-bit load
+ *   fetches exactly one group.
+ */
+#ifndef NVQ_H
+#define NVQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    NVQ_OK = 0,
+    NVQ_ERR_INVALID_ARG = 1, /* NULL pointer, unknown enum value */
+    NVQ_ERR_SHAPE = 2,       /* N, K, M out of range, K % 32 != 0 */
+    NVQ_ERR_ALIGN = 3,       /* pointer not aligned as stated above */
+    NVQ_ERR_UNSUPPORTED = 4, /* valid request this build cannot run */
+    NVQ_ERR_HIP = 5,         /* a HIP runtime call failed */
+    NVQ_ERR_WORKSPACE = 6    /* workspace missing or too small */
+};
+
+enum { NVQ_F32 = 0, NVQ_BF16 = 1 };  /* y_dtype */
+enum { NVQ_W4A8 = 0, NVQ_W4A16 = 1 }; /* precision */
+
+/* Upper bounds accepted by the entry points. */
+#define NVQ_MAX_M 32
+#define NVQ_MAX_K 65536
+
+/* Human-readable name of a status code (host pointer to a static string). */
+const char *nvq_status_string(int status);
+
+/* Text of the last HIP error seen by this thread's most recent failing call
+ * (host pointer to a static buffer; empty string if none). */
+const char *nvq_last_hip_error(void);
+
+/*
+ * nvq_pack_int4 -- quantise and pack weights (load time, not per token).
+ * Paper: weight format paragraph of the W4A8 section (32-weight blocks, one
+ * fp16 scale, nibbles centred at 8).  Scale rule (this build's reading, the
+ * paper gives none): s = fp16_rne(absmax / 7); code = clamp(rne(w / s), -8, 7)
+ * with IEEE binary32 division; a zero scale gives all-zero codes.
+ *   W        [N][K] fp32, device, read only
+ *   group    must be 32
+ *   qweight  [N][K/2] u8, device, written
+ *   scales   [N][K/32] fp16 bits, device, written
+ * A block whose absmax/7 overflows fp16 gets an infinite scale and zero codes.
+ */
+int nvq_pack_int4(const float *W, int64_t N, int64_t K, int group,
+                  uint8_t *qweight, uint16_t *scales, void *stream);
+
+/*
+ * nvq_quant_act_i8 -- dynamic int8 quantisation of activations.
+ * Paper: appendix "F16 -> Q8 Activation Quantization": s = amax / 127,
+ * q = round(x / s) clamped to [-127, 127]; the result is reused by every
+ * matmul that reads the same input.  round = half-to-even, "/" = IEEE
+ * binary32 division; activations are bfloat16.
+ *   x_bf16    [M][K] bf16 bits, read only
+ *   act_group 0  = one scale per token (xscale is [M]);
+ *             32 = one scale per 32 elements, the paper's granularity
+ *                  (xscale is [M][K/32])
+ *   xq        [M][K] int8, written
+ *   xscale    fp32, written
+ *   xgsum     [M][K/32] int32, written: sum of the codes of each block of 32,
+ *             the "sum_x" term of the paper's deferred bias correction.
+ *             Required (the W4A8 GEMV consumes it).
+ */
+int nvq_quant_act_i8(const uint16_t *x_bf16, int M, int K, int act_group,
+                     int8_t *xq, float *xscale, int32_t *xgsum, void *stream);
+
+/*
+ * nvq_gemv_w4a16 -- y[m][n] = sum_g s_w[n][g] * sum_{j<32} code[n][32g+j] * x[m][32g+j]
+ * with bf16 activations, weights dequantised in registers, fp32 accumulate.
+ * Paper: the W4A16 branch of the precision dispatch (kernel table, row
+ * "matvec_w4a16": in-register dequantisation, cross-lane reduction, no
+ * integer dot product).
+ *   y        [M][N], fp32 or bf16 according to y_dtype, written
+ */
+int nvq_gemv_w4a16(const uint8_t *qweight, const uint16_t *scales, int N, int K,
+                   const uint16_t *x_bf16, int M, void *y, int y_dtype, void *stream);
+
+/*
+ * nvq_gemv_w4a8 -- acc[m][n][g] = sum_{j<32} code[n][32g+j] * xq[m][32g+j]  (int32),
+ * y[m][n] = xscale[m] * sum_g s_w[n][g] * acc[m][n][g]                (act_group 0)
+ *         = sum_g s_w[n][g] * xscale[m][g] * acc[m][n][g]             (act_group 32)
+ * Paper: W4A8 kernel description and appendix "W4A8 dp4a Matrix-Vector
+ * Product": packed int8 dot products on the unsigned nibbles, int32
+ * accumulate, then result = s_w * s_x * (sumi - 8 * sum_x).
+ *   xq, xscale, xgsum  as written by nvq_quant_act_i8 with the same act_group
+ *   acc_debug  NULL, or [M][N][K/32] int32 that receives every block
+ *              accumulator (for bit-exact checks; slower)
+ */
+int nvq_gemv_w4a8(const uint8_t *qweight, const uint16_t *scales, int N, int K,
+                  const int8_t *xq, const float *xscale, const int32_t *xgsum,
+                  int act_group, int M, void *y, int y_dtype, int32_t *acc_debug,
+                  void *stream);
+
+/*
+ * One linear layer of a decode step.  `precision` is the routing decision of
+ * the paper's rule route(i) = W4A16 if normalised score >= tau else W4A8; all
+ * linears of one transformer block carry their block's decision.
+ */
+typedef struct nvq_linear {
+    const uint8_t *qweight;  /* [N][K/2] */
+    const uint16_t *scales;  /* [N][K/32] */
+    int32_t N, K;
+    const uint16_t *x_bf16;  /* [M][K] input of this layer */
+    void *y;                 /* [M][N] output */
+    int32_t y_dtype;         /* NVQ_F32 | NVQ_BF16 */
+    int32_t precision;       /* NVQ_W4A8 | NVQ_W4A16 */
+} nvq_linear;
+
+/*
+ * nvq_decode_linears -- walk a list of linears in order under its precision
+ * map (the hot loop of one decode step, linear layers only).
+ * Paper: routing rule of the precision-dispatch section; activation codes
+ * are reused across projections that read the same input; the whole step is
+ * issued without per-kernel host round trips (the paper's graph-capture
+ * paragraph gives the reason).
+ *   layers   host array of n entries (read during the call only)
+ *   Entries complete in order: entry i may read what an earlier entry wrote.
+ *   Consecutive entries with the same x_bf16, K and precision form a phase:
+ *   they share one activation quantisation and run concurrently.
+ *   workspace  device buffer of at least nvq_decode_workspace_bytes(...)
+ *              bytes, 256-byte aligned; its contents are scratch.
+ * nvq_decode_workspace_bytes returns 0 for invalid arguments.
+ */
+size_t nvq_decode_workspace_bytes(const nvq_linear *layers, int n, int M, int act_group);
+int nvq_decode_linears(const nvq_linear *layers, int n, int M, int act_group,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * nvq_precision_from_scores -- host helper: the normalise-and-assign tail of
+ * the paper's Algorithm 1.  scores (host, L doubles) are min-max normalised;
+ * if max - min < eps every normalised score is 0; out[i] = NVQ_W4A16 if the
+ * normalised score >= tau else NVQ_W4A8.  Pure host code, no GPU work.
+ */
+int nvq_precision_from_scores(const double *scores, int L, double tau, double eps,
+                              int32_t *out);
+
+/*
+ * Measurement helpers (not part of the method): a streaming read that sums a
+ * buffer into `out` (8 bytes) and a plain copy, used to find the HBM ceiling
+ * of the machine and to calibrate profiler byte counters.  bytes % 16 == 0.
+ */
+int nvq_stream_read(const void *src, size_t bytes, void *out, void *stream);
+int nvq_stream_copy(void *dst, const void *src, size_t bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NVQ_H */

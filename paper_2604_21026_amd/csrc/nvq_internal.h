@@ -1,0 +1,88 @@
+// Internal declarations shared by the translation units of libnvq (host side
+// and gfx950 device helpers).  Not installed; the public ABI is include/nvq.h.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "nvq.h"
+
+namespace nvq {
+
+// ---- host helpers ---------------------------------------------------------
+void set_hip_error(hipError_t e, const char *where);
+int device_cu_count();  // compute units of the current device (cached)
+
+#define NVQ_HIP_TRY(expr)                                   \
+    do {                                                    \
+        hipError_t e_ = (expr);                             \
+        if (e_ != hipSuccess) {                             \
+            ::nvq::set_hip_error(e_, #expr);                \
+            return NVQ_ERR_HIP;                             \
+        }                                                   \
+    } while (0)
+
+static inline bool aligned(const void *p, size_t a) {
+    return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0;
+}
+
+// Up to four weight matrices that read the same input can be served by one
+// GEMV launch (q/k/v, gate/up).  Rows are numbered consecutively across the
+// segments; row_end[i] is the first row after segment i.
+constexpr int kMaxSeg = 4;
+struct GemvSegs {
+    const uint4 *qw[kMaxSeg];     // [N_i][G] one uint4 = one group of 32 nibbles
+    const uint16_t *sc[kMaxSeg];  // [N_i][G] fp16 bits
+    void *y[kMaxSeg];             // [M][N_i]
+    int32_t *dbg[kMaxSeg];        // [M][N_i][G] or nullptr
+    int N[kMaxSeg];
+    int row_end[kMaxSeg];
+    int y_dtype[kMaxSeg];
+    int nseg;
+    int total_rows;
+};
+
+// Internal launchers (validated arguments; enqueue only).
+int launch_quant_act(const uint16_t *x, int M, int K, int act_group, int8_t *xq, float *xscale,
+                     int32_t *xgsum, hipStream_t st);
+int launch_gemv_w4a8(const GemvSegs &segs, int K, const int8_t *xq, const float *xscale,
+                     const int32_t *xgsum, int act_group, int M, hipStream_t st);
+int launch_gemv_w4a16(const GemvSegs &segs, int K, const uint16_t *x, int M, hipStream_t st);
+
+// ---- device helpers -------------------------------------------------------
+#if defined(__HIPCC__)
+
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t h) {
+    return __uint_as_float(h << 16);
+}
+
+// fp32 -> bf16 bits, round to nearest even (finite inputs).
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float half_bits_to_float(uint16_t h) {
+    _Float16 v = __builtin_bit_cast(_Float16, h);
+    return (float)v;
+}
+
+// Sum across the LPR lanes of an aligned lane group; every lane gets the sum.
+template <int LPR>
+__device__ __forceinline__ float group_sum(float v) {
+#pragma unroll
+    for (int off = LPR / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+__device__ __forceinline__ void store_out(void *y, int y_dtype, int64_t idx, float v) {
+    if (y_dtype == NVQ_F32)
+        reinterpret_cast<float *>(y)[idx] = v;
+    else
+        reinterpret_cast<uint16_t *>(y)[idx] = float_to_bf16_bits(v);
+}
+
+#endif  // __HIPCC__
+
+}  // namespace nvq

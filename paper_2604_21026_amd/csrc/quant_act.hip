@@ -1,0 +1,119 @@
+// nvq_quant_act_i8: bf16 activations -> int8 codes, fp32 scale(s) and the
+// per-32 code sums that the W4A8 GEMV's deferred correction needs.
+// Paper, appendix "F16 -> Q8 Activation Quantization": s = amax / 127,
+// q = round(x / s), clamp to [-127, 127].  Rounding is half-to-even and the
+// division is IEEE binary32, so a CPU run of the same rule gives equal codes.
+//
+// One workgroup per token.  A thread handles chunks of 8 consecutive values
+// (one 128-bit load); four neighbouring lanes therefore cover one group of 32
+// and reduce its code sum (and, for per-group scales, its absmax) with two
+// cross-lane exchanges.  Pass 1 finds the token's absmax, pass 2 re-reads the
+// (cache-resident) row and quantises.
+#include "nvq_internal.h"
+
+namespace nvq {
+
+constexpr int kQuantThreads = 256;
+
+__device__ __forceinline__ float chunk_absmax(const uint4 &v) {
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    float a = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        a = fmaxf(a, fabsf(bf16_bits_to_float(w[i] & 0xffffu)));
+        a = fmaxf(a, fabsf(bf16_bits_to_float(w[i] >> 16)));
+    }
+    return a;
+}
+
+__device__ __forceinline__ int quant_one(float x, float s) {
+    float r = rintf(x / s);
+    r = fminf(fmaxf(r, -127.0f), 127.0f);
+    return (int)r;
+}
+
+template <bool PER_GROUP>
+__global__ __launch_bounds__(kQuantThreads) void quant_act_kernel(
+    const uint4 *__restrict__ x, int K, int8_t *__restrict__ xq, float *__restrict__ xscale,
+    int32_t *__restrict__ xgsum) {
+    const int m = blockIdx.x;
+    const int chunks = K / 8;  // multiple of 4
+    const int G = K / 32;
+    const uint4 *xr = x + (int64_t)m * chunks;
+    uint2 *qr = reinterpret_cast<uint2 *>(xq + (int64_t)m * K);
+    int32_t *gs = xgsum + (int64_t)m * G;
+
+    float s_tok = 0.0f;
+    if (!PER_GROUP) {
+        __shared__ float red[kQuantThreads / 64];
+        float a = 0.0f;
+        for (int c = threadIdx.x; c < chunks; c += kQuantThreads) a = fmaxf(a, chunk_absmax(xr[c]));
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) a = fmaxf(a, __shfl_xor(a, off, 64));
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = a;
+        __syncthreads();
+        a = red[0];
+#pragma unroll
+        for (int i = 1; i < kQuantThreads / 64; ++i) a = fmaxf(a, red[i]);
+        s_tok = a / 127.0f;
+        if (threadIdx.x == 0) xscale[m] = s_tok;
+    }
+
+    // chunks is a multiple of 4 and the stride a multiple of 4, so the four
+    // lanes of a team are valid or invalid together.
+    for (int c = threadIdx.x; c < chunks; c += kQuantThreads) {
+        const uint4 v = xr[c];
+        float s = s_tok;
+        if (PER_GROUP) {
+            float a = chunk_absmax(v);
+            a = fmaxf(a, __shfl_xor(a, 1, 64));
+            a = fmaxf(a, __shfl_xor(a, 2, 64));
+            s = a / 127.0f;
+            if ((c & 3) == 0) xscale[(int64_t)m * G + (c >> 2)] = s;
+        }
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        int q[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            q[2 * i] = (s != 0.0f) ? quant_one(bf16_bits_to_float(w[i] & 0xffffu), s) : 0;
+            q[2 * i + 1] = (s != 0.0f) ? quant_one(bf16_bits_to_float(w[i] >> 16), s) : 0;
+        }
+        int sum = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) sum += q[i];
+        uint2 out;
+        out.x = (uint32_t)(q[0] & 0xff) | ((uint32_t)(q[1] & 0xff) << 8) |
+                ((uint32_t)(q[2] & 0xff) << 16) | ((uint32_t)(q[3] & 0xff) << 24);
+        out.y = (uint32_t)(q[4] & 0xff) | ((uint32_t)(q[5] & 0xff) << 8) |
+                ((uint32_t)(q[6] & 0xff) << 16) | ((uint32_t)(q[7] & 0xff) << 24);
+        qr[c] = out;
+        sum += __shfl_xor(sum, 1, 64);
+        sum += __shfl_xor(sum, 2, 64);
+        if ((c & 3) == 0) gs[c >> 2] = sum;
+    }
+}
+
+int launch_quant_act(const uint16_t *x, int M, int K, int act_group, int8_t *xq, float *xscale,
+                     int32_t *xgsum, hipStream_t st) {
+    if (act_group == 0)
+        hipLaunchKernelGGL(quant_act_kernel<false>, dim3(M), dim3(kQuantThreads), 0, st,
+                           reinterpret_cast<const uint4 *>(x), K, xq, xscale, xgsum);
+    else
+        hipLaunchKernelGGL(quant_act_kernel<true>, dim3(M), dim3(kQuantThreads), 0, st,
+                           reinterpret_cast<const uint4 *>(x), K, xq, xscale, xgsum);
+    NVQ_HIP_TRY(hipGetLastError());
+    return NVQ_OK;
+}
+
+}  // namespace nvq
+
+extern "C" int nvq_quant_act_i8(const uint16_t *x_bf16, int M, int K, int act_group, int8_t *xq,
+                                float *xscale, int32_t *xgsum, void *stream) {
+    if (!x_bf16 || !xq || !xscale || !xgsum) return NVQ_ERR_INVALID_ARG;
+    if (act_group != 0 && act_group != 32) return NVQ_ERR_INVALID_ARG;
+    if (M <= 0 || M > NVQ_MAX_M || K <= 0 || (K % 32) != 0 || K > NVQ_MAX_K) return NVQ_ERR_SHAPE;
+    if (!nvq::aligned(x_bf16, 16) || !nvq::aligned(xq, 16) || !nvq::aligned(xscale, 4) ||
+        !nvq::aligned(xgsum, 4))
+        return NVQ_ERR_ALIGN;
+    return nvq::launch_quant_act(x_bf16, M, K, act_group, xq, xscale, xgsum, (hipStream_t)stream);
+}

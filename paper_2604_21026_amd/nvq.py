@@ -1,0 +1,216 @@
+"""Thin ctypes binding over libnvq.so (C ABI in include/nvq.h).
+
+Argument marshalling only: torch supplies device memory and the current
+stream, every computation happens in the library's HIP kernels.  There is no
+fallback: if libnvq.so is missing, loading fails with an error.
+"""
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libnvq.so")
+
+F32, BF16 = 0, 1
+W4A8, W4A16 = 0, 1
+MAX_M = 32
+
+EXPORTS = (
+    "nvq_status_string", "nvq_last_hip_error", "nvq_pack_int4", "nvq_quant_act_i8",
+    "nvq_gemv_w4a16", "nvq_gemv_w4a8", "nvq_decode_workspace_bytes", "nvq_decode_linears",
+    "nvq_precision_from_scores", "nvq_stream_read", "nvq_stream_copy",
+)
+
+
+class NvqError(RuntimeError):
+    def __init__(self, status: int, what: str, detail: str = ""):
+        self.status = status
+        super().__init__("%s failed: status %d (%s)%s" % (what, status, _status_string(status),
+                                                          (": " + detail) if detail else ""))
+
+
+class Linear(C.Structure):
+    """Mirror of `nvq_linear`."""
+    _fields_ = [("qweight", C.c_void_p), ("scales", C.c_void_p), ("N", C.c_int32),
+                ("K", C.c_int32), ("x_bf16", C.c_void_p), ("y", C.c_void_p),
+                ("y_dtype", C.c_int32), ("precision", C.c_int32)]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load libnvq.so (built beforehand by paper_2604_21026_amd.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            "%s not found: build it with `python -m paper_2604_21026_amd.build`" % LIB_PATH)
+    L = C.CDLL(LIB_PATH)
+    vp, ci, i64, sz = C.c_void_p, C.c_int, C.c_int64, C.c_size_t
+    L.nvq_status_string.restype = C.c_char_p
+    L.nvq_status_string.argtypes = [ci]
+    L.nvq_last_hip_error.restype = C.c_char_p
+    L.nvq_last_hip_error.argtypes = []
+    L.nvq_pack_int4.argtypes = [vp, i64, i64, ci, vp, vp, vp]
+    L.nvq_quant_act_i8.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp]
+    L.nvq_gemv_w4a16.argtypes = [vp, vp, ci, ci, vp, ci, vp, ci, vp]
+    L.nvq_gemv_w4a8.argtypes = [vp, vp, ci, ci, vp, vp, vp, ci, ci, vp, ci, vp, vp]
+    L.nvq_decode_workspace_bytes.restype = sz
+    L.nvq_decode_workspace_bytes.argtypes = [vp, ci, ci, ci]
+    L.nvq_decode_linears.argtypes = [vp, ci, ci, ci, vp, sz, vp]
+    L.nvq_precision_from_scores.argtypes = [vp, ci, C.c_double, C.c_double, vp]
+    L.nvq_stream_read.argtypes = [vp, sz, vp, vp]
+    L.nvq_stream_copy.argtypes = [vp, vp, sz, vp]
+    for f in ("nvq_pack_int4", "nvq_quant_act_i8", "nvq_gemv_w4a16", "nvq_gemv_w4a8",
+              "nvq_decode_linears", "nvq_precision_from_scores", "nvq_stream_read",
+              "nvq_stream_copy"):
+        getattr(L, f).restype = ci
+    _lib = L
+    return L
+
+
+def _status_string(status: int) -> str:
+    return lib().nvq_status_string(status).decode()
+
+
+def _check(status: int, what: str):
+    if status != 0:
+        detail = lib().nvq_last_hip_error().decode() if status == 5 else ""
+        raise NvqError(status, what, detail)
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev(t: torch.Tensor, dtype, name: str) -> int:
+    if not t.is_cuda:
+        raise ValueError("%s must be a device tensor" % name)
+    if t.dtype != dtype:
+        raise ValueError("%s must be %s, got %s" % (name, dtype, t.dtype))
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    return t.data_ptr()
+
+
+def _y_dtype(dtype) -> int:
+    if dtype == torch.float32:
+        return F32
+    if dtype == torch.bfloat16:
+        return BF16
+    raise ValueError("output dtype must be float32 or bfloat16")
+
+
+# ---- entry points (same names as the C ABI) ----------------------------------
+def pack_int4(W: torch.Tensor, group: int = 32):
+    """W fp32 [N,K] (device) -> qweight u8 [N,K/2], scales int16 (fp16 bits) [N,K/32]."""
+    N, K = W.shape
+    q = torch.empty((N, K // 2), dtype=torch.uint8, device=W.device)
+    s = torch.empty((N, K // 32), dtype=torch.int16, device=W.device)
+    _check(lib().nvq_pack_int4(_dev(W, torch.float32, "W"), N, K, group, q.data_ptr(),
+                               s.data_ptr(), _stream()), "nvq_pack_int4")
+    return q, s
+
+
+def quant_act_i8(x: torch.Tensor, act_group: int = 0):
+    """x bf16 [M,K] -> xq i8 [M,K], xscale f32 [M] or [M,K/32], xgsum i32 [M,K/32]."""
+    M, K = x.shape
+    xq = torch.empty((M, K), dtype=torch.int8, device=x.device)
+    xs = torch.empty((M,) if act_group == 0 else (M, K // 32), dtype=torch.float32,
+                     device=x.device)
+    gs = torch.empty((M, K // 32), dtype=torch.int32, device=x.device)
+    _check(lib().nvq_quant_act_i8(_dev(x, torch.bfloat16, "x"), M, K, act_group, xq.data_ptr(),
+                                  xs.data_ptr(), gs.data_ptr(), _stream()), "nvq_quant_act_i8")
+    return xq, xs, gs
+
+
+def gemv_w4a16(qweight, scales, x, out_dtype=torch.float32, out: Optional[torch.Tensor] = None):
+    N, K = qweight.shape[0], qweight.shape[1] * 2
+    M = x.shape[0]
+    if x.shape[1] != K or tuple(scales.shape) != (N, K // 32):
+        raise ValueError("shape mismatch")
+    y = out if out is not None else torch.empty((M, N), dtype=out_dtype, device=x.device)
+    _check(lib().nvq_gemv_w4a16(_dev(qweight, torch.uint8, "qweight"),
+                                _dev(scales, torch.int16, "scales"), N, K,
+                                _dev(x, torch.bfloat16, "x"), M, _dev(y, y.dtype, "y"),
+                                _y_dtype(y.dtype), _stream()), "nvq_gemv_w4a16")
+    return y
+
+
+def gemv_w4a8(qweight, scales, xq, xscale, xgsum, act_group: int = 0,
+              out_dtype=torch.float32, want_acc: bool = False,
+              out: Optional[torch.Tensor] = None):
+    N, K = qweight.shape[0], qweight.shape[1] * 2
+    M = xq.shape[0]
+    if xq.shape[1] != K or tuple(scales.shape) != (N, K // 32):
+        raise ValueError("shape mismatch")
+    y = out if out is not None else torch.empty((M, N), dtype=out_dtype, device=xq.device)
+    acc = (torch.empty((M, N, K // 32), dtype=torch.int32, device=xq.device)
+           if want_acc else None)
+    _check(lib().nvq_gemv_w4a8(_dev(qweight, torch.uint8, "qweight"),
+                               _dev(scales, torch.int16, "scales"), N, K,
+                               _dev(xq, torch.int8, "xq"), _dev(xscale, torch.float32, "xscale"),
+                               _dev(xgsum, torch.int32, "xgsum"), act_group, M,
+                               _dev(y, y.dtype, "y"), _y_dtype(y.dtype),
+                               acc.data_ptr() if want_acc else None, _stream()),
+           "nvq_gemv_w4a8")
+    return (y, acc) if want_acc else y
+
+
+class DecodeList:
+    """A host-side `nvq_linear[]` plus the tensors it points to and its workspace."""
+
+    def __init__(self, entries: Sequence[dict], M: int, act_group: int = 0):
+        self.M, self.act_group = M, act_group
+        self.n = len(entries)
+        self.arr = (Linear * max(self.n, 1))()
+        self.keep: List[torch.Tensor] = []
+        dev = None
+        for i, e in enumerate(entries):
+            q, s, x, y = e["qweight"], e["scales"], e["x"], e["y"]
+            N, K = q.shape[0], q.shape[1] * 2
+            if tuple(x.shape) != (M, K) or tuple(y.shape) != (M, N):
+                raise ValueError("entry %d: shape mismatch" % i)
+            self.arr[i] = Linear(_dev(q, torch.uint8, "qweight"), _dev(s, torch.int16, "scales"),
+                                 N, K, _dev(x, torch.bfloat16, "x"), _dev(y, y.dtype, "y"),
+                                 _y_dtype(y.dtype), int(e["precision"]))
+            self.keep += [q, s, x, y]
+            dev = q.device
+        need = lib().nvq_decode_workspace_bytes(C.byref(self.arr), self.n, M, act_group)
+        if self.n and need == 0:
+            raise NvqError(1, "nvq_decode_workspace_bytes")
+        self.workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev or "cuda")
+
+    def run(self):
+        _check(lib().nvq_decode_linears(C.byref(self.arr), self.n, self.M, self.act_group,
+                                        self.workspace.data_ptr(), self.workspace.numel(),
+                                        _stream()), "nvq_decode_linears")
+
+
+def decode_linears(entries: Sequence[dict], M: int, act_group: int = 0) -> DecodeList:
+    """Run one walk over `entries` (dicts with qweight, scales, x, y, precision)."""
+    dl = DecodeList(entries, M, act_group)
+    dl.run()
+    return dl
+
+
+def precision_from_scores(scores: Sequence[float], tau: float = 0.7, eps: float = 1e-12):
+    n = len(scores)
+    s = (C.c_double * n)(*[float(v) for v in scores])
+    out = (C.c_int32 * n)()
+    _check(lib().nvq_precision_from_scores(s, n, tau, eps, out), "nvq_precision_from_scores")
+    return list(out)
+
+
+def stream_read(buf: torch.Tensor, sink: torch.Tensor):
+    _check(lib().nvq_stream_read(buf.data_ptr(), buf.numel() * buf.element_size(),
+                                 sink.data_ptr(), _stream()), "nvq_stream_read")
+
+
+def stream_copy(dst: torch.Tensor, src: torch.Tensor):
+    _check(lib().nvq_stream_copy(dst.data_ptr(), src.data_ptr(),
+                                 src.numel() * src.element_size(), _stream()), "nvq_stream_copy")

@@ -1,0 +1,293 @@
+"""GPU parity: every entry point of libnvq, called through the C ABI, against
+the CPU oracle on the same seeded inputs.
+
+Bars: packed int4 bytes, fp16 scale bits, int8 activation codes, activation
+scales, block sums and W4A8 int32 accumulators are bit-exact; floating-point
+outputs are within 1e-3 relative L2 of the float64 oracle (fp32 accumulation;
+the observed error is around 1e-6)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2604_21026_amd import nvq, synth
+from tests import np_ref
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-3
+DEV = "cuda"
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def u16(t):
+    return t.cpu().view(torch.int16).numpy().view(np.uint16)
+
+
+def packed(seed, N, K):
+    W = synth.make_weight(seed, N, K)
+    q, s = oracle.pack_int4(W.numpy())
+    return W, q, s
+
+
+def to_dev_packed(q, s):
+    return (torch.from_numpy(q).to(DEV), torch.from_numpy(s.view(np.int16)).to(DEV))
+
+
+def act(seed, M, K, outliers=True):
+    return synth.make_activation(seed, M, K, outliers)
+
+
+# ---- a1 pack -----------------------------------------------------------------
+@pytest.mark.parametrize("N,K", [(5, 32), (64, 2048), (33, 3072), (257, 4096), (7, 14336),
+                                 (1, 64), (1031, 1024)])
+def test_pack_int4_bit_exact(N, K):
+    say("pack", N, K)
+    W, q_ref, s_ref = packed(1000 + N, N, K)
+    q, s = nvq.pack_int4(W.to(DEV))
+    torch.cuda.synchronize()
+    assert np.array_equal(q.cpu().numpy(), q_ref)
+    assert np.array_equal(u16(s), s_ref)
+
+
+def test_pack_int4_edge_values():
+    say("pack edge")
+    W = torch.zeros(4, 64)
+    S7 = 2.0 ** -7
+    W[0, :12] = torch.tensor([7, 2.5, 3.5, -0.5, 0.5, 1.5, -2.5, -3.5, 6.5, -6.5, 4.5, 5.5]) * S7
+    W[1, 40] = 0.5                      # one zero group, one single-spike group
+    W[2, :32] = 1e-7                    # scale in the fp16 subnormal range
+    W[2, 32:] = -3e-6
+    W[3, 5] = 7 * 65504.0               # largest finite fp16 scale
+    q_ref, s_ref = oracle.pack_int4(W.numpy())
+    q, s = nvq.pack_int4(W.to(DEV))
+    torch.cuda.synchronize()
+    assert np.array_equal(q.cpu().numpy(), q_ref)
+    assert np.array_equal(u16(s), s_ref)
+    assert np_ref.unpack_codes(q.cpu().numpy())[0, :12].tolist() == [7, 2, 4, 0, 0, 2, -2, -4, 6, -6, 4, 6]
+
+
+# ---- a2 activation quantisation ----------------------------------------------
+@pytest.mark.parametrize("M,K,group", [(1, 32, 0), (1, 2048, 0), (3, 3072, 0), (1, 4096, 0),
+                                       (2, 8192, 0), (1, 14336, 0), (32, 4096, 0),
+                                       (1, 4096, 32), (4, 14336, 32), (2, 96, 32)])
+def test_quant_act_bit_exact(M, K, group):
+    say("quant", M, K, group)
+    x = act(2000 + K + M, M, K)
+    xq_r, xs_r, gs_r = oracle.quant_act_i8(u16(x), group)
+    xq, xs, gs = nvq.quant_act_i8(x.to(DEV), group)
+    torch.cuda.synchronize()
+    assert np.array_equal(xq.cpu().numpy(), xq_r)
+    assert np.array_equal(xs.cpu().numpy().view(np.uint32), xs_r.view(np.uint32))
+    assert np.array_equal(gs.cpu().numpy(), gs_r)
+
+
+def test_quant_act_edge_values():
+    say("quant edge")
+    x = torch.zeros(3, 64)
+    x[1, :11] = torch.tensor([127.0, 0.5, 1.5, 2.5, -127.0, 3.5, -0.5, -1.5, -2.5, 126.5, 125.5])
+    x[2, 40] = -3.0
+    xb = x.to(torch.bfloat16)
+    for group in (0, 32):
+        xq_r, xs_r, gs_r = oracle.quant_act_i8(u16(xb), group)
+        xq, xs, gs = nvq.quant_act_i8(xb.to(DEV), group)
+        torch.cuda.synchronize()
+        assert np.array_equal(xq.cpu().numpy(), xq_r)
+        assert np.array_equal(xs.cpu().numpy(), xs_r)
+        assert np.array_equal(gs.cpu().numpy(), gs_r)
+    assert xq_r[1, :11].tolist() == [127, 0, 2, 2, -127, 4, 0, -2, -2, 126, 126]
+
+
+# ---- a3 W4A8 -------------------------------------------------------------------
+W4A8_CASES = [
+    # N, K, M, act_group: every lane/row decomposition of the batch-1 kernel, ragged row
+    # tails, more rows than one grid pass, the generic kernel (M > 1, K > 16384)
+    (3, 32, 1, 0), (37, 1024, 1, 0), (70, 2048, 1, 0), (45, 2080, 1, 0), (29, 3072, 1, 0),
+    (61, 4096, 1, 0), (19, 6144, 1, 0), (23, 8192, 1, 0), (11, 10240, 1, 0), (9, 12288, 1, 0),
+    (13, 14336, 1, 0), (7, 16384, 1, 0), (5, 16416, 1, 0),
+    (20011, 2048, 1, 0), (9003, 4096, 1, 0), (2501, 14336, 1, 0), (3000, 3072, 1, 0),
+    (33, 4096, 1, 32), (21, 14336, 1, 32), (18, 3072, 1, 32),
+    (40, 4096, 2, 0), (40, 4096, 4, 0), (17, 3072, 5, 0), (24, 14336, 8, 0), (12, 2048, 32, 0),
+    (20, 4096, 3, 32),
+]
+
+
+@pytest.mark.parametrize("N,K,M,group", W4A8_CASES)
+def test_gemv_w4a8_acc_bit_exact_and_output(N, K, M, group):
+    say("w4a8", N, K, M, group)
+    _, q, s = packed(3000 + N, N, K)
+    x = act(3100 + K, M, K)
+    xq_r, xs_r, gs_r = oracle.quant_act_i8(u16(x), group)
+    y_r, acc_r = oracle.gemv_w4a8(q, s, xq_r, xs_r, group, want_acc=True)
+    qd, sd = to_dev_packed(q, s)
+    xq, xs, gs = nvq.quant_act_i8(x.to(DEV), group)
+    y, acc = nvq.gemv_w4a8(qd, sd, xq, xs, gs, group, want_acc=True)
+    y2 = nvq.gemv_w4a8(qd, sd, xq, xs, gs, group)            # the non-debug kernel
+    torch.cuda.synchronize()
+    assert np.array_equal(acc.cpu().numpy(), acc_r)
+    assert np_ref.rel_l2(y.cpu().numpy(), y_r) < TOL
+    assert torch.equal(y, y2)
+    assert np_ref.rel_l2(y.cpu().numpy(), y_r) < 1e-5        # what fp32 accumulation gives
+
+
+def test_gemv_w4a8_accepts_every_nibble_and_extreme_codes():
+    say("w4a8 extremes")
+    rng = np.random.default_rng(17)
+    N, K = 50, 4096
+    q = rng.integers(0, 256, (N, K // 2), dtype=np.uint8)      # includes nibble 0 = code -8
+    q[0, :] = 0x00
+    q[1, :] = 0xFF
+    s = rng.integers(0x1400, 0x2c00, (N, K // 32)).astype(np.uint16)
+    xq = rng.integers(-127, 128, (1, K)).astype(np.int8)
+    xq[0, :64] = -127
+    xs = np.array([0.03125], np.float32)
+    gs = xq.astype(np.int32).reshape(1, K // 32, 32).sum(axis=2).astype(np.int32)
+    y_r, acc_r = oracle.gemv_w4a8(q, s, xq, xs, want_acc=True)
+    assert acc_r.max() == 32512
+    qd, sd = to_dev_packed(q, s)
+    y, acc = nvq.gemv_w4a8(qd, sd, torch.from_numpy(xq).to(DEV), torch.from_numpy(xs).to(DEV),
+                           torch.from_numpy(gs).to(DEV), want_acc=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(acc.cpu().numpy(), acc_r)
+    assert np_ref.rel_l2(y.cpu().numpy(), y_r) < TOL
+
+
+# ---- a4 W4A16 ------------------------------------------------------------------
+W4A16_CASES = [(n, k, m) for (n, k, m, g) in W4A8_CASES if g == 0]
+
+
+@pytest.mark.parametrize("N,K,M", W4A16_CASES)
+def test_gemv_w4a16_output(N, K, M):
+    say("w4a16", N, K, M)
+    _, q, s = packed(4000 + N, N, K)
+    x = act(4100 + K, M, K)
+    y_r = oracle.gemv_w4a16(q, s, u16(x))
+    qd, sd = to_dev_packed(q, s)
+    y = nvq.gemv_w4a16(qd, sd, x.to(DEV))
+    torch.cuda.synchronize()
+    err = np_ref.rel_l2(y.cpu().numpy(), y_r)
+    say("  rel_l2", err)
+    assert err < TOL
+
+
+def test_gemv_w4a16_accepts_every_nibble():
+    say("w4a16 nibbles")
+    rng = np.random.default_rng(18)
+    N, K = 40, 3072
+    q = rng.integers(0, 256, (N, K // 2), dtype=np.uint8)
+    s = rng.integers(0x1400, 0x2c00, (N, K // 32)).astype(np.uint16)
+    x = act(77, 1, K)
+    y_r = oracle.gemv_w4a16(q, s, u16(x))
+    qd, sd = to_dev_packed(q, s)
+    y = nvq.gemv_w4a16(qd, sd, x.to(DEV))
+    torch.cuda.synchronize()
+    assert np_ref.rel_l2(y.cpu().numpy(), y_r) < TOL
+
+
+@pytest.mark.parametrize("prec", [nvq.W4A8, nvq.W4A16])
+def test_bf16_output_is_the_rounded_fp32_output(prec):
+    say("bf16 out", prec)
+    N, K = 100, 4096
+    _, q, s = packed(5000, N, K)
+    x = act(5001, 1, K).to(DEV)
+    qd, sd = to_dev_packed(q, s)
+    if prec == nvq.W4A16:
+        y32 = nvq.gemv_w4a16(qd, sd, x)
+        y16 = nvq.gemv_w4a16(qd, sd, x, out_dtype=torch.bfloat16)
+    else:
+        xq, xs, gs = nvq.quant_act_i8(x)
+        y32 = nvq.gemv_w4a8(qd, sd, xq, xs, gs)
+        y16 = nvq.gemv_w4a8(qd, sd, xq, xs, gs, out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    assert torch.equal(y16, y32.to(torch.bfloat16))
+
+
+# ---- a5 walker -------------------------------------------------------------------
+def tiny_model_entries(M, seed=6000, hidden=256, kv=64, ffn=704, blocks=3, bits=(0, 1, 0)):
+    """Three transformer-block-shaped groups of seven linears; K = 256 and 704
+    (22 groups: a ragged lane tail)."""
+    entries, host = [], []
+    for b in range(blocks):
+        xs = [act(seed + 10 * b + p, M, k, True) for p, k in enumerate([hidden, hidden, hidden, ffn])]
+        shapes = [(hidden, hidden, 0), (kv, hidden, 0), (kv, hidden, 0), (hidden, hidden, 1),
+                  (ffn, hidden, 2), (ffn, hidden, 2), (hidden, ffn, 3)]
+        for slot, (N, K, p) in enumerate(shapes):
+            _, q, s = packed(seed + 100 * b + slot, N, K)
+            host.append(dict(qweight=q, scales=s, x=u16(xs[p]), precision=bits[b]))
+            qd, sd = to_dev_packed(q, s)
+            entries.append(dict(qweight=qd, scales=sd, x=None, xkey=(b, p), xhost=xs[p],
+                                y=torch.zeros((M, N), dtype=torch.float32, device=DEV),
+                                precision=bits[b]))
+    # entries of one phase must share one device buffer (the walker keys on the pointer)
+    bufs = {}
+    for e in entries:
+        if e["xkey"] not in bufs:
+            bufs[e["xkey"]] = e["xhost"].to(DEV)
+        e["x"] = bufs[e["xkey"]]
+    return entries, host
+
+
+@pytest.mark.parametrize("M,group", [(1, 0), (1, 32), (3, 0)])
+def test_decode_linears_matches_oracle_walker_and_standalone_calls(M, group):
+    say("walker", M, group)
+    entries, host = tiny_model_entries(M)
+    ys_ref = oracle.decode_linears(host, M, group)
+    nvq.decode_linears(entries, M, group)
+    torch.cuda.synchronize()
+    for e, h, y_r in zip(entries, host, ys_ref):
+        got = e["y"].cpu().numpy()
+        assert np_ref.rel_l2(got, y_r) < TOL
+        # same result as the standalone entry point with the same arguments
+        if e["precision"] == nvq.W4A16:
+            alone = nvq.gemv_w4a16(e["qweight"], e["scales"], e["x"])
+            other = None
+        else:
+            xq, xs, gs = nvq.quant_act_i8(e["x"], group)
+            alone = nvq.gemv_w4a8(e["qweight"], e["scales"], xq, xs, gs, group)
+            other = nvq.gemv_w4a16(e["qweight"], e["scales"], e["x"])
+        assert torch.equal(alone, e["y"])
+        if other is not None:                      # the precision bit was respected
+            assert not torch.equal(other, e["y"])
+
+
+def test_decode_linears_runs_in_order_on_chained_buffers():
+    say("walker chain")
+    # entry 1 reads what entry 0 wrote (bf16 output feeding the next input)
+    M, K0, N0, N1 = 1, 2048, 4096, 512
+    _, q0, s0 = packed(7000, N0, K0)
+    W1 = synth.make_weight(7001, N1, N0)
+    q1, s1 = oracle.pack_int4(W1.numpy())
+    x0 = act(7002, M, K0)
+    q0d, s0d = to_dev_packed(q0, s0)
+    q1d, s1d = to_dev_packed(q1, s1)
+    mid = torch.zeros((M, N0), dtype=torch.bfloat16, device=DEV)
+    out = torch.zeros((M, N1), dtype=torch.float32, device=DEV)
+    for p0, p1 in [(1, 0), (0, 1)]:
+        mid.zero_(); out.zero_()
+        nvq.decode_linears([dict(qweight=q0d, scales=s0d, x=x0.to(DEV), y=mid, precision=p0),
+                            dict(qweight=q1d, scales=s1d, x=mid, y=out, precision=p1)], M)
+        torch.cuda.synchronize()
+        # oracle on the GPU's own intermediate (bf16 rounding of entry 0 is checked above)
+        mid_h = u16(mid)
+        ys = oracle.decode_linears([dict(qweight=q1, scales=s1, x=mid_h, precision=p1)], M)
+        assert np_ref.rel_l2(out.cpu().numpy(), ys[0]) < TOL
+        y0 = oracle.decode_linears([dict(qweight=q0, scales=s0, x=u16(x0), precision=p0)], M)[0]
+        assert np_ref.rel_l2(mid.float().cpu().numpy(), y0) < 4e-3   # bf16 output rounding
+
+
+def test_measurement_helpers():
+    say("stream helpers")
+    src = torch.randint(0, 255, (1 << 20,), dtype=torch.uint8, device=DEV)
+    dst = torch.zeros_like(src)
+    sink = torch.zeros(1, dtype=torch.int64, device=DEV)
+    nvq.stream_copy(dst, src)
+    nvq.stream_read(src, sink)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
+    w = src.cpu().numpy().view(np.uint32).reshape(-1, 4)
+    want = int((w[:, 0] ^ w[:, 1] ^ w[:, 2] ^ w[:, 3]).astype(np.uint64).sum())
+    # per-lane sums wrap at 32 bits before the 64-bit atomic; compare modulo 2^32
+    assert int(sink.item()) % (1 << 32) == want % (1 << 32)
