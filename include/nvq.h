@@ -148,15 +148,45 @@ typedef struct nvq_linear {
  * paragraph gives the reason).
  *   layers   host array of n entries (read during the call only)
  *   Entries complete in order: entry i may read what an earlier entry wrote.
- *   Consecutive entries with the same x_bf16, K and precision form a phase:
- *   they share one activation quantisation and run concurrently.
+ *   Consecutive entries with the same x_bf16, K and precision form a phase
+ *   (at most four entries): they share one activation quantisation and run
+ *   concurrently.  Phases are strictly ordered.
  *   workspace  device buffer of at least nvq_decode_workspace_bytes(...)
  *              bytes, 256-byte aligned; its contents are scratch.
+ * At M = 1 the whole list runs as ONE persistent kernel that keeps streaming
+ * the weights of coming phases while a phase waits for its input (needs every
+ * K <= 14336 with K % 64 == 0 and 4-byte aligned scales); otherwise one or
+ * two launches per phase are enqueued.  Both give the same results.
+ * nvq_decode_linears copies its phase table to the device on every call
+ * (a blocking copy of a few KiB); a plan does that once.
  * nvq_decode_workspace_bytes returns 0 for invalid arguments.
  */
 size_t nvq_decode_workspace_bytes(const nvq_linear *layers, int n, int M, int act_group);
 int nvq_decode_linears(const nvq_linear *layers, int n, int M, int act_group,
                        void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Plans: the same walk, prepared once and run many times (the role graph
+ * capture plays in the paper's decode loop).  A plan is a small host object
+ * (the only thing the library allocates, with new/delete); it keeps a copy of
+ * the layer list and owns nothing on the device.  The workspace must stay
+ * untouched by others between nvq_plan_create and nvq_plan_destroy, and runs
+ * of one plan must not overlap (issue them on one stream).
+ *   nvq_plan_create  validates, uploads the phase table on `stream`
+ *   nvq_plan_run     enqueues one walk on `stream`
+ *   nvq_plan_info    streaming = 1 if the persistent kernel is used
+ *   nvq_plan_status  synchronises `stream` and reports whether a wait inside
+ *                    the persistent kernel gave up (its spins are bounded so
+ *                    that a grid that cannot be co-resident ends with an
+ *                    error instead of a hang); outputs are invalid then
+ */
+typedef struct nvq_plan nvq_plan;
+int nvq_plan_create(const nvq_linear *layers, int n, int M, int act_group, void *workspace,
+                    size_t workspace_bytes, void *stream, nvq_plan **plan);
+int nvq_plan_run(nvq_plan *plan, void *stream);
+int nvq_plan_info(const nvq_plan *plan, int *streaming, int *phases);
+int nvq_plan_status(nvq_plan *plan, void *stream, int *timed_out);
+void nvq_plan_destroy(nvq_plan *plan);
 
 /*
  * nvq_precision_from_scores -- host helper: the normalise-and-assign tail of

@@ -1,42 +1,63 @@
-// nvq_decode_linears: walk the linear layers of one decode step under a
-// per-layer precision map.  Paper: routing rule of the precision-dispatch
-// section (W4A16 if the layer's normalised score reaches the threshold, else
-// W4A8); activation codes are computed once per input and reused by every
-// projection that reads it.
+// nvq_decode_linears / nvq_plan_*: walk the linear layers of one decode step
+// under a per-layer precision map.  Paper: routing rule of the
+// precision-dispatch section (W4A16 if the layer's normalised score reaches
+// the threshold, else W4A8); activation codes are computed once per input and
+// reused by every projection that reads it; the step is issued without
+// per-kernel host round trips (paragraph on graph capture for decode).
 //
 // The host groups consecutive entries that read the same input with the same
-// precision into a phase (q/k/v, gate/up) and serves a phase with one fused
-// GEMV launch over up to four weight matrices.  Launches are only enqueued,
-// never waited for, so a caller can record the whole walk into a HIP graph.
-#include "nvq_internal.h"
+// precision into a phase (q/k/v, gate/up; at most four matrices per phase).
+// Batch 1 runs the whole list in one launch of the persistent streaming
+// kernel (decode_stream.hip).  Other batch sizes, and shapes the streaming
+// kernel does not take, run one quantisation launch per W4A8 phase and one
+// fused GEMV launch per phase on the caller's stream.
+#include <new>
+#include <vector>
+
+#include "decode_stream.h"
 
 namespace nvq {
 
+namespace {
+
+size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+constexpr int kMaxStreamWg = 1024;  // flag words reserved in the workspace
+
+// Workspace layout (offsets from a 256-byte aligned base).
 struct Workspace {
-    int8_t *xq;
-    float *xscale;
-    int32_t *xgsum;
+    int8_t *xq;         // [M][maxK]           activation codes (per-phase launches)
+    float *xscale;      // [M][maxK/32]
+    int32_t *xgsum;     // [M][maxK/32]
+    StreamPhase *tab;   // [n]                 phase table of the streaming kernel
+    uint32_t *flags;    // [kMaxStreamWg]      one word per workgroup
+    uint32_t *status;   // [64]                word 0: a wait timed out
+    void *dummy;        // 1 KiB               target of the ring's filler loads
     size_t bytes;
 };
 
-static size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
-
-// Scratch for the activation codes of the widest layer.
-static Workspace carve(void *base, int maxK, int M) {
+Workspace carve(void *base, int maxK, int M, int n) {
     Workspace w;
+    char *b = reinterpret_cast<char *>(base);
     const size_t G = (size_t)maxK / 32;
     size_t off = 0;
-    w.xq = reinterpret_cast<int8_t *>(reinterpret_cast<char *>(base) + off);
-    off += round_up((size_t)M * maxK, 256);
-    w.xscale = reinterpret_cast<float *>(reinterpret_cast<char *>(base) + off);
-    off += round_up((size_t)M * G * 4, 256);
-    w.xgsum = reinterpret_cast<int32_t *>(reinterpret_cast<char *>(base) + off);
-    off += round_up((size_t)M * G * 4, 256);
+    auto take = [&](size_t bytes) {
+        char *p = b + off;
+        off += round_up(bytes, 256);
+        return p;
+    };
+    w.xq = reinterpret_cast<int8_t *>(take((size_t)M * maxK));
+    w.xscale = reinterpret_cast<float *>(take((size_t)M * G * 4));
+    w.xgsum = reinterpret_cast<int32_t *>(take((size_t)M * G * 4));
+    w.tab = reinterpret_cast<StreamPhase *>(take((size_t)(n > 0 ? n : 1) * sizeof(StreamPhase)));
+    w.flags = reinterpret_cast<uint32_t *>(take(kMaxStreamWg * 4));
+    w.status = reinterpret_cast<uint32_t *>(take(256));
+    w.dummy = take(1024);
     w.bytes = off;
     return w;
 }
 
-static int check_layers(const nvq_linear *L, int n, int M, int act_group, int *maxK) {
+int check_layers(const nvq_linear *L, int n, int M, int act_group, int *maxK) {
     if (!L || n < 0) return NVQ_ERR_INVALID_ARG;
     if (act_group != 0 && act_group != 32) return NVQ_ERR_INVALID_ARG;
     if (M <= 0 || M > NVQ_MAX_M) return NVQ_ERR_SHAPE;
@@ -56,63 +77,223 @@ static int check_layers(const nvq_linear *L, int n, int M, int act_group, int *m
     return NVQ_OK;
 }
 
+// Consecutive entries with the same input, K and precision, at most kMaxSeg.
+struct Phase {
+    int first, count;
+};
+
+std::vector<Phase> group_phases(const nvq_linear *L, int n) {
+    std::vector<Phase> out;
+    int i = 0;
+    while (i < n) {
+        int j = i + 1;
+        while (j < n && j - i < kMaxSeg && L[j].x_bf16 == L[i].x_bf16 && L[j].K == L[i].K &&
+               L[j].precision == L[i].precision)
+            ++j;
+        out.push_back({i, j - i});
+        i = j;
+    }
+    return out;
+}
+
+// True if phase b reads the same input as phase a with the same precision
+// (a phase split only because it had more than kMaxSeg matrices).
+bool same_input(const nvq_linear *L, const Phase &a, const Phase &b) {
+    return L[a.first].x_bf16 == L[b.first].x_bf16 && L[a.first].K == L[b.first].K &&
+           L[a.first].precision == L[b.first].precision;
+}
+
+GemvSegs make_segs(const nvq_linear *L, const Phase &ph) {
+    GemvSegs S = {};
+    int rows = 0;
+    for (int k = 0; k < ph.count; ++k) {
+        const nvq_linear &e = L[ph.first + k];
+        S.qw[k] = reinterpret_cast<const uint4 *>(e.qweight);
+        S.sc[k] = e.scales;
+        S.y[k] = e.y;
+        S.dbg[k] = nullptr;
+        S.N[k] = e.N;
+        rows += e.N;
+        S.row_end[k] = rows;
+        S.y_dtype[k] = e.y_dtype;
+    }
+    S.nseg = ph.count;
+    S.total_rows = rows;
+    return S;
+}
+
+// One launch (or two) per phase on the caller's stream.
+int walk_per_phase(const nvq_linear *L, const std::vector<Phase> &phases, int M, int act_group,
+                   const Workspace &ws, hipStream_t st) {
+    for (size_t p = 0; p < phases.size(); ++p) {
+        const Phase &ph = phases[p];
+        const nvq_linear &e0 = L[ph.first];
+        const bool w4a8 = e0.precision == NVQ_W4A8;
+        if (w4a8 && !(p > 0 && same_input(L, phases[p - 1], ph))) {
+            const int q = launch_quant_act(e0.x_bf16, M, e0.K, act_group, ws.xq, ws.xscale,
+                                           ws.xgsum, st);
+            if (q != NVQ_OK) return q;
+        }
+        const GemvSegs S = make_segs(L, ph);
+        const int g = w4a8 ? launch_gemv_w4a8(S, e0.K, ws.xq, ws.xscale, ws.xgsum, act_group, M, st)
+                           : launch_gemv_w4a16(S, e0.K, e0.x_bf16, M, st);
+        if (g != NVQ_OK) return g;
+    }
+    return NVQ_OK;
+}
+
+// Phase table for the streaming kernel; empty if some phase does not qualify.
+std::vector<StreamPhase> stream_table(const nvq_linear *L, const std::vector<Phase> &phases, int M,
+                                      int nwg) {
+    std::vector<StreamPhase> tab;
+    if (M != 1 || nwg <= 0 || nwg > kMaxStreamWg) return tab;
+    const int waves = nwg * kStreamWaves;
+    for (const Phase &ph : phases) {
+        const nvq_linear &e0 = L[ph.first];
+        const int G = e0.K / 32;
+        if (e0.K > kStreamMaxK || (G & 1)) return {};
+        StreamPhase sp = {};
+        int rows = 0;
+        for (int k = 0; k < ph.count; ++k) {
+            const nvq_linear &e = L[ph.first + k];
+            if (!aligned(e.scales, 4)) return {};
+            sp.qw[k] = reinterpret_cast<const uint4 *>(e.qweight);
+            sp.sc[k] = e.scales;
+            sp.y[k] = e.y;
+            rows += e.N;
+            sp.row_end[k] = rows;
+            sp.y_dtype[k] = e.y_dtype;
+        }
+        sp.x = e0.x_bf16;
+        sp.nseg = ph.count;
+        sp.total_rows = rows;
+        sp.K = e0.K;
+        sp.G = G;
+        sp.gpl = (G + 63) / 64;
+        sp.precision = e0.precision;
+        sp.rows_per_wave = (rows + waves - 1) / waves;
+        if (sp.rows_per_wave * kStreamWaves > kStreamYStage) return {};
+        tab.push_back(sp);
+    }
+    return tab;
+}
+
+__global__ void fill_u32_kernel(uint32_t *p, int n, uint32_t v) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+}  // namespace
+
 }  // namespace nvq
+
+struct nvq_plan {
+    std::vector<nvq_linear> layers;
+    std::vector<nvq::Phase> phases;
+    nvq::Workspace ws;
+    int M, act_group;
+    int nwg;           // workgroups of the streaming kernel, 0 = per-phase launches
+    int nphase;        // entries of the device phase table
+    uint32_t runs;     // walks issued so far (advances the flag base)
+};
 
 extern "C" size_t nvq_decode_workspace_bytes(const nvq_linear *layers, int n, int M,
                                              int act_group) {
     int maxK = 0;
     if (nvq::check_layers(layers, n, M, act_group, &maxK) != NVQ_OK) return 0;
-    return nvq::carve(nullptr, maxK, M).bytes;
+    return nvq::carve(nullptr, maxK, M, n).bytes;
 }
 
-extern "C" int nvq_decode_linears(const nvq_linear *layers, int n, int M, int act_group,
-                                  void *workspace, size_t workspace_bytes, void *stream) {
+extern "C" int nvq_plan_create(const nvq_linear *layers, int n, int M, int act_group,
+                               void *workspace, size_t workspace_bytes, void *stream,
+                               nvq_plan **plan_out) {
     using namespace nvq;
+    if (!plan_out) return NVQ_ERR_INVALID_ARG;
+    *plan_out = nullptr;
     int maxK = 0;
     const int rc = check_layers(layers, n, M, act_group, &maxK);
     if (rc != NVQ_OK) return rc;
-    if (n == 0) return NVQ_OK;
     if (!workspace || !aligned(workspace, 256)) return NVQ_ERR_WORKSPACE;
-    const Workspace ws = carve(workspace, maxK, M);
+    const Workspace ws = carve(workspace, maxK, M, n);
     if (workspace_bytes < ws.bytes) return NVQ_ERR_WORKSPACE;
+    nvq_plan *pl = new (std::nothrow) nvq_plan();
+    if (!pl) return NVQ_ERR_UNSUPPORTED;
+    pl->layers.assign(layers, layers + n);
+    pl->phases = group_phases(pl->layers.data(), n);
+    pl->ws = ws;
+    pl->M = M;
+    pl->act_group = act_group;
+    pl->runs = 0;
+    pl->nwg = 0;
+    pl->nphase = 0;
     hipStream_t st = (hipStream_t)stream;
-
-    int i = 0;
-    while (i < n) {
-        // a phase: consecutive entries with the same input, K and precision
-        int j = i + 1;
-        while (j < n && layers[j].x_bf16 == layers[i].x_bf16 && layers[j].K == layers[i].K &&
-               layers[j].precision == layers[i].precision)
-            ++j;
-        const int K = layers[i].K;
-        if (layers[i].precision == NVQ_W4A8) {
-            const int q = launch_quant_act(layers[i].x_bf16, M, K, act_group, ws.xq, ws.xscale,
-                                           ws.xgsum, st);
-            if (q != NVQ_OK) return q;
+    const int nwg = n > 0 ? stream_grid_limit() : 0;
+    const std::vector<StreamPhase> tab = stream_table(pl->layers.data(), pl->phases, M, nwg);
+    if (!tab.empty()) {
+        // pageable source: the copy has left the host buffer when the call returns
+        hipError_t e = hipMemcpyAsync(ws.tab, tab.data(), tab.size() * sizeof(StreamPhase),
+                                      hipMemcpyHostToDevice, st);
+        if (e == hipSuccess) {
+            hipLaunchKernelGGL(fill_u32_kernel, dim3((kMaxStreamWg + 64 + 255) / 256), dim3(256), 0,
+                               st, ws.flags, kMaxStreamWg + 64, 0u);  // flags and status
+            e = hipGetLastError();
         }
-        for (int b = i; b < j; b += kMaxSeg) {
-            GemvSegs S = {};
-            int rows = 0;
-            const int e = b + kMaxSeg < j ? b + kMaxSeg : j;
-            for (int s = b; s < e; ++s) {
-                const int k = s - b;
-                S.qw[k] = reinterpret_cast<const uint4 *>(layers[s].qweight);
-                S.sc[k] = layers[s].scales;
-                S.y[k] = layers[s].y;
-                S.dbg[k] = nullptr;
-                S.N[k] = layers[s].N;
-                rows += layers[s].N;
-                S.row_end[k] = rows;
-                S.y_dtype[k] = layers[s].y_dtype;
-            }
-            S.nseg = e - b;
-            S.total_rows = rows;
-            const int g = layers[i].precision == NVQ_W4A8
-                              ? launch_gemv_w4a8(S, K, ws.xq, ws.xscale, ws.xgsum, act_group, M, st)
-                              : launch_gemv_w4a16(S, K, layers[i].x_bf16, M, st);
-            if (g != NVQ_OK) return g;
+        if (e != hipSuccess) {
+            set_hip_error(e, "nvq_plan_create");
+            delete pl;
+            return NVQ_ERR_HIP;
         }
-        i = j;
+        pl->nwg = nwg;
+        pl->nphase = (int)tab.size();
     }
+    *plan_out = pl;
     return NVQ_OK;
+}
+
+extern "C" int nvq_plan_run(nvq_plan *pl, void *stream) {
+    using namespace nvq;
+    if (!pl) return NVQ_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    if (pl->layers.empty()) return NVQ_OK;
+    if (pl->nwg > 0) {
+        const uint32_t base = pl->runs * (uint32_t)pl->nphase;
+        ++pl->runs;
+        return launch_decode_stream(pl->ws.tab, pl->nphase, pl->act_group, pl->ws.flags,
+                                    pl->ws.status, base, pl->ws.dummy, pl->nwg, st);
+    }
+    return walk_per_phase(pl->layers.data(), pl->phases, pl->M, pl->act_group, pl->ws, st);
+}
+
+extern "C" int nvq_plan_info(const nvq_plan *pl, int *streaming, int *phases) {
+    if (!pl) return NVQ_ERR_INVALID_ARG;
+    if (streaming) *streaming = pl->nwg > 0 ? 1 : 0;
+    if (phases) *phases = (int)pl->phases.size();
+    return NVQ_OK;
+}
+
+extern "C" int nvq_plan_status(nvq_plan *pl, void *stream, int *timed_out) {
+    if (!pl || !timed_out) return NVQ_ERR_INVALID_ARG;
+    uint32_t v = 0;
+    if (pl->nwg > 0) {
+        NVQ_HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
+        NVQ_HIP_TRY(hipMemcpy(&v, pl->ws.status, 4, hipMemcpyDeviceToHost));
+    }
+    *timed_out = (int)v;
+    return NVQ_OK;
+}
+
+extern "C" void nvq_plan_destroy(nvq_plan *pl) { delete pl; }
+
+extern "C" int nvq_decode_linears(const nvq_linear *layers, int n, int M, int act_group,
+                                  void *workspace, size_t workspace_bytes, void *stream) {
+    if (n == 0) {
+        int maxK = 0;
+        return nvq::check_layers(layers, n, M, act_group, &maxK);
+    }
+    nvq_plan *pl = nullptr;
+    int rc = nvq_plan_create(layers, n, M, act_group, workspace, workspace_bytes, stream, &pl);
+    if (rc != NVQ_OK) return rc;
+    rc = nvq_plan_run(pl, stream);
+    nvq_plan_destroy(pl);
+    return rc;
 }

@@ -1,0 +1,41 @@
+// Interface between the host-side walker and the persistent streaming kernel.
+#pragma once
+
+#include "nvq_internal.h"
+
+namespace nvq {
+
+constexpr int kStreamWaves = 4;                          // streaming waves per workgroup
+constexpr int kStreamThreads = (kStreamWaves + 1) * 64;  // plus one control wave
+constexpr int kStreamMaxK = 14336;                       // widest input the LDS stage holds
+constexpr int kStreamYStage = 1024;                      // output rows staged per workgroup
+
+// One phase = up to four weight matrices that read the same input vector.
+// Lives in device memory; every field is read wave-uniformly.
+struct StreamPhase {
+    const uint4 *qw[kMaxSeg];
+    const uint16_t *sc[kMaxSeg];
+    void *y[kMaxSeg];
+    int row_end[kMaxSeg];  // first row after segment i (rows numbered across segments)
+    int y_dtype[kMaxSeg];
+    const uint16_t *x;     // bf16 [K]
+    int nseg, total_rows;
+    int K, G, gpl;         // G = K/32 (even), gpl = ceil(G/64) <= 7
+    int precision;         // NVQ_W4A8 | NVQ_W4A16
+    int rows_per_wave;     // ceil(total_rows / (workgroups * kStreamWaves))
+    int pad_;
+};
+
+// Workgroups the streaming kernel may be launched with (all must be
+// co-resident): the number of compute units, or 0 if the kernel does not fit.
+int stream_grid_limit();
+
+// Enqueue one walk.  `flags` holds one word per workgroup and `status` one
+// word (set to 1 if a wait timed out); both persist between runs of the same
+// table, with `flag_base` advanced by nphase per run.  `dummy` is any valid
+// 1 KiB of device memory.
+int launch_decode_stream(const StreamPhase *tab_dev, int nphase, int act_group, uint32_t *flags,
+                         uint32_t *status, uint32_t flag_base, const void *dummy, int nwg,
+                         hipStream_t st);
+
+}  // namespace nvq

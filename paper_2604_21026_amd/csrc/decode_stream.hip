@@ -1,0 +1,571 @@
+// Persistent streaming kernel for a whole decode step at batch 1.
+//
+// Why: one decode step is a chain of ~130 dependent phases (q/k/v, o, gate/up,
+// down per block) of 1-10 us each at HBM speed.  Launching a kernel per phase
+// leaves the memory system idle at every boundary; the paper removes its
+// launch bubbles with graph capture (paragraph "CUDA graph capture for
+// decode").  Here the whole layer list runs in ONE launch, and, because
+// weights never depend on activations, every wave keeps fetching the weights
+// of the coming phases while it waits for the current phase's input.
+//
+// Structure of a workgroup (one per compute unit, all co-resident):
+//   * kStreamWaves streaming waves.  Each owns a contiguous range of rows in
+//     every phase and sees its work as one flat sequence of 1 KiB chunks
+//     (64 groups x 16 B of one weight row) across all phases.  Chunks are
+//     fetched with non-temporal global->LDS loads into a per-wave ring of
+//     kSlots slots and consumed in order; the ring is refilled as soon as a
+//     pair of slots has been consumed, independent of phase boundaries.
+//     The fp16 scales travel the same way (one dword load per lane serves a
+//     pair of chunks).  A streaming wave issues no other vector-memory
+//     operation, so the number of loads in flight behind any chunk is a
+//     compile-time constant and one `s_waitcnt vmcnt(n)` tells when a pair of
+//     chunks has landed.
+//   * one control wave.  It alone talks to global memory besides the weight
+//     stream: it waits until every workgroup has finished the previous phase
+//     (one flag word per workgroup, no atomics), copies the phase's input
+//     vector into LDS, and after the phase writes the workgroup's outputs
+//     from LDS to memory and publishes its own flag.
+//   Activation quantisation (W4A8 phases) is done by the streaming waves
+//   cooperatively out of LDS, once per workgroup per phase.
+//
+// Phases are strictly ordered: phase p+1 reads its input only after every
+// workgroup has published phase p.  A bounded spin turns a stuck wait (e.g.
+// the grid not co-resident) into an error status instead of a hang.
+#include "decode_stream.h"
+
+namespace nvq {
+
+namespace {
+
+typedef __attribute__((address_space(3))) void *lds_void_ptr;
+
+constexpr int kSlots = 24;            // 1 KiB weight slots per streaming wave
+constexpr int kUnits = kSlots / 2;    // a unit = two chunks + their scales = 3 loads
+constexpr int kOpsPerUnit = 3;
+constexpr int kXStageBytes = kStreamMaxK * 2;  // bf16 input vector
+constexpr uint32_t kSpinLimit = 4u << 20;      // polls before giving up (seconds)
+
+// s_waitcnt immediate that waits for vmcnt <= n only (gfx9 encoding:
+// vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] at [15:14]).
+constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0f70; }
+
+struct Shared {
+    uint4 ring[kStreamWaves][kSlots][64];
+    uint32_t sring[kStreamWaves][kUnits][64];
+    uint4 xstage[kXStageBytes / 16];
+    float xsg[kStreamMaxK / 32];      // per-group activation scales (act_group 32)
+    float ystage[kStreamYStage];
+    float amax_part[kStreamWaves];
+    int abort;
+};
+
+__device__ __forceinline__ void lds_barrier() {
+    // every LDS access issued so far has completed before anyone passes
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+__device__ __forceinline__ uint32_t lds_addr(const void *p) {
+    return (uint32_t)(uintptr_t)p;  // LDS pointers are 32-bit offsets
+}
+
+// LDS reads of a streaming wave are written as instructions: the compiler
+// would otherwise put a full vmcnt(0) wait in front of every LDS read while
+// global->LDS loads are in flight, and drain the weight ring each time.
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 lds_read16(uint32_t addr) {
+    u32x4_t v;
+    asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(addr) : "memory");
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ uint32_t lds_read4(uint32_t addr) {
+    uint32_t v;
+    asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(addr) : "memory");
+    return v;
+}
+
+// LDS writes likewise (the compiler also guards them with vmcnt(0)).  The
+// data reaches LDS before the next lds_barrier(), which waits for lgkmcnt(0).
+__device__ __forceinline__ void lds_write4(uint32_t addr, uint32_t v) {
+    asm volatile("ds_write_b32 %0, %1" : : "v"(addr), "v"(v) : "memory");
+}
+__device__ __forceinline__ void lds_write8(uint32_t addr, uint32_t lo, uint32_t hi) {
+    typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+    u32x2_t v = {lo, hi};
+    asm volatile("ds_write_b64 %0, %1" : : "v"(addr), "v"(v) : "memory");
+}
+
+// Position in a streaming wave's flat chunk sequence (all fields uniform).
+struct Cursor {
+    int p, nphase;
+    int row, row_stop, i, gpl, G;
+    int seg, seg_end;
+    const uint4 *qrow;
+    const uint16_t *srow;
+};
+
+__device__ __forceinline__ void cursor_set_segment(Cursor &c, const StreamPhase &ph) {
+    int seg = 0, first = 0;
+#pragma unroll
+    for (int s = 1; s < kMaxSeg; ++s)
+        if (s < ph.nseg && c.row >= ph.row_end[s - 1]) {
+            seg = s;
+            first = ph.row_end[s - 1];
+        }
+    const uint4 *q = ph.qw[0];
+    const uint16_t *sc = ph.sc[0];
+    int end = ph.row_end[0];
+#pragma unroll
+    for (int s = 1; s < kMaxSeg; ++s)
+        if (seg == s) {
+            q = ph.qw[s];
+            sc = ph.sc[s];
+            end = ph.row_end[s];
+        }
+    c.seg = seg;
+    c.seg_end = end;
+    c.qrow = q + (int64_t)(c.row - first) * c.G;
+    c.srow = sc + (int64_t)(c.row - first) * c.G;
+}
+
+// Enter phase c.p (skipping phases in which this wave owns no rows).
+__device__ __forceinline__ void cursor_enter(Cursor &c, const StreamPhase *tab, int gw) {
+    while (c.p < c.nphase) {
+        const StreamPhase &ph = tab[c.p];
+        const int r0 = gw * ph.rows_per_wave;
+        int r1 = r0 + ph.rows_per_wave;
+        r1 = r1 < ph.total_rows ? r1 : ph.total_rows;
+        if (r0 < r1) {
+            c.row = r0;
+            c.row_stop = r1;
+            c.i = 0;
+            c.gpl = ph.gpl;
+            c.G = ph.G;
+            cursor_set_segment(c, ph);
+            return;
+        }
+        ++c.p;
+    }
+}
+
+__device__ __forceinline__ void cursor_advance(Cursor &c, const StreamPhase *tab, int gw) {
+    if (++c.i < c.gpl) return;
+    c.i = 0;
+    ++c.row;
+    c.qrow += c.G;
+    c.srow += c.G;
+    if (c.row == c.row_stop) {
+        ++c.p;
+        cursor_enter(c, tab, gw);
+    } else if (c.row == c.seg_end) {
+        cursor_set_segment(c, tab[c.p]);
+    }
+}
+
+// Issue the three loads of one unit into unit slot `us` of this wave's ring.
+// Past the end of the stream the loads re-read a dummy line so that the
+// number of loads in flight stays constant.
+__device__ __forceinline__ void issue_unit(Cursor &c, const StreamPhase *tab, int gw, Shared &sh,
+                                           int w, int us, int lane, const uint4 *dummy) {
+    const bool a_ok = c.p < c.nphase;
+    const uint4 *qa = a_ok ? c.qrow + c.i * 64 : dummy;
+    const uint32_t *sa = a_ok ? reinterpret_cast<const uint32_t *>(c.srow + c.i * 64)
+                              : reinterpret_cast<const uint32_t *>(dummy);
+    const int ga = a_ok ? c.G - c.i * 64 : 64;  // valid groups in chunk A
+    if (a_ok) cursor_advance(c, tab, gw);
+    const bool b_ok = c.p < c.nphase;
+    const uint4 *qb = b_ok ? c.qrow + c.i * 64 : dummy;
+    const uint32_t *sb = b_ok ? reinterpret_cast<const uint32_t *>(c.srow + c.i * 64)
+                              : reinterpret_cast<const uint32_t *>(dummy);
+    const int gb = b_ok ? c.G - c.i * 64 : 64;
+    if (b_ok) cursor_advance(c, tab, gw);
+
+    // scales: lanes 0-31 fetch chunk A's 32 dwords, lanes 32-63 chunk B's
+    const int hl = lane & 31;
+    const bool upper = lane >= 32;
+    const uint32_t *sp = (upper ? sb : sa) + hl;
+    if (2 * hl < (upper ? gb : ga))
+        __builtin_amdgcn_global_load_lds((const void *)sp, (lds_void_ptr)&sh.sring[w][us][0], 4, 0,
+                                         2);
+    if (lane < ga)
+        __builtin_amdgcn_global_load_lds((const void *)(qa + lane),
+                                         (lds_void_ptr)&sh.ring[w][2 * us][0], 16, 0, 2);
+    if (lane < gb)
+        __builtin_amdgcn_global_load_lds((const void *)(qb + lane),
+                                         (lds_void_ptr)&sh.ring[w][2 * us + 1][0], 16, 0, 2);
+}
+
+// ---- arithmetic of one chunk ----------------------------------------------
+__device__ __forceinline__ int dot_w4a8(const uint4 &w, const uint32_t (&x)[8], int acc) {
+    const uint32_t wv[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        const uint32_t lo = wv[d] & 0x0f0f0f0fu;
+        const uint32_t hi = (wv[d] >> 4) & 0x0f0f0f0fu;
+        acc = __builtin_amdgcn_sdot4((int)lo, (int)x[d], acc, false);
+        acc = __builtin_amdgcn_sdot4((int)hi, (int)x[4 + d], acc, false);
+    }
+    return acc;
+}
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a),
+                                           __builtin_bit_cast(bf16x2_t, b), c, false);
+}
+
+// Two accumulator chains so that consecutive dot instructions are independent.
+__device__ __forceinline__ float dot_w4a16(const uint4 &w, const uint32_t (&x)[16], float off) {
+    const uint32_t wv[4] = {w.x, w.y, w.z, w.w};
+    constexpr uint32_t kMagic = 0x43434343u;
+    float a0 = off, a1 = 0.0f;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        const uint32_t lo = wv[d] & 0x0f0f0f0fu;
+        const uint32_t hi = (wv[d] >> 4) & 0x0f0f0f0fu;
+        const uint32_t l01 = __builtin_amdgcn_perm(kMagic, lo, 0x04010400u);
+        const uint32_t l23 = __builtin_amdgcn_perm(kMagic, lo, 0x04030402u);
+        const uint32_t h01 = __builtin_amdgcn_perm(kMagic, hi, 0x04010400u);
+        const uint32_t h23 = __builtin_amdgcn_perm(kMagic, hi, 0x04030402u);
+        a0 = dot2_bf16(l01, x[2 * d], a0);
+        a1 = dot2_bf16(l23, x[2 * d + 1], a1);
+        a0 = dot2_bf16(h01, x[8 + 2 * d], a0);
+        a1 = dot2_bf16(h23, x[8 + 2 * d + 1], a1);
+    }
+    return a0 + a1;
+}
+
+// Sum over the 64 lanes; the result is valid in every lane.
+__device__ __forceinline__ float wave_sum(float v) {
+    // quad_perm [1,0,3,2], quad_perm [2,3,0,1], row_half_mirror, row_mirror
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xb1, 0xf, 0xf, true));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4e, 0xf, 0xf, true));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xf, 0xf, true));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xf, 0xf, true));
+    v += __shfl_xor(v, 16, 64);
+    v += __shfl_xor(v, 32, 64);
+    return v;
+}
+
+// ---- consuming one phase ----------------------------------------------------
+struct StreamState {
+    Cursor ic;       // issue cursor
+    uint32_t slot;   // ring slot of the next chunk to consume (chunks are consumed in order)
+    uint32_t uslot;  // unit slot the next refill goes to
+};
+
+template <int PREC, int GPL, bool PER_GROUP>
+__device__ __forceinline__ void consume_phase(const StreamPhase &ph, const StreamPhase *tab,
+                                              StreamState &st, Shared &sh, int w, int gw, int lane,
+                                              const uint4 *dummy, float xs_token) {
+    constexpr int XR = PREC == NVQ_W4A8 ? 8 : 16;
+    // activations of the groups this lane owns, from the LDS stage
+    uint32_t xr[GPL][XR];
+    int neg8[GPL];
+    float xoff[GPL];
+    float xsg[GPL];
+#pragma unroll
+    for (int i = 0; i < GPL; ++i) {
+        const int g = i * 64 + lane;
+        const bool ok = g < ph.G;
+        const int gc = ok ? g : 0;
+        const uint32_t src = lds_addr(sh.xstage) + gc * (XR * 4);
+#pragma unroll
+        for (int q = 0; q < XR / 4; ++q) {
+            const uint4 a = lds_read16(src + q * 16);
+            xr[i][4 * q + 0] = ok ? a.x : 0u;
+            xr[i][4 * q + 1] = ok ? a.y : 0u;
+            xr[i][4 * q + 2] = ok ? a.z : 0u;
+            xr[i][4 * q + 3] = ok ? a.w : 0u;
+        }
+        if constexpr (PREC == NVQ_W4A8) {
+            int s = 0;
+#pragma unroll
+            for (int d = 0; d < 8; ++d) s = __builtin_amdgcn_sdot4(0x01010101, (int)xr[i][d], s, false);
+            neg8[i] = -8 * s;
+            xsg[i] = PER_GROUP ? __uint_as_float(lds_read4(lds_addr(sh.xsg) + gc * 4)) : 1.0f;
+        } else {
+            float s = 0.0f;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) s = dot2_bf16(0x3f803f80u, xr[i][j], s);
+            xoff[i] = -136.0f * s;
+        }
+    }
+
+    const int r0 = gw * ph.rows_per_wave;
+    int r1 = r0 + ph.rows_per_wave;
+    r1 = r1 < ph.total_rows ? r1 : ph.total_rows;
+    const int wg_row0 = (gw - w) * ph.rows_per_wave;
+    const uint32_t ring_base = lds_addr(&sh.ring[w][0][0]) + lane * 16;
+    const uint32_t sring_base = lds_addr(&sh.sring[w][0][0]) + lane * 2;
+
+    for (int row = r0; row < r1; ++row) {
+        float sum = 0.0f;
+#pragma unroll
+        for (int i = 0; i < GPL; ++i) {
+            const uint32_t slot = st.slot;
+            if ((slot & 1u) == 0)  // first chunk of a unit: wait until the unit has landed
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm(kOpsPerUnit * (kUnits - 1)));
+            u32x4_t wraw;
+            uint32_t sbits;
+            asm volatile("ds_read_b128 %0, %2\n\tds_read_u16 %1, %3\n\ts_waitcnt lgkmcnt(0)"
+                         : "=&v"(wraw), "=&v"(sbits)
+                         : "v"(ring_base + slot * 1024u), "v"(sring_base + slot * 128u)
+                         : "memory");
+            const uint4 wv = make_uint4(wraw.x, wraw.y, wraw.z, wraw.w);
+            float sw = half_bits_to_float((uint16_t)sbits);
+            if constexpr (PREC == NVQ_W4A8) {
+                const int acc = dot_w4a8(wv, xr[i], neg8[i]);
+                if (PER_GROUP) sw *= xsg[i];
+                sum = fmaf(sw, (float)acc, sum);
+            } else {
+                sum = fmaf(sw, dot_w4a16(wv, xr[i], xoff[i]), sum);
+            }
+            if (slot & 1u) {  // second chunk of a unit consumed: refill its two slots
+                issue_unit(st.ic, tab, gw, sh, w, (int)st.uslot, lane, dummy);
+                st.uslot = st.uslot + 1 == kUnits ? 0 : st.uslot + 1;
+            }
+            st.slot = slot + 1 == kSlots ? 0 : slot + 1;
+        }
+        sum = wave_sum(sum);
+        if (lane == 0)
+            lds_write4(lds_addr(&sh.ystage[row - wg_row0]),
+                       __float_as_uint(PREC == NVQ_W4A8 ? sum * xs_token : sum));
+    }
+}
+
+// Quantise the staged bf16 input in place (streaming waves, cooperatively).
+// On return xstage holds K int8 codes; returns the per-token scale (1 when the
+// scales are per group).
+template <bool PER_GROUP>
+__device__ __forceinline__ float quantise_stage(const StreamPhase &ph, Shared &sh, int w, int lane) {
+    const int t = w * 64 + lane;             // 0 .. kStreamWaves*64-1
+    constexpr int NT = kStreamWaves * 64;
+    constexpr int MAXC = kStreamMaxK / 8 / NT;  // chunks of 8 values per lane
+    const int chunks = ph.K / 8;
+    uint4 raw[MAXC];
+    float amax = 0.0f;
+#pragma unroll
+    for (int k = 0; k < MAXC; ++k) {
+        const int c = t + k * NT;
+        raw[k] = make_uint4(0, 0, 0, 0);
+        if (k * NT < chunks) {  // uniform: this round holds data for some lane
+            if (c < chunks) raw[k] = lds_read16(lds_addr(sh.xstage) + c * 16);
+            const uint32_t wv[4] = {raw[k].x, raw[k].y, raw[k].z, raw[k].w};
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                amax = fmaxf(amax, fabsf(bf16_bits_to_float(wv[d] & 0xffffu)));
+                amax = fmaxf(amax, fabsf(bf16_bits_to_float(wv[d] >> 16)));
+            }
+        }
+    }
+    float s_tok = 0.0f;
+    if (!PER_GROUP) {
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
+        if (lane == 0) lds_write4(lds_addr(&sh.amax_part[w]), __float_as_uint(amax));
+    }
+    lds_barrier();  // everyone has read its raw values; partial maxima are visible
+    if (!PER_GROUP) {
+        float a = 0.0f;
+#pragma unroll
+        for (int i = 0; i < kStreamWaves; ++i)
+            a = fmaxf(a, __uint_as_float(lds_read4(lds_addr(&sh.amax_part[i]))));
+        s_tok = a / 127.0f;
+    }
+    const uint32_t qstage = lds_addr(sh.xstage);
+#pragma unroll
+    for (int k = 0; k < MAXC; ++k) {
+        if (k * NT >= chunks) break;
+        const int c = t + k * NT;
+        const uint32_t wv[4] = {raw[k].x, raw[k].y, raw[k].z, raw[k].w};
+        float s = s_tok;
+        if (PER_GROUP) {
+            float a = 0.0f;
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                a = fmaxf(a, fabsf(bf16_bits_to_float(wv[d] & 0xffffu)));
+                a = fmaxf(a, fabsf(bf16_bits_to_float(wv[d] >> 16)));
+            }
+            a = fmaxf(a, __shfl_xor(a, 1, 64));
+            a = fmaxf(a, __shfl_xor(a, 2, 64));
+            s = a / 127.0f;
+            if (c < chunks && (c & 3) == 0) lds_write4(lds_addr(&sh.xsg[c >> 2]), __float_as_uint(s));
+        }
+        uint32_t out[2] = {0, 0};
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            int q0 = 0, q1 = 0;
+            if (s != 0.0f) {
+                float r0 = rintf(bf16_bits_to_float(wv[d] & 0xffffu) / s);
+                float r1 = rintf(bf16_bits_to_float(wv[d] >> 16) / s);
+                q0 = (int)fminf(fmaxf(r0, -127.0f), 127.0f);
+                q1 = (int)fminf(fmaxf(r1, -127.0f), 127.0f);
+            }
+            out[d >> 1] |= ((uint32_t)(q0 & 0xff) | ((uint32_t)(q1 & 0xff) << 8)) << (16 * (d & 1));
+        }
+        if (c < chunks) lds_write8(qstage + c * 8, out[0], out[1]);
+    }
+    lds_barrier();  // codes (and group scales) are visible
+    return PER_GROUP ? 1.0f : s_tok;  // group scales are applied per chunk instead
+}
+
+template <int PREC, bool PER_GROUP>
+__device__ __forceinline__ void consume_dispatch(const StreamPhase &ph, const StreamPhase *tab,
+                                                 StreamState &st, Shared &sh, int w, int gw,
+                                                 int lane, const uint4 *dummy, float xs) {
+    switch (ph.gpl) {
+        case 1: consume_phase<PREC, 1, PER_GROUP>(ph, tab, st, sh, w, gw, lane, dummy, xs); break;
+        case 2: consume_phase<PREC, 2, PER_GROUP>(ph, tab, st, sh, w, gw, lane, dummy, xs); break;
+        case 3: consume_phase<PREC, 3, PER_GROUP>(ph, tab, st, sh, w, gw, lane, dummy, xs); break;
+        case 4: consume_phase<PREC, 4, PER_GROUP>(ph, tab, st, sh, w, gw, lane, dummy, xs); break;
+        case 5: consume_phase<PREC, 5, PER_GROUP>(ph, tab, st, sh, w, gw, lane, dummy, xs); break;
+        case 6: consume_phase<PREC, 6, PER_GROUP>(ph, tab, st, sh, w, gw, lane, dummy, xs); break;
+        default: consume_phase<PREC, 7, PER_GROUP>(ph, tab, st, sh, w, gw, lane, dummy, xs); break;
+    }
+}
+
+template <bool PER_GROUP>
+__global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
+    const StreamPhase *__restrict__ tab, int nphase, uint32_t *__restrict__ flags,
+    uint32_t *__restrict__ status, uint32_t flag_base, const uint4 *__restrict__ dummy) {
+    __shared__ Shared sh;
+    // 0..kStreamWaves-1 stream, kStreamWaves = control; made provably wave-uniform
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const int wg = blockIdx.x;
+    const int nwg = gridDim.x;
+    if (threadIdx.x == 0) sh.abort = 0;
+
+    if (w < kStreamWaves) {
+        // ---------------- streaming wave ----------------
+        const int gw = wg * kStreamWaves + w;
+        StreamState st;
+        st.ic.p = 0;
+        st.ic.nphase = nphase;
+        cursor_enter(st.ic, tab, gw);
+        st.slot = 0;
+        st.uslot = 0;
+        for (int u = 0; u < kUnits; ++u)  // fill the ring
+            issue_unit(st.ic, tab, gw, sh, w, u, lane, dummy);
+        for (int p = 0; p < nphase; ++p) {
+            const StreamPhase &ph = tab[p];
+            lds_barrier();  // B1: input vector staged (or abort raised)
+            if (lds_read4(lds_addr(&sh.abort))) break;
+            float xs = 1.0f;
+            if (ph.precision == NVQ_W4A8) {
+                xs = quantise_stage<PER_GROUP>(ph, sh, w, lane);  // B2, B3 inside
+                consume_dispatch<NVQ_W4A8, PER_GROUP>(ph, tab, st, sh, w, gw, lane, dummy, xs);
+            } else {
+                consume_dispatch<NVQ_W4A16, false>(ph, tab, st, sh, w, gw, lane, dummy, xs);
+            }
+            lds_barrier();  // B4: outputs staged
+        }
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // no load may outlive the wave
+    } else {
+        // ---------------- control wave ----------------
+        for (int p = 0; p < nphase; ++p) {
+            const StreamPhase &ph = tab[p];
+            bool ok = true;
+            if (p > 0) {
+                // every workgroup must have published phase p-1
+                const uint32_t target = flag_base + (uint32_t)p;
+                uint32_t spins = 0;
+                for (;;) {
+                    bool all = true;
+                    for (int f0 = 0; f0 < nwg; f0 += 256) {  // four independent loads per lane
+                        uint32_t v[4];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const int f = f0 + j * 64 + lane;
+                            v[j] = f < nwg ? __hip_atomic_load(flags + f, __ATOMIC_RELAXED,
+                                                               __HIP_MEMORY_SCOPE_AGENT)
+                                           : target;
+                        }
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) all = all && (int32_t)(v[j] - target) >= 0;
+                    }
+                    if (__all(all)) break;
+                    if (++spins > kSpinLimit) {
+                        ok = false;
+                        break;
+                    }
+                    __builtin_amdgcn_s_sleep(1);
+                }
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+            }
+            if (!ok) {
+                if (lane == 0) {
+                    sh.abort = 1;
+                    __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+                lds_barrier();  // B1 with abort raised: everybody leaves
+                break;
+            }
+            // stage the input vector (bf16, K values): global->LDS, all loads in flight at once
+            const uint4 *xsrc = reinterpret_cast<const uint4 *>(ph.x);
+            const int n16 = ph.K / 8;
+            for (int c0 = 0; c0 < n16; c0 += 64)
+                if (c0 + lane < n16)
+                    __builtin_amdgcn_global_load_lds((const void *)(xsrc + c0 + lane),
+                                                     (lds_void_ptr)&sh.xstage[c0], 16, 0, 0);
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+            lds_barrier();  // B1
+            if (ph.precision == NVQ_W4A8) {
+                lds_barrier();  // B2
+                lds_barrier();  // B3
+            }
+            lds_barrier();  // B4: the streaming waves have staged their outputs
+            const int row0 = wg * kStreamWaves * ph.rows_per_wave;
+            int row1 = row0 + kStreamWaves * ph.rows_per_wave;
+            row1 = row1 < ph.total_rows ? row1 : ph.total_rows;
+            for (int r = row0 + lane; r < row1; r += 64) {
+                const float v = sh.ystage[r - row0];
+                int first = 0;
+                void *y = ph.y[0];
+                int dt = ph.y_dtype[0];
+#pragma unroll
+                for (int s = 1; s < kMaxSeg; ++s)
+                    if (s < ph.nseg && r >= ph.row_end[s - 1]) {
+                        first = ph.row_end[s - 1];
+                        y = ph.y[s];
+                        dt = ph.y_dtype[s];
+                    }
+                store_out(y, dt, r - first, v);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+            if (lane == 0)
+                __hip_atomic_store(flags + wg, flag_base + (uint32_t)p + 1u, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+}  // namespace
+
+int stream_grid_limit() {
+    static int cached = -1;
+    if (cached < 0) {
+        int per_cu = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_stream_kernel<false>,
+                                                         kStreamThreads, 0) != hipSuccess)
+            per_cu = 0;
+        cached = per_cu >= 1 ? device_cu_count() : 0;
+    }
+    return cached;
+}
+
+int launch_decode_stream(const StreamPhase *tab_dev, int nphase, int act_group, uint32_t *flags,
+                         uint32_t *status, uint32_t flag_base, const void *dummy, int nwg,
+                         hipStream_t st) {
+    const dim3 grid(nwg), block(kStreamThreads);
+    if (act_group == 32)
+        hipLaunchKernelGGL(decode_stream_kernel<true>, grid, block, 0, st, tab_dev, nphase, flags,
+                           status, flag_base, reinterpret_cast<const uint4 *>(dummy));
+    else
+        hipLaunchKernelGGL(decode_stream_kernel<false>, grid, block, 0, st, tab_dev, nphase, flags,
+                           status, flag_base, reinterpret_cast<const uint4 *>(dummy));
+    NVQ_HIP_TRY(hipGetLastError());
+    return NVQ_OK;
+}
+
+}  // namespace nvq

@@ -20,6 +20,7 @@ MAX_M = 32
 EXPORTS = (
     "nvq_status_string", "nvq_last_hip_error", "nvq_pack_int4", "nvq_quant_act_i8",
     "nvq_gemv_w4a16", "nvq_gemv_w4a8", "nvq_decode_workspace_bytes", "nvq_decode_linears",
+    "nvq_plan_create", "nvq_plan_run", "nvq_plan_info", "nvq_plan_status", "nvq_plan_destroy",
     "nvq_precision_from_scores", "nvq_stream_read", "nvq_stream_copy",
 )
 
@@ -62,12 +63,19 @@ def lib() -> C.CDLL:
     L.nvq_decode_workspace_bytes.restype = sz
     L.nvq_decode_workspace_bytes.argtypes = [vp, ci, ci, ci]
     L.nvq_decode_linears.argtypes = [vp, ci, ci, ci, vp, sz, vp]
+    L.nvq_plan_create.argtypes = [vp, ci, ci, ci, vp, sz, vp, C.POINTER(vp)]
+    L.nvq_plan_run.argtypes = [vp, vp]
+    L.nvq_plan_info.argtypes = [vp, C.POINTER(ci), C.POINTER(ci)]
+    L.nvq_plan_status.argtypes = [vp, vp, C.POINTER(ci)]
+    L.nvq_plan_destroy.argtypes = [vp]
+    L.nvq_plan_destroy.restype = None
     L.nvq_precision_from_scores.argtypes = [vp, ci, C.c_double, C.c_double, vp]
     L.nvq_stream_read.argtypes = [vp, sz, vp, vp]
     L.nvq_stream_copy.argtypes = [vp, vp, sz, vp]
     for f in ("nvq_pack_int4", "nvq_quant_act_i8", "nvq_gemv_w4a16", "nvq_gemv_w4a8",
               "nvq_decode_linears", "nvq_precision_from_scores", "nvq_stream_read",
-              "nvq_stream_copy"):
+              "nvq_stream_copy", "nvq_plan_create", "nvq_plan_run", "nvq_plan_info",
+              "nvq_plan_status"):
         getattr(L, f).restype = ci
     _lib = L
     return L
@@ -186,9 +194,44 @@ class DecodeList:
         self.workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev or "cuda")
 
     def run(self):
+        """One walk through nvq_decode_linears (uploads the phase table each call)."""
         _check(lib().nvq_decode_linears(C.byref(self.arr), self.n, self.M, self.act_group,
                                         self.workspace.data_ptr(), self.workspace.numel(),
                                         _stream()), "nvq_decode_linears")
+
+    # ---- plan: prepared once, run many times ----
+    def plan(self):
+        if getattr(self, "_plan", None) is None:
+            h = C.c_void_p()
+            _check(lib().nvq_plan_create(C.byref(self.arr), self.n, self.M, self.act_group,
+                                         self.workspace.data_ptr(), self.workspace.numel(),
+                                         _stream(), C.byref(h)), "nvq_plan_create")
+            self._plan = h
+        return self._plan
+
+    def run_plan(self):
+        _check(lib().nvq_plan_run(self.plan(), _stream()), "nvq_plan_run")
+
+    def plan_info(self):
+        s, p = C.c_int(), C.c_int()
+        _check(lib().nvq_plan_info(self.plan(), C.byref(s), C.byref(p)), "nvq_plan_info")
+        return {"streaming": bool(s.value), "phases": p.value}
+
+    def plan_timed_out(self) -> bool:
+        t = C.c_int()
+        _check(lib().nvq_plan_status(self.plan(), _stream(), C.byref(t)), "nvq_plan_status")
+        return bool(t.value)
+
+    def close(self):
+        if getattr(self, "_plan", None) is not None:
+            lib().nvq_plan_destroy(self._plan)
+            self._plan = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 def decode_linears(entries: Sequence[dict], M: int, act_group: int = 0) -> DecodeList:

@@ -240,7 +240,7 @@ def test_decode_linears_matches_oracle_walker_and_standalone_calls(M, group):
     for e, h, y_r in zip(entries, host, ys_ref):
         got = e["y"].cpu().numpy()
         assert np_ref.rel_l2(got, y_r) < TOL
-        # same result as the standalone entry point with the same arguments
+        # same result (up to fp32 summation order) as the standalone entry point
         if e["precision"] == nvq.W4A16:
             alone = nvq.gemv_w4a16(e["qweight"], e["scales"], e["x"])
             other = None
@@ -248,9 +248,9 @@ def test_decode_linears_matches_oracle_walker_and_standalone_calls(M, group):
             xq, xs, gs = nvq.quant_act_i8(e["x"], group)
             alone = nvq.gemv_w4a8(e["qweight"], e["scales"], xq, xs, gs, group)
             other = nvq.gemv_w4a16(e["qweight"], e["scales"], e["x"])
-        assert torch.equal(alone, e["y"])
+        assert np_ref.rel_l2(e["y"].cpu().numpy(), alone.cpu().numpy()) < 1e-5
         if other is not None:                      # the precision bit was respected
-            assert not torch.equal(other, e["y"])
+            assert np_ref.rel_l2(e["y"].cpu().numpy(), other.cpu().numpy()) > 1e-4
 
 
 def test_decode_linears_runs_in_order_on_chained_buffers():
@@ -291,3 +291,84 @@ def test_measurement_helpers():
     want = int((w[:, 0] ^ w[:, 1] ^ w[:, 2] ^ w[:, 3]).astype(np.uint64).sum())
     # per-lane sums wrap at 32 bits before the 64-bit atomic; compare modulo 2^32
     assert int(sink.item()) % (1 << 32) == want % (1 << 32)
+
+
+# ---- persistent streaming walker (batch 1) ------------------------------------------
+def model_entries(shapes_per_block, bits, M=1, seed=8000):
+    """shapes_per_block: list of (N, K, phase-in-block); one x buffer per (block, phase)."""
+    entries, host = [], []
+    for b, bit in enumerate(bits):
+        bufs = {}
+        for slot, (N, K, p) in enumerate(shapes_per_block):
+            if p not in bufs:
+                xh = act(seed + 50 * b + p, M, K)
+                bufs[p] = (xh, xh.to(DEV))
+            _, q, s = packed(seed + 100 * b + slot, N, K)
+            qd, sd = to_dev_packed(q, s)
+            entries.append(dict(qweight=qd, scales=sd, x=bufs[p][1], precision=bit,
+                                y=torch.zeros((M, N), dtype=torch.float32, device=DEV)))
+            host.append(dict(qweight=q, scales=s, x=u16(bufs[p][0]), precision=bit))
+    return entries, host
+
+
+STREAM_MODELS = {
+    # llama-1b block shapes, two blocks, one of each precision
+    "1b": ([(2048, 2048, 0), (512, 2048, 0), (512, 2048, 0), (2048, 2048, 1),
+            (8192, 2048, 2), (8192, 2048, 2), (2048, 8192, 3)], (0, 1)),
+    # ragged: rows that do not divide over the waves, K with a partial last chunk (G = 66, 98)
+    "ragged": ([(1000, 2112, 0), (37, 2112, 0), (3, 2112, 1), (2500, 3136, 2), (777, 3136, 2),
+                (64, 14336, 3)], (1, 0, 0)),
+    # 8b block shapes, one W4A8 block
+    "8b": ([(4096, 4096, 0), (1024, 4096, 0), (1024, 4096, 0), (4096, 4096, 1),
+            (14336, 4096, 2), (14336, 4096, 2), (4096, 14336, 3)], (0,)),
+}
+
+
+@pytest.mark.parametrize("name,group", [("1b", 0), ("ragged", 0), ("ragged", 32), ("8b", 0),
+                                        ("8b", 32)])
+def test_streaming_plan_matches_oracle_on_repeated_runs(name, group):
+    say("stream plan", name, group)
+    shapes, bits = STREAM_MODELS[name]
+    entries, host = model_entries(shapes, bits)
+    ys_ref = oracle.decode_linears(host, 1, group)
+    dl = nvq.DecodeList(entries, 1, group)
+    info = dl.plan_info()
+    say("  plan", info)
+    assert info["streaming"], "batch-1 walk should use the persistent kernel"
+    for rep in range(3):
+        for e in entries:
+            e["y"].zero_()
+        dl.run_plan()
+        assert not dl.plan_timed_out()
+        for e, y_r in zip(entries, ys_ref):
+            err = np_ref.rel_l2(e["y"].cpu().numpy(), y_r)
+            assert err < TOL, (rep, err)
+            assert err < 1e-5, (rep, err)
+    dl.close()
+
+
+def test_streaming_plan_orders_dependent_phases():
+    say("stream chain")
+    # four phases, each reading the bf16 output of the one before it
+    dims = [2048, 4096, 1024, 6144, 512]
+    hostW = [oracle.pack_int4(synth.make_weight(8800 + i, dims[i + 1], dims[i]).numpy())
+             for i in range(4)]
+    x0 = act(8899, 1, dims[0])
+    bufs = [x0.to(DEV)] + [torch.zeros((1, d), dtype=torch.bfloat16, device=DEV) for d in dims[1:]]
+    entries = []
+    for i, (q, s) in enumerate(hostW):
+        qd, sd = to_dev_packed(q, s)
+        entries.append(dict(qweight=qd, scales=sd, x=bufs[i], y=bufs[i + 1], precision=i % 2))
+    dl = nvq.DecodeList(entries, 1)
+    assert dl.plan_info()["streaming"]
+    for rep in range(3):
+        for b in bufs[1:]:
+            b.zero_()
+        dl.run_plan()
+        assert not dl.plan_timed_out()
+        # each stage against the oracle applied to the GPU's own previous stage
+        for i, (q, s) in enumerate(hostW):
+            y_r = oracle.decode_linears([dict(qweight=q, scales=s, x=u16(bufs[i]),
+                                              precision=i % 2)], 1)[0]
+            assert np_ref.rel_l2(bufs[i + 1].float().cpu().numpy(), y_r) < 4e-3, (rep, i)
+    dl.close()
