@@ -79,14 +79,19 @@ def entries_for(layers, bits, nvq):
 
 
 def time_steps(dl, steps, warmup, torch):
+    """K walks of the prepared plan, bracketed by device synchronisation."""
+    dl.plan()
     for _ in range(warmup):
-        dl.run()
+        dl.run_plan()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(steps):
-        dl.run()
+        dl.run_plan()
     torch.cuda.synchronize()
-    return (time.perf_counter() - t0) / steps
+    sec = (time.perf_counter() - t0) / steps
+    if dl.plan_timed_out():
+        raise RuntimeError("a wait inside the streaming kernel timed out; results invalid")
+    return sec
 
 
 def roofline_leg(layers, torch, nvq, synth, reps=5):

@@ -179,6 +179,13 @@ int nvq_decode_linears(const nvq_linear *layers, int n, int M, int act_group,
  *                    the persistent kernel gave up (its spins are bounded so
  *                    that a grid that cannot be co-resident ends with an
  *                    error instead of a hang); outputs are invalid then
+ *   nvq_plan_trace   diagnostic: give a device buffer of phases * 8 uint64
+ *                    (or NULL to stop); later runs of the persistent kernel
+ *                    store workgroup 0's timestamps per phase in it (100 MHz
+ *                    wall clock): [0] wait begins, [1] previous phase seen
+ *                    complete, [2] input staged, [3] phase computed,
+ *                    [4] outputs published, [5..7] first streaming wave:
+ *                    input seen, activations ready, own rows done
  */
 typedef struct nvq_plan nvq_plan;
 int nvq_plan_create(const nvq_linear *layers, int n, int M, int act_group, void *workspace,
@@ -186,6 +193,7 @@ int nvq_plan_create(const nvq_linear *layers, int n, int M, int act_group, void 
 int nvq_plan_run(nvq_plan *plan, void *stream);
 int nvq_plan_info(const nvq_plan *plan, int *streaming, int *phases);
 int nvq_plan_status(nvq_plan *plan, void *stream, int *timed_out);
+int nvq_plan_trace(nvq_plan *plan, uint64_t *buf, size_t bytes);
 void nvq_plan_destroy(nvq_plan *plan);
 
 /*

@@ -195,6 +195,7 @@ struct nvq_plan {
     int nwg;           // workgroups of the streaming kernel, 0 = per-phase launches
     int nphase;        // entries of the device phase table
     uint32_t runs;     // walks issued so far (advances the flag base)
+    unsigned long long *trace;  // device buffer for per-phase timestamps, or nullptr
 };
 
 extern "C" size_t nvq_decode_workspace_bytes(const nvq_linear *layers, int n, int M,
@@ -224,6 +225,7 @@ extern "C" int nvq_plan_create(const nvq_linear *layers, int n, int M, int act_g
     pl->M = M;
     pl->act_group = act_group;
     pl->runs = 0;
+    pl->trace = nullptr;
     pl->nwg = 0;
     pl->nphase = 0;
     hipStream_t st = (hipStream_t)stream;
@@ -259,7 +261,7 @@ extern "C" int nvq_plan_run(nvq_plan *pl, void *stream) {
         const uint32_t base = pl->runs * (uint32_t)pl->nphase;
         ++pl->runs;
         return launch_decode_stream(pl->ws.tab, pl->nphase, pl->act_group, pl->ws.flags,
-                                    pl->ws.status, base, pl->ws.dummy, pl->nwg, st);
+                                    pl->ws.status, base, pl->ws.dummy, pl->nwg, pl->trace, st);
     }
     return walk_per_phase(pl->layers.data(), pl->phases, pl->M, pl->act_group, pl->ws, st);
 }
@@ -268,6 +270,14 @@ extern "C" int nvq_plan_info(const nvq_plan *pl, int *streaming, int *phases) {
     if (!pl) return NVQ_ERR_INVALID_ARG;
     if (streaming) *streaming = pl->nwg > 0 ? 1 : 0;
     if (phases) *phases = (int)pl->phases.size();
+    return NVQ_OK;
+}
+
+extern "C" int nvq_plan_trace(nvq_plan *pl, uint64_t *buf, size_t bytes) {
+    if (!pl) return NVQ_ERR_INVALID_ARG;
+    if (buf && (bytes < (size_t)pl->nphase * nvq::kStreamTraceSlots * 8 || !nvq::aligned(buf, 8)))
+        return NVQ_ERR_WORKSPACE;
+    pl->trace = reinterpret_cast<unsigned long long *>(buf);
     return NVQ_OK;
 }
 

@@ -33,9 +33,13 @@ int stream_grid_limit();
 // Enqueue one walk.  `flags` holds one word per workgroup and `status` one
 // word (set to 1 if a wait timed out); both persist between runs of the same
 // table, with `flag_base` advanced by nphase per run.  `dummy` is any valid
-// 1 KiB of device memory.
+// 1 KiB of device memory.  `trace` is nullptr or nphase * 8 words that
+// receive workgroup 0's per-phase timestamps.
 int launch_decode_stream(const StreamPhase *tab_dev, int nphase, int act_group, uint32_t *flags,
                          uint32_t *status, uint32_t flag_base, const void *dummy, int nwg,
-                         hipStream_t st);
+                         unsigned long long *trace, hipStream_t st);
+
+// Timestamps written per phase when a trace buffer is given (see the kernel).
+constexpr int kStreamTraceSlots = 8;
 
 }  // namespace nvq

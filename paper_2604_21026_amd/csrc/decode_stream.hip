@@ -424,10 +424,21 @@ __device__ __forceinline__ void consume_dispatch(const StreamPhase &ph, const St
     }
 }
 
+// Optional per-phase timestamps (100 MHz wall clock) of workgroup 0:
+// trace[p][0..4] control wave: wait begin, flags seen, input staged, phase
+// computed, outputs published; trace[p][5..7] streaming wave 0: input seen,
+// activations ready, own rows done.
+constexpr int kTraceSlots = 8;
+__device__ __forceinline__ void trace_mark(unsigned long long *trace, int wg, int lane, int p,
+                                           int slot) {
+    if (trace && wg == 0 && lane == 0) trace[p * kTraceSlots + slot] = wall_clock64();
+}
+
 template <bool PER_GROUP>
 __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
     const StreamPhase *__restrict__ tab, int nphase, uint32_t *__restrict__ flags,
-    uint32_t *__restrict__ status, uint32_t flag_base, const uint4 *__restrict__ dummy) {
+    uint32_t *__restrict__ status, uint32_t flag_base, const uint4 *__restrict__ dummy,
+    unsigned long long *__restrict__ trace) {
     __shared__ Shared sh;
     // 0..kStreamWaves-1 stream, kStreamWaves = control; made provably wave-uniform
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -451,13 +462,17 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
             const StreamPhase &ph = tab[p];
             lds_barrier();  // B1: input vector staged (or abort raised)
             if (lds_read4(lds_addr(&sh.abort))) break;
+            if (w == 0) trace_mark(trace, wg, lane, p, 5);
             float xs = 1.0f;
             if (ph.precision == NVQ_W4A8) {
                 xs = quantise_stage<PER_GROUP>(ph, sh, w, lane);  // B2, B3 inside
+                if (w == 0) trace_mark(trace, wg, lane, p, 6);
                 consume_dispatch<NVQ_W4A8, PER_GROUP>(ph, tab, st, sh, w, gw, lane, dummy, xs);
             } else {
+                if (w == 0) trace_mark(trace, wg, lane, p, 6);
                 consume_dispatch<NVQ_W4A16, false>(ph, tab, st, sh, w, gw, lane, dummy, xs);
             }
+            if (w == 0) trace_mark(trace, wg, lane, p, 7);
             lds_barrier();  // B4: outputs staged
         }
         __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // no load may outlive the wave
@@ -466,6 +481,7 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
         for (int p = 0; p < nphase; ++p) {
             const StreamPhase &ph = tab[p];
             bool ok = true;
+            trace_mark(trace, wg, lane, p, 0);
             if (p > 0) {
                 // every workgroup must have published phase p-1
                 const uint32_t target = flag_base + (uint32_t)p;
@@ -501,6 +517,7 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
                 lds_barrier();  // B1 with abort raised: everybody leaves
                 break;
             }
+            trace_mark(trace, wg, lane, p, 1);
             // stage the input vector (bf16, K values): global->LDS, all loads in flight at once
             const uint4 *xsrc = reinterpret_cast<const uint4 *>(ph.x);
             const int n16 = ph.K / 8;
@@ -509,12 +526,14 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
                     __builtin_amdgcn_global_load_lds((const void *)(xsrc + c0 + lane),
                                                      (lds_void_ptr)&sh.xstage[c0], 16, 0, 0);
             __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+            trace_mark(trace, wg, lane, p, 2);
             lds_barrier();  // B1
             if (ph.precision == NVQ_W4A8) {
                 lds_barrier();  // B2
                 lds_barrier();  // B3
             }
             lds_barrier();  // B4: the streaming waves have staged their outputs
+            trace_mark(trace, wg, lane, p, 3);
             const int row0 = wg * kStreamWaves * ph.rows_per_wave;
             int row1 = row0 + kStreamWaves * ph.rows_per_wave;
             row1 = row1 < ph.total_rows ? row1 : ph.total_rows;
@@ -536,6 +555,7 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
             if (lane == 0)
                 __hip_atomic_store(flags + wg, flag_base + (uint32_t)p + 1u, __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
+            trace_mark(trace, wg, lane, p, 4);
         }
     }
 }
@@ -556,14 +576,14 @@ int stream_grid_limit() {
 
 int launch_decode_stream(const StreamPhase *tab_dev, int nphase, int act_group, uint32_t *flags,
                          uint32_t *status, uint32_t flag_base, const void *dummy, int nwg,
-                         hipStream_t st) {
+                         unsigned long long *trace, hipStream_t st) {
     const dim3 grid(nwg), block(kStreamThreads);
     if (act_group == 32)
         hipLaunchKernelGGL(decode_stream_kernel<true>, grid, block, 0, st, tab_dev, nphase, flags,
-                           status, flag_base, reinterpret_cast<const uint4 *>(dummy));
+                           status, flag_base, reinterpret_cast<const uint4 *>(dummy), trace);
     else
         hipLaunchKernelGGL(decode_stream_kernel<false>, grid, block, 0, st, tab_dev, nphase, flags,
-                           status, flag_base, reinterpret_cast<const uint4 *>(dummy));
+                           status, flag_base, reinterpret_cast<const uint4 *>(dummy), trace);
     NVQ_HIP_TRY(hipGetLastError());
     return NVQ_OK;
 }

@@ -20,7 +20,8 @@ MAX_M = 32
 EXPORTS = (
     "nvq_status_string", "nvq_last_hip_error", "nvq_pack_int4", "nvq_quant_act_i8",
     "nvq_gemv_w4a16", "nvq_gemv_w4a8", "nvq_decode_workspace_bytes", "nvq_decode_linears",
-    "nvq_plan_create", "nvq_plan_run", "nvq_plan_info", "nvq_plan_status", "nvq_plan_destroy",
+    "nvq_plan_create", "nvq_plan_run", "nvq_plan_info", "nvq_plan_status", "nvq_plan_trace",
+    "nvq_plan_destroy",
     "nvq_precision_from_scores", "nvq_stream_read", "nvq_stream_copy",
 )
 
@@ -67,6 +68,7 @@ def lib() -> C.CDLL:
     L.nvq_plan_run.argtypes = [vp, vp]
     L.nvq_plan_info.argtypes = [vp, C.POINTER(ci), C.POINTER(ci)]
     L.nvq_plan_status.argtypes = [vp, vp, C.POINTER(ci)]
+    L.nvq_plan_trace.argtypes = [vp, vp, sz]
     L.nvq_plan_destroy.argtypes = [vp]
     L.nvq_plan_destroy.restype = None
     L.nvq_precision_from_scores.argtypes = [vp, ci, C.c_double, C.c_double, vp]
@@ -75,7 +77,7 @@ def lib() -> C.CDLL:
     for f in ("nvq_pack_int4", "nvq_quant_act_i8", "nvq_gemv_w4a16", "nvq_gemv_w4a8",
               "nvq_decode_linears", "nvq_precision_from_scores", "nvq_stream_read",
               "nvq_stream_copy", "nvq_plan_create", "nvq_plan_run", "nvq_plan_info",
-              "nvq_plan_status"):
+              "nvq_plan_status", "nvq_plan_trace"):
         getattr(L, f).restype = ci
     _lib = L
     return L
@@ -221,6 +223,12 @@ class DecodeList:
         t = C.c_int()
         _check(lib().nvq_plan_status(self.plan(), _stream(), C.byref(t)), "nvq_plan_status")
         return bool(t.value)
+
+    def trace(self, buf: Optional[torch.Tensor]):
+        """Attach (or detach with None) an int64 device tensor of phases*8 timestamps."""
+        self._trace = buf
+        _check(lib().nvq_plan_trace(self.plan(), buf.data_ptr() if buf is not None else None,
+                                    buf.numel() * 8 if buf is not None else 0), "nvq_plan_trace")
 
     def close(self):
         if getattr(self, "_plan", None) is not None:
