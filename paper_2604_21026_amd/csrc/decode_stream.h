@@ -5,8 +5,8 @@
 
 namespace nvq {
 
-constexpr int kStreamWaves = 4;                          // streaming waves per workgroup
-constexpr int kStreamThreads = (kStreamWaves + 1) * 64;  // plus one control wave
+constexpr int kStreamWaves = 8;  // waves per workgroup (two per SIMD)
+constexpr int kStreamThreads = kStreamWaves * 64;
 constexpr int kStreamMaxK = 14336;                       // widest input the LDS stage holds
 constexpr int kStreamYStage = 1024;                      // output rows staged per workgroup
 

@@ -20,11 +20,13 @@
 //     operation, so the number of loads in flight behind any chunk is a
 //     compile-time constant and one `s_waitcnt vmcnt(n)` tells when a pair of
 //     chunks has landed.
-//   * one control wave.  It alone talks to global memory besides the weight
-//     stream: it waits until every workgroup has finished the previous phase
-//     (one flag word per workgroup, no atomics), copies the phase's input
-//     vector into LDS, and after the phase writes the workgroup's outputs
-//     from LDS to memory and publishes its own flag.
+//   * control duties, carried by wave 0 between its own rows.  It alone talks
+//     to global memory besides the weight stream: it waits until every
+//     workgroup has finished the previous phase (one flag word per workgroup,
+//     no atomics), copies the phase's input vector into LDS, and after the
+//     phase writes the workgroup's outputs from LDS to memory and publishes
+//     its own flag.  Its extra memory operations queue behind its ring loads,
+//     which only makes the ring's counted waits conservative.
 //   Activation quantisation (W4A8 phases) is done by the streaming waves
 //   cooperatively out of LDS, once per workgroup per phase.
 //
@@ -39,7 +41,7 @@ namespace {
 
 typedef __attribute__((address_space(3))) void *lds_void_ptr;
 
-constexpr int kSlots = 24;            // 1 KiB weight slots per streaming wave
+constexpr int kSlots = 12;            // 1 KiB weight slots per streaming wave
 constexpr int kUnits = kSlots / 2;    // a unit = two chunks + their scales = 3 loads
 constexpr int kOpsPerUnit = 3;
 constexpr int kXStageBytes = kStreamMaxK * 2;  // bf16 input vector
@@ -234,23 +236,36 @@ __device__ __forceinline__ float dot_w4a16(const uint4 &w, const uint32_t (&x)[1
     return a0 + a1;
 }
 
-// Sum over the 64 lanes; the result is valid in every lane.
-__device__ __forceinline__ float wave_sum(float v) {
-    // quad_perm [1,0,3,2], quad_perm [2,3,0,1], row_half_mirror, row_mirror
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xb1, 0xf, 0xf, true));
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4e, 0xf, 0xf, true));
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xf, 0xf, true));
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xf, 0xf, true));
-    v += __shfl_xor(v, 16, 64);
-    v += __shfl_xor(v, 32, 64);
+// Sum over the 64 lanes with data-parallel-primitive moves only (no LDS
+// traffic); the total is valid in lane 63.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_move(float x) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL,
+                                                                 ROW_MASK, 0xf, false));
+}
+__device__ __forceinline__ float wave_sum_to_lane63(float v) {
+    v += dpp_move<0xb1, 0xf>(v);   // quad_perm [1,0,3,2]
+    v += dpp_move<0x4e, 0xf>(v);   // quad_perm [2,3,0,1]
+    v += dpp_move<0x141, 0xf>(v);  // row_half_mirror
+    v += dpp_move<0x140, 0xf>(v);  // row_mirror: every lane of a row of 16 holds the row sum
+    v += dpp_move<0x142, 0xa>(v);  // row_bcast15 into rows 1 and 3
+    v += dpp_move<0x143, 0xc>(v);  // row_bcast31 into rows 2 and 3
     return v;
 }
 
 // ---- consuming one phase ----------------------------------------------------
 struct StreamState {
     Cursor ic;       // issue cursor
-    uint32_t slot;   // ring slot of the next chunk to consume (chunks are consumed in order)
+    uint32_t rslot;  // ring slot of the next chunk to read from LDS (chunks are read in order)
     uint32_t uslot;  // unit slot the next refill goes to
+};
+
+// One chunk as it sits in registers between its LDS read and its use.
+template <bool WITH_X>
+struct ChunkRegs {
+    u32x4_t w;
+    uint32_t s;
+    u32x4_t x[WITH_X ? 4 : 1];
 };
 
 template <int PREC, int GPL, bool PER_GROUP>
@@ -258,76 +273,138 @@ __device__ __forceinline__ void consume_phase(const StreamPhase &ph, const Strea
                                               StreamState &st, Shared &sh, int w, int gw, int lane,
                                               const uint4 *dummy, float xs_token) {
     constexpr int XR = PREC == NVQ_W4A8 ? 8 : 16;
-    // activations of the groups this lane owns, from the LDS stage
-    uint32_t xr[GPL][XR];
+    // Activations stay in registers for the whole phase unless that would take
+    // more than 64 registers (bf16 activations of more than four chunks); then
+    // they are re-read from the LDS stage together with each weight chunk.
+    constexpr bool XREG = PREC == NVQ_W4A8 || GPL <= 4;
+    constexpr int NX = XREG ? GPL : 1;
+    uint32_t xr[NX][XR];
     int neg8[GPL];
     float xoff[GPL];
     float xsg[GPL];
+    uint32_t xaddr[GPL];  // LDS address of the lane's group in the stage (!XREG)
+    bool okv[GPL];        // the lane's group exists (false past the end of a ragged row)
 #pragma unroll
     for (int i = 0; i < GPL; ++i) {
         const int g = i * 64 + lane;
         const bool ok = g < ph.G;
         const int gc = ok ? g : 0;
+        okv[i] = ok;
         const uint32_t src = lds_addr(sh.xstage) + gc * (XR * 4);
+        xaddr[i] = src;
+        uint32_t t[XR];
 #pragma unroll
         for (int q = 0; q < XR / 4; ++q) {
             const uint4 a = lds_read16(src + q * 16);
-            xr[i][4 * q + 0] = ok ? a.x : 0u;
-            xr[i][4 * q + 1] = ok ? a.y : 0u;
-            xr[i][4 * q + 2] = ok ? a.z : 0u;
-            xr[i][4 * q + 3] = ok ? a.w : 0u;
+            t[4 * q + 0] = ok ? a.x : 0u;
+            t[4 * q + 1] = ok ? a.y : 0u;
+            t[4 * q + 2] = ok ? a.z : 0u;
+            t[4 * q + 3] = ok ? a.w : 0u;
         }
         if constexpr (PREC == NVQ_W4A8) {
-            int s = 0;
+            int sum = 0;
 #pragma unroll
-            for (int d = 0; d < 8; ++d) s = __builtin_amdgcn_sdot4(0x01010101, (int)xr[i][d], s, false);
-            neg8[i] = -8 * s;
+            for (int d = 0; d < 8; ++d) sum = __builtin_amdgcn_sdot4(0x01010101, (int)t[d], sum, false);
+            neg8[i] = -8 * sum;
             xsg[i] = PER_GROUP ? __uint_as_float(lds_read4(lds_addr(sh.xsg) + gc * 4)) : 1.0f;
         } else {
-            float s = 0.0f;
+            float sum = 0.0f;
 #pragma unroll
-            for (int j = 0; j < 16; ++j) s = dot2_bf16(0x3f803f80u, xr[i][j], s);
-            xoff[i] = -136.0f * s;
+            for (int j = 0; j < 16; ++j) sum = dot2_bf16(0x3f803f80u, t[j], sum);
+            xoff[i] = -136.0f * sum;
+        }
+        if constexpr (XREG) {
+#pragma unroll
+            for (int d = 0; d < XR; ++d) xr[i][d] = t[d];
         }
     }
-
+    // Lanes past the end of a ragged row (K no multiple of 2048) read ring
+    // slots that no load has written: their scale is forced to zero and their
+    // activations are zero, so whatever bits sit there contribute exactly 0.
     const int r0 = gw * ph.rows_per_wave;
     int r1 = r0 + ph.rows_per_wave;
     r1 = r1 < ph.total_rows ? r1 : ph.total_rows;
+    if (r0 >= r1) return;
     const int wg_row0 = (gw - w) * ph.rows_per_wave;
     const uint32_t ring_base = lds_addr(&sh.ring[w][0][0]) + lane * 16;
     const uint32_t sring_base = lds_addr(&sh.sring[w][0][0]) + lane * 2;
+
+    ChunkRegs<!XREG> nxt;
+    // Start the LDS reads of the next chunk in stream order; i_next is its
+    // position in its row.  Entering a new unit first waits until the unit has
+    // landed: at that point every unit but the one being read and the one
+    // still to be refilled is in flight behind it.
+    auto fetch = [&](int i_next) {
+        const uint32_t slot = st.rslot;
+        if ((slot & 1u) == 0) __builtin_amdgcn_s_waitcnt(vmcnt_imm(kOpsPerUnit * (kUnits - 2)));
+        asm volatile("ds_read_b128 %0, %2\n\tds_read_u16 %1, %3"
+                     : "=&v"(nxt.w), "=&v"(nxt.s)
+                     : "v"(ring_base + slot * 1024u), "v"(sring_base + slot * 128u)
+                     : "memory");
+        if constexpr (!XREG) {
+            asm volatile("ds_read_b128 %0, %4\n\tds_read_b128 %1, %4 offset:16\n\t"
+                         "ds_read_b128 %2, %4 offset:32\n\tds_read_b128 %3, %4 offset:48"
+                         : "=&v"(nxt.x[0]), "=&v"(nxt.x[1]), "=&v"(nxt.x[2]), "=&v"(nxt.x[3])
+                         : "v"(xaddr[i_next])
+                         : "memory");
+        }
+        st.rslot = slot + 1 == kSlots ? 0 : slot + 1;
+    };
+    // Wait for the reads started by fetch().  The registers are tied to the
+    // wait so that no use (and no copy) of them can be scheduled before it; the
+    // wait sits in the same iteration as the fetch, never across the loop
+    // back-edge, where the compiler may insert register copies.
+    auto landed = [&]() {
+        if constexpr (XREG) {
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(nxt.w), "+v"(nxt.s) : : "memory");
+        } else {
+            asm volatile("s_waitcnt lgkmcnt(0)"
+                         : "+v"(nxt.w), "+v"(nxt.s), "+v"(nxt.x[0]), "+v"(nxt.x[1]), "+v"(nxt.x[2]),
+                           "+v"(nxt.x[3])
+                         : : "memory");
+        }
+    };
+    fetch(0);
+    landed();
 
     for (int row = r0; row < r1; ++row) {
         float sum = 0.0f;
 #pragma unroll
         for (int i = 0; i < GPL; ++i) {
-            const uint32_t slot = st.slot;
-            if ((slot & 1u) == 0)  // first chunk of a unit: wait until the unit has landed
-                __builtin_amdgcn_s_waitcnt(vmcnt_imm(kOpsPerUnit * (kUnits - 1)));
-            u32x4_t wraw;
-            uint32_t sbits;
-            asm volatile("ds_read_b128 %0, %2\n\tds_read_u16 %1, %3\n\ts_waitcnt lgkmcnt(0)"
-                         : "=&v"(wraw), "=&v"(sbits)
-                         : "v"(ring_base + slot * 1024u), "v"(sring_base + slot * 128u)
-                         : "memory");
-            const uint4 wv = make_uint4(wraw.x, wraw.y, wraw.z, wraw.w);
-            float sw = half_bits_to_float((uint16_t)sbits);
+            const ChunkRegs<!XREG> cur = nxt;
+            // slot the current chunk came from = the one before rslot
+            const uint32_t cslot = st.rslot == 0 ? kSlots - 1 : st.rslot - 1;
+            const bool more = !(i == GPL - 1 && row == r1 - 1);
+            if (more) fetch(i == GPL - 1 ? 0 : i + 1);
+
+            const uint4 wv = make_uint4(cur.w.x, cur.w.y, cur.w.z, cur.w.w);
+            float sw = okv[i] ? half_bits_to_float((uint16_t)cur.s) : 0.0f;
             if constexpr (PREC == NVQ_W4A8) {
                 const int acc = dot_w4a8(wv, xr[i], neg8[i]);
                 if (PER_GROUP) sw *= xsg[i];
                 sum = fmaf(sw, (float)acc, sum);
-            } else {
+            } else if constexpr (XREG) {
                 sum = fmaf(sw, dot_w4a16(wv, xr[i], xoff[i]), sum);
+            } else {
+                uint32_t xv[16];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    xv[4 * q + 0] = cur.x[q].x;
+                    xv[4 * q + 1] = cur.x[q].y;
+                    xv[4 * q + 2] = cur.x[q].z;
+                    xv[4 * q + 3] = cur.x[q].w;
+                }
+                const float part = dot_w4a16(wv, xv, xoff[i]);
+                sum = fmaf(sw, okv[i] ? part : 0.0f, sum);
             }
-            if (slot & 1u) {  // second chunk of a unit consumed: refill its two slots
+            if (cslot & 1u) {  // second chunk of a unit used up: refill the unit's two slots
                 issue_unit(st.ic, tab, gw, sh, w, (int)st.uslot, lane, dummy);
                 st.uslot = st.uslot + 1 == kUnits ? 0 : st.uslot + 1;
             }
-            st.slot = slot + 1 == kSlots ? 0 : slot + 1;
+            if (more) landed();
         }
-        sum = wave_sum(sum);
-        if (lane == 0)
+        sum = wave_sum_to_lane63(sum);
+        if (lane == 63)
             lds_write4(lds_addr(&sh.ystage[row - wg_row0]),
                        __float_as_uint(PREC == NVQ_W4A8 ? sum * xs_token : sum));
     }
@@ -340,7 +417,7 @@ template <bool PER_GROUP>
 __device__ __forceinline__ float quantise_stage(const StreamPhase &ph, Shared &sh, int w, int lane) {
     const int t = w * 64 + lane;             // 0 .. kStreamWaves*64-1
     constexpr int NT = kStreamWaves * 64;
-    constexpr int MAXC = kStreamMaxK / 8 / NT;  // chunks of 8 values per lane
+    constexpr int MAXC = (kStreamMaxK / 8 + NT - 1) / NT;  // chunks of 8 values per lane
     const int chunks = ph.K / 8;
     uint4 raw[MAXC];
     float amax = 0.0f;
@@ -440,46 +517,27 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
     uint32_t *__restrict__ status, uint32_t flag_base, const uint4 *__restrict__ dummy,
     unsigned long long *__restrict__ trace) {
     __shared__ Shared sh;
-    // 0..kStreamWaves-1 stream, kStreamWaves = control; made provably wave-uniform
+    // wave index, made provably wave-uniform; wave 0 also carries the control duties
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     const int wg = blockIdx.x;
     const int nwg = gridDim.x;
     if (threadIdx.x == 0) sh.abort = 0;
 
-    if (w < kStreamWaves) {
-        // ---------------- streaming wave ----------------
-        const int gw = wg * kStreamWaves + w;
-        StreamState st;
-        st.ic.p = 0;
-        st.ic.nphase = nphase;
-        cursor_enter(st.ic, tab, gw);
-        st.slot = 0;
-        st.uslot = 0;
-        for (int u = 0; u < kUnits; ++u)  // fill the ring
-            issue_unit(st.ic, tab, gw, sh, w, u, lane, dummy);
-        for (int p = 0; p < nphase; ++p) {
-            const StreamPhase &ph = tab[p];
-            lds_barrier();  // B1: input vector staged (or abort raised)
-            if (lds_read4(lds_addr(&sh.abort))) break;
-            if (w == 0) trace_mark(trace, wg, lane, p, 5);
-            float xs = 1.0f;
-            if (ph.precision == NVQ_W4A8) {
-                xs = quantise_stage<PER_GROUP>(ph, sh, w, lane);  // B2, B3 inside
-                if (w == 0) trace_mark(trace, wg, lane, p, 6);
-                consume_dispatch<NVQ_W4A8, PER_GROUP>(ph, tab, st, sh, w, gw, lane, dummy, xs);
-            } else {
-                if (w == 0) trace_mark(trace, wg, lane, p, 6);
-                consume_dispatch<NVQ_W4A16, false>(ph, tab, st, sh, w, gw, lane, dummy, xs);
-            }
-            if (w == 0) trace_mark(trace, wg, lane, p, 7);
-            lds_barrier();  // B4: outputs staged
-        }
-        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // no load may outlive the wave
-    } else {
-        // ---------------- control wave ----------------
-        for (int p = 0; p < nphase; ++p) {
-            const StreamPhase &ph = tab[p];
+    const int gw = wg * kStreamWaves + w;
+    StreamState st;
+    st.ic.p = 0;
+    st.ic.nphase = nphase;
+    cursor_enter(st.ic, tab, gw);
+    st.rslot = 0;
+    st.uslot = 0;
+    for (int u = 0; u < kUnits; ++u)  // fill the ring
+        issue_unit(st.ic, tab, gw, sh, w, u, lane, dummy);
+
+    for (int p = 0; p < nphase; ++p) {
+        const StreamPhase &ph = tab[p];
+        if (w == 0) {
+            // ---- control duty 1: wait for the previous phase, stage the input ----
             bool ok = true;
             trace_mark(trace, wg, lane, p, 0);
             if (p > 0) {
@@ -509,36 +567,44 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
                 }
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
             }
-            if (!ok) {
-                if (lane == 0) {
-                    sh.abort = 1;
-                    __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                }
-                lds_barrier();  // B1 with abort raised: everybody leaves
-                break;
-            }
             trace_mark(trace, wg, lane, p, 1);
-            // stage the input vector (bf16, K values): global->LDS, all loads in flight at once
-            const uint4 *xsrc = reinterpret_cast<const uint4 *>(ph.x);
-            const int n16 = ph.K / 8;
-            for (int c0 = 0; c0 < n16; c0 += 64)
-                if (c0 + lane < n16)
-                    __builtin_amdgcn_global_load_lds((const void *)(xsrc + c0 + lane),
-                                                     (lds_void_ptr)&sh.xstage[c0], 16, 0, 0);
-            __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-            trace_mark(trace, wg, lane, p, 2);
-            lds_barrier();  // B1
-            if (ph.precision == NVQ_W4A8) {
-                lds_barrier();  // B2
-                lds_barrier();  // B3
+            if (ok) {
+                // the input vector (bf16, K values): global->LDS, all loads in flight at once
+                const uint4 *xsrc = reinterpret_cast<const uint4 *>(ph.x);
+                const int n16 = ph.K / 8;
+                for (int c0 = 0; c0 < n16; c0 += 64)
+                    if (c0 + lane < n16)
+                        __builtin_amdgcn_global_load_lds((const void *)(xsrc + c0 + lane),
+                                                         (lds_void_ptr)&sh.xstage[c0], 16, 0, 0);
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+            } else if (lane == 0) {
+                lds_write4(lds_addr(&sh.abort), 1u);
+                __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
-            lds_barrier();  // B4: the streaming waves have staged their outputs
+            trace_mark(trace, wg, lane, p, 2);
+        }
+        lds_barrier();  // B1: input vector staged (or abort raised)
+        if (lds_read4(lds_addr(&sh.abort))) break;
+        if (w == 0) trace_mark(trace, wg, lane, p, 5);
+        float xs = 1.0f;
+        if (ph.precision == NVQ_W4A8) {
+            xs = quantise_stage<PER_GROUP>(ph, sh, w, lane);  // B2, B3 inside
+            if (w == 0) trace_mark(trace, wg, lane, p, 6);
+            consume_dispatch<NVQ_W4A8, PER_GROUP>(ph, tab, st, sh, w, gw, lane, dummy, xs);
+        } else {
+            if (w == 0) trace_mark(trace, wg, lane, p, 6);
+            consume_dispatch<NVQ_W4A16, false>(ph, tab, st, sh, w, gw, lane, dummy, xs);
+        }
+        if (w == 0) trace_mark(trace, wg, lane, p, 7);
+        lds_barrier();  // B4: outputs staged
+        if (w == 0) {
+            // ---- control duty 2: write the workgroup's outputs, publish the phase ----
             trace_mark(trace, wg, lane, p, 3);
             const int row0 = wg * kStreamWaves * ph.rows_per_wave;
             int row1 = row0 + kStreamWaves * ph.rows_per_wave;
             row1 = row1 < ph.total_rows ? row1 : ph.total_rows;
             for (int r = row0 + lane; r < row1; r += 64) {
-                const float v = sh.ystage[r - row0];
+                const float v = __uint_as_float(lds_read4(lds_addr(&sh.ystage[r - row0])));
                 int first = 0;
                 void *y = ph.y[0];
                 int dt = ph.y_dtype[0];
@@ -558,6 +624,7 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
             trace_mark(trace, wg, lane, p, 4);
         }
     }
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // no load may outlive the wave
 }
 
 }  // namespace
