@@ -150,7 +150,10 @@ typedef struct nvq_linear {
  *   Entries complete in order: entry i may read what an earlier entry wrote.
  *   Consecutive entries with the same x_bf16, K and precision form a phase
  *   (at most four entries): they share one activation quantisation and run
- *   concurrently.  Phases are strictly ordered.
+ *   concurrently.  Results are those of running the phases one after the
+ *   other: a phase whose input overlaps an earlier phase's output, or whose
+ *   output overlaps an earlier phase's input or output, starts only after
+ *   that phase has completed; phases that share no buffer may overlap.
  *   workspace  device buffer of at least nvq_decode_workspace_bytes(...)
  *              bytes, 256-byte aligned; its contents are scratch.
  * At M = 1 the whole list runs as ONE persistent kernel that keeps streaming
@@ -172,9 +175,13 @@ int nvq_decode_linears(const nvq_linear *layers, int n, int M, int act_group,
  * the layer list and owns nothing on the device.  The workspace must stay
  * untouched by others between nvq_plan_create and nvq_plan_destroy, and runs
  * of one plan must not overlap (issue them on one stream).
- *   nvq_plan_create  validates, uploads the phase table on `stream`
+ *   nvq_plan_create  validates, uploads the phase table on `stream`.  flags:
+ *                    NVQ_PLAN_ORDERED makes every phase wait for the one
+ *                    before it even when they share no buffer (the timing of
+ *                    a fully dependent chain on independent inputs)
  *   nvq_plan_run     enqueues one walk on `stream`
- *   nvq_plan_info    streaming = 1 if the persistent kernel is used
+ *   nvq_plan_info    streaming = 1 if the persistent kernel is used; waits =
+ *                    number of phases that wait for an earlier phase
  *   nvq_plan_status  synchronises `stream` and reports whether a wait inside
  *                    the persistent kernel gave up (its spins are bounded so
  *                    that a grid that cannot be co-resident ends with an
@@ -182,16 +189,17 @@ int nvq_decode_linears(const nvq_linear *layers, int n, int M, int act_group,
  *   nvq_plan_trace   diagnostic: give a device buffer of phases * 8 uint64
  *                    (or NULL to stop); later runs of the persistent kernel
  *                    store workgroup 0's timestamps per phase in it (100 MHz
- *                    wall clock): [0] wait begins, [1] previous phase seen
- *                    complete, [2] input staged, [3] phase computed,
- *                    [4] outputs published, [5..7] first streaming wave:
- *                    input seen, activations ready, own rows done
+ *                    wall clock), taken by its first wave: [0] phase entered,
+ *                    [1] dependency satisfied, [2] input staged, [3] all
+ *                    waves done (published phases only), [4] published,
+ *                    [5] input seen, [6] activations ready, [7] own rows done
  */
 typedef struct nvq_plan nvq_plan;
-int nvq_plan_create(const nvq_linear *layers, int n, int M, int act_group, void *workspace,
-                    size_t workspace_bytes, void *stream, nvq_plan **plan);
+enum { NVQ_PLAN_DEFAULT = 0, NVQ_PLAN_ORDERED = 1 };
+int nvq_plan_create(const nvq_linear *layers, int n, int M, int act_group, int flags,
+                    void *workspace, size_t workspace_bytes, void *stream, nvq_plan **plan);
 int nvq_plan_run(nvq_plan *plan, void *stream);
-int nvq_plan_info(const nvq_plan *plan, int *streaming, int *phases);
+int nvq_plan_info(const nvq_plan *plan, int *streaming, int *phases, int *waits);
 int nvq_plan_status(nvq_plan *plan, void *stream, int *timed_out);
 int nvq_plan_trace(nvq_plan *plan, uint64_t *buf, size_t bytes);
 void nvq_plan_destroy(nvq_plan *plan);

@@ -142,9 +142,17 @@ int walk_per_phase(const nvq_linear *L, const std::vector<Phase> &phases, int M,
     return NVQ_OK;
 }
 
+struct Range {
+    uintptr_t lo, hi;
+};
+bool overlap(const Range &a, const Range &b) { return a.lo < b.hi && b.lo < a.hi; }
+
 // Phase table for the streaming kernel; empty if some phase does not qualify.
+// Each phase records the latest earlier phase it conflicts with (it reads what
+// that phase wrote, or writes what that phase read or wrote); with `ordered`
+// every phase is made to depend on its predecessor.
 std::vector<StreamPhase> stream_table(const nvq_linear *L, const std::vector<Phase> &phases, int M,
-                                      int nwg) {
+                                      int nwg, bool ordered) {
     std::vector<StreamPhase> tab;
     if (M != 1 || nwg <= 0 || nwg > kMaxStreamWg) return tab;
     const int waves = nwg * kStreamWaves;
@@ -172,8 +180,35 @@ std::vector<StreamPhase> stream_table(const nvq_linear *L, const std::vector<Pha
         sp.gpl = (G + 63) / 64;
         sp.precision = e0.precision;
         sp.rows_per_wave = (rows + waves - 1) / waves;
-        if (sp.rows_per_wave * kStreamWaves > kStreamYStage) return {};
+        sp.wait_phase = -1;
+        sp.publish = 0;
         tab.push_back(sp);
+    }
+    const size_t P = tab.size();
+    std::vector<Range> xin(P);
+    std::vector<std::vector<Range>> yout(P);
+    for (size_t p = 0; p < P; ++p) {
+        const nvq_linear &e0 = L[phases[p].first];
+        xin[p] = {(uintptr_t)e0.x_bf16, (uintptr_t)e0.x_bf16 + (size_t)M * e0.K * 2};
+        for (int k = 0; k < phases[p].count; ++k) {
+            const nvq_linear &e = L[phases[p].first + k];
+            const size_t bytes = (size_t)M * e.N * (e.y_dtype == NVQ_F32 ? 4 : 2);
+            yout[p].push_back({(uintptr_t)e.y, (uintptr_t)e.y + bytes});
+        }
+    }
+    for (size_t p = 1; p < P; ++p) {
+        int dep = ordered ? (int)p - 1 : -1;
+        for (size_t q = 0; q < p && !ordered; ++q) {
+            bool hit = false;
+            for (const Range &yq : yout[q]) {
+                hit = hit || overlap(xin[p], yq);  // read after write
+                for (const Range &yp : yout[p]) hit = hit || overlap(yp, yq);  // write after write
+            }
+            for (const Range &yp : yout[p]) hit = hit || overlap(yp, xin[q]);  // write after read
+            if (hit) dep = (int)q;
+        }
+        tab[p].wait_phase = dep;
+        if (dep >= 0) tab[dep].publish = 1;
     }
     return tab;
 }
@@ -194,6 +229,7 @@ struct nvq_plan {
     int M, act_group;
     int nwg;           // workgroups of the streaming kernel, 0 = per-phase launches
     int nphase;        // entries of the device phase table
+    int nwaits;        // phases that wait for an earlier phase (streaming kernel)
     uint32_t runs;     // walks issued so far (advances the flag base)
     unsigned long long *trace;  // device buffer for per-phase timestamps, or nullptr
 };
@@ -205,11 +241,11 @@ extern "C" size_t nvq_decode_workspace_bytes(const nvq_linear *layers, int n, in
     return nvq::carve(nullptr, maxK, M, n).bytes;
 }
 
-extern "C" int nvq_plan_create(const nvq_linear *layers, int n, int M, int act_group,
+extern "C" int nvq_plan_create(const nvq_linear *layers, int n, int M, int act_group, int flags,
                                void *workspace, size_t workspace_bytes, void *stream,
                                nvq_plan **plan_out) {
     using namespace nvq;
-    if (!plan_out) return NVQ_ERR_INVALID_ARG;
+    if (!plan_out || (flags & ~NVQ_PLAN_ORDERED)) return NVQ_ERR_INVALID_ARG;
     *plan_out = nullptr;
     int maxK = 0;
     const int rc = check_layers(layers, n, M, act_group, &maxK);
@@ -228,9 +264,11 @@ extern "C" int nvq_plan_create(const nvq_linear *layers, int n, int M, int act_g
     pl->trace = nullptr;
     pl->nwg = 0;
     pl->nphase = 0;
+    pl->nwaits = 0;
     hipStream_t st = (hipStream_t)stream;
     const int nwg = n > 0 ? stream_grid_limit() : 0;
-    const std::vector<StreamPhase> tab = stream_table(pl->layers.data(), pl->phases, M, nwg);
+    const std::vector<StreamPhase> tab =
+        stream_table(pl->layers.data(), pl->phases, M, nwg, (flags & NVQ_PLAN_ORDERED) != 0);
     if (!tab.empty()) {
         // pageable source: the copy has left the host buffer when the call returns
         hipError_t e = hipMemcpyAsync(ws.tab, tab.data(), tab.size() * sizeof(StreamPhase),
@@ -247,6 +285,7 @@ extern "C" int nvq_plan_create(const nvq_linear *layers, int n, int M, int act_g
         }
         pl->nwg = nwg;
         pl->nphase = (int)tab.size();
+        for (const StreamPhase &sp : tab) pl->nwaits += sp.wait_phase >= 0;
     }
     *plan_out = pl;
     return NVQ_OK;
@@ -266,10 +305,11 @@ extern "C" int nvq_plan_run(nvq_plan *pl, void *stream) {
     return walk_per_phase(pl->layers.data(), pl->phases, pl->M, pl->act_group, pl->ws, st);
 }
 
-extern "C" int nvq_plan_info(const nvq_plan *pl, int *streaming, int *phases) {
+extern "C" int nvq_plan_info(const nvq_plan *pl, int *streaming, int *phases, int *waits) {
     if (!pl) return NVQ_ERR_INVALID_ARG;
     if (streaming) *streaming = pl->nwg > 0 ? 1 : 0;
     if (phases) *phases = (int)pl->phases.size();
+    if (waits) *waits = pl->nwaits;
     return NVQ_OK;
 }
 
@@ -301,7 +341,8 @@ extern "C" int nvq_decode_linears(const nvq_linear *layers, int n, int M, int ac
         return nvq::check_layers(layers, n, M, act_group, &maxK);
     }
     nvq_plan *pl = nullptr;
-    int rc = nvq_plan_create(layers, n, M, act_group, workspace, workspace_bytes, stream, &pl);
+    int rc = nvq_plan_create(layers, n, M, act_group, NVQ_PLAN_DEFAULT, workspace, workspace_bytes,
+                             stream, &pl);
     if (rc != NVQ_OK) return rc;
     rc = nvq_plan_run(pl, stream);
     nvq_plan_destroy(pl);

@@ -8,7 +8,6 @@ namespace nvq {
 constexpr int kStreamWaves = 8;  // waves per workgroup (two per SIMD)
 constexpr int kStreamThreads = kStreamWaves * 64;
 constexpr int kStreamMaxK = 14336;                       // widest input the LDS stage holds
-constexpr int kStreamYStage = 1024;                      // output rows staged per workgroup
 
 // One phase = up to four weight matrices that read the same input vector.
 // Lives in device memory; every field is read wave-uniformly.
@@ -23,6 +22,8 @@ struct StreamPhase {
     int K, G, gpl;         // G = K/32 (even), gpl = ceil(G/64) <= 7
     int precision;         // NVQ_W4A8 | NVQ_W4A16
     int rows_per_wave;     // ceil(total_rows / (workgroups * kStreamWaves))
+    int wait_phase;        // latest earlier phase this one depends on, or -1
+    int publish;           // 1 if a later phase depends on this one
     int pad_;
 };
 

@@ -23,16 +23,20 @@
 //   * control duties, carried by wave 0 between its own rows.  It alone talks
 //     to global memory besides the weight stream: it waits until every
 //     workgroup has finished the previous phase (one flag word per workgroup,
-//     no atomics), copies the phase's input vector into LDS, and after the
-//     phase writes the workgroup's outputs from LDS to memory and publishes
-//     its own flag.  Its extra memory operations queue behind its ring loads,
+//     no atomics), copies the phase's input vector into LDS, and after a
+//     phase that others depend on publishes its own flag.  Every wave writes
+//     its own output rows (one store instruction per 64 rows).  Its extra memory operations queue behind its ring loads,
 //     which only makes the ring's counted waits conservative.
 //   Activation quantisation (W4A8 phases) is done by the streaming waves
 //   cooperatively out of LDS, once per workgroup per phase.
 //
-// Phases are strictly ordered: phase p+1 reads its input only after every
-// workgroup has published phase p.  A bounded spin turns a stuck wait (e.g.
-// the grid not co-resident) into an error status instead of a hang.
+// Ordering: the host marks, per phase, the latest earlier phase whose buffers
+// it depends on (its input overlaps that phase's outputs, or its outputs
+// overlap that phase's input or outputs).  Such a phase reads its input only
+// after every workgroup has published the phase it depends on; a phase that
+// depends on nothing has its input fetched one phase ahead.  A bounded spin
+// turns a stuck wait (e.g. the grid not co-resident) into an error status
+// instead of a hang.
 #include "decode_stream.h"
 
 namespace nvq {
@@ -41,7 +45,7 @@ namespace {
 
 typedef __attribute__((address_space(3))) void *lds_void_ptr;
 
-constexpr int kSlots = 12;            // 1 KiB weight slots per streaming wave
+constexpr int kSlots = 10;            // 1 KiB weight slots per wave
 constexpr int kUnits = kSlots / 2;    // a unit = two chunks + their scales = 3 loads
 constexpr int kOpsPerUnit = 3;
 constexpr int kXStageBytes = kStreamMaxK * 2;  // bf16 input vector
@@ -54,9 +58,8 @@ constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0f70; }
 struct Shared {
     uint4 ring[kStreamWaves][kSlots][64];
     uint32_t sring[kStreamWaves][kUnits][64];
-    uint4 xstage[kXStageBytes / 16];
-    float xsg[kStreamMaxK / 32];      // per-group activation scales (act_group 32)
-    float ystage[kStreamYStage];
+    uint4 xstage[2][kXStageBytes / 16];  // input vectors of phases p (p & 1) and p + 1
+    float xsg[kStreamMaxK / 32];         // per-group activation scales (act_group 32)
     float amax_part[kStreamWaves];
     int abort;
 };
@@ -271,7 +274,8 @@ struct ChunkRegs {
 template <int PREC, int GPL, bool PER_GROUP>
 __device__ __forceinline__ void consume_phase(const StreamPhase &ph, const StreamPhase *tab,
                                               StreamState &st, Shared &sh, int w, int gw, int lane,
-                                              const uint4 *dummy, float xs_token) {
+                                              const uint4 *dummy, float xs_token,
+                                              uint32_t stage /* LDS address of the input */) {
     constexpr int XR = PREC == NVQ_W4A8 ? 8 : 16;
     // Activations stay in registers for the whole phase unless that would take
     // more than 64 registers (bf16 activations of more than four chunks); then
@@ -290,7 +294,7 @@ __device__ __forceinline__ void consume_phase(const StreamPhase &ph, const Strea
         const bool ok = g < ph.G;
         const int gc = ok ? g : 0;
         okv[i] = ok;
-        const uint32_t src = lds_addr(sh.xstage) + gc * (XR * 4);
+        const uint32_t src = stage + gc * (XR * 4);
         xaddr[i] = src;
         uint32_t t[XR];
 #pragma unroll
@@ -325,7 +329,6 @@ __device__ __forceinline__ void consume_phase(const StreamPhase &ph, const Strea
     int r1 = r0 + ph.rows_per_wave;
     r1 = r1 < ph.total_rows ? r1 : ph.total_rows;
     if (r0 >= r1) return;
-    const int wg_row0 = (gw - w) * ph.rows_per_wave;
     const uint32_t ring_base = lds_addr(&sh.ring[w][0][0]) + lane * 16;
     const uint32_t sring_base = lds_addr(&sh.sring[w][0][0]) + lane * 2;
 
@@ -367,6 +370,7 @@ __device__ __forceinline__ void consume_phase(const StreamPhase &ph, const Strea
     fetch(0);
     landed();
 
+    float yv = 0.0f;  // results of up to 64 rows, one per lane, until they are stored
     for (int row = r0; row < r1; ++row) {
         float sum = 0.0f;
 #pragma unroll
@@ -404,9 +408,27 @@ __device__ __forceinline__ void consume_phase(const StreamPhase &ph, const Strea
             if (more) landed();
         }
         sum = wave_sum_to_lane63(sum);
-        if (lane == 63)
-            lds_write4(lds_addr(&sh.ystage[row - wg_row0]),
-                       __float_as_uint(PREC == NVQ_W4A8 ? sum * xs_token : sum));
+        // park the row's result in lane (row - r0) % 64; one store per 64 rows
+        const float tot =
+            __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, sum), 63));
+        const int k = row - r0;
+        if (lane == (k & 63)) yv = PREC == NVQ_W4A8 ? tot * xs_token : tot;
+        if ((k & 63) == 63 || row == r1 - 1) {
+            const int r = row - (k & 63) + lane;  // the row this lane holds
+            if (r <= row) {
+                int first = 0;
+                void *y = ph.y[0];
+                int dt = ph.y_dtype[0];
+#pragma unroll
+                for (int sgm = 1; sgm < kMaxSeg; ++sgm)
+                    if (sgm < ph.nseg && r >= ph.row_end[sgm - 1]) {
+                        first = ph.row_end[sgm - 1];
+                        y = ph.y[sgm];
+                        dt = ph.y_dtype[sgm];
+                    }
+                store_out(y, dt, r - first, yv);
+            }
+        }
     }
 }
 
@@ -414,7 +436,8 @@ __device__ __forceinline__ void consume_phase(const StreamPhase &ph, const Strea
 // On return xstage holds K int8 codes; returns the per-token scale (1 when the
 // scales are per group).
 template <bool PER_GROUP>
-__device__ __forceinline__ float quantise_stage(const StreamPhase &ph, Shared &sh, int w, int lane) {
+__device__ __forceinline__ float quantise_stage(const StreamPhase &ph, Shared &sh, int w, int lane,
+                                                uint32_t stage) {
     const int t = w * 64 + lane;             // 0 .. kStreamWaves*64-1
     constexpr int NT = kStreamWaves * 64;
     constexpr int MAXC = (kStreamMaxK / 8 + NT - 1) / NT;  // chunks of 8 values per lane
@@ -426,7 +449,7 @@ __device__ __forceinline__ float quantise_stage(const StreamPhase &ph, Shared &s
         const int c = t + k * NT;
         raw[k] = make_uint4(0, 0, 0, 0);
         if (k * NT < chunks) {  // uniform: this round holds data for some lane
-            if (c < chunks) raw[k] = lds_read16(lds_addr(sh.xstage) + c * 16);
+            if (c < chunks) raw[k] = lds_read16(stage + c * 16);
             const uint32_t wv[4] = {raw[k].x, raw[k].y, raw[k].z, raw[k].w};
 #pragma unroll
             for (int d = 0; d < 4; ++d) {
@@ -449,7 +472,7 @@ __device__ __forceinline__ float quantise_stage(const StreamPhase &ph, Shared &s
             a = fmaxf(a, __uint_as_float(lds_read4(lds_addr(&sh.amax_part[i]))));
         s_tok = a / 127.0f;
     }
-    const uint32_t qstage = lds_addr(sh.xstage);
+    const uint32_t qstage = stage;
 #pragma unroll
     for (int k = 0; k < MAXC; ++k) {
         if (k * NT >= chunks) break;
@@ -489,15 +512,16 @@ __device__ __forceinline__ float quantise_stage(const StreamPhase &ph, Shared &s
 template <int PREC, bool PER_GROUP>
 __device__ __forceinline__ void consume_dispatch(const StreamPhase &ph, const StreamPhase *tab,
                                                  StreamState &st, Shared &sh, int w, int gw,
-                                                 int lane, const uint4 *dummy, float xs) {
+                                                 int lane, const uint4 *dummy, float xs,
+                                                 uint32_t stage) {
     switch (ph.gpl) {
-        case 1: consume_phase<PREC, 1, PER_GROUP>(ph, tab, st, sh, w, gw, lane, dummy, xs); break;
-        case 2: consume_phase<PREC, 2, PER_GROUP>(ph, tab, st, sh, w, gw, lane, dummy, xs); break;
-        case 3: consume_phase<PREC, 3, PER_GROUP>(ph, tab, st, sh, w, gw, lane, dummy, xs); break;
-        case 4: consume_phase<PREC, 4, PER_GROUP>(ph, tab, st, sh, w, gw, lane, dummy, xs); break;
-        case 5: consume_phase<PREC, 5, PER_GROUP>(ph, tab, st, sh, w, gw, lane, dummy, xs); break;
-        case 6: consume_phase<PREC, 6, PER_GROUP>(ph, tab, st, sh, w, gw, lane, dummy, xs); break;
-        default: consume_phase<PREC, 7, PER_GROUP>(ph, tab, st, sh, w, gw, lane, dummy, xs); break;
+        case 1: consume_phase<PREC, 1, PER_GROUP>(ph, tab, st, sh, w, gw, lane, dummy, xs, stage); break;
+        case 2: consume_phase<PREC, 2, PER_GROUP>(ph, tab, st, sh, w, gw, lane, dummy, xs, stage); break;
+        case 3: consume_phase<PREC, 3, PER_GROUP>(ph, tab, st, sh, w, gw, lane, dummy, xs, stage); break;
+        case 4: consume_phase<PREC, 4, PER_GROUP>(ph, tab, st, sh, w, gw, lane, dummy, xs, stage); break;
+        case 5: consume_phase<PREC, 5, PER_GROUP>(ph, tab, st, sh, w, gw, lane, dummy, xs, stage); break;
+        case 6: consume_phase<PREC, 6, PER_GROUP>(ph, tab, st, sh, w, gw, lane, dummy, xs, stage); break;
+        default: consume_phase<PREC, 7, PER_GROUP>(ph, tab, st, sh, w, gw, lane, dummy, xs, stage); break;
     }
 }
 
@@ -534,15 +558,29 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
     for (int u = 0; u < kUnits; ++u)  // fill the ring
         issue_unit(st.ic, tab, gw, sh, w, u, lane, dummy);
 
+    // Stage the input vector of phase q (bf16, K values) with global->LDS
+    // loads, all in flight at once; completion is awaited later with vmcnt(0).
+    auto stage_input = [&](int q) {
+        const StreamPhase &pq = tab[q];
+        const uint4 *xsrc = reinterpret_cast<const uint4 *>(pq.x);
+        const int n16 = pq.K / 8;
+        for (int c0 = 0; c0 < n16; c0 += 64)
+            if (c0 + lane < n16)
+                __builtin_amdgcn_global_load_lds((const void *)(xsrc + c0 + lane),
+                                                 (lds_void_ptr)&sh.xstage[q & 1][c0], 16, 0, 0);
+    };
+    bool staged = false;  // wave 0: the current phase's input is already on its way
+
     for (int p = 0; p < nphase; ++p) {
         const StreamPhase &ph = tab[p];
+        const uint32_t stage = lds_addr(&sh.xstage[p & 1][0]);
         if (w == 0) {
-            // ---- control duty 1: wait for the previous phase, stage the input ----
+            // ---- control duty 1: honour the phase's dependency, have its input in LDS ----
             bool ok = true;
             trace_mark(trace, wg, lane, p, 0);
-            if (p > 0) {
-                // every workgroup must have published phase p-1
-                const uint32_t target = flag_base + (uint32_t)p;
+            if (ph.wait_phase >= 0) {
+                // every workgroup must have published phase wait_phase
+                const uint32_t target = flag_base + (uint32_t)ph.wait_phase + 1u;
                 uint32_t spins = 0;
                 for (;;) {
                     bool all = true;
@@ -569,13 +607,7 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
             }
             trace_mark(trace, wg, lane, p, 1);
             if (ok) {
-                // the input vector (bf16, K values): global->LDS, all loads in flight at once
-                const uint4 *xsrc = reinterpret_cast<const uint4 *>(ph.x);
-                const int n16 = ph.K / 8;
-                for (int c0 = 0; c0 < n16; c0 += 64)
-                    if (c0 + lane < n16)
-                        __builtin_amdgcn_global_load_lds((const void *)(xsrc + c0 + lane),
-                                                         (lds_void_ptr)&sh.xstage[c0], 16, 0, 0);
+                if (!staged) stage_input(p);
                 __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
             } else if (lane == 0) {
                 lds_write4(lds_addr(&sh.abort), 1u);
@@ -583,45 +615,39 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
             }
             trace_mark(trace, wg, lane, p, 2);
         }
-        lds_barrier();  // B1: input vector staged (or abort raised)
+        // B1: this phase's input is staged (or abort raised); every wave has
+        // left the previous phase, so the other stage buffer is free
+        lds_barrier();
         if (lds_read4(lds_addr(&sh.abort))) break;
-        if (w == 0) trace_mark(trace, wg, lane, p, 5);
+        if (w == 0) {
+            trace_mark(trace, wg, lane, p, 5);
+            // start fetching the next phase's input now if it depends on nothing
+            staged = p + 1 < nphase && tab[p + 1].wait_phase < 0;
+            if (staged) stage_input(p + 1);
+        }
         float xs = 1.0f;
         if (ph.precision == NVQ_W4A8) {
-            xs = quantise_stage<PER_GROUP>(ph, sh, w, lane);  // B2, B3 inside
+            xs = quantise_stage<PER_GROUP>(ph, sh, w, lane, stage);  // B2, B3 inside
             if (w == 0) trace_mark(trace, wg, lane, p, 6);
-            consume_dispatch<NVQ_W4A8, PER_GROUP>(ph, tab, st, sh, w, gw, lane, dummy, xs);
+            consume_dispatch<NVQ_W4A8, PER_GROUP>(ph, tab, st, sh, w, gw, lane, dummy, xs, stage);
         } else {
             if (w == 0) trace_mark(trace, wg, lane, p, 6);
-            consume_dispatch<NVQ_W4A16, false>(ph, tab, st, sh, w, gw, lane, dummy, xs);
+            consume_dispatch<NVQ_W4A16, false>(ph, tab, st, sh, w, gw, lane, dummy, xs, stage);
         }
         if (w == 0) trace_mark(trace, wg, lane, p, 7);
-        lds_barrier();  // B4: outputs staged
-        if (w == 0) {
-            // ---- control duty 2: write the workgroup's outputs, publish the phase ----
-            trace_mark(trace, wg, lane, p, 3);
-            const int row0 = wg * kStreamWaves * ph.rows_per_wave;
-            int row1 = row0 + kStreamWaves * ph.rows_per_wave;
-            row1 = row1 < ph.total_rows ? row1 : ph.total_rows;
-            for (int r = row0 + lane; r < row1; r += 64) {
-                const float v = __uint_as_float(lds_read4(lds_addr(&sh.ystage[r - row0])));
-                int first = 0;
-                void *y = ph.y[0];
-                int dt = ph.y_dtype[0];
-#pragma unroll
-                for (int s = 1; s < kMaxSeg; ++s)
-                    if (s < ph.nseg && r >= ph.row_end[s - 1]) {
-                        first = ph.row_end[s - 1];
-                        y = ph.y[s];
-                        dt = ph.y_dtype[s];
-                    }
-                store_out(y, dt, r - first, v);
+        if (ph.publish) {
+            // a later phase reads or overwrites what this one touched: make the
+            // workgroup's outputs visible device-wide, then raise its flag
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // this wave's stores have completed
+            lds_barrier();                             // B4
+            if (w == 0) {
+                trace_mark(trace, wg, lane, p, 3);
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+                if (lane == 0)
+                    __hip_atomic_store(flags + wg, flag_base + (uint32_t)p + 1u, __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+                trace_mark(trace, wg, lane, p, 4);
             }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-            if (lane == 0)
-                __hip_atomic_store(flags + wg, flag_base + (uint32_t)p + 1u, __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
-            trace_mark(trace, wg, lane, p, 4);
         }
     }
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // no load may outlive the wave

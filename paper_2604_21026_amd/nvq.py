@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(HERE, "libnvq.so")
 F32, BF16 = 0, 1
 W4A8, W4A16 = 0, 1
 MAX_M = 32
+PLAN_ORDERED = 1
 
 EXPORTS = (
     "nvq_status_string", "nvq_last_hip_error", "nvq_pack_int4", "nvq_quant_act_i8",
@@ -64,9 +65,9 @@ def lib() -> C.CDLL:
     L.nvq_decode_workspace_bytes.restype = sz
     L.nvq_decode_workspace_bytes.argtypes = [vp, ci, ci, ci]
     L.nvq_decode_linears.argtypes = [vp, ci, ci, ci, vp, sz, vp]
-    L.nvq_plan_create.argtypes = [vp, ci, ci, ci, vp, sz, vp, C.POINTER(vp)]
+    L.nvq_plan_create.argtypes = [vp, ci, ci, ci, ci, vp, sz, vp, C.POINTER(vp)]
     L.nvq_plan_run.argtypes = [vp, vp]
-    L.nvq_plan_info.argtypes = [vp, C.POINTER(ci), C.POINTER(ci)]
+    L.nvq_plan_info.argtypes = [vp, C.POINTER(ci), C.POINTER(ci), C.POINTER(ci)]
     L.nvq_plan_status.argtypes = [vp, vp, C.POINTER(ci)]
     L.nvq_plan_trace.argtypes = [vp, vp, sz]
     L.nvq_plan_destroy.argtypes = [vp]
@@ -174,8 +175,10 @@ def gemv_w4a8(qweight, scales, xq, xscale, xgsum, act_group: int = 0,
 class DecodeList:
     """A host-side `nvq_linear[]` plus the tensors it points to and its workspace."""
 
-    def __init__(self, entries: Sequence[dict], M: int, act_group: int = 0):
+    def __init__(self, entries: Sequence[dict], M: int, act_group: int = 0,
+                 ordered: bool = False):
         self.M, self.act_group = M, act_group
+        self.ordered = ordered
         self.n = len(entries)
         self.arr = (Linear * max(self.n, 1))()
         self.keep: List[torch.Tensor] = []
@@ -206,6 +209,7 @@ class DecodeList:
         if getattr(self, "_plan", None) is None:
             h = C.c_void_p()
             _check(lib().nvq_plan_create(C.byref(self.arr), self.n, self.M, self.act_group,
+                                         PLAN_ORDERED if self.ordered else 0,
                                          self.workspace.data_ptr(), self.workspace.numel(),
                                          _stream(), C.byref(h)), "nvq_plan_create")
             self._plan = h
@@ -215,9 +219,10 @@ class DecodeList:
         _check(lib().nvq_plan_run(self.plan(), _stream()), "nvq_plan_run")
 
     def plan_info(self):
-        s, p = C.c_int(), C.c_int()
-        _check(lib().nvq_plan_info(self.plan(), C.byref(s), C.byref(p)), "nvq_plan_info")
-        return {"streaming": bool(s.value), "phases": p.value}
+        s, p, w = C.c_int(), C.c_int(), C.c_int()
+        _check(lib().nvq_plan_info(self.plan(), C.byref(s), C.byref(p), C.byref(w)),
+               "nvq_plan_info")
+        return {"streaming": bool(s.value), "phases": p.value, "waits": w.value}
 
     def plan_timed_out(self) -> bool:
         t = C.c_int()

@@ -324,17 +324,21 @@ STREAM_MODELS = {
 }
 
 
-@pytest.mark.parametrize("name,group", [("1b", 0), ("ragged", 0), ("ragged", 32), ("8b", 0),
-                                        ("8b", 32)])
-def test_streaming_plan_matches_oracle_on_repeated_runs(name, group):
-    say("stream plan", name, group)
+@pytest.mark.parametrize("name,group,ordered", [("1b", 0, False), ("1b", 0, True),
+                                                ("ragged", 0, False), ("ragged", 32, True),
+                                                ("8b", 0, False), ("8b", 32, False),
+                                                ("8b", 0, True)])
+def test_streaming_plan_matches_oracle_on_repeated_runs(name, group, ordered):
+    say("stream plan", name, group, ordered)
     shapes, bits = STREAM_MODELS[name]
     entries, host = model_entries(shapes, bits)
     ys_ref = oracle.decode_linears(host, 1, group)
-    dl = nvq.DecodeList(entries, 1, group)
+    dl = nvq.DecodeList(entries, 1, group, ordered=ordered)
     info = dl.plan_info()
     say("  plan", info)
     assert info["streaming"], "batch-1 walk should use the persistent kernel"
+    # independent buffers: no phase has to wait unless ordering is forced
+    assert info["waits"] == (info["phases"] - 1 if ordered else 0)
     for rep in range(3):
         for e in entries:
             e["y"].zero_()
@@ -360,7 +364,8 @@ def test_streaming_plan_orders_dependent_phases():
         qd, sd = to_dev_packed(q, s)
         entries.append(dict(qweight=qd, scales=sd, x=bufs[i], y=bufs[i + 1], precision=i % 2))
     dl = nvq.DecodeList(entries, 1)
-    assert dl.plan_info()["streaming"]
+    info = dl.plan_info()
+    assert info["streaming"] and info["waits"] == 3      # the analysis found the chain
     for rep in range(3):
         for b in bufs[1:]:
             b.zero_()
