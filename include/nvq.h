@@ -157,9 +157,8 @@ typedef struct nvq_linear {
  *   workspace  device buffer of at least nvq_decode_workspace_bytes(...)
  *              bytes, 256-byte aligned; its contents are scratch.
  * At M = 1 the whole list runs as ONE persistent kernel that keeps streaming
- * the weights of coming phases while a phase waits for its input (needs every
- * K <= 14336 with K % 64 == 0 and 4-byte aligned scales); otherwise one or
- * two launches per phase are enqueued.  Both give the same results.
+ * the weights of coming phases while a phase is being set up (needs every
+ * K <= 14336); otherwise one or two launches per phase are enqueued.  Both give the same results.
  * nvq_decode_linears copies its phase table to the device on every call
  * (a blocking copy of a few KiB); a plan does that once.
  * nvq_decode_workspace_bytes returns 0 for invalid arguments.

@@ -159,12 +159,11 @@ std::vector<StreamPhase> stream_table(const nvq_linear *L, const std::vector<Pha
     for (const Phase &ph : phases) {
         const nvq_linear &e0 = L[ph.first];
         const int G = e0.K / 32;
-        if (e0.K > kStreamMaxK || (G & 1)) return {};
+        if (e0.K > kStreamMaxK) return {};
         StreamPhase sp = {};
         int rows = 0;
         for (int k = 0; k < ph.count; ++k) {
             const nvq_linear &e = L[ph.first + k];
-            if (!aligned(e.scales, 4)) return {};
             sp.qw[k] = reinterpret_cast<const uint4 *>(e.qweight);
             sp.sc[k] = e.scales;
             sp.y[k] = e.y;
