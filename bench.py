@@ -2,17 +2,19 @@
 """Benchmark of the decode-linear hot path on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--model llama-8b]
-                    [--map mixed|w4a8|w4a16] [--leg all|step|roofline|cpu]
+                    [--map mixed|w4a8|w4a16] [--leg all|step|cpu] [--extra]
 
-A step is one nvq_decode_linears walk over every linear layer of one decode
-step (batch 1) of the named Llama-shaped model: activation quantisation for
-the W4A8 layers, all GEMVs, lm_head included where the model has one.  All
-weights and activations are resident in HBM before the timed region.  Prints
-one JSON line (see the design doc for the fields).
+A step is one walk (one run of a prepared nvq plan = one launch of the
+persistent streaming kernel) over every linear layer of one decode step at
+batch 1 of the named Llama-shaped model: activation quantisation for the W4A8
+layers, all GEMVs, lm_head (W4A16) where the model has one.  All weights and
+activations are resident in HBM before the timed region; every layer reads its
+own seeded input buffer.  Prints one JSON line; the design doc explains the fields.
 """
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -21,20 +23,22 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+STREAM_KERNEL = "nvq::decode_stream_kernel<false>"
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--model", default="llama-8b", choices=["llama-1b", "llama-3b", "llama-8b"])
     ap.add_argument("--map", default="mixed", choices=["mixed", "w4a8", "w4a16"])
-    ap.add_argument("--leg", default="all", choices=["all", "step", "roofline", "cpu"])
-    ap.add_argument("--batch", type=int, default=1)
+    ap.add_argument("--leg", default="all", choices=["all", "step", "cpu", "calib"],
+                    help="calib: run only the plain copy kernel (1 GiB, for scaling profiler "
+                         "byte counters)")
     ap.add_argument("--act-group", type=int, default=0, choices=[0, 32])
-    ap.add_argument("--extra-maps", action="store_true",
-                    help="also time the all-W4A8 and all-W4A16 maps (reported under config)")
+    ap.add_argument("--extra", action="store_true",
+                    help="also time the all-W4A8 / all-W4A16 maps and the fully ordered chain")
     return ap.parse_args()
 
 
@@ -44,13 +48,13 @@ def block_bits(model, which, synth):
         return [0] * nb
     if which == "w4a16":
         return [1] * nb
-    # seeded map: 1B 50% W4A8, 3B 25% W4A16, 8B 50/50
+    # seeded maps: 1B half W4A8, 3B a quarter W4A16, 8B half and half
     n16 = {"llama-1b": nb // 2, "llama-3b": nb // 4, "llama-8b": nb // 2}[model]
     return synth.make_precision_map(nb, n16)
 
 
 def build_model(model, M, torch, nvq, synth, dev):
-    """Pack every layer on the GPU (one fp32 tensor alive at a time)."""
+    """Generate and pack every layer on the GPU (one fp32 tensor alive at a time)."""
     specs = synth.model_linears(model)
     layers = []
     xbuf = {}
@@ -79,60 +83,42 @@ def entries_for(layers, bits, nvq):
 
 
 def time_steps(dl, steps, warmup, torch):
-    """K walks of the prepared plan, bracketed by device synchronisation."""
+    """K walks of the prepared plan.  Returns (wall seconds per step between two device
+    synchronisations, seconds per launch from HIP events on the launch stream)."""
     dl.plan()
     for _ in range(warmup):
         dl.run_plan()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        dl.run_plan()
-    torch.cuda.synchronize()
-    sec = (time.perf_counter() - t0) / steps
-    if dl.plan_timed_out():
-        raise RuntimeError("a wait inside the streaming kernel timed out; results invalid")
-    return sec
-
-
-def roofline_leg(layers, torch, nvq, synth, reps=5):
-    """The dominant kernel in isolation: the batch-1 W4A8 GEMV on the largest
-    per-block matrix shape, rotating over every block's copy so that no launch
-    finds its weights in cache.  Timed with HIP events on the launch stream."""
-    cand = [L for L in layers if L["spec"].block >= 0]
-    big = max(L["spec"].N * L["spec"].K for L in cand)
-    mats = [L for L in cand if L["spec"].N * L["spec"].K == big and L["spec"].slot in (4, 6)]
-    slot = mats[0]["spec"].slot
-    mats = [L for L in mats if L["spec"].slot == slot]
-    sp = mats[0]["spec"]
-    xq, xs, gs = nvq.quant_act_i8(mats[0]["x"][:1].contiguous())
-    for L in mats:
-        nvq.gemv_w4a8(L["qweight"], L["scales"], xq, xs, gs, out=L["y"][:1])
-    torch.cuda.synchronize()
     st = torch.cuda.current_stream()
     e0 = torch.cuda.Event(enable_timing=True)
     e1 = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
     e0.record(st)
-    for _ in range(reps):
-        for L in mats:
-            nvq.gemv_w4a8(L["qweight"], L["scales"], xq, xs, gs, out=L["y"][:1])
+    for _ in range(steps):
+        dl.run_plan()
     e1.record(st)
     torch.cuda.synchronize()
-    n = reps * len(mats)
-    avg_s = e0.elapsed_time(e1) * 1e-3 / n
-    bytes_per_launch = synth.weight_bytes(sp.N, sp.K)
-    gbs = bytes_per_launch / avg_s / 1e9
-    G = sp.K // 32
-    kernel = "gemv_w4a8_m1_kernel<%d, 64, false, false>" % ((G + 63) // 64)
-    return {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None, "kernel": kernel,
-            "shape": "N=%d K=%d M=1" % (sp.N, sp.K), "launches": n,
-            "avg_launch_us": round(avg_s * 1e6, 2), "bytes_per_launch": bytes_per_launch}
+    wall = (time.perf_counter() - t0) / steps
+    if dl.plan_timed_out():
+        raise RuntimeError("a wait inside the streaming kernel timed out; results invalid")
+    return wall, e0.elapsed_time(e1) * 1e-3 / steps
+
+
+def traffic_from_profile(model, which):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by a
+    copy kernel of known size); read from the committed summary, None if it is not there."""
+    path = os.path.join(ROOT, "profiles", "decode_stream_%s_%s_pmc.md" % (model, which))
+    try:
+        m = re.search(r"traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read())
+        return float(m.group(1)) if m else None
+    except OSError:
+        return None
 
 
 def cpu_leg(model, bits, M, synth, budget_s=20.0):
-    """The oracle's walker on a bounded sample of the same workload: the first
-    blocks of the model (as many as fit the time budget, at least one), inputs
-    generated and packed on the CPU by the oracle itself."""
+    """The oracle's walker on a bounded sample of the same workload: the first blocks of the
+    model (as many as the time budget allows, at most four), inputs generated and packed on
+    the CPU by the oracle itself."""
     import numpy as np
     import torch
     import oracle
@@ -152,7 +138,7 @@ def cpu_leg(model, bits, M, synth, budget_s=20.0):
         blocks += 1
         if time.perf_counter() - t_gen0 > budget_s * 0.4 or blocks >= 4:
             break
-    oracle.decode_linears(host, M)                       # warm caches / thread pool
+    oracle.decode_linears(host, M)                       # warm caches and the thread pool
     reps, t0 = 0, time.perf_counter()
     while reps < 3 or (time.perf_counter() - t0 < budget_s * 0.4 and reps < 50):
         oracle.decode_linears(host, M)
@@ -175,7 +161,17 @@ def main():
     import torch
     from paper_2604_21026_amd import nvq, synth
 
-    M = a.batch
+    if a.leg == "calib":
+        torch.cuda.set_device(0)
+        src = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            nvq.stream_copy(dst, src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calib": "nvq::stream_copy_kernel", "bytes_read": 1 << 30,
+                          "bytes_written": 1 << 30, "launches": 5}))
+        return
+    M = 1
     bits = block_bits(a.model, a.map, synth)
     specs = synth.model_linears(a.model)
     step_bytes = sum(synth.weight_bytes(s.N, s.K) for s in specs)
@@ -185,13 +181,13 @@ def main():
         "ms_per_step": None, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int4 weights; int8 x int4 -> int32 (W4A8) and bf16 x int4 -> f32 (W4A16)",
         "data": "synthetic",
-        "config": {"workload": "%s-shaped decode step, batch %d, %d linears, precision map %s "
-                               "(%d of %d blocks W4A16%s)" %
-                               (a.model, M, len(specs), a.map, sum(bits), len(bits),
+        "config": {"workload": "%s-shaped decode step, batch 1, %d linears in %s, precision map "
+                               "%s (%d of %d blocks W4A16%s), own input buffer per layer" %
+                               (a.model, len(specs), "one launch", a.map, sum(bits), len(bits),
                                 ", lm_head W4A16" if specs[-1].block < 0 else ""),
                    "act_group": a.act_group, "weight_bytes_per_step": step_bytes},
     }
-    if a.leg in ("all", "step", "roofline"):
+    if a.leg in ("all", "step"):
         if not torch.cuda.is_available():
             print("bench.py: no GPU visible", file=sys.stderr)
             sys.exit(3)
@@ -199,22 +195,31 @@ def main():
         torch.cuda.set_device(0)
         nvq.lib()
         layers = build_model(a.model, M, torch, nvq, synth, dev)
-        if a.leg in ("all", "step"):
-            dl = nvq.DecodeList(entries_for(layers, bits, nvq), M, a.act_group)
-            sec = time_steps(dl, a.steps, a.warmup, torch)
-            out["value"] = round(M / sec, 2)
-            out["ms_per_step"] = round(sec * 1e3, 4)
-            gbs = step_bytes / sec / 1e9
-            out["config"]["step_hbm_gbs"] = round(gbs, 1)
-            out["config"]["step_frac_of_peak"] = round(gbs / HBM_PEAK_GBS, 4)
-            if a.extra_maps:
-                for name in ("w4a8", "w4a16"):
-                    b2 = block_bits(a.model, name, synth)
-                    d2 = nvq.DecodeList(entries_for(layers, b2, nvq), M, a.act_group)
-                    s2 = time_steps(d2, max(a.steps // 2, 1), max(a.warmup // 2, 1), torch)
-                    out["config"]["tokens_per_s_all_" + name] = round(M / s2, 2)
-        if a.leg in ("all", "roofline"):
-            out["roofline"] = roofline_leg(layers, torch, nvq, synth)
+        dl = nvq.DecodeList(entries_for(layers, bits, nvq), M, a.act_group)
+        info = dl.plan_info()
+        wall, per_launch = time_steps(dl, a.steps, a.warmup, torch)
+        out["value"] = round(M / wall, 2)
+        out["ms_per_step"] = round(wall * 1e3, 4)
+        out["config"]["plan"] = info
+        gbs = step_bytes / per_launch / 1e9
+        out["roofline"] = {
+            "bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": traffic_from_profile(a.model, a.map),
+            "kernel": STREAM_KERNEL if info["streaming"] else "per-phase launches",
+            "launches": a.steps, "avg_launch_us": round(per_launch * 1e6, 2),
+            "bytes_per_launch": step_bytes}
+        dl.close()
+        if a.extra:
+            for name in ("w4a8", "w4a16"):
+                d2 = nvq.DecodeList(entries_for(layers, block_bits(a.model, name, synth), nvq), M,
+                                    a.act_group)
+                w2, _ = time_steps(d2, max(a.steps // 2, 1), max(a.warmup // 2, 1), torch)
+                out["config"]["tokens_per_s_all_" + name] = round(M / w2, 2)
+                d2.close()
+            d3 = nvq.DecodeList(entries_for(layers, bits, nvq), M, a.act_group, ordered=True)
+            w3, _ = time_steps(d3, max(a.steps // 2, 1), max(a.warmup // 2, 1), torch)
+            out["config"]["tokens_per_s_ordered_chain"] = round(M / w3, 2)
+            d3.close()
         del layers
         torch.cuda.empty_cache()
     if a.leg in ("all", "cpu"):
