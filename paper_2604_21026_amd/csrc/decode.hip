@@ -33,10 +33,11 @@ struct Workspace {
     uint32_t *flags;    // [kMaxStreamWg]      one word per workgroup
     uint32_t *status;   // [64]                word 0: a wait timed out
     void *dummy;        // 1 KiB               target of the ring's filler loads
+    char *images;       // prepared activation images of the streaming kernel
     size_t bytes;
 };
 
-Workspace carve(void *base, int maxK, int M, int n) {
+Workspace carve(void *base, int maxK, int M, int n, size_t image_bytes) {
     Workspace w;
     char *b = reinterpret_cast<char *>(base);
     const size_t G = (size_t)maxK / 32;
@@ -53,15 +54,18 @@ Workspace carve(void *base, int maxK, int M, int n) {
     w.flags = reinterpret_cast<uint32_t *>(take(kMaxStreamWg * 4));
     w.status = reinterpret_cast<uint32_t *>(take(256));
     w.dummy = take(1024);
+    w.images = take(image_bytes);
     w.bytes = off;
     return w;
 }
 
-int check_layers(const nvq_linear *L, int n, int M, int act_group, int *maxK) {
+int check_layers(const nvq_linear *L, int n, int M, int act_group, int *maxK,
+                 size_t *image_bytes) {
     if (!L || n < 0) return NVQ_ERR_INVALID_ARG;
     if (act_group != 0 && act_group != 32) return NVQ_ERR_INVALID_ARG;
     if (M <= 0 || M > NVQ_MAX_M) return NVQ_ERR_SHAPE;
     int mk = 32;
+    size_t ib = 0;
     for (int i = 0; i < n; ++i) {
         const nvq_linear &e = L[i];
         if (!e.qweight || !e.scales || !e.x_bf16 || !e.y) return NVQ_ERR_INVALID_ARG;
@@ -72,8 +76,11 @@ int check_layers(const nvq_linear *L, int n, int M, int act_group, int *maxK) {
             !aligned(e.y, e.y_dtype == NVQ_F32 ? 4 : 2))
             return NVQ_ERR_ALIGN;
         if (e.K > mk) mk = e.K;
+        // upper bound: every entry its own phase with a prepared image
+        if (e.K <= kStreamMaxK) ib += (size_t)stream_image_bytes(e.K, e.precision, act_group);
     }
     *maxK = mk;
+    *image_bytes = ib;
     return NVQ_OK;
 }
 
@@ -152,7 +159,8 @@ bool overlap(const Range &a, const Range &b) { return a.lo < b.hi && b.lo < a.hi
 // that phase wrote, or writes what that phase read or wrote); with `ordered`
 // every phase is made to depend on its predecessor.
 std::vector<StreamPhase> stream_table(const nvq_linear *L, const std::vector<Phase> &phases, int M,
-                                      int nwg, bool ordered) {
+                                      int act_group, int nwg, bool ordered, char *images,
+                                      int *nimages) {
     std::vector<StreamPhase> tab;
     if (M != 1 || nwg <= 0 || nwg > kMaxStreamWg) return tab;
     const int waves = nwg * kStreamWaves;
@@ -181,6 +189,8 @@ std::vector<StreamPhase> stream_table(const nvq_linear *L, const std::vector<Pha
         sp.rows_per_wave = (rows + waves - 1) / waves;
         sp.wait_phase = -1;
         sp.publish = 0;
+        sp.img = nullptr;
+        sp.img_chunks = 0;
         tab.push_back(sp);
     }
     const size_t P = tab.size();
@@ -209,6 +219,25 @@ std::vector<StreamPhase> stream_table(const nvq_linear *L, const std::vector<Pha
         tab[p].wait_phase = dep;
         if (dep >= 0) tab[dep].publish = 1;
     }
+    // Activation images.  A phase that waits for nothing gets its image
+    // prepared in global memory; in LDS, even phases sit at the bottom of the
+    // image area and odd phases at the top, so consecutive images do not
+    // overlap unless they are too large together.
+    size_t off = 0;
+    int count = 0, prev_bytes = 0;
+    for (size_t p = 0; p < P; ++p) {
+        const int bytes = stream_image_bytes(tab[p].K, tab[p].precision, act_group);
+        if (tab[p].wait_phase < 0) {
+            tab[p].img = reinterpret_cast<const uint4 *>(images + off);
+            tab[p].img_chunks = bytes / 1024;
+            off += (size_t)bytes;
+            ++count;
+        }
+        tab[p].img_lds = (p & 1) ? kStreamImageArea - bytes : 0;
+        tab[p].enter_barrier = p > 0 && prev_bytes + bytes > kStreamImageArea;
+        prev_bytes = bytes;
+    }
+    *nimages = count;
     return tab;
 }
 
@@ -229,6 +258,7 @@ struct nvq_plan {
     int nwg;           // workgroups of the streaming kernel, 0 = per-phase launches
     int nphase;        // entries of the device phase table
     int nwaits;        // phases that wait for an earlier phase (streaming kernel)
+    int nimages;       // phases whose activation image is prepared in the prologue
     uint32_t runs;     // walks issued so far (advances the flag base)
     unsigned long long *trace;  // device buffer for per-phase timestamps, or nullptr
 };
@@ -236,8 +266,9 @@ struct nvq_plan {
 extern "C" size_t nvq_decode_workspace_bytes(const nvq_linear *layers, int n, int M,
                                              int act_group) {
     int maxK = 0;
-    if (nvq::check_layers(layers, n, M, act_group, &maxK) != NVQ_OK) return 0;
-    return nvq::carve(nullptr, maxK, M, n).bytes;
+    size_t ib = 0;
+    if (nvq::check_layers(layers, n, M, act_group, &maxK, &ib) != NVQ_OK) return 0;
+    return nvq::carve(nullptr, maxK, M, n, ib).bytes;
 }
 
 extern "C" int nvq_plan_create(const nvq_linear *layers, int n, int M, int act_group, int flags,
@@ -247,10 +278,11 @@ extern "C" int nvq_plan_create(const nvq_linear *layers, int n, int M, int act_g
     if (!plan_out || (flags & ~NVQ_PLAN_ORDERED)) return NVQ_ERR_INVALID_ARG;
     *plan_out = nullptr;
     int maxK = 0;
-    const int rc = check_layers(layers, n, M, act_group, &maxK);
+    size_t ib = 0;
+    const int rc = check_layers(layers, n, M, act_group, &maxK, &ib);
     if (rc != NVQ_OK) return rc;
     if (!workspace || !aligned(workspace, 256)) return NVQ_ERR_WORKSPACE;
-    const Workspace ws = carve(workspace, maxK, M, n);
+    const Workspace ws = carve(workspace, maxK, M, n, ib);
     if (workspace_bytes < ws.bytes) return NVQ_ERR_WORKSPACE;
     nvq_plan *pl = new (std::nothrow) nvq_plan();
     if (!pl) return NVQ_ERR_UNSUPPORTED;
@@ -264,10 +296,13 @@ extern "C" int nvq_plan_create(const nvq_linear *layers, int n, int M, int act_g
     pl->nwg = 0;
     pl->nphase = 0;
     pl->nwaits = 0;
+    pl->nimages = 0;
     hipStream_t st = (hipStream_t)stream;
     const int nwg = n > 0 ? stream_grid_limit() : 0;
+    int nimages = 0;
     const std::vector<StreamPhase> tab =
-        stream_table(pl->layers.data(), pl->phases, M, nwg, (flags & NVQ_PLAN_ORDERED) != 0);
+        stream_table(pl->layers.data(), pl->phases, M, act_group, nwg,
+                     (flags & NVQ_PLAN_ORDERED) != 0, ws.images, &nimages);
     if (!tab.empty()) {
         // pageable source: the copy has left the host buffer when the call returns
         hipError_t e = hipMemcpyAsync(ws.tab, tab.data(), tab.size() * sizeof(StreamPhase),
@@ -284,6 +319,7 @@ extern "C" int nvq_plan_create(const nvq_linear *layers, int n, int M, int act_g
         }
         pl->nwg = nwg;
         pl->nphase = (int)tab.size();
+        pl->nimages = nimages;
         for (const StreamPhase &sp : tab) pl->nwaits += sp.wait_phase >= 0;
     }
     *plan_out = pl;
@@ -296,9 +332,9 @@ extern "C" int nvq_plan_run(nvq_plan *pl, void *stream) {
     hipStream_t st = (hipStream_t)stream;
     if (pl->layers.empty()) return NVQ_OK;
     if (pl->nwg > 0) {
-        const uint32_t base = pl->runs * (uint32_t)pl->nphase;
+        const uint32_t base = pl->runs * (uint32_t)(pl->nphase + 2);
         ++pl->runs;
-        return launch_decode_stream(pl->ws.tab, pl->nphase, pl->act_group, pl->ws.flags,
+        return launch_decode_stream(pl->ws.tab, pl->nphase, pl->nimages, pl->act_group, pl->ws.flags,
                                     pl->ws.status, base, pl->ws.dummy, pl->nwg, pl->trace, st);
     }
     return walk_per_phase(pl->layers.data(), pl->phases, pl->M, pl->act_group, pl->ws, st);
@@ -337,7 +373,8 @@ extern "C" int nvq_decode_linears(const nvq_linear *layers, int n, int M, int ac
                                   void *workspace, size_t workspace_bytes, void *stream) {
     if (n == 0) {
         int maxK = 0;
-        return nvq::check_layers(layers, n, M, act_group, &maxK);
+        size_t ib = 0;
+        return nvq::check_layers(layers, n, M, act_group, &maxK, &ib);
     }
     nvq_plan *pl = nullptr;
     int rc = nvq_plan_create(layers, n, M, act_group, NVQ_PLAN_DEFAULT, workspace, workspace_bytes,

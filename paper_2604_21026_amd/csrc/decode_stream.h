@@ -7,7 +7,9 @@ namespace nvq {
 
 constexpr int kStreamWaves = 8;  // waves per workgroup (two per SIMD)
 constexpr int kStreamThreads = kStreamWaves * 64;
-constexpr int kStreamMaxK = 14336;                       // widest input the LDS stage holds
+constexpr int kStreamMaxK = 14336;     // widest input an activation image holds
+constexpr int kStreamImageMax = 31744;  // largest image, padded to whole KiB (bf16, K = 14336)
+constexpr int kStreamImageArea = 49152; // LDS bytes for the images of two consecutive phases
 
 // One phase = up to four weight matrices that read the same input vector.
 // Lives in device memory; every field is read wave-uniformly.
@@ -24,21 +26,33 @@ struct StreamPhase {
     int rows_per_wave;     // ceil(total_rows / (workgroups * kStreamWaves))
     int wait_phase;        // latest earlier phase this one depends on, or -1
     int publish;           // 1 if a later phase depends on this one
-    int pad_;
+    int img_chunks;        // KiB chunks of the prepared image (0 if built in the kernel)
+    int img_lds;           // byte offset of the phase's image inside the LDS image area
+    int enter_barrier;     // 1: the image overlaps the previous phase's in LDS
+    const uint4 *img;      // prepared image in global memory, or nullptr
 };
 
 // Workgroups the streaming kernel may be launched with (all must be
 // co-resident): the number of compute units, or 0 if the kernel does not fit.
 int stream_grid_limit();
 
+// Bytes of the activation image of a layer with K inputs, padded to whole KiB.
+static inline int stream_image_bytes(int K, int precision, int act_group) {
+    const int G = K / 32;
+    const int raw = precision == NVQ_W4A8 ? 36 * G + (act_group == 32 ? 4 * G : 0) + 16 : 68 * G;
+    return (raw + 1023) / 1024 * 1024;
+}
+
 // Enqueue one walk.  `flags` holds one word per workgroup and `status` one
 // word (set to 1 if a wait timed out); both persist between runs of the same
-// table, with `flag_base` advanced by nphase per run.  `dummy` is any valid
+// table, with `flag_base` advanced by nphase + 2 per run (base + 1: images
+// ready, base + 2 + p: phase p published).  `nimages` = phases with a prepared
+// image (0 skips the prologue).  `dummy` is any valid
 // 1 KiB of device memory.  `trace` is nullptr or nphase * 8 words that
 // receive workgroup 0's per-phase timestamps.
-int launch_decode_stream(const StreamPhase *tab_dev, int nphase, int act_group, uint32_t *flags,
-                         uint32_t *status, uint32_t flag_base, const void *dummy, int nwg,
-                         unsigned long long *trace, hipStream_t st);
+int launch_decode_stream(const StreamPhase *tab_dev, int nphase, int nimages, int act_group,
+                         uint32_t *flags, uint32_t *status, uint32_t flag_base, const void *dummy,
+                         int nwg, unsigned long long *trace, hipStream_t st);
 
 // Timestamps written per phase when a trace buffer is given (see the kernel).
 constexpr int kStreamTraceSlots = 8;

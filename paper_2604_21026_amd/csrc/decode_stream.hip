@@ -11,8 +11,8 @@
 // Structure.  One workgroup of kStreamWaves waves per compute unit, all
 // co-resident.  Each wave owns a contiguous range of rows in every phase and
 // sees its work as one flat sequence of 1 KiB chunks across all phases:
-//   - per phase, first its share of the phase's input vector (512 bf16 values
-//     per chunk, chunks dealt round-robin to the waves of the workgroup),
+//   - per phase, first its share of the phase's activation image (chunks dealt
+//     round-robin to the waves of the workgroup),
 //   - then its weight rows (64 groups x 16 B of one row per chunk).
 // Chunks are fetched with non-temporal global->LDS loads into a per-wave ring
 // of kSlots slots and consumed in order; a slot is refilled as soon as its
@@ -22,12 +22,16 @@
 // chunk, so the number of loads in flight behind a chunk is a compile-time
 // constant and one `s_waitcnt vmcnt(n)` tells when it has landed.
 //
-// Per phase the workgroup prepares the input once: each wave takes its share
-// out of its ring, the waves agree on the absmax (W4A8), quantise or copy
-// their shares into an LDS buffer laid out in 16-byte planes, and store per
-// group the constant that the deferred offset correction needs.  Then every
-// wave walks its weight chunks; the lane's activations of a chunk's group
-// come from that LDS buffer.
+// Activations.  A phase's input is needed by every wave in a prepared form,
+// the "image": int8 codes (W4A8) or bf16 values (W4A16) laid out in planes of
+// G x 16 bytes, plus per group the constant of the deferred offset correction
+// (-8*sum(codes) or -136*sum(x)), plus the scale(s).  For a phase that depends
+// on no earlier phase the image is built ONCE per step, in global memory, by
+// one workgroup in a prologue (instead of once per compute unit), and then
+// travels through the rings like weights; two images fit in LDS, so a wave
+// that has finished its rows copies its share of the next image at once and
+// one barrier per phase remains.  A dependent phase builds its image in LDS
+// from the raw input after its wait.
 //
 // Ordering.  The host marks, per phase, the latest earlier phase whose
 // buffers it conflicts with.  Such a phase takes its input only after every
@@ -50,11 +54,11 @@ typedef const __attribute__((address_space(4))) StreamPhase CPhase;
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 
-constexpr int kSlots = 12;                 // ring slots per wave (1 KiB weights + 256 B scales)
+constexpr int kSlots = 11;                 // ring slots per wave (1 KiB weights + 256 B scales)
 constexpr int kOpsPerChunk = 2;            // scale load + weight load
-constexpr int kMaxG = kStreamMaxK / 32;    // 448 groups
 constexpr int kXChunkElems = 512;          // bf16 values per input chunk
 constexpr int kMaxXShare = (kStreamMaxK / kXChunkElems + kStreamWaves - 1) / kStreamWaves;  // 4
+constexpr int kMaxImgShare = (kStreamImageMax / 1024 + kStreamWaves - 1) / kStreamWaves;     // 4
 constexpr uint32_t kSpinLimit = 4u << 20;  // polls before a wait gives up (seconds)
 
 // s_waitcnt immediate that waits for vmcnt <= n only (gfx9 encoding:
@@ -64,9 +68,7 @@ constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0f70; }
 struct Shared {
     uint4 ring[kStreamWaves][kSlots][64];
     uint32_t sring[kStreamWaves][kSlots][64];  // one dword per lane: zero-extended fp16 scale
-    uint4 xbuf[kStreamMaxK * 2 / 16];  // the phase's activations in planes of G x 16 bytes
-    uint32_t xaux[kMaxG];              // per group: -8*sum(codes) (int) or -136*sum(x) (float)
-    float xsg[kMaxG];                  // per-group activation scales (act_group 32)
+    uint4 area[kStreamImageArea / 16];  // activation images of two consecutive phases
     float amax_part[kStreamWaves];
     int abort;
 };
@@ -150,16 +152,17 @@ __device__ __forceinline__ float quad_max(float v) {
 
 // ---- the issue side: where the wave's next chunk comes from -------------------
 // All fields are wave-uniform.  A run is a sequence of chunks at a constant
-// pointer stride: the wave's share of a phase's input, or consecutive weight
-// rows inside one matrix (a single row when K is no multiple of 2048).
+// pointer stride: the wave's share of a phase's activation image, or
+// consecutive weight rows inside one matrix (a single row when K is no
+// multiple of 2048).
 struct Issue {
     const uint4 *q;     // next chunk: 64 x 16 bytes
-    const uint16_t *s;  // its 64 scales (the dummy line for input chunks)
+    const uint16_t *s;  // its 64 scales (the dummy line for image chunks)
     int qstep, sstep;   // pointer advance per chunk, in elements
     int left;           // chunks left in the run
     int tail;           // valid lanes in the run's last chunk (64 = all)
     int p;              // phase of the run
-    int part;           // 0: input share issued next, 1: weight rows
+    int part;           // 0: image share issued next, 1: weight rows
     int row, row_stop;  // weight rows of phase p not yet turned into runs
 };
 
@@ -177,23 +180,18 @@ __device__ __forceinline__ void issue_next_run(Issue &c, CPhase *tab, int nphase
         }
         CPhase &ph = tab[c.p];
         if (c.part == 0) {
-            // the wave's share of the input vector: chunks w, w + waves, ...
             c.part = 1;
             c.row = gw * ph.rows_per_wave;
             const int stop = c.row + ph.rows_per_wave;
             c.row_stop = stop < ph.total_rows ? stop : ph.total_rows;
-            const int nxc = (ph.K + kXChunkElems - 1) / kXChunkElems;
-            if (w < nxc) {
-                const int n = (nxc - w + kStreamWaves - 1) / kStreamWaves;
-                const int last = w + (n - 1) * kStreamWaves;
-                const int tail = ph.K / 8 - last * 64;  // 16-byte pieces left for the last chunk
-                const bool ahead = ph.wait_phase < 0;   // else the input is read after the wait
-                c.q = ahead ? reinterpret_cast<const uint4 *>(ph.x) + w * 64 : dummy;
+            // the wave's share of the prepared image: chunks w, w + waves, ...
+            if (ph.img && w < ph.img_chunks) {
+                c.q = ph.img + w * 64;
                 c.s = reinterpret_cast<const uint16_t *>(dummy);
-                c.qstep = ahead ? kStreamWaves * 64 : 0;
+                c.qstep = kStreamWaves * 64;
                 c.sstep = 0;
-                c.left = n;
-                c.tail = ahead && tail < 64 ? tail : 64;
+                c.left = (ph.img_chunks - w + kStreamWaves - 1) / kStreamWaves;
+                c.tail = 64;  // images are padded to whole chunks
                 return;
             }
         }
@@ -294,6 +292,150 @@ __device__ __forceinline__ float dot_w4a16(const u32x4_t &w, const u32x4_t (&x)[
     return a0 + a1;
 }
 
+// ---- activation images ---------------------------------------------------------
+// Byte layout of an image (identical in global memory and in LDS):
+//   W4A8 : plane 0 (codes of elements 0..15 of each group, G x 16 B), plane 1
+//          (elements 16..31), aux[G] int32 = -8*sum(codes), then for per-group
+//          scales xsg[G] fp32, then the per-token scale (fp32, 16 B reserved);
+//   W4A16: planes 0..3 (elements 8q..8q+7 as bf16, G x 16 B each), aux[G] fp32
+//          = -136*sum(x).
+template <bool PER_GROUP>
+struct ImgLayout {
+    int aux, xsg, stok;  // byte offsets
+    __device__ __forceinline__ ImgLayout(bool w4a8, int G) {
+        aux = (w4a8 ? 32 : 64) * G;
+        xsg = aux + 4 * G;
+        stok = xsg + (PER_GROUP ? 4 * G : 0);
+    }
+};
+
+struct LdsWriter {
+    uint32_t base;
+    __device__ __forceinline__ void w4(int off, uint32_t v) const { lds_write4(base + off, v); }
+    __device__ __forceinline__ void w8(int off, uint32_t lo, uint32_t hi) const {
+        lds_write8(base + off, lo, hi);
+    }
+    __device__ __forceinline__ void w16(int off, const uint4 &v) const {
+        lds_write16(base + off, v);
+    }
+};
+struct GlobalWriter {
+    char *base;
+    __device__ __forceinline__ void w4(int off, uint32_t v) const {
+        *reinterpret_cast<uint32_t *>(base + off) = v;
+    }
+    __device__ __forceinline__ void w8(int off, uint32_t lo, uint32_t hi) const {
+        *reinterpret_cast<uint2 *>(base + off) = make_uint2(lo, hi);
+    }
+    __device__ __forceinline__ void w16(int off, const uint4 &v) const {
+        *reinterpret_cast<uint4 *>(base + off) = v;
+    }
+};
+
+__device__ __forceinline__ float chunk_absmax(const uint4 &v) {
+    const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
+    float a = 0.0f;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        a = fmaxf(a, fabsf(bf16_bits_to_float(wv[d] & 0xffffu)));
+        a = fmaxf(a, fabsf(bf16_bits_to_float(wv[d] >> 16)));
+    }
+    return a;
+}
+
+// One lane's eight consecutive bf16 values (a quarter of group g; the four
+// lanes of a group sit next to each other) go into the image.  Quantisation
+// follows the paper's appendix "F16 -> Q8 Activation Quantization":
+// q = round(x / s) clamped to [-127, 127], round half to even, IEEE division.
+template <bool PER_GROUP, class Writer>
+__device__ __forceinline__ void image_put(const Writer &wr, const ImgLayout<PER_GROUP> &L,
+                                          bool w4a8, int G, int g, int lane, const uint4 &raw,
+                                          float s_tok) {
+    const int quarter = lane & 3;
+    const bool valid = g < G;
+    const uint32_t wv[4] = {raw.x, raw.y, raw.z, raw.w};
+    if (w4a8) {
+        float s = s_tok;
+        if (PER_GROUP) {
+            s = quad_max(chunk_absmax(raw)) / 127.0f;
+            if (valid && quarter == 0) wr.w4(L.xsg + g * 4, __float_as_uint(s));
+        }
+        uint32_t out[2] = {0, 0};
+        int qsum = 0;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            int q0 = 0, q1 = 0;
+            if (s != 0.0f) {
+                const float r0 = rintf(bf16_bits_to_float(wv[d] & 0xffffu) / s);
+                const float r1 = rintf(bf16_bits_to_float(wv[d] >> 16) / s);
+                q0 = (int)fminf(fmaxf(r0, -127.0f), 127.0f);
+                q1 = (int)fminf(fmaxf(r1, -127.0f), 127.0f);
+            }
+            qsum += q0 + q1;
+            out[d >> 1] |= ((uint32_t)(q0 & 0xff) | ((uint32_t)(q1 & 0xff) << 8)) << (16 * (d & 1));
+        }
+        qsum = quad_sum(qsum);
+        if (valid) {
+            wr.w8((quarter >> 1) * (G * 16) + g * 16 + (quarter & 1) * 8, out[0], out[1]);
+            if (quarter == 0) wr.w4(L.aux + g * 4, (uint32_t)(-8 * qsum));
+        }
+    } else {
+        float part = 0.0f;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) part = dot2_bf16(0x3f803f80u, wv[d], part);
+        part = quad_sum(part);
+        if (valid) {
+            wr.w16(quarter * (G * 16) + g * 16, raw);
+            if (quarter == 0) wr.w4(L.aux + g * 4, __float_as_uint(-136.0f * part));
+        }
+    }
+}
+
+// Build the image of phase `ph` from its raw input, all waves of the workgroup
+// together: wave w handles the 512-value pieces w, w + waves, ...  The caller
+// guarantees that nobody still reads the destination and that sh.amax_part is
+// free; one barrier is used inside (absmax exchange, W4A8 per-token only).
+template <bool PER_GROUP, class Writer>
+__device__ __forceinline__ void image_build(const Writer &wr, CPhase &ph, Shared &sh, int w,
+                                            int lane) {
+    const bool w4a8 = ph.precision == NVQ_W4A8;
+    const int G = ph.G, K = ph.K;
+    const ImgLayout<PER_GROUP> L(w4a8, G);
+    const int nxc = (K + kXChunkElems - 1) / kXChunkElems;
+    const uint4 *x = reinterpret_cast<const uint4 *>(ph.x);
+    uint4 xsh[kMaxXShare];
+    float amax = 0.0f;
+#pragma unroll
+    for (int k = 0; k < kMaxXShare; ++k) {
+        const int j = w + k * kStreamWaves;
+        xsh[k] = make_uint4(0, 0, 0, 0);
+        if (j < nxc) {
+            if (j * 64 + lane < K / 8) xsh[k] = x[j * 64 + lane];
+            amax = fmaxf(amax, chunk_absmax(xsh[k]));
+        }
+    }
+    float s_tok = 0.0f;
+    if (w4a8 && !PER_GROUP) {
+        amax = wave_max_to_lane63(amax);
+        if (lane == 63) lds_write4(lds_addr(&sh.amax_part[w]), __float_as_uint(amax));
+        lds_barrier();
+        const uint4 a = lds_read16(lds_addr(&sh.amax_part[0]));
+        const uint4 b = lds_read16(lds_addr(&sh.amax_part[4]));
+        float m = fmaxf(fmaxf(__uint_as_float(a.x), __uint_as_float(a.y)),
+                        fmaxf(__uint_as_float(a.z), __uint_as_float(a.w)));
+        m = fmaxf(m, fmaxf(fmaxf(__uint_as_float(b.x), __uint_as_float(b.y)),
+                           fmaxf(__uint_as_float(b.z), __uint_as_float(b.w))));
+        s_tok = m / 127.0f;
+        if (w == 0 && lane == 0) wr.w4(L.stok, __float_as_uint(s_tok));
+    }
+#pragma unroll
+    for (int k = 0; k < kMaxXShare; ++k) {
+        const int j = w + k * kStreamWaves;
+        if (j < nxc)
+            image_put<PER_GROUP>(wr, L, w4a8, G, j * 16 + (lane >> 2), lane, xsh[k], s_tok);
+    }
+}
+
 // ---- per-wave stream state ---------------------------------------------------------
 struct Stream {
     Issue ic;
@@ -308,11 +450,35 @@ __device__ __forceinline__ void trace_mark(unsigned long long *trace, int wg, in
     if (trace && wg == 0 && w == 0 && lane == 0) trace[p * kTraceSlots + slot] = wall_clock64();
 }
 
+// Wave 0: spin until every workgroup's flag has reached `target`.
+__device__ __forceinline__ bool wait_flags(const uint32_t *flags, int nwg, uint32_t target,
+                                           int lane) {
+    uint32_t spins = 0;
+    for (;;) {
+        bool all = true;
+        for (int f0 = 0; f0 < nwg; f0 += 256) {  // four independent loads per lane
+            uint32_t v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int f = f0 + j * 64 + lane;
+                v[j] = f < nwg ? __hip_atomic_load(flags + f, __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_AGENT)
+                               : target;
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) all = all && (int32_t)(v[j] - target) >= 0;
+        }
+        if (__all(all)) return true;
+        if (++spins > kSpinLimit) return false;
+        __builtin_amdgcn_s_sleep(1);
+    }
+}
+
 template <bool PER_GROUP>
 __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
-    const StreamPhase *__restrict__ tab_generic, int nphase, uint32_t *__restrict__ flags,
-    uint32_t *__restrict__ status, uint32_t flag_base, const uint4 *__restrict__ dummy,
-    unsigned long long *__restrict__ trace) {
+    const StreamPhase *__restrict__ tab_generic, int nphase, int nimages,
+    uint32_t *__restrict__ flags, uint32_t *__restrict__ status, uint32_t flag_base,
+    const uint4 *__restrict__ dummy, unsigned long long *__restrict__ trace) {
     __shared__ Shared sh;
     CPhase *tab = (CPhase *)tab_generic;
     // wave index, made provably wave-uniform; wave 0 also talks to the other workgroups
@@ -322,12 +488,42 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
     const int nwg = gridDim.x;
     const int gw = wg * kStreamWaves + w;
     if (threadIdx.x == 0) lds_write4(lds_addr(&sh.abort), 0u);
+    trace_mark(trace, wg, w, lane, 0, 5);  // kernel entered
+
+    // ---- prologue: images of the phases that depend on no earlier phase, one
+    // ---- workgroup per phase; then everybody waits for everybody
+    if (nimages > 0) {
+        for (int p = wg; p < nphase; p += nwg) {
+            CPhase &ph = tab[p];
+            if (ph.img) {
+                const GlobalWriter wr = {reinterpret_cast<char *>(const_cast<uint4 *>(ph.img))};
+                image_build<PER_GROUP>(wr, ph, sh, w, lane);
+                lds_barrier();  // sh.amax_part may be reused
+            }
+        }
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // this wave's image stores have completed
+        lds_barrier();
+        bool ok = true;
+        if (w == 0) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+            if (lane == 0)
+                __hip_atomic_store(flags + wg, flag_base + 1u, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            ok = wait_flags(flags, nwg, flag_base + 1u, lane);
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+            if (!ok && lane == 0) {
+                lds_write4(lds_addr(&sh.abort), 1u);
+                __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        lds_barrier();
+        if (lds_read4(lds_addr(&sh.abort))) return;
+    }
+    trace_mark(trace, wg, w, lane, 0, 3);  // prologue done
 
     const uint32_t ring_base = lds_addr(&sh.ring[w][0][0]) + lane * 16;
     const uint32_t sring_base = lds_addr(&sh.sring[w][0][0]) + lane * 4;
-    const uint32_t xbuf_base = lds_addr(sh.xbuf);
-    const uint32_t xaux_base = lds_addr(sh.xaux);
-    const uint32_t xsg_base = lds_addr(sh.xsg);
+    const uint32_t area_base = lds_addr(sh.area);
 
     Stream st;
     st.ic.p = 0;
@@ -359,153 +555,49 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
     for (int p = 0; p < nphase; ++p) {
         CPhase &ph = tab[p];
         const int G = ph.G;
-        const int K = ph.K;
         const bool w4a8 = ph.precision == NVQ_W4A8;
+        const ImgLayout<PER_GROUP> L(w4a8, G);
+        const uint32_t img = area_base + (uint32_t)ph.img_lds;
         trace_mark(trace, wg, w, lane, p, 0);
 
         // ---- dependency: wait until every workgroup has published phase wait_phase ----
-        const bool dependent = ph.wait_phase >= 0;
-        if (dependent) {
+        if (ph.wait_phase >= 0) {
             if (w == 0) {
-                const uint32_t target = flag_base + (uint32_t)ph.wait_phase + 1u;
-                uint32_t spins = 0;
-                bool ok = true;
-                for (;;) {
-                    bool all = true;
-                    for (int f0 = 0; f0 < nwg; f0 += 256) {  // four independent loads per lane
-                        uint32_t v[4];
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const int f = f0 + j * 64 + lane;
-                            v[j] = f < nwg ? __hip_atomic_load(flags + f, __ATOMIC_RELAXED,
-                                                               __HIP_MEMORY_SCOPE_AGENT)
-                                           : target;
-                        }
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) all = all && (int32_t)(v[j] - target) >= 0;
-                    }
-                    if (__all(all)) break;
-                    if (++spins > kSpinLimit) {
-                        ok = false;
-                        break;
-                    }
-                    __builtin_amdgcn_s_sleep(1);
-                }
+                const bool ok =
+                    wait_flags(flags, nwg, flag_base + 2u + (uint32_t)ph.wait_phase, lane);
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
                 if (!ok && lane == 0) {
                     lds_write4(lds_addr(&sh.abort), 1u);
                     __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
             }
-            lds_barrier();  // the dependency is satisfied (or abort raised) for the whole workgroup
+            lds_barrier();  // satisfied (or abort raised) for the whole workgroup
             if (lds_read4(lds_addr(&sh.abort))) break;
+        } else if (ph.enter_barrier) {
+            lds_barrier();  // this image overlaps the previous one: everybody must have left it
         }
         trace_mark(trace, wg, w, lane, p, 1);
 
-        // ---- this wave's share of the input vector: chunks w, w + waves, ... -----------
-        const int nxc = (K + kXChunkElems - 1) / kXChunkElems;
-        uint4 xsh[kMaxXShare];
-        float amax = 0.0f;
+        // ---- the phase's activation image in LDS -----------------------------------------
+        if (ph.img) {
+            // prepared in the prologue: copy this wave's share out of its ring
 #pragma unroll
-        for (int k = 0; k < kMaxXShare; ++k) {
-            xsh[k] = make_uint4(0, 0, 0, 0);
-            const int j = w + k * kStreamWaves;  // chunk index (uniform)
-            if (j < nxc) {
-                uint32_t unused;
-                uint4 v = pop_chunk(unused);  // a dummy chunk when the phase is dependent
-                const bool valid = j * 64 + lane < K / 8;
-                if (dependent)
-                    v = valid ? reinterpret_cast<const uint4 *>(ph.x)[j * 64 + lane]
-                              : make_uint4(0, 0, 0, 0);
-                if (!valid) v = make_uint4(0, 0, 0, 0);
-                xsh[k] = v;
-                const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-                for (int d = 0; d < 4; ++d) {
-                    amax = fmaxf(amax, fabsf(bf16_bits_to_float(wv[d] & 0xffffu)));
-                    amax = fmaxf(amax, fabsf(bf16_bits_to_float(wv[d] >> 16)));
+            for (int k = 0; k < kMaxImgShare; ++k) {
+                const int j = w + k * kStreamWaves;
+                if (j < ph.img_chunks) {
+                    uint32_t unused;
+                    const uint4 v = pop_chunk(unused);
+                    lds_write16(img + j * 1024 + lane * 16, v);
                 }
             }
-        }
-        if (w4a8 && !PER_GROUP) {
-            amax = wave_max_to_lane63(amax);
-            if (lane == 63) lds_write4(lds_addr(&sh.amax_part[w]), __float_as_uint(amax));
+        } else {
+            // built here from the raw input (after the wait above, which also
+            // guarantees that every wave has left the previous phase)
+            const LdsWriter wr = {img};
+            image_build<PER_GROUP>(wr, ph, sh, w, lane);
         }
         trace_mark(trace, wg, w, lane, p, 2);
-        // B1: every wave has left the previous phase (the activation buffer is
-        // free) and, for W4A8, the partial maxima are visible
-        lds_barrier();
-        trace_mark(trace, wg, w, lane, p, 5);
-
-        float s_tok = 0.0f;
-        if (w4a8 && !PER_GROUP) {
-            const uint4 a = lds_read16(lds_addr(&sh.amax_part[0]));
-            const uint4 b = lds_read16(lds_addr(&sh.amax_part[4]));
-            float m = fmaxf(fmaxf(__uint_as_float(a.x), __uint_as_float(a.y)),
-                            fmaxf(__uint_as_float(a.z), __uint_as_float(a.w)));
-            m = fmaxf(m, fmaxf(fmaxf(__uint_as_float(b.x), __uint_as_float(b.y)),
-                               fmaxf(__uint_as_float(b.z), __uint_as_float(b.w))));
-            s_tok = m / 127.0f;
-        }
-        // Each lane holds 8 consecutive values = a quarter of group g; the four
-        // lanes of a group sit next to each other.
-        const int quarter = lane & 3;
-#pragma unroll
-        for (int k = 0; k < kMaxXShare; ++k) {
-            const int j = w + k * kStreamWaves;
-            if (j < nxc) {
-                const int g = j * 16 + (lane >> 2);
-                const bool valid = g < G;
-                const uint32_t wv[4] = {xsh[k].x, xsh[k].y, xsh[k].z, xsh[k].w};
-                if (w4a8) {
-                    float s = s_tok;
-                    if (PER_GROUP) {
-                        float a = 0.0f;
-#pragma unroll
-                        for (int d = 0; d < 4; ++d) {
-                            a = fmaxf(a, fabsf(bf16_bits_to_float(wv[d] & 0xffffu)));
-                            a = fmaxf(a, fabsf(bf16_bits_to_float(wv[d] >> 16)));
-                        }
-                        s = quad_max(a) / 127.0f;
-                        if (valid && quarter == 0) lds_write4(xsg_base + g * 4, __float_as_uint(s));
-                    }
-                    uint32_t out[2] = {0, 0};
-                    int qsum = 0;
-#pragma unroll
-                    for (int d = 0; d < 4; ++d) {
-                        int q0 = 0, q1 = 0;
-                        if (s != 0.0f) {
-                            const float r0 = rintf(bf16_bits_to_float(wv[d] & 0xffffu) / s);
-                            const float r1 = rintf(bf16_bits_to_float(wv[d] >> 16) / s);
-                            q0 = (int)fminf(fmaxf(r0, -127.0f), 127.0f);
-                            q1 = (int)fminf(fmaxf(r1, -127.0f), 127.0f);
-                        }
-                        qsum += q0 + q1;
-                        out[d >> 1] |= ((uint32_t)(q0 & 0xff) | ((uint32_t)(q1 & 0xff) << 8))
-                                       << (16 * (d & 1));
-                    }
-                    qsum = quad_sum(qsum);
-                    if (valid) {
-                        // codes of elements 0..15 in plane 0, 16..31 in plane 1
-                        lds_write8(xbuf_base + (quarter >> 1) * (G * 16) + g * 16 + (quarter & 1) * 8,
-                                   out[0], out[1]);
-                        if (quarter == 0) lds_write4(xaux_base + g * 4, (uint32_t)(-8 * qsum));
-                    }
-                } else {
-                    float part = 0.0f;
-#pragma unroll
-                    for (int d = 0; d < 4; ++d) part = dot2_bf16(0x3f803f80u, wv[d], part);
-                    part = quad_sum(part);
-                    if (valid) {
-                        // elements 8q..8q+7 in plane q
-                        lds_write16(xbuf_base + quarter * (G * 16) + g * 16, xsh[k]);
-                        if (quarter == 0)
-                            lds_write4(xaux_base + g * 4, __float_as_uint(-136.0f * part));
-                    }
-                }
-            }
-        }
-        lds_barrier();  // B2: the activations of the phase are in place
+        lds_barrier();  // the image is complete
         trace_mark(trace, wg, w, lane, p, 6);
 
         // ---- this wave's weight rows ---------------------------------------------------
@@ -514,7 +606,8 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
         int r1 = r0 + ph.rows_per_wave;
         r1 = r1 < ph.total_rows ? r1 : ph.total_rows;
         const int nchunks = r1 > r0 ? (r1 - r0) * gpl : 0;
-        const float xs = (w4a8 && !PER_GROUP) ? s_tok : 1.0f;
+        const float xs =
+            (w4a8 && !PER_GROUP) ? __uint_as_float(lds_read4(img + L.stok)) : 1.0f;
         const uint32_t plane = (uint32_t)G * 16u;
         int i = 0;        // chunk position inside the row
         int row = r0;
@@ -524,8 +617,8 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
             // the lane's group of this chunk and its activations
             const int g = i * 64 + lane;
             const bool ok = g < G;
-            const uint32_t ga = xbuf_base + (ok ? g : 0) * 16;
-            const uint32_t aux_a = xaux_base + (ok ? g : 0) * 4;
+            const uint32_t ga = img + (ok ? g : 0) * 16;
+            const uint32_t aux_a = img + L.aux + (ok ? g : 0) * 4;
             u32x4_t xa, xb, xc = {0, 0, 0, 0}, xd = {0, 0, 0, 0};
             uint32_t aux, sgbits = 0;
             if (w4a8) {
@@ -536,7 +629,7 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
                 if (PER_GROUP)
                     asm volatile("ds_read_b32 %0, %1"
                                  : "=&v"(sgbits)
-                                 : "v"(xsg_base + (ok ? g : 0) * 4)
+                                 : "v"(img + L.xsg + (ok ? g : 0) * 4)
                                  : "memory");
             } else {
                 asm volatile("ds_read_b128 %0, %5\n\tds_read_b128 %1, %6\n\tds_read_b128 %2, %7\n\t"
@@ -599,7 +692,7 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
                 trace_mark(trace, wg, w, lane, p, 3);
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
                 if (lane == 0)
-                    __hip_atomic_store(flags + wg, flag_base + (uint32_t)p + 1u, __ATOMIC_RELAXED,
+                    __hip_atomic_store(flags + wg, flag_base + 2u + (uint32_t)p, __ATOMIC_RELAXED,
                                        __HIP_MEMORY_SCOPE_AGENT);
                 trace_mark(trace, wg, w, lane, p, 4);
             }
@@ -622,16 +715,17 @@ int stream_grid_limit() {
     return cached;
 }
 
-int launch_decode_stream(const StreamPhase *tab_dev, int nphase, int act_group, uint32_t *flags,
-                         uint32_t *status, uint32_t flag_base, const void *dummy, int nwg,
-                         unsigned long long *trace, hipStream_t st) {
+int launch_decode_stream(const StreamPhase *tab_dev, int nphase, int nimages, int act_group,
+                         uint32_t *flags, uint32_t *status, uint32_t flag_base, const void *dummy,
+                         int nwg, unsigned long long *trace, hipStream_t st) {
     const dim3 grid(nwg), block(kStreamThreads);
     if (act_group == 32)
-        hipLaunchKernelGGL(decode_stream_kernel<true>, grid, block, 0, st, tab_dev, nphase, flags,
-                           status, flag_base, reinterpret_cast<const uint4 *>(dummy), trace);
+        hipLaunchKernelGGL(decode_stream_kernel<true>, grid, block, 0, st, tab_dev, nphase, nimages,
+                           flags, status, flag_base, reinterpret_cast<const uint4 *>(dummy), trace);
     else
-        hipLaunchKernelGGL(decode_stream_kernel<false>, grid, block, 0, st, tab_dev, nphase, flags,
-                           status, flag_base, reinterpret_cast<const uint4 *>(dummy), trace);
+        hipLaunchKernelGGL(decode_stream_kernel<false>, grid, block, 0, st, tab_dev, nphase,
+                           nimages, flags, status, flag_base,
+                           reinterpret_cast<const uint4 *>(dummy), trace);
     NVQ_HIP_TRY(hipGetLastError());
     return NVQ_OK;
 }
