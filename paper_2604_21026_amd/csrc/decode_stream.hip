@@ -8,12 +8,10 @@
 // depend on activations, every wave keeps fetching the weights of the coming
 // phases while the current phase is being set up.
 //
-// Structure.  One workgroup of kStreamWaves waves per compute unit, all
-// co-resident.  Each wave owns a contiguous range of rows in every phase and
-// sees its work as one flat sequence of 1 KiB chunks across all phases:
-//   - per phase, first its share of the phase's activation image (chunks dealt
-//     round-robin to the waves of the workgroup),
-//   - then its weight rows (64 groups x 16 B of one row per chunk).
+// Structure.  One workgroup per compute unit, all co-resident: kStreamWaves
+// streaming waves and one loader wave.  Each streaming wave owns a contiguous
+// range of rows in every phase and sees its work as one flat sequence of
+// 1 KiB chunks (64 groups x 16 B of one weight row) across all phases.
 // Chunks are fetched with non-temporal global->LDS loads into a per-wave ring
 // of kSlots slots and consumed in order; a slot is refilled as soon as its
 // chunk has been taken out, independent of phase boundaries.  The fp16 scales
@@ -27,11 +25,14 @@
 // G x 16 bytes, plus per group the constant of the deferred offset correction
 // (-8*sum(codes) or -136*sum(x)), plus the scale(s).  For a phase that depends
 // on no earlier phase the image is built ONCE per step, in global memory, by
-// one workgroup in a prologue (instead of once per compute unit), and then
-// travels through the rings like weights; two images fit in LDS, so a wave
-// that has finished its rows copies its share of the next image at once and
-// one barrier per phase remains.  A dependent phase builds its image in LDS
-// from the raw input after its wait.
+// one workgroup in a prologue (instead of once per compute unit).  The loader
+// wave copies images from there into LDS one phase ahead (two images fit) and
+// announces them through an LDS word; streaming waves report the phases they
+// have finished through one LDS word each, which tells the loader when an
+// image may be overwritten.  On this path the streaming waves never meet at a
+// barrier, so they may drift up to a phase apart and absorb each other's
+// jitter.  A dependent phase builds its image in LDS from the raw input after
+// its wait, all streaming waves together, with workgroup barriers.
 //
 // Ordering.  The host marks, per phase, the latest earlier phase whose
 // buffers it conflicts with.  Such a phase takes its input only after every
@@ -58,7 +59,7 @@ constexpr int kSlots = 11;                 // ring slots per wave (1 KiB weights
 constexpr int kOpsPerChunk = 2;            // scale load + weight load
 constexpr int kXChunkElems = 512;          // bf16 values per input chunk
 constexpr int kMaxXShare = (kStreamMaxK / kXChunkElems + kStreamWaves - 1) / kStreamWaves;  // 4
-constexpr int kMaxImgShare = (kStreamImageMax / 1024 + kStreamWaves - 1) / kStreamWaves;     // 4
+
 constexpr uint32_t kSpinLimit = 4u << 20;  // polls before a wait gives up (seconds)
 
 // s_waitcnt immediate that waits for vmcnt <= n only (gfx9 encoding:
@@ -70,6 +71,8 @@ struct Shared {
     uint32_t sring[kStreamWaves][kSlots][64];  // one dword per lane: zero-extended fp16 scale
     uint4 area[kStreamImageArea / 16];  // activation images of two consecutive phases
     float amax_part[kStreamWaves];
+    uint32_t progress[kStreamWaves];  // phases finished by each streaming wave
+    uint32_t img_ready;               // images of phases < img_ready are in LDS
     int abort;
 };
 
@@ -94,6 +97,13 @@ __device__ __forceinline__ uint32_t lds_read4(uint32_t addr) {
     uint32_t v;
     asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(addr) : "memory");
     return v;
+}
+// an LDS word that every lane reads from the same address, as a scalar: the
+// compiler cannot see through the instruction, and control flow that depended
+// on a per-lane value would push the wave-uniform stream state into vector
+// registers
+__device__ __forceinline__ uint32_t lds_read4_uniform(uint32_t addr) {
+    return (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_read4(addr));
 }
 __device__ __forceinline__ void lds_write4(uint32_t addr, uint32_t v) {
     asm volatile("ds_write_b32 %0, %1" : : "v"(addr), "v"(v) : "memory");
@@ -152,17 +162,16 @@ __device__ __forceinline__ float quad_max(float v) {
 
 // ---- the issue side: where the wave's next chunk comes from -------------------
 // All fields are wave-uniform.  A run is a sequence of chunks at a constant
-// pointer stride: the wave's share of a phase's activation image, or
-// consecutive weight rows inside one matrix (a single row when K is no
-// multiple of 2048).
+// pointer stride: consecutive weight rows inside one matrix (a single row
+// when K is no multiple of 2048).
 struct Issue {
     const uint4 *q;     // next chunk: 64 x 16 bytes
-    const uint16_t *s;  // its 64 scales (the dummy line for image chunks)
+    const uint16_t *s;  // its 64 scales
     int qstep, sstep;   // pointer advance per chunk, in elements
     int left;           // chunks left in the run
     int tail;           // valid lanes in the run's last chunk (64 = all)
     int p;              // phase of the run
-    int part;           // 0: image share issued next, 1: weight rows
+    int part;           // 0: row range of phase p not yet set up
     int row, row_stop;  // weight rows of phase p not yet turned into runs
 };
 
@@ -184,16 +193,6 @@ __device__ __forceinline__ void issue_next_run(Issue &c, CPhase *tab, int nphase
             c.row = gw * ph.rows_per_wave;
             const int stop = c.row + ph.rows_per_wave;
             c.row_stop = stop < ph.total_rows ? stop : ph.total_rows;
-            // the wave's share of the prepared image: chunks w, w + waves, ...
-            if (ph.img && w < ph.img_chunks) {
-                c.q = ph.img + w * 64;
-                c.s = reinterpret_cast<const uint16_t *>(dummy);
-                c.qstep = kStreamWaves * 64;
-                c.sstep = 0;
-                c.left = (ph.img_chunks - w + kStreamWaves - 1) / kStreamWaves;
-                c.tail = 64;  // images are padded to whole chunks
-                return;
-            }
         }
         if (c.row < c.row_stop) {
             int first = 0, end = ph.row_end[0];
@@ -398,6 +397,10 @@ __device__ __forceinline__ void image_put(const Writer &wr, const ImgLayout<PER_
 template <bool PER_GROUP, class Writer>
 __device__ __forceinline__ void image_build(const Writer &wr, CPhase &ph, Shared &sh, int w,
                                             int lane) {
+    if (w >= kStreamWaves) {  // the loader wave only keeps the barrier count
+        if (ph.precision == NVQ_W4A8 && !PER_GROUP) lds_barrier();
+        return;
+    }
     const bool w4a8 = ph.precision == NVQ_W4A8;
     const int G = ph.G, K = ph.K;
     const ImgLayout<PER_GROUP> L(w4a8, G);
@@ -517,13 +520,78 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
             }
         }
         lds_barrier();
-        if (lds_read4(lds_addr(&sh.abort))) return;
+        if (lds_read4_uniform(lds_addr(&sh.abort))) return;
     }
     trace_mark(trace, wg, w, lane, 0, 3);  // prologue done
+    const uint32_t area_base = lds_addr(sh.area);
+    const uint32_t progress_a = lds_addr(&sh.progress[0]);
+    const uint32_t ready_a = lds_addr(&sh.img_ready);
+    const uint32_t abort_a = lds_addr(&sh.abort);
+    if (threadIdx.x < kStreamWaves) lds_write4(progress_a + threadIdx.x * 4, 0u);
+    if (threadIdx.x == 0) lds_write4(ready_a, 0u);
+    lds_barrier();
 
+    if (w == kStreamWaves) {
+        // ================= loader wave =================
+        // Copies prepared images into LDS ahead of the streaming waves and
+        // mirrors every workgroup barrier they execute.
+        int q = 0;  // first phase whose image has not been dealt with
+        // Load the images of independent phases up to `limit`.  Returns false on abort.
+        auto prefetch = [&](int limit) -> bool {
+            while (q <= limit && q < nphase && tab[q].wait_phase < 0) {
+                CPhase &pq = tab[q];
+                // the LDS region is free once every wave has finished phase `need - 1`
+                const uint32_t need = (uint32_t)(pq.enter_barrier ? q : (q > 0 ? q - 1 : 0));
+                uint32_t spins = 0;
+                for (;;) {
+                    const uint4 a = lds_read16(progress_a), b = lds_read16(progress_a + 16);
+                    uint32_t m = a.x < a.y ? a.x : a.y;
+                    m = m < a.z ? m : a.z;
+                    m = m < a.w ? m : a.w;
+                    m = m < b.x ? m : b.x;
+                    m = m < b.y ? m : b.y;
+                    m = m < b.z ? m : b.z;
+                    m = m < b.w ? m : b.w;
+                    if ((uint32_t)__builtin_amdgcn_readfirstlane((int)m) >= need) break;
+                    if (lds_read4_uniform(abort_a)) return false;
+                    if (++spins > kSpinLimit) {
+                        lds_write4(abort_a, 1u);
+                        return false;
+                    }
+                    __builtin_amdgcn_s_sleep(4);
+                }
+                const uint32_t dst = (uint32_t)pq.img_lds;
+                for (int j = 0; j < pq.img_chunks; ++j)
+                    __builtin_amdgcn_global_load_lds(
+                        (const void *)(pq.img + j * 64 + lane),
+                        (lds_void_ptr)(reinterpret_cast<char *>(sh.area) + dst + j * 1024), 16, 0, 0);
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+                ++q;
+                if (lane == 0) lds_write4(ready_a, (uint32_t)q);
+            }
+            return true;
+        };
+        for (int p = 0; p < nphase; ++p) {
+            CPhase &ph = tab[p];
+            if (ph.wait_phase >= 0) {
+                lds_barrier();  // dependency satisfied
+                if (lds_read4_uniform(abort_a)) break;
+                const LdsWriter wr = {0};
+                image_build<PER_GROUP>(wr, ph, sh, w, lane);  // barrier count only
+                lds_barrier();  // image complete
+                q = p + 1;
+            } else if (!prefetch(p)) {
+                break;
+            }
+            if (!prefetch(p + 1)) break;
+            if (ph.publish) lds_barrier();
+        }
+        return;
+    }
+
+    // ================= streaming waves =================
     const uint32_t ring_base = lds_addr(&sh.ring[w][0][0]) + lane * 16;
     const uint32_t sring_base = lds_addr(&sh.sring[w][0][0]) + lane * 4;
-    const uint32_t area_base = lds_addr(sh.area);
 
     Stream st;
     st.ic.p = 0;
@@ -552,7 +620,8 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
         return make_uint4(v.x, v.y, v.z, v.w);
     };
 
-    for (int p = 0; p < nphase; ++p) {
+    bool aborted = false;
+    for (int p = 0; p < nphase && !aborted; ++p) {
         CPhase &ph = tab[p];
         const int G = ph.G;
         const bool w4a8 = ph.precision == NVQ_W4A8;
@@ -560,44 +629,45 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
         const uint32_t img = area_base + (uint32_t)ph.img_lds;
         trace_mark(trace, wg, w, lane, p, 0);
 
-        // ---- dependency: wait until every workgroup has published phase wait_phase ----
         if (ph.wait_phase >= 0) {
+            // ---- dependent phase: wait until every workgroup has published phase
+            // ---- wait_phase, then build the image from the raw input, all together
             if (w == 0) {
                 const bool ok =
                     wait_flags(flags, nwg, flag_base + 2u + (uint32_t)ph.wait_phase, lane);
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
                 if (!ok && lane == 0) {
-                    lds_write4(lds_addr(&sh.abort), 1u);
+                    lds_write4(abort_a, 1u);
                     __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
             }
-            lds_barrier();  // satisfied (or abort raised) for the whole workgroup
-            if (lds_read4(lds_addr(&sh.abort))) break;
-        } else if (ph.enter_barrier) {
-            lds_barrier();  // this image overlaps the previous one: everybody must have left it
-        }
-        trace_mark(trace, wg, w, lane, p, 1);
-
-        // ---- the phase's activation image in LDS -----------------------------------------
-        if (ph.img) {
-            // prepared in the prologue: copy this wave's share out of its ring
-#pragma unroll
-            for (int k = 0; k < kMaxImgShare; ++k) {
-                const int j = w + k * kStreamWaves;
-                if (j < ph.img_chunks) {
-                    uint32_t unused;
-                    const uint4 v = pop_chunk(unused);
-                    lds_write16(img + j * 1024 + lane * 16, v);
-                }
-            }
-        } else {
-            // built here from the raw input (after the wait above, which also
-            // guarantees that every wave has left the previous phase)
+            lds_barrier();  // satisfied (or abort raised); every wave has left the previous phase
+            if (lds_read4_uniform(abort_a)) break;
+            trace_mark(trace, wg, w, lane, p, 1);
             const LdsWriter wr = {img};
             image_build<PER_GROUP>(wr, ph, sh, w, lane);
+            trace_mark(trace, wg, w, lane, p, 2);
+            lds_barrier();  // the image is complete
+        } else {
+            // ---- independent phase: the loader wave announces the image
+            trace_mark(trace, wg, w, lane, p, 1);
+            uint32_t spins = 0;
+            while (lds_read4_uniform(ready_a) < (uint32_t)(p + 1)) {
+                if (lds_read4_uniform(abort_a) || ++spins > kSpinLimit) {
+                    aborted = true;
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(1);
+            }
+            if (aborted) {
+                if (lane == 0) {
+                    lds_write4(abort_a, 1u);
+                    __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+                break;
+            }
+            trace_mark(trace, wg, w, lane, p, 2);
         }
-        trace_mark(trace, wg, w, lane, p, 2);
-        lds_barrier();  // the image is complete
         trace_mark(trace, wg, w, lane, p, 6);
 
         // ---- this wave's weight rows ---------------------------------------------------
@@ -681,6 +751,8 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
                 ++row;
             }
         }
+        // this wave no longer reads the phase's image
+        if (lane == 0) lds_write4(progress_a + w * 4, (uint32_t)(p + 1));
         trace_mark(trace, wg, w, lane, p, 7);
 
         if (ph.publish) {
