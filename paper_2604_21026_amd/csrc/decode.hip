@@ -220,11 +220,17 @@ std::vector<StreamPhase> stream_table(const nvq_linear *L, const std::vector<Pha
         if (dep >= 0) tab[dep].publish = 1;
     }
     // Activation images.  A phase that waits for nothing gets its image
-    // prepared in global memory; in LDS, even phases sit at the bottom of the
-    // image area and odd phases at the top, so consecutive images do not
-    // overlap unless they are too large together.
+    // prepared in global memory.  In LDS the images of consecutive phases are
+    // laid out one after the other in a circular area; img_need names the
+    // latest phase whose image a new one overwrites (every wave must have
+    // finished that phase before the new image may be loaded).
     size_t off = 0;
-    int count = 0, prev_bytes = 0;
+    int count = 0;
+    struct Live {
+        int phase, lo, hi;
+    };
+    std::vector<Live> live;
+    int cursor = 0;
     for (size_t p = 0; p < P; ++p) {
         const int bytes = stream_image_bytes(tab[p].K, tab[p].precision, act_group);
         if (tab[p].wait_phase < 0) {
@@ -233,9 +239,20 @@ std::vector<StreamPhase> stream_table(const nvq_linear *L, const std::vector<Pha
             off += (size_t)bytes;
             ++count;
         }
-        tab[p].img_lds = (p & 1) ? kStreamImageArea - bytes : 0;
-        tab[p].enter_barrier = p > 0 && prev_bytes + bytes > kStreamImageArea;
-        prev_bytes = bytes;
+        if (cursor + bytes > kStreamImageArea) cursor = 0;
+        int need = -1;
+        std::vector<Live> keep;
+        for (const Live &l : live) {
+            if (l.lo < cursor + bytes && cursor < l.hi)
+                need = l.phase > need ? l.phase : need;
+            else
+                keep.push_back(l);
+        }
+        live.swap(keep);
+        live.push_back({(int)p, cursor, cursor + bytes});
+        tab[p].img_lds = cursor;
+        tab[p].img_need = need;
+        cursor += bytes;
     }
     *nimages = count;
     return tab;

@@ -9,7 +9,7 @@ constexpr int kStreamWaves = 8;  // streaming waves per workgroup (two per SIMD)
 constexpr int kStreamThreads = (kStreamWaves + 1) * 64;  // plus the loader wave
 constexpr int kStreamMaxK = 14336;     // widest input an activation image holds
 constexpr int kStreamImageMax = 31744;  // largest image, padded to whole KiB (bf16, K = 14336)
-constexpr int kStreamImageArea = 49152; // LDS bytes for the images of two consecutive phases
+constexpr int kStreamImageArea = 59392; // LDS bytes that hold the images of consecutive phases
 
 // One phase = up to four weight matrices that read the same input vector.
 // Lives in device memory; every field is read wave-uniformly.
@@ -28,7 +28,7 @@ struct StreamPhase {
     int publish;           // 1 if a later phase depends on this one
     int img_chunks;        // KiB chunks of the prepared image (0 if built in the kernel)
     int img_lds;           // byte offset of the phase's image inside the LDS image area
-    int enter_barrier;     // 1: the image overlaps the previous phase's in LDS
+    int img_need;          // latest phase whose image this one overwrites in LDS, or -1
     const uint4 *img;      // prepared image in global memory, or nullptr
 };
 

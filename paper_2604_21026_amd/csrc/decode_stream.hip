@@ -55,12 +55,13 @@ typedef const __attribute__((address_space(4))) StreamPhase CPhase;
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 
-constexpr int kSlots = 11;                 // ring slots per wave (1 KiB weights + 256 B scales)
+constexpr int kSlots = 10;                 // ring slots per wave (1 KiB weights + 256 B scales)
 constexpr int kOpsPerChunk = 2;            // scale load + weight load
 constexpr int kXChunkElems = 512;          // bf16 values per input chunk
 constexpr int kMaxXShare = (kStreamMaxK / kXChunkElems + kStreamWaves - 1) / kStreamWaves;  // 4
 
 constexpr uint32_t kSpinLimit = 4u << 20;  // polls before a wait gives up (seconds)
+constexpr int kLookahead = 3;              // phases the loader wave may run ahead
 
 // s_waitcnt immediate that waits for vmcnt <= n only (gfx9 encoding:
 // vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] at [15:14]).
@@ -69,7 +70,7 @@ constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0f70; }
 struct Shared {
     uint4 ring[kStreamWaves][kSlots][64];
     uint32_t sring[kStreamWaves][kSlots][64];  // one dword per lane: zero-extended fp16 scale
-    uint4 area[kStreamImageArea / 16];  // activation images of two consecutive phases
+    uint4 area[kStreamImageArea / 16];  // activation images of consecutive phases (circular)
     float amax_part[kStreamWaves];
     uint32_t progress[kStreamWaves];  // phases finished by each streaming wave
     uint32_t img_ready;               // images of phases < img_ready are in LDS
@@ -536,42 +537,41 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
         // Copies prepared images into LDS ahead of the streaming waves and
         // mirrors every workgroup barrier they execute.
         int q = 0;  // first phase whose image has not been dealt with
-        // Load the images of independent phases up to `limit`.  Returns false on abort.
-        auto prefetch = [&](int limit) -> bool {
-            while (q <= limit && q < nphase && tab[q].wait_phase < 0) {
-                CPhase &pq = tab[q];
-                // the LDS region is free once every wave has finished phase `need - 1`
-                const uint32_t need = (uint32_t)(pq.enter_barrier ? q : (q > 0 ? q - 1 : 0));
-                uint32_t spins = 0;
-                for (;;) {
-                    const uint4 a = lds_read16(progress_a), b = lds_read16(progress_a + 16);
-                    uint32_t m = a.x < a.y ? a.x : a.y;
-                    m = m < a.z ? m : a.z;
-                    m = m < a.w ? m : a.w;
-                    m = m < b.x ? m : b.x;
-                    m = m < b.y ? m : b.y;
-                    m = m < b.z ? m : b.z;
-                    m = m < b.w ? m : b.w;
-                    if ((uint32_t)__builtin_amdgcn_readfirstlane((int)m) >= need) break;
-                    if (lds_read4_uniform(abort_a)) return false;
-                    if (++spins > kSpinLimit) {
-                        lds_write4(abort_a, 1u);
-                        return false;
-                    }
-                    __builtin_amdgcn_s_sleep(4);
+        // Load the image of independent phase q (blocks until its LDS region is
+        // free: every wave has finished phase img_need).  False on abort.
+        auto load_image = [&]() -> bool {
+            CPhase &pq = tab[q];
+            const uint32_t need = (uint32_t)(pq.img_need + 1);
+            uint32_t spins = 0;
+            for (;;) {
+                const uint4 a = lds_read16(progress_a), b = lds_read16(progress_a + 16);
+                uint32_t m = a.x < a.y ? a.x : a.y;
+                m = m < a.z ? m : a.z;
+                m = m < a.w ? m : a.w;
+                m = m < b.x ? m : b.x;
+                m = m < b.y ? m : b.y;
+                m = m < b.z ? m : b.z;
+                m = m < b.w ? m : b.w;
+                if ((uint32_t)__builtin_amdgcn_readfirstlane((int)m) >= need) break;
+                if (lds_read4_uniform(abort_a)) return false;
+                if (++spins > kSpinLimit) {
+                    lds_write4(abort_a, 1u);
+                    return false;
                 }
-                const uint32_t dst = (uint32_t)pq.img_lds;
-                for (int j = 0; j < pq.img_chunks; ++j)
-                    __builtin_amdgcn_global_load_lds(
-                        (const void *)(pq.img + j * 64 + lane),
-                        (lds_void_ptr)(reinterpret_cast<char *>(sh.area) + dst + j * 1024), 16, 0, 0);
-                __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-                ++q;
-                if (lane == 0) lds_write4(ready_a, (uint32_t)q);
+                __builtin_amdgcn_s_sleep(2);
             }
+            const uint32_t dst = (uint32_t)pq.img_lds;
+            for (int j = 0; j < pq.img_chunks; ++j)
+                __builtin_amdgcn_global_load_lds(
+                    (const void *)(pq.img + j * 64 + lane),
+                    (lds_void_ptr)(reinterpret_cast<char *>(sh.area) + dst + j * 1024), 16, 0, 0);
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+            ++q;
+            if (lane == 0) lds_write4(ready_a, (uint32_t)q);
             return true;
         };
-        for (int p = 0; p < nphase; ++p) {
+        bool live = true;
+        for (int p = 0; p < nphase && live; ++p) {
             CPhase &ph = tab[p];
             if (ph.wait_phase >= 0) {
                 lds_barrier();  // dependency satisfied
@@ -580,11 +580,14 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
                 image_build<PER_GROUP>(wr, ph, sh, w, lane);  // barrier count only
                 lds_barrier();  // image complete
                 q = p + 1;
-            } else if (!prefetch(p)) {
-                break;
             }
-            if (!prefetch(p + 1)) break;
-            if (ph.publish) lds_barrier();
+            // Run ahead of the streaming waves.  Only regions that free up
+            // without a barrier of phase p or later may be waited for here:
+            // the streaming waves may need this wave at such a barrier first.
+            while (live && q < nphase && q <= p + kLookahead && tab[q].wait_phase < 0 &&
+                   tab[q].img_need < p)
+                live = load_image();
+            if (ph.publish && live) lds_barrier();
         }
         return;
     }
@@ -669,6 +672,14 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
             trace_mark(trace, wg, w, lane, p, 2);
         }
         trace_mark(trace, wg, w, lane, p, 6);
+        // Two streaming waves share a SIMD and the hardware favours the older
+        // one whenever both can issue, which lets it refill its ring sooner and
+        // leaves the younger one a phase or two behind.  Alternating the wave
+        // priority from phase to phase evens this out.
+        if (((w >> 2) ^ p) & 1)
+            __builtin_amdgcn_s_setprio(2);
+        else
+            __builtin_amdgcn_s_setprio(0);
 
         // ---- this wave's weight rows ---------------------------------------------------
         const int gpl = ph.gpl;
