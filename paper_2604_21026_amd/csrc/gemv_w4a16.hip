@@ -13,7 +13,9 @@
 // fp32; only the order of fp32 additions differs from a wide reference.
 //
 // Batch 1 (fast path): decomposition as in gemv_tile.h with the lane's bf16
-// activations register-resident (16 dwords per owned group).
+// activations register-resident (16 dwords per owned group).  Two to 32
+// tokens go to the matrix-core kernel (gemv_mfma.hip), other cases to the
+// generic kernel.
 #include "gemv_tile.h"
 
 namespace nvq {
@@ -202,6 +204,7 @@ int launch_gemv_w4a16(const GemvSegs &S, int K, const uint16_t *x, int M, hipStr
             default: return launch_m1<8, 64>(S, G, x, st);
         }
     }
+    if (gemv_mfma_supported(S, K, M)) return launch_gemv_mfma(S, K, NVQ_W4A16, x, nullptr, M, st);
     const dim3 grid(gemv_grid(S.total_rows, 4, 8)), block(256);
     hipLaunchKernelGGL((gemv_w4a16_generic_kernel<4>), grid, block, 0, st, S, G, M,
                        reinterpret_cast<const uint4 *>(x));

@@ -12,7 +12,8 @@
 // Batch 1 (fast path): see gemv_tile.h for the lane/row decomposition; the
 // int8 codes of the lane's groups are register-resident, the loop body per
 // 32 weights is one 128-bit load, 12 bit operations, 8 dot4, one convert and
-// one FMA.  Any other case (M > 1, K > 16384) takes the generic kernel, which
+// one FMA.  Two to 32 tokens with a per-token scale go to the matrix-core
+// kernel (gemv_mfma.hip); any other case takes the generic kernel, which
 // re-reads activations from memory.
 #include "gemv_tile.h"
 
@@ -198,6 +199,8 @@ int launch_gemv_w4a8(const GemvSegs &S, int K, const int8_t *xq, const float *xs
             default: return launch_m1<8, 64>(S, G, xq, xscale, xgsum, pg, debug, st);
         }
     }
+    if (!pg && gemv_mfma_supported(S, K, M))
+        return launch_gemv_mfma(S, K, NVQ_W4A8, xq, xscale, M, st);
     const dim3 grid(gemv_grid(S.total_rows, 4, 8)), block(256);
     const uint4 *x4 = reinterpret_cast<const uint4 *>(xq);
 #define NVQ_GO(PG, DBG)                                                                      \

@@ -48,6 +48,12 @@ int launch_quant_act(const uint16_t *x, int M, int K, int act_group, int8_t *xq,
 int launch_gemv_w4a8(const GemvSegs &segs, int K, const int8_t *xq, const float *xscale,
                      const int32_t *xgsum, int act_group, int M, hipStream_t st);
 int launch_gemv_w4a16(const GemvSegs &segs, int K, const uint16_t *x, int M, hipStream_t st);
+// Matrix-core path for 2 <= M <= 32 tokens (per-token activation scale, K a
+// multiple of 128, scale rows 8-byte aligned); `x` is the int8 codes or the
+// bf16 activations according to `precision`.
+bool gemv_mfma_supported(const GemvSegs &segs, int K, int M);
+int launch_gemv_mfma(const GemvSegs &segs, int K, int precision, const void *x,
+                     const float *xscale, int M, hipStream_t st);
 
 // ---- device helpers -------------------------------------------------------
 #if defined(__HIPCC__)

@@ -112,6 +112,10 @@ W4A8_CASES = [
     (33, 4096, 1, 32), (21, 14336, 1, 32), (18, 3072, 1, 32),
     (40, 4096, 2, 0), (40, 4096, 4, 0), (17, 3072, 5, 0), (24, 14336, 8, 0), (12, 2048, 32, 0),
     (20, 4096, 3, 32),
+    # matrix-core kernel (2 <= M <= 32, K % 128 == 0): one and two token tiles, ragged row
+    # and token tails, fewer K columns than waves, 1 / 2 / 4 row tiles per workgroup
+    (5, 128, 2, 0), (100, 4096, 16, 0), (70, 3072, 17, 0), (33, 14336, 32, 0), (16, 512, 9, 0),
+    (16400, 2048, 8, 0), (33000, 1024, 24, 0),
 ]
 
 
@@ -133,18 +137,20 @@ def test_gemv_w4a8_acc_bit_exact_and_output(N, K, M, group):
     assert np_ref.rel_l2(y.cpu().numpy(), y_r) < 1e-5        # what fp32 accumulation gives
 
 
-def test_gemv_w4a8_accepts_every_nibble_and_extreme_codes():
-    say("w4a8 extremes")
+@pytest.mark.parametrize("M", [1, 20])
+def test_gemv_w4a8_accepts_every_nibble_and_extreme_codes(M):
+    say("w4a8 extremes", M)
     rng = np.random.default_rng(17)
     N, K = 50, 4096
     q = rng.integers(0, 256, (N, K // 2), dtype=np.uint8)      # includes nibble 0 = code -8
     q[0, :] = 0x00
     q[1, :] = 0xFF
     s = rng.integers(0x1400, 0x2c00, (N, K // 32)).astype(np.uint16)
-    xq = rng.integers(-127, 128, (1, K)).astype(np.int8)
+    xq = rng.integers(-127, 128, (M, K)).astype(np.int8)
     xq[0, :64] = -127
-    xs = np.array([0.03125], np.float32)
-    gs = xq.astype(np.int32).reshape(1, K // 32, 32).sum(axis=2).astype(np.int32)
+    xq[M - 1, 64:128] = 127
+    xs = np.linspace(0.03125, 0.0625, M).astype(np.float32)
+    gs = xq.astype(np.int32).reshape(M, K // 32, 32).sum(axis=2).astype(np.int32)
     y_r, acc_r = oracle.gemv_w4a8(q, s, xq, xs, want_acc=True)
     assert acc_r.max() == 32512
     qd, sd = to_dev_packed(q, s)
@@ -153,6 +159,23 @@ def test_gemv_w4a8_accepts_every_nibble_and_extreme_codes():
     torch.cuda.synchronize()
     assert np.array_equal(acc.cpu().numpy(), acc_r)
     assert np_ref.rel_l2(y.cpu().numpy(), y_r) < TOL
+
+
+def test_batched_w4a8_rows_equal_the_single_token_results():
+    say("w4a8 batch rows")
+    # the matrix-core kernel and the batch-1 kernel compute the same int32 accumulators
+    N, K, M = 48, 4096, 19
+    _, q, s = packed(3500, N, K)
+    x = act(3501, M, K).to(DEV)
+    qd, sd = to_dev_packed(q, s)
+    xq, xs, gs = nvq.quant_act_i8(x, 0)
+    y, acc = nvq.gemv_w4a8(qd, sd, xq, xs, gs, 0, want_acc=True)
+    for m in (0, 7, 16, 18):
+        y1, acc1 = nvq.gemv_w4a8(qd, sd, xq[m:m + 1].contiguous(), xs[m:m + 1].contiguous(),
+                                 gs[m:m + 1].contiguous(), 0, want_acc=True)
+        torch.cuda.synchronize()
+        assert torch.equal(acc[m], acc1[0])
+        assert np_ref.rel_l2(y[m].cpu().numpy(), y1[0].cpu().numpy()) < 1e-5
 
 
 # ---- a4 W4A16 ------------------------------------------------------------------
@@ -173,13 +196,14 @@ def test_gemv_w4a16_output(N, K, M):
     assert err < TOL
 
 
-def test_gemv_w4a16_accepts_every_nibble():
-    say("w4a16 nibbles")
+@pytest.mark.parametrize("M", [1, 20])
+def test_gemv_w4a16_accepts_every_nibble(M):
+    say("w4a16 nibbles", M)
     rng = np.random.default_rng(18)
     N, K = 40, 3072
     q = rng.integers(0, 256, (N, K // 2), dtype=np.uint8)
     s = rng.integers(0x1400, 0x2c00, (N, K // 32)).astype(np.uint16)
-    x = act(77, 1, K)
+    x = act(77, M, K)
     y_r = oracle.gemv_w4a16(q, s, u16(x))
     qd, sd = to_dev_packed(q, s)
     y = nvq.gemv_w4a16(qd, sd, x.to(DEV))
