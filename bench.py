@@ -37,6 +37,9 @@ def parse():
                     help="calib: run only the plain copy kernel (1 GiB, for scaling profiler "
                          "byte counters)")
     ap.add_argument("--act-group", type=int, default=0, choices=[0, 32])
+    ap.add_argument("--batch", type=int, default=1,
+                    help="tokens per step (1 = the headline workload; 2..32 = the small-batch "
+                         "variant on the matrix cores, one launch per phase)")
     ap.add_argument("--extra", action="store_true",
                     help="also time the all-W4A8 / all-W4A16 maps and the fully ordered chain")
     return ap.parse_args()
@@ -171,19 +174,25 @@ def main():
         print(json.dumps({"calib": "nvq::stream_copy_kernel", "bytes_read": 1 << 30,
                           "bytes_written": 1 << 30, "launches": 5}))
         return
-    M = 1
+    M = a.batch
+    if not 1 <= M <= 32:
+        print("bench.py: --batch must be 1..32", file=sys.stderr)
+        sys.exit(2)
     bits = block_bits(a.model, a.map, synth)
     specs = synth.model_linears(a.model)
     step_bytes = sum(synth.weight_bytes(s.N, s.K) for s in specs)
     out = {
-        "metric": "decode linear-layer tokens/s + achieved HBM GB/s (% of peak), 8B shapes, batch 1",
+        "metric": "decode linear-layer tokens/s + achieved HBM GB/s (%% of peak), 8B shapes, "
+                  "batch %d" % M,
         "value": None, "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": None, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int4 weights; int8 x int4 -> int32 (W4A8) and bf16 x int4 -> f32 (W4A16)",
         "data": "synthetic",
-        "config": {"workload": "%s-shaped decode step, batch 1, %d linears in %s, precision map "
+        "config": {"workload": "%s-shaped decode step, batch %d, %d linears in %s, precision map "
                                "%s (%d of %d blocks W4A16%s), own input buffer per layer" %
-                               (a.model, len(specs), "one launch", a.map, sum(bits), len(bits),
+                               (a.model, M, len(specs),
+                                "one launch" if M == 1 else "one launch per phase", a.map,
+                                sum(bits), len(bits),
                                 ", lm_head W4A16" if specs[-1].block < 0 else ""),
                    "act_group": a.act_group, "weight_bytes_per_step": step_bytes},
     }
@@ -206,7 +215,7 @@ def main():
             "bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": traffic_from_profile(a.model, a.map),
             "kernel": STREAM_KERNEL if info["streaming"] else "per-phase launches",
-            "launches": a.steps, "avg_launch_us": round(per_launch * 1e6, 2),
+            "launches": a.steps, "avg_launch_us": round(per_launch * 1e6, 2),  # per step
             "bytes_per_launch": step_bytes}
         dl.close()
         if a.extra:

@@ -22,6 +22,8 @@ FLAGS = [
     "-ffp-contract=off",
     # packed-fp32 instructions are kept out of the generated code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # MFMA results go to ordinary vector registers (no accumulator-register copies)
+    "-mllvm", "-amdgpu-mfma-vgpr-form=1",
     "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
 ]
 

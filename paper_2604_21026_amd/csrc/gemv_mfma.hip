@@ -25,9 +25,15 @@
 // Memory: lane (n, kb) loads the 16 bytes of group 4c + kb of row n, so a
 // wave reads 64 contiguous bytes of 16 rows per load; a 4x4 transpose across
 // the four 16-lane rows (two permlane32 and two permlane16 swaps) then gives
-// the lane dword kb of groups 4c..4c+3.  A workgroup owns 16 * R consecutive
-// rows; its eight waves split K by 64-byte columns and their partial tiles
-// are summed through LDS in a fixed order.
+// the lane dword kb of groups 4c..4c+3.  The activation operands are loaded
+// the same way, 16 bytes per lane with whole 64-byte runs per token and
+// instruction, and brought into operand order with the same swaps: narrower
+// loads that fetch each lane's operand bytes directly touch four times as many
+// cache lines per instruction and were bound by the L1 lookup rate.
+//
+// A workgroup owns 16 * R consecutive rows; its W (8 or 16) waves split K by
+// 64-byte columns, each requests all loads of a pass of B columns before the
+// first MFMA, and the partial tiles are summed through LDS in wave order.
 #include "gemv_tile.h"
 
 namespace nvq {
@@ -39,8 +45,6 @@ typedef float float4v __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned uint2v __attribute__((ext_vector_type(2)));
 typedef unsigned uint4v __attribute__((ext_vector_type(4)));
-
-constexpr int kMfmaWaves = 8;
 
 __device__ __forceinline__ uint4v load_stream(const uint4 *p) {
     return __builtin_nontemporal_load(reinterpret_cast<const uint4v *>(p));
@@ -67,11 +71,23 @@ template <>
 struct Act<NVQ_W4A8> {
     typedef long operand;
     static constexpr int kBytes = 1;
-    __device__ static operand load(const char *p, bool ok) {
-        const uint32_t lo = *reinterpret_cast<const uint32_t *>(p);
-        const uint32_t hi = *reinterpret_cast<const uint32_t *>(p + 16);
-        const uint64_t v = (uint64_t)lo | ((uint64_t)hi << 32);
-        return ok ? (long)v : 0l;
+    // Raw activations of a column (4 groups x 32 codes = 128 bytes per token):
+    // lane (m, kb) loads the two halves of group kb of token m.
+    static constexpr int kRaw = 2;
+    static constexpr int kLaneBytes = 32;  // byte offset of lane-row kb: kb * 32
+    __device__ static void load(const char *p, uint4v (&raw)[kRaw]) {
+        raw[0] = *reinterpret_cast<const uint4v *>(p);
+        raw[1] = *reinterpret_cast<const uint4v *>(p + 16);
+    }
+    // Operands of groups 0..3: dword kb of each half (codes 4kb..4kb+3 and
+    // 16+4kb..16+4kb+3), the choice the weight operand makes.
+    __device__ static void operands(const uint4v (&raw)[kRaw], operand (&a)[4]) {
+        uint32_t lo[4] = {raw[0].x, raw[0].y, raw[0].z, raw[0].w};
+        uint32_t hi[4] = {raw[1].x, raw[1].y, raw[1].z, raw[1].w};
+        transpose_rows(lo);
+        transpose_rows(hi);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) a[i] = (long)((uint64_t)lo[i] | ((uint64_t)hi[i] << 32));
     }
     __device__ static operand weights(uint32_t v) {
         const uint32_t lo = v & 0x0f0f0f0fu, hi = (v >> 4) & 0x0f0f0f0fu;
@@ -94,12 +110,29 @@ template <>
 struct Act<NVQ_W4A16> {
     typedef bf16x8 operand;
     static constexpr int kBytes = 2;
-    __device__ static operand load(const char *p, bool ok) {
-        const uint2 lo = *reinterpret_cast<const uint2 *>(p);
-        const uint2 hi = *reinterpret_cast<const uint2 *>(p + 32);
-        uint4 v = make_uint4(lo.x, lo.y, hi.x, hi.y);
-        if (!ok) v = make_uint4(0, 0, 0, 0);
-        return __builtin_bit_cast(bf16x8, v);
+    // Raw activations of a column (4 groups x 32 bf16 = 256 bytes per token):
+    // lane (m, kb) loads the 16-byte piece kb of each group of token m, so one
+    // load instruction reads 64 contiguous bytes per token.
+    static constexpr int kRaw = 4;
+    static constexpr int kLaneBytes = 16;
+    __device__ static void load(const char *p, uint4v (&raw)[kRaw]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) raw[i] = *reinterpret_cast<const uint4v *>(p + 64 * i);
+    }
+    // Lane-row kb needs activations 4kb..4kb+3 and 16+4kb..16+4kb+3 of a group:
+    // the first or second half of piece kb/2 and of piece 2 + kb/2.  For the
+    // first dwords of the halves, x and z of the four pieces: a permlane16 swap
+    // gives rows (x0 z0 x2 z2) and (x1 z1 x3 z3), a permlane32 swap of those
+    // (x0 z0 x1 z1) and (x2 z2 x3 z3); the same for the second dwords y and w.
+    __device__ static void operands(const uint4v (&raw)[kRaw], operand (&a)[4]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint2v xz = __builtin_amdgcn_permlane16_swap(raw[i].x, raw[i].z, false, false);
+            const uint2v x = __builtin_amdgcn_permlane32_swap(xz.x, xz.y, false, false);
+            const uint2v yw = __builtin_amdgcn_permlane16_swap(raw[i].y, raw[i].w, false, false);
+            const uint2v y = __builtin_amdgcn_permlane32_swap(yw.x, yw.y, false, false);
+            a[i] = __builtin_bit_cast(bf16x8, make_uint4(x.x, y.x, x.y, y.y));
+        }
     }
     __device__ static operand weights(uint32_t v) {
         constexpr uint32_t kMagic = 0x43434343u;  // high byte of bf16(128 + n)
@@ -125,35 +158,50 @@ struct Act<NVQ_W4A16> {
     typedef float4v offset_t;
 };
 
-// One 64-byte column (four groups) of the lane's row in each of R row tiles.
-template <int R>
+// One 64-byte column (four groups) of the lane's row in each of R row tiles,
+// and the lane's activation operands for the four groups.
+template <int PREC, int R, int MT>
 struct Column {
     uint4v w[R];  // group 4c + kb of row n
     uint2 s[R];   // fp16 scales of groups 4c .. 4c+3 of row n
+    uint4v a[MT][Act<PREC>::kRaw];
 };
 
-template <int PREC, int R, int MT, bool DEBUG>
-__global__ __launch_bounds__(kMfmaWaves * 64) void gemv_mfma_kernel(
+// A workgroup of W waves owns 16 * R consecutive rows at a time; wave w takes
+// the columns w, w + W, ... of those rows, B columns per pass: every load of a
+// pass is requested before the first MFMA, so a wave has B * R KiB of weights
+// in flight and the compute units overlap the passes of their resident waves.
+template <int PREC, int R, int MT, int W, int B, bool DEBUG>
+__global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(
     GemvSegs S, int G, int M, const char *__restrict__ xin, const float *__restrict__ xscale) {
     typedef Act<PREC> A;
     constexpr int kTile = R * MT * 4;  // result registers per lane
-    __shared__ float red[kMfmaWaves][kTile][64];
+    __shared__ float red[W][kTile][64];
 
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int n = lane & 15, kb = lane >> 4;
     const int C4 = G >> 2;
-    const int64_t row_bytes = (int64_t)G * 32 * A::kBytes;
+    const uint32_t row_bytes = (uint32_t)G * 32 * A::kBytes;
     const int units = (S.total_rows + 16 * R - 1) / (16 * R);
 
-    // The lane's token in each token tile and where its part of a group starts.
-    const char *xrow[MT];
-    bool xok[MT];
+    // Byte offset of the lane's part of group 0 for its token in each token
+    // tile.  Tokens past M read token 0: an MFMA keeps tokens apart and the
+    // results of those tokens are never stored.
+    uint32_t xoff[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         const int m = mt * 16 + n;
-        xok[mt] = m < M;
-        xrow[mt] = xin + (xok[mt] ? m : 0) * row_bytes + kb * 4 * A::kBytes;
+        xoff[mt] = (m < M ? m : 0) * row_bytes + kb * A::kLaneBytes;
     }
+    // Per-token activation scale of the lane's result registers (W4A8).
+    float xs[MT][4];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            const int m = mt * 16 + kb * 4 + jj;
+            xs[mt][jj] = (PREC == NVQ_W4A8 && m < M) ? xscale[m] : 1.0f;
+        }
 
     for (int unit = blockIdx.x; unit < units; unit += gridDim.x) {
         RowRef rr[R];
@@ -166,102 +214,113 @@ __global__ __launch_bounds__(kMfmaWaves * 64) void gemv_mfma_kernel(
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) f[r][mt][j] = 0.0f;
+                for (int jj = 0; jj < 4; ++jj) f[r][mt][jj] = 0.0f;
 
-        auto fetch = [&](int c, Column<R> &col) {
+        for (int c0 = w; c0 < C4; c0 += W * B) {
+            Column<PREC, R, MT> col[B];
 #pragma unroll
-            for (int r = 0; r < R; ++r) {
-                col.w[r] = load_stream(rr[r].qw + 4 * c + kb);
-                col.s[r] = *reinterpret_cast<const uint2 *>(rr[r].sc + 4 * c);
+            for (int b = 0; b < B; ++b) {
+                const int c = c0 + b * W;
+                const bool ok = c < C4;  // (wave-uniform)
+                const int cc = ok ? c : C4 - 1;
+                const char *xcol = xin + (size_t)cc * (128 * A::kBytes);
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) A::load(xcol + xoff[mt], col[b].a[mt]);
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    col[b].w[r] = load_stream(rr[r].qw + 4 * cc + kb);
+                    const uint2 sc = *reinterpret_cast<const uint2 *>(rr[r].sc + 4 * cc);
+                    // a column past the end of the row contributes zero
+                    col[b].s[r] = make_uint2(ok ? sc.x : 0u, ok ? sc.y : 0u);
+                }
             }
-        };
-
-        Column<R> cur;
-        if (w < C4) fetch(w, cur);
-        for (int c = w; c < C4; c += kMfmaWaves) {
-            Column<R> nxt = cur;
-            if (c + kMfmaWaves < C4) fetch(c + kMfmaWaves, nxt);
-
-            uint32_t t[R][4];
-            float sw[R][4];
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int r = 0; r < R; ++r) {
-                t[r][0] = cur.w[r].x;
-                t[r][1] = cur.w[r].y;
-                t[r][2] = cur.w[r].z;
-                t[r][3] = cur.w[r].w;
-                transpose_rows(t[r]);
-                sw[r][0] = half_bits_to_float((uint16_t)(cur.s[r].x & 0xffffu));
-                sw[r][1] = half_bits_to_float((uint16_t)(cur.s[r].x >> 16));
-                sw[r][2] = half_bits_to_float((uint16_t)(cur.s[r].y & 0xffffu));
-                sw[r][3] = half_bits_to_float((uint16_t)(cur.s[r].y >> 16));
-            }
+            for (int b = 0; b < B; ++b) {
+                const int c = c0 + b * W;
+                uint32_t q[R][4];
+                float sw[R][4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int g = 4 * c + i;
+                for (int r = 0; r < R; ++r) {
+                    q[r][0] = col[b].w[r].x;
+                    q[r][1] = col[b].w[r].y;
+                    q[r][2] = col[b].w[r].z;
+                    q[r][3] = col[b].w[r].w;
+                    transpose_rows(q[r]);
+                    sw[r][0] = half_bits_to_float((uint16_t)(col[b].s[r].x & 0xffffu));
+                    sw[r][1] = half_bits_to_float((uint16_t)(col[b].s[r].x >> 16));
+                    sw[r][2] = half_bits_to_float((uint16_t)(col[b].s[r].y & 0xffffu));
+                    sw[r][3] = half_bits_to_float((uint16_t)(col[b].s[r].y >> 16));
+                }
+                typename A::operand act[MT][4];
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
-                    const typename A::operand a =
-                        A::load(xrow[mt] + (int64_t)g * 32 * A::kBytes, xok[mt]);
-                    const typename A::offset_t off = A::offset(a);
+                for (int mt = 0; mt < MT; ++mt) A::operands(col[b].a[mt], act[mt]);
 #pragma unroll
-                    for (int r = 0; r < R; ++r) {
-                        int4v raw;
-                        const float4v p = A::product(a, A::weights(t[r][i]), off, raw);
-                        f[r][mt][0] = fmaf(sw[r][i], p.x, f[r][mt][0]);
-                        f[r][mt][1] = fmaf(sw[r][i], p.y, f[r][mt][1]);
-                        f[r][mt][2] = fmaf(sw[r][i], p.z, f[r][mt][2]);
-                        f[r][mt][3] = fmaf(sw[r][i], p.w, f[r][mt][3]);
-                        if (DEBUG && PREC == NVQ_W4A8) {
-                            if (rr[r].valid && rr[r].dbg) {
-                                const int acc[4] = {raw.x, raw.y, raw.z, raw.w};
+                for (int i = 0; i < 4; ++i) {
 #pragma unroll
-                                for (int j = 0; j < 4; ++j) {
-                                    const int m = mt * 16 + kb * 4 + j;
-                                    if (m < M)
-                                        rr[r].dbg[((int64_t)m * rr[r].N + rr[r].n) * G + g] =
-                                            acc[j];
+                    for (int mt = 0; mt < MT; ++mt) {
+                        const typename A::operand a = act[mt][i];
+                        const typename A::offset_t off = A::offset(a);
+#pragma unroll
+                        for (int r = 0; r < R; ++r) {
+                            int4v raw;
+                            const float4v p = A::product(a, A::weights(q[r][i]), off, raw);
+                            f[r][mt][0] = fmaf(sw[r][i], p.x, f[r][mt][0]);
+                            f[r][mt][1] = fmaf(sw[r][i], p.y, f[r][mt][1]);
+                            f[r][mt][2] = fmaf(sw[r][i], p.z, f[r][mt][2]);
+                            f[r][mt][3] = fmaf(sw[r][i], p.w, f[r][mt][3]);
+                            if (DEBUG && PREC == NVQ_W4A8) {
+                                if (rr[r].valid && rr[r].dbg && c < C4) {
+                                    const int acc[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+                                    for (int jj = 0; jj < 4; ++jj) {
+                                        const int m = mt * 16 + kb * 4 + jj;
+                                        if (m < M)
+                                            rr[r].dbg[((int64_t)m * rr[r].N + rr[r].n) * G + 4 * c +
+                                                      i] = acc[jj];
+                                    }
                                 }
                             }
                         }
                     }
                 }
             }
-            cur = nxt;
+            __builtin_amdgcn_sched_barrier(0);
         }
 
-        // Sum the eight K slices in wave order.
+        // Sum the K slices of the waves in wave order.
 #pragma unroll
         for (int r = 0; r < R; ++r)
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) red[w][(r * MT + mt) * 4 + j][lane] = f[r][mt][j];
+                for (int jj = 0; jj < 4; ++jj)
+                    red[w][(r * MT + mt) * 4 + jj][lane] = f[r][mt][jj] * xs[mt][jj];
         __syncthreads();
-        for (int e = threadIdx.x; e < kTile * 64; e += kMfmaWaves * 64) {
-            const int reg = e >> 6, l = e & 63;
-            float sum = 0.0f;
 #pragma unroll
-            for (int q = 0; q < kMfmaWaves; ++q) sum += red[q][reg][l];
-            const int r = reg / (MT * 4), mt = (reg >> 2) % MT, j = reg & 3;
-            const int m = mt * 16 + (l >> 4) * 4 + j;
-            const RowRef o = locate_row(S, (unit * R + r) * 16 + (l & 15), G);
-            if (o.valid && m < M) {
-                if (PREC == NVQ_W4A8) sum *= xscale[m];
-                store_out(o.y, o.y_dtype, (int64_t)m * o.N + o.n, sum);
+        for (int pass = 0; pass < (kTile + W - 1) / W; ++pass) {
+            const int reg = pass * W + w;
+            if (reg < kTile) {
+                float sum = 0.0f;
+#pragma unroll
+                for (int k = 0; k < W; ++k) sum += red[k][reg][lane];
+                const int r = reg / (MT * 4), mt = (reg >> 2) % MT, jj = reg & 3;
+                const int m = mt * 16 + kb * 4 + jj;
+                const RowRef o = locate_row(S, (unit * R + r) * 16 + n, G);
+                if (o.valid && m < M) store_out(o.y, o.y_dtype, (int64_t)m * o.N + o.n, sum);
             }
         }
         __syncthreads();
     }
 }
 
-template <int PREC, int R, int MT, bool DEBUG>
+template <int PREC, int R, int MT, int W, int B, bool DEBUG>
 int launch_one(const GemvSegs &S, int G, int M, const void *x, const float *xscale,
                hipStream_t st) {
     const int units = (S.total_rows + 16 * R - 1) / (16 * R);
-    const int cap = device_cu_count() * 4;
-    const dim3 grid(units < cap ? units : cap), block(kMfmaWaves * 64);
-    hipLaunchKernelGGL((gemv_mfma_kernel<PREC, R, MT, DEBUG>), grid, block, 0, st, S, G, M,
+    const int cap = device_cu_count() * 8;
+    const dim3 grid(units < cap ? units : cap), block(W * 64);
+    hipLaunchKernelGGL((gemv_mfma_kernel<PREC, R, MT, W, B, DEBUG>), grid, block, 0, st, S, G, M,
                        reinterpret_cast<const char *>(x), xscale);
     NVQ_HIP_TRY(hipGetLastError());
     return NVQ_OK;
@@ -271,20 +330,18 @@ template <int PREC>
 int launch_prec(const GemvSegs &S, int G, int M, const void *x, const float *xscale, bool debug,
                 hipStream_t st) {
     const bool wide = M > 16;
-    if (debug)  // accumulator dump: one row tile per workgroup
-        return wide ? launch_one<PREC, 1, 2, true>(S, G, M, x, xscale, st)
-                    : launch_one<PREC, 1, 1, true>(S, G, M, x, xscale, st);
-    // Row tiles per workgroup: share the activation operand between as many
-    // tiles as still leaves two workgroups for every compute unit.
+    // Eight waves share a row tile, so that a compute unit holds two or three
+    // workgroups whose load and compute passes overlap; sixteen when there are
+    // too few tiles for that and each wave still gets two columns (K >= 4096).
     const int tiles = (S.total_rows + 15) / 16;
-    const int want = 2 * device_cu_count();
-    const int R = tiles >= 4 * want ? 4 : tiles >= 2 * want ? 2 : 1;
-#define NVQ_GO(RR)                                                              \
-    return wide ? launch_one<PREC, RR, 2, false>(S, G, M, x, xscale, st)       \
-                : launch_one<PREC, RR, 1, false>(S, G, M, x, xscale, st)
-    if (R == 4) NVQ_GO(4);
-    if (R == 2) NVQ_GO(2);
-    NVQ_GO(1);
+    const bool many = (G >> 2) >= 32 && tiles <= 2 * device_cu_count();
+#define NVQ_GO(MT, W, DBG) return launch_one<PREC, 1, MT, W, 2, DBG>(S, G, M, x, xscale, st)
+    if (debug) {  // accumulator dump, same summation order as the plain kernel
+        if (wide) { if (many) NVQ_GO(2, 16, true); else NVQ_GO(2, 8, true); }
+        if (many) NVQ_GO(1, 16, true); else NVQ_GO(1, 8, true);
+    }
+    if (wide) { if (many) NVQ_GO(2, 16, false); else NVQ_GO(2, 8, false); }
+    if (many) NVQ_GO(1, 16, false); else NVQ_GO(1, 8, false);
 #undef NVQ_GO
 }
 
