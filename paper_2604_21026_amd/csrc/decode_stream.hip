@@ -55,7 +55,7 @@ typedef const __attribute__((address_space(4))) StreamPhase CPhase;
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 
-constexpr int kSlots = 10;                 // ring slots per wave (1 KiB weights + 256 B scales)
+constexpr int kSlots = 6;                 // ring slots per wave (1 KiB weights + 256 B scales)
 constexpr int kOpsPerChunk = 2;            // scale load + weight load
 constexpr int kXChunkElems = 512;          // bf16 values per input chunk
 constexpr int kMaxXShare = (kStreamMaxK / kXChunkElems + kStreamWaves - 1) / kStreamWaves;  // 4
@@ -423,12 +423,13 @@ __device__ __forceinline__ void image_build(const Writer &wr, CPhase &ph, Shared
         amax = wave_max_to_lane63(amax);
         if (lane == 63) lds_write4(lds_addr(&sh.amax_part[w]), __float_as_uint(amax));
         lds_barrier();
-        const uint4 a = lds_read16(lds_addr(&sh.amax_part[0]));
-        const uint4 b = lds_read16(lds_addr(&sh.amax_part[4]));
-        float m = fmaxf(fmaxf(__uint_as_float(a.x), __uint_as_float(a.y)),
-                        fmaxf(__uint_as_float(a.z), __uint_as_float(a.w)));
-        m = fmaxf(m, fmaxf(fmaxf(__uint_as_float(b.x), __uint_as_float(b.y)),
-                           fmaxf(__uint_as_float(b.z), __uint_as_float(b.w))));
+        float m = 0.0f;
+#pragma unroll
+        for (int k = 0; k < kStreamWaves; k += 4) {
+            const uint4 a = lds_read16(lds_addr(&sh.amax_part[k]));
+            m = fmaxf(m, fmaxf(fmaxf(__uint_as_float(a.x), __uint_as_float(a.y)),
+                               fmaxf(__uint_as_float(a.z), __uint_as_float(a.w))));
+        }
         s_tok = m / 127.0f;
         if (w == 0 && lane == 0) wr.w4(L.stok, __float_as_uint(s_tok));
     }
@@ -494,6 +495,19 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
     if (threadIdx.x == 0) lds_write4(lds_addr(&sh.abort), 0u);
     trace_mark(trace, wg, w, lane, 0, 5);  // kernel entered
 
+    // The streaming waves request their first chunks at once: weights depend on
+    // nothing, so the ring fills while the prologue below prepares the images.
+    Stream st;
+    st.ic.p = 0;
+    st.ic.part = 0;
+    st.ic.left = 0;
+    st.slot = 0;
+    if (w < kStreamWaves) {
+        issue_next_run(st.ic, tab, nphase, w, gw, dummy);
+        for (int u = 0; u < kSlots; ++u)  // fill the ring
+            issue_chunk(st.ic, tab, nphase, sh, w, gw, u, lane, dummy);
+    }
+
     // ---- prologue: images of the phases that depend on no earlier phase, one
     // ---- workgroup per phase; then everybody waits for everybody
     if (nimages > 0) {
@@ -544,14 +558,15 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
             const uint32_t need = (uint32_t)(pq.img_need + 1);
             uint32_t spins = 0;
             for (;;) {
-                const uint4 a = lds_read16(progress_a), b = lds_read16(progress_a + 16);
-                uint32_t m = a.x < a.y ? a.x : a.y;
-                m = m < a.z ? m : a.z;
-                m = m < a.w ? m : a.w;
-                m = m < b.x ? m : b.x;
-                m = m < b.y ? m : b.y;
-                m = m < b.z ? m : b.z;
-                m = m < b.w ? m : b.w;
+                uint32_t m = 0xffffffffu;
+#pragma unroll
+                for (int k = 0; k < kStreamWaves; k += 4) {
+                    const uint4 a = lds_read16(progress_a + 4 * k);
+                    m = m < a.x ? m : a.x;
+                    m = m < a.y ? m : a.y;
+                    m = m < a.z ? m : a.z;
+                    m = m < a.w ? m : a.w;
+                }
                 if ((uint32_t)__builtin_amdgcn_readfirstlane((int)m) >= need) break;
                 if (lds_read4_uniform(abort_a)) return false;
                 if (++spins > kSpinLimit) {
@@ -596,14 +611,6 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
     const uint32_t ring_base = lds_addr(&sh.ring[w][0][0]) + lane * 16;
     const uint32_t sring_base = lds_addr(&sh.sring[w][0][0]) + lane * 4;
 
-    Stream st;
-    st.ic.p = 0;
-    st.ic.part = 0;
-    st.ic.left = 0;
-    issue_next_run(st.ic, tab, nphase, w, gw, dummy);
-    st.slot = 0;
-    for (int u = 0; u < kSlots; ++u)  // fill the ring
-        issue_chunk(st.ic, tab, nphase, sh, w, gw, u, lane, dummy);
 
     // Take the next chunk of the stream out of the ring (16 bytes and one
     // scale per lane) and refill its slot at once.  When a chunk is taken, the
@@ -676,10 +683,11 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
         // one whenever both can issue, which lets it refill its ring sooner and
         // leaves the younger one a phase or two behind.  Alternating the wave
         // priority from phase to phase evens this out.
-        if (((w >> 2) ^ p) & 1)
-            __builtin_amdgcn_s_setprio(2);
-        else
-            __builtin_amdgcn_s_setprio(0);
+        switch (((w >> 2) + p) % 3) {
+            case 0: __builtin_amdgcn_s_setprio(0); break;
+            case 1: __builtin_amdgcn_s_setprio(1); break;
+            default: __builtin_amdgcn_s_setprio(2); break;
+        }
 
         // ---- this wave's weight rows ---------------------------------------------------
         const int gpl = ph.gpl;
