@@ -40,6 +40,8 @@
 // atomics), and its input is read after the wait instead of being streamed
 // ahead.  A bounded spin turns a stuck wait (e.g. the grid not co-resident)
 // into an error status instead of a hang.
+#include <type_traits>
+
 #include "decode_stream.h"
 
 namespace nvq {
@@ -694,25 +696,22 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
         const int r0 = gw * ph.rows_per_wave;
         int r1 = r0 + ph.rows_per_wave;
         r1 = r1 < ph.total_rows ? r1 : ph.total_rows;
-        const int nchunks = r1 > r0 ? (r1 - r0) * gpl : 0;
+        const int nrows = r1 > r0 ? r1 - r0 : 0;
         const float xs =
             (w4a8 && !PER_GROUP) ? __uint_as_float(lds_read4(img + L.stok)) : 1.0f;
         const uint32_t plane = (uint32_t)G * 16u;
-        int i = 0;        // chunk position inside the row
-        int row = r0;
-        float sum = 0.0f;
         float yv = 0.0f;  // results of up to 64 rows, one per lane, until they are stored
-        for (int c = 0; c < nchunks; ++c) {
-            // the lane's group of this chunk and its activations
+
+        // The lane's activations of group g = i * 64 + lane (clamped to a valid group)
+        // out of the LDS image; nothing is waited for.
+        auto request_x = [&](int i, u32x4_t(&x)[4], uint32_t &aux, uint32_t &sgbits, bool &ok) {
             const int g = i * 64 + lane;
-            const bool ok = g < G;
+            ok = g < G;
             const uint32_t ga = img + (ok ? g : 0) * 16;
             const uint32_t aux_a = img + L.aux + (ok ? g : 0) * 4;
-            u32x4_t xa, xb, xc = {0, 0, 0, 0}, xd = {0, 0, 0, 0};
-            uint32_t aux, sgbits = 0;
             if (w4a8) {
                 asm volatile("ds_read_b128 %0, %3\n\tds_read_b128 %1, %4\n\tds_read_b32 %2, %5"
-                             : "=&v"(xa), "=&v"(xb), "=&v"(aux)
+                             : "=&v"(x[0]), "=&v"(x[1]), "=&v"(aux)
                              : "v"(ga), "v"(ga + plane), "v"(aux_a)
                              : "memory");
                 if (PER_GROUP)
@@ -723,51 +722,113 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
             } else {
                 asm volatile("ds_read_b128 %0, %5\n\tds_read_b128 %1, %6\n\tds_read_b128 %2, %7\n\t"
                              "ds_read_b128 %3, %8\n\tds_read_b32 %4, %9"
-                             : "=&v"(xa), "=&v"(xb), "=&v"(xc), "=&v"(xd), "=&v"(aux)
+                             : "=&v"(x[0]), "=&v"(x[1]), "=&v"(x[2]), "=&v"(x[3]), "=&v"(aux)
                              : "v"(ga), "v"(ga + plane), "v"(ga + 2 * plane), "v"(ga + 3 * plane),
                                "v"(aux_a)
                              : "memory");
             }
-            uint32_t sbits;
-            const uint4 wq = pop_chunk(sbits);  // its lgkmcnt(0) also covers the reads above
-            // nothing below may be scheduled (or copied) before that wait
-            asm volatile("" : "+v"(xa), "+v"(xb), "+v"(xc), "+v"(xd), "+v"(aux), "+v"(sgbits));
+        };
+        // One chunk against the lane's activations of its group, added to `sum`.
+        auto chunk_term = [&](float sum, const uint4 &wq, uint32_t sbits, const u32x4_t(&x)[4],
+                              uint32_t aux, uint32_t sgbits, bool ok) -> float {
             const u32x4_t wv = {wq.x, wq.y, wq.z, wq.w};
             float sw = ok ? half_bits_to_float((uint16_t)sbits) : 0.0f;
             if (w4a8) {
-                const int acc = dot_w4a8(wv, xa, xb, (int)aux);
+                const int acc = dot_w4a8(wv, x[0], x[1], (int)aux);
                 if (PER_GROUP) sw *= __uint_as_float(sgbits);
-                sum = fmaf(sw, (float)acc, sum);
-            } else {
-                const u32x4_t xq[4] = {xa, xb, xc, xd};
-                sum = fmaf(sw, dot_w4a16(wv, xq, __uint_as_float(aux)), sum);
+                return fmaf(sw, (float)acc, sum);
             }
-            if (++i == gpl) {
-                // end of a row: reduce, park the result in lane (row - r0) % 64
-                i = 0;
-                const float tot = __builtin_bit_cast(
-                    float, __builtin_amdgcn_readlane(
-                               __builtin_bit_cast(int, wave_sum_to_lane63(sum)), 63));
-                sum = 0.0f;
-                const int k = row - r0;
-                if (lane == (k & 63)) yv = tot * xs;
-                if ((k & 63) == 63 || row == r1 - 1) {  // one store per 64 rows
-                    const int r = row - (k & 63) + lane;
-                    if (r <= row) {
-                        int first = 0;
-                        void *y = ph.y[0];
-                        int dt = ph.y_dtype[0];
+            return fmaf(sw, dot_w4a16(wv, x, __uint_as_float(aux)), sum);
+        };
+        // End of row `row`: reduce over the lanes, park the result in lane
+        // (row - r0) % 64, store once per 64 rows.
+        auto finish_row = [&](int row, float sum) {
+            const float tot = __builtin_bit_cast(
+                float,
+                __builtin_amdgcn_readlane(__builtin_bit_cast(int, wave_sum_to_lane63(sum)), 63));
+            const int k = row - r0;
+            if (lane == (k & 63)) yv = tot * xs;
+            if ((k & 63) == 63 || row == r1 - 1) {
+                const int r = row - (k & 63) + lane;
+                if (r <= row) {
+                    int first = 0;
+                    void *y = ph.y[0];
+                    int dt = ph.y_dtype[0];
 #pragma unroll
-                        for (int sgm = 1; sgm < kMaxSeg; ++sgm)
-                            if (sgm < ph.nseg && r >= ph.row_end[sgm - 1]) {
-                                first = ph.row_end[sgm - 1];
-                                y = ph.y[sgm];
-                                dt = ph.y_dtype[sgm];
-                            }
-                        store_out(y, dt, r - first, yv);
+                    for (int sgm = 1; sgm < kMaxSeg; ++sgm)
+                        if (sgm < ph.nseg && r >= ph.row_end[sgm - 1]) {
+                            first = ph.row_end[sgm - 1];
+                            y = ph.y[sgm];
+                            dt = ph.y_dtype[sgm];
+                        }
+                    store_out(y, dt, r - first, yv);
+                }
+            }
+        };
+        // Rows of at most kRegGpl chunks: the lane meets the same GPL groups in
+        // every row, so their activations are taken out of the image once per
+        // phase and stay in registers.  (Reading them per chunk makes LDS the
+        // bound of the W4A16 phases: 64 bytes per lane and chunk on top of the
+        // ring's 20.)
+        auto rows_in_registers = [&](auto gpl_const) {
+            constexpr int GPL = decltype(gpl_const)::value;
+            u32x4_t x[GPL][4];
+            uint32_t aux[GPL], sgb[GPL];
+            bool ok[GPL];
+#pragma unroll
+            for (int i = 0; i < GPL; ++i) {
+                x[i][2] = x[i][3] = u32x4_t{0, 0, 0, 0};
+                sgb[i] = 0;
+                request_x(i, x[i], aux[i], sgb[i], ok[i]);
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+            for (int i = 0; i < GPL; ++i)  // nothing may be scheduled (or copied) before that wait
+                asm volatile(""
+                             : "+v"(x[i][0]), "+v"(x[i][1]), "+v"(x[i][2]), "+v"(x[i][3]),
+                               "+v"(aux[i]), "+v"(sgb[i]));
+            for (int row = r0; row < r0 + nrows; ++row) {
+                float sum = 0.0f;
+#pragma unroll
+                for (int i = 0; i < GPL; ++i) {
+                    uint32_t sbits;
+                    const uint4 wq = pop_chunk(sbits);
+                    sum = chunk_term(sum, wq, sbits, x[i], aux[i], sgb[i], ok[i]);
+                }
+                finish_row(row, sum);
+            }
+        };
+        switch (gpl) {
+            case 1: rows_in_registers(std::integral_constant<int, 1>()); break;
+            case 2: rows_in_registers(std::integral_constant<int, 2>()); break;
+            case 3: rows_in_registers(std::integral_constant<int, 3>()); break;
+            case 4: rows_in_registers(std::integral_constant<int, 4>()); break;
+            default: {
+                // longer rows: activations out of the image for every chunk
+                int i = 0;
+                int row = r0;
+                float sum = 0.0f;
+                const int nchunks = nrows * gpl;
+                for (int c = 0; c < nchunks; ++c) {
+                    u32x4_t x[4];
+                    x[2] = x[3] = u32x4_t{0, 0, 0, 0};
+                    uint32_t aux, sgbits = 0;
+                    bool ok;
+                    request_x(i, x, aux, sgbits, ok);
+                    uint32_t sbits;
+                    const uint4 wq = pop_chunk(sbits);  // its lgkmcnt(0) also covers the reads above
+                    // nothing below may be scheduled (or copied) before that wait
+                    asm volatile(""
+                                 : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(aux),
+                                   "+v"(sgbits));
+                    sum = chunk_term(sum, wq, sbits, x, aux, sgbits, ok);
+                    if (++i == gpl) {
+                        i = 0;
+                        finish_row(row, sum);
+                        sum = 0.0f;
+                        ++row;
                     }
                 }
-                ++row;
             }
         }
         // this wave no longer reads the phase's image
