@@ -5,7 +5,7 @@
 
 namespace nvq {
 
-constexpr int kStreamWaves = 12;  // streaming waves per workgroup (two per SIMD)
+constexpr int kStreamWaves = 12;  // streaming waves per workgroup (three per SIMD)
 constexpr int kStreamThreads = (kStreamWaves + 1) * 64;  // plus the loader wave
 constexpr int kStreamMaxK = 14336;     // widest input an activation image holds
 constexpr int kStreamImageMax = 31744;  // largest image, padded to whole KiB (bf16, K = 14336)

@@ -9,16 +9,17 @@
 // phases while the current phase is being set up.
 //
 // Structure.  One workgroup per compute unit, all co-resident: kStreamWaves
-// streaming waves and one loader wave.  Each streaming wave owns a contiguous
-// range of rows in every phase and sees its work as one flat sequence of
-// 1 KiB chunks (64 groups x 16 B of one weight row) across all phases.
-// Chunks are fetched with non-temporal global->LDS loads into a per-wave ring
-// of kSlots slots and consumed in order; a slot is refilled as soon as its
-// chunk has been taken out, independent of phase boundaries.  The fp16 scales
-// travel the same way (one 2-byte load per lane and chunk).  Ring loads are
-// the only vector-memory loads of a wave on the fast path, issued two per
-// chunk, so the number of loads in flight behind a chunk is a compile-time
-// constant and one `s_waitcnt vmcnt(n)` tells when it has landed.
+// streaming waves (three per SIMD) and one loader wave.  Each streaming wave
+// owns a contiguous range of rows in every phase and sees its work as one flat
+// sequence of 1 KiB chunks (64 groups x 16 B of one weight row) across all
+// phases.  Chunks are fetched with non-temporal global->LDS loads into a
+// per-wave ring of kSlots slots and consumed in order; a slot is refilled as
+// soon as its chunk has been taken out, independent of phase boundaries, and
+// the ring is first filled before anything else happens in the kernel.  The
+// fp16 scales travel the same way (one 2-byte load per lane and chunk).  Ring
+// loads are the only vector-memory loads of a wave on the fast path, issued
+// two per chunk, so the number of loads in flight behind a chunk is a
+// compile-time constant and one `s_waitcnt vmcnt(n)` tells when it has landed.
 //
 // Activations.  A phase's input is needed by every wave in a prepared form,
 // the "image": int8 codes (W4A8) or bf16 values (W4A16) laid out in planes of
@@ -26,13 +27,24 @@
 // (-8*sum(codes) or -136*sum(x)), plus the scale(s).  For a phase that depends
 // on no earlier phase the image is built ONCE per step, in global memory, by
 // one workgroup in a prologue (instead of once per compute unit).  The loader
-// wave copies images from there into LDS one phase ahead (two images fit) and
-// announces them through an LDS word; streaming waves report the phases they
-// have finished through one LDS word each, which tells the loader when an
-// image may be overwritten.  On this path the streaming waves never meet at a
-// barrier, so they may drift up to a phase apart and absorb each other's
+// wave copies images from there into a circular LDS area up to kLookahead
+// phases ahead and announces them through an LDS word; streaming waves report
+// the phases they have finished through one LDS word each, which tells the
+// loader when a region may be overwritten.  On this path the streaming waves
+// never meet at a barrier, so they may drift apart and absorb each other's
 // jitter.  A dependent phase builds its image in LDS from the raw input after
 // its wait, all streaming waves together, with workgroup barriers.
+//
+// A lane meets the same few groups in every row of a phase (group i*64+lane
+// for chunk i of the row), so for rows of up to four chunks it takes their
+// activations out of the image once per phase and keeps them in registers;
+// only longer rows read them from LDS per chunk.  Reading them per chunk made
+// LDS, not HBM, the bound of the W4A16 phases (64 bytes per lane and chunk).
+//
+// Two or three streaming waves share a SIMD and the hardware favours the
+// oldest whenever several can issue, which lets it refill its ring sooner and
+// leaves the others behind; the wave priority therefore rotates from phase to
+// phase.
 //
 // Ordering.  The host marks, per phase, the latest earlier phase whose
 // buffers it conflicts with.  Such a phase takes its input only after every
@@ -681,10 +693,8 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
             trace_mark(trace, wg, w, lane, p, 2);
         }
         trace_mark(trace, wg, w, lane, p, 6);
-        // Two streaming waves share a SIMD and the hardware favours the older
-        // one whenever both can issue, which lets it refill its ring sooner and
-        // leaves the younger one a phase or two behind.  Alternating the wave
-        // priority from phase to phase evens this out.
+        // Waves w, w + 4, w + 8 share a SIMD; rotate their priorities so that none
+        // of them is favoured for long (see the header).
         switch (((w >> 2) + p) % 3) {
             case 0: __builtin_amdgcn_s_setprio(0); break;
             case 1: __builtin_amdgcn_s_setprio(1); break;
