@@ -9,8 +9,10 @@
 // precision into a phase (q/k/v, gate/up; at most four matrices per phase).
 // Batch 1 runs the whole list in one launch of the persistent streaming
 // kernel (decode_stream.hip).  Other batch sizes, and shapes the streaming
-// kernel does not take, run one quantisation launch per W4A8 phase and one
-// fused GEMV launch per phase on the caller's stream.
+// kernel does not take, run on the caller's stream as launches per phase (one
+// quantisation launch per W4A8 phase and one fused GEMV launch), or, for 2..32
+// tokens of shapes the matrix-core kernel takes, as two launches per batch of
+// mutually independent phases (one grid quantises, one multiplies).
 #include <new>
 #include <vector>
 
@@ -34,10 +36,29 @@ struct Workspace {
     uint32_t *status;   // [64]                word 0: a wait timed out
     void *dummy;        // 1 KiB               target of the ring's filler loads
     char *images;       // prepared activation images of the streaming kernel
+    GroupPhase *gtab;   // [n]                 phase table of the grouped small-batch launches
+    uint16_t *gjobs;    // [n]                 W4A8 phases, batch after batch
+    uint16_t *gunits;   // [group_units]       phase of every 16-row tile, batch after batch
+    char *gquant;       // per-phase activation codes, scales and code sums
     size_t bytes;
 };
 
-Workspace carve(void *base, int maxK, int M, int n, size_t image_bytes) {
+// Sizes that depend on the layer list (upper bounds: every entry its own phase).
+struct ListSizes {
+    int maxK;
+    size_t image_bytes;  // activation images of the streaming kernel (M = 1)
+    size_t group_units;  // 16-row tiles of all entries (M > 1)
+    size_t group_quant;  // codes + scales + code sums of all W4A8 entries (M > 1)
+};
+
+size_t quant_bytes(int M, int K) {
+    return round_up((size_t)M * K, 256) + round_up((size_t)M * 4, 256) +
+           round_up((size_t)M * (K / 32) * 4, 256);
+}
+
+Workspace carve(void *base, int M, int n, const ListSizes &ls) {
+    const int maxK = ls.maxK;
+    const size_t image_bytes = ls.image_bytes;
     Workspace w;
     char *b = reinterpret_cast<char *>(base);
     const size_t G = (size_t)maxK / 32;
@@ -55,17 +76,21 @@ Workspace carve(void *base, int maxK, int M, int n, size_t image_bytes) {
     w.status = reinterpret_cast<uint32_t *>(take(256));
     w.dummy = take(1024);
     w.images = take(image_bytes);
+    const size_t nn = (size_t)(n > 0 ? n : 1);
+    w.gtab = reinterpret_cast<GroupPhase *>(take(M > 1 ? nn * sizeof(GroupPhase) : 0));
+    w.gjobs = reinterpret_cast<uint16_t *>(take(M > 1 ? nn * 2 : 0));
+    w.gunits = reinterpret_cast<uint16_t *>(take(M > 1 ? ls.group_units * 2 : 0));
+    w.gquant = take(M > 1 ? ls.group_quant : 0);
     w.bytes = off;
     return w;
 }
 
-int check_layers(const nvq_linear *L, int n, int M, int act_group, int *maxK,
-                 size_t *image_bytes) {
+int check_layers(const nvq_linear *L, int n, int M, int act_group, ListSizes *sizes) {
     if (!L || n < 0) return NVQ_ERR_INVALID_ARG;
     if (act_group != 0 && act_group != 32) return NVQ_ERR_INVALID_ARG;
     if (M <= 0 || M > NVQ_MAX_M) return NVQ_ERR_SHAPE;
     int mk = 32;
-    size_t ib = 0;
+    size_t ib = 0, gu = 0, gq = 0;
     for (int i = 0; i < n; ++i) {
         const nvq_linear &e = L[i];
         if (!e.qweight || !e.scales || !e.x_bf16 || !e.y) return NVQ_ERR_INVALID_ARG;
@@ -78,9 +103,13 @@ int check_layers(const nvq_linear *L, int n, int M, int act_group, int *maxK,
         if (e.K > mk) mk = e.K;
         // upper bound: every entry its own phase with a prepared image
         if (e.K <= kStreamMaxK) ib += (size_t)stream_image_bytes(e.K, e.precision, act_group);
+        gu += (size_t)(e.N + 15) / 16 + 1;
+        if (e.precision == NVQ_W4A8) gq += quant_bytes(M, e.K);
     }
-    *maxK = mk;
-    *image_bytes = ib;
+    sizes->maxK = mk;
+    sizes->image_bytes = ib;
+    sizes->group_units = gu;
+    sizes->group_quant = gq;
     return NVQ_OK;
 }
 
@@ -154,6 +183,95 @@ struct Range {
 };
 bool overlap(const Range &a, const Range &b) { return a.lo < b.hi && b.lo < a.hi; }
 
+// Per phase the latest earlier phase it conflicts with (it reads what that
+// phase wrote, or writes what that phase read or wrote), or -1; with `ordered`
+// every phase depends on its predecessor.
+std::vector<int> phase_deps(const nvq_linear *L, const std::vector<Phase> &phases, int M,
+                            bool ordered) {
+    const size_t P = phases.size();
+    std::vector<int> deps(P, -1);
+    std::vector<Range> xin(P);
+    std::vector<std::vector<Range>> yout(P);
+    for (size_t p = 0; p < P; ++p) {
+        const nvq_linear &e0 = L[phases[p].first];
+        xin[p] = {(uintptr_t)e0.x_bf16, (uintptr_t)e0.x_bf16 + (size_t)M * e0.K * 2};
+        for (int k = 0; k < phases[p].count; ++k) {
+            const nvq_linear &e = L[phases[p].first + k];
+            const size_t bytes = (size_t)M * e.N * (e.y_dtype == NVQ_F32 ? 4 : 2);
+            yout[p].push_back({(uintptr_t)e.y, (uintptr_t)e.y + bytes});
+        }
+    }
+    for (size_t p = 1; p < P; ++p) {
+        int dep = ordered ? (int)p - 1 : -1;
+        for (size_t q = 0; q < p && !ordered; ++q) {
+            bool hit = false;
+            for (const Range &yq : yout[q]) {
+                hit = hit || overlap(xin[p], yq);  // read after write
+                for (const Range &yp : yout[p]) hit = hit || overlap(yp, yq);  // write after write
+            }
+            for (const Range &yp : yout[p]) hit = hit || overlap(yp, xin[q]);  // write after read
+            if (hit) dep = (int)q;
+        }
+        deps[p] = dep;
+    }
+    return deps;
+}
+
+// Small batches on the matrix cores, grouped: phases that do not depend on
+// each other form a batch, and a batch is two launches: one grid quantises the
+// inputs of all its W4A8 phases, one grid holds the row tiles of all its
+// phases.  Empty if some phase does not qualify for the matrix-core kernel.
+struct GroupBatch {
+    int job_first, njobs;    // range in the job list
+    int unit_first, nunits;  // range in the unit list
+};
+struct GroupPlan {
+    std::vector<GroupPhase> tab;
+    std::vector<uint16_t> jobs, units;
+    std::vector<GroupBatch> batches;
+};
+GroupPlan group_plan(const nvq_linear *L, const std::vector<Phase> &phases, int M, int act_group,
+                     bool ordered, const Workspace &ws) {
+    GroupPlan gp;
+    if (M < 2 || act_group != 0 || phases.size() > 65535) return gp;
+    for (const Phase &ph : phases)
+        if (!gemv_mfma_supported(make_segs(L, ph), L[ph.first].K, M)) return gp;
+    const std::vector<int> deps = phase_deps(L, phases, M, ordered);
+    size_t qoff = 0;
+    GroupBatch cur = {0, 0, 0, 0};
+    int batch_first = 0;
+    for (size_t p = 0; p < phases.size(); ++p) {
+        const nvq_linear &e0 = L[phases[p].first];
+        if (deps[p] >= batch_first) {  // depends on a phase of the open batch: close it
+            gp.batches.push_back(cur);
+            cur = {(int)gp.jobs.size(), 0, (int)gp.units.size(), 0};
+            batch_first = (int)p;
+        }
+        GroupPhase g = {};
+        g.segs = make_segs(L, phases[p]);
+        g.x_bf16 = e0.x_bf16;
+        g.G = e0.K / 32;
+        g.precision = e0.precision;
+        g.unit_begin = cur.nunits;
+        if (e0.precision == NVQ_W4A8) {
+            char *b = ws.gquant + qoff;
+            g.xq = reinterpret_cast<int8_t *>(b);
+            g.xscale = reinterpret_cast<float *>(b + round_up((size_t)M * e0.K, 256));
+            g.xgsum = reinterpret_cast<int32_t *>(b + round_up((size_t)M * e0.K, 256) +
+                                                  round_up((size_t)M * 4, 256));
+            qoff += quant_bytes(M, e0.K);
+            gp.jobs.push_back((uint16_t)p);
+            ++cur.njobs;
+        }
+        const int tiles = (g.segs.total_rows + 15) / 16;
+        gp.units.insert(gp.units.end(), (size_t)tiles, (uint16_t)p);
+        cur.nunits += tiles;
+        gp.tab.push_back(g);
+    }
+    gp.batches.push_back(cur);
+    return gp;
+}
+
 // Phase table for the streaming kernel; empty if some phase does not qualify.
 // Each phase records the latest earlier phase it conflicts with (it reads what
 // that phase wrote, or writes what that phase read or wrote); with `ordered`
@@ -194,30 +312,10 @@ std::vector<StreamPhase> stream_table(const nvq_linear *L, const std::vector<Pha
         tab.push_back(sp);
     }
     const size_t P = tab.size();
-    std::vector<Range> xin(P);
-    std::vector<std::vector<Range>> yout(P);
-    for (size_t p = 0; p < P; ++p) {
-        const nvq_linear &e0 = L[phases[p].first];
-        xin[p] = {(uintptr_t)e0.x_bf16, (uintptr_t)e0.x_bf16 + (size_t)M * e0.K * 2};
-        for (int k = 0; k < phases[p].count; ++k) {
-            const nvq_linear &e = L[phases[p].first + k];
-            const size_t bytes = (size_t)M * e.N * (e.y_dtype == NVQ_F32 ? 4 : 2);
-            yout[p].push_back({(uintptr_t)e.y, (uintptr_t)e.y + bytes});
-        }
-    }
+    const std::vector<int> deps = phase_deps(L, phases, M, ordered);
     for (size_t p = 1; p < P; ++p) {
-        int dep = ordered ? (int)p - 1 : -1;
-        for (size_t q = 0; q < p && !ordered; ++q) {
-            bool hit = false;
-            for (const Range &yq : yout[q]) {
-                hit = hit || overlap(xin[p], yq);  // read after write
-                for (const Range &yp : yout[p]) hit = hit || overlap(yp, yq);  // write after write
-            }
-            for (const Range &yp : yout[p]) hit = hit || overlap(yp, xin[q]);  // write after read
-            if (hit) dep = (int)q;
-        }
-        tab[p].wait_phase = dep;
-        if (dep >= 0) tab[dep].publish = 1;
+        tab[p].wait_phase = deps[p];
+        if (deps[p] >= 0) tab[deps[p]].publish = 1;
     }
     // Activation images.  A phase that waits for nothing gets its image
     // prepared in global memory.  In LDS the images of consecutive phases are
@@ -276,16 +374,16 @@ struct nvq_plan {
     int nphase;        // entries of the device phase table
     int nwaits;        // phases that wait for an earlier phase (streaming kernel)
     int nimages;       // phases whose activation image is prepared in the prologue
+    std::vector<nvq::GroupBatch> batches;  // grouped small-batch launches (empty: not used)
     uint32_t runs;     // walks issued so far (advances the flag base)
     unsigned long long *trace;  // device buffer for per-phase timestamps, or nullptr
 };
 
 extern "C" size_t nvq_decode_workspace_bytes(const nvq_linear *layers, int n, int M,
                                              int act_group) {
-    int maxK = 0;
-    size_t ib = 0;
-    if (nvq::check_layers(layers, n, M, act_group, &maxK, &ib) != NVQ_OK) return 0;
-    return nvq::carve(nullptr, maxK, M, n, ib).bytes;
+    nvq::ListSizes ls;
+    if (nvq::check_layers(layers, n, M, act_group, &ls) != NVQ_OK) return 0;
+    return nvq::carve(nullptr, M, n, ls).bytes;
 }
 
 extern "C" int nvq_plan_create(const nvq_linear *layers, int n, int M, int act_group, int flags,
@@ -294,12 +392,11 @@ extern "C" int nvq_plan_create(const nvq_linear *layers, int n, int M, int act_g
     using namespace nvq;
     if (!plan_out || (flags & ~NVQ_PLAN_ORDERED)) return NVQ_ERR_INVALID_ARG;
     *plan_out = nullptr;
-    int maxK = 0;
-    size_t ib = 0;
-    const int rc = check_layers(layers, n, M, act_group, &maxK, &ib);
+    ListSizes ls;
+    const int rc = check_layers(layers, n, M, act_group, &ls);
     if (rc != NVQ_OK) return rc;
     if (!workspace || !aligned(workspace, 256)) return NVQ_ERR_WORKSPACE;
-    const Workspace ws = carve(workspace, maxK, M, n, ib);
+    const Workspace ws = carve(workspace, M, n, ls);
     if (workspace_bytes < ws.bytes) return NVQ_ERR_WORKSPACE;
     nvq_plan *pl = new (std::nothrow) nvq_plan();
     if (!pl) return NVQ_ERR_UNSUPPORTED;
@@ -338,6 +435,27 @@ extern "C" int nvq_plan_create(const nvq_linear *layers, int n, int M, int act_g
         pl->nphase = (int)tab.size();
         pl->nimages = nimages;
         for (const StreamPhase &sp : tab) pl->nwaits += sp.wait_phase >= 0;
+    } else if (n > 0) {
+        const GroupPlan gp = group_plan(pl->layers.data(), pl->phases, M, act_group,
+                                        (flags & NVQ_PLAN_ORDERED) != 0, ws);
+        if (!gp.tab.empty()) {
+            // pageable sources: the copies have left the host buffers when the calls return
+            hipError_t e = hipMemcpyAsync(ws.gtab, gp.tab.data(), gp.tab.size() * sizeof(GroupPhase),
+                                          hipMemcpyHostToDevice, st);
+            if (e == hipSuccess && !gp.jobs.empty())
+                e = hipMemcpyAsync(ws.gjobs, gp.jobs.data(), gp.jobs.size() * 2,
+                                   hipMemcpyHostToDevice, st);
+            if (e == hipSuccess)
+                e = hipMemcpyAsync(ws.gunits, gp.units.data(), gp.units.size() * 2,
+                                   hipMemcpyHostToDevice, st);
+            if (e != hipSuccess) {
+                set_hip_error(e, "nvq_plan_create");
+                delete pl;
+                return NVQ_ERR_HIP;
+            }
+            pl->batches = gp.batches;
+            pl->nwaits = (int)gp.batches.size() - 1;
+        }
     }
     *plan_out = pl;
     return NVQ_OK;
@@ -353,6 +471,17 @@ extern "C" int nvq_plan_run(nvq_plan *pl, void *stream) {
         ++pl->runs;
         return launch_decode_stream(pl->ws.tab, pl->nphase, pl->nimages, pl->act_group, pl->ws.flags,
                                     pl->ws.status, base, pl->ws.dummy, pl->nwg, pl->trace, st);
+    }
+    if (!pl->batches.empty()) {
+        for (const GroupBatch &b : pl->batches) {
+            int rc = launch_quant_act_group(pl->ws.gtab, pl->ws.gjobs + b.job_first, b.njobs, pl->M,
+                                            st);
+            if (rc != NVQ_OK) return rc;
+            rc = launch_gemv_mfma_group(pl->ws.gtab, pl->ws.gunits + b.unit_first, b.nunits, pl->M,
+                                        st);
+            if (rc != NVQ_OK) return rc;
+        }
+        return NVQ_OK;
     }
     return walk_per_phase(pl->layers.data(), pl->phases, pl->M, pl->act_group, pl->ws, st);
 }
@@ -389,9 +518,8 @@ extern "C" void nvq_plan_destroy(nvq_plan *pl) { delete pl; }
 extern "C" int nvq_decode_linears(const nvq_linear *layers, int n, int M, int act_group,
                                   void *workspace, size_t workspace_bytes, void *stream) {
     if (n == 0) {
-        int maxK = 0;
-        size_t ib = 0;
-        return nvq::check_layers(layers, n, M, act_group, &maxK, &ib);
+        nvq::ListSizes ls;
+        return nvq::check_layers(layers, n, M, act_group, &ls);
     }
     nvq_plan *pl = nullptr;
     int rc = nvq_plan_create(layers, n, M, act_group, NVQ_PLAN_DEFAULT, workspace, workspace_bytes,

@@ -171,12 +171,17 @@ struct Column {
 // the columns w, w + W, ... of those rows, B columns per pass: every load of a
 // pass is requested before the first MFMA, so a wave has B * R KiB of weights
 // in flight and the compute units overlap the passes of their resident waves.
+//
+// mfma_units works through the units unit_first, unit_first + unit_step, ...
+// of one phase (a unit = 16 * R rows); `red` is W x (R * MT * 4) x 64 floats
+// of LDS.
 template <int PREC, int R, int MT, int W, int B, bool DEBUG>
-__global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(
-    GemvSegs S, int G, int M, const char *__restrict__ xin, const float *__restrict__ xscale) {
+__device__ __forceinline__ void mfma_units(const GemvSegs &S, int G, int M,
+                                           const char *__restrict__ xin,
+                                           const float *__restrict__ xscale, int unit_first,
+                                           int unit_step, float (*red)[R * MT * 4][64]) {
     typedef Act<PREC> A;
     constexpr int kTile = R * MT * 4;  // result registers per lane
-    __shared__ float red[W][kTile][64];
 
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int n = lane & 15, kb = lane >> 4;
@@ -203,7 +208,7 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(
             xs[mt][jj] = (PREC == NVQ_W4A8 && m < M) ? xscale[m] : 1.0f;
         }
 
-    for (int unit = blockIdx.x; unit < units; unit += gridDim.x) {
+    for (int unit = unit_first; unit < units; unit += unit_step) {
         RowRef rr[R];
 #pragma unroll
         for (int r = 0; r < R; ++r) rr[r] = locate_row(S, (unit * R + r) * 16 + n, G);
@@ -315,6 +320,32 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(
 }
 
 template <int PREC, int R, int MT, int W, int B, bool DEBUG>
+__global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(
+    GemvSegs S, int G, int M, const char *__restrict__ xin, const float *__restrict__ xscale) {
+    __shared__ float red[W][R * MT * 4][64];
+    mfma_units<PREC, R, MT, W, B, DEBUG>(S, G, M, xin, xscale, blockIdx.x, gridDim.x, red);
+}
+
+// Grouped launch: the row tiles of many phases in one grid, one tile per
+// workgroup.  unit_phase[u] names the phase of grid unit u.
+constexpr int kGroupWaves = 8;
+template <int MT>
+__global__ __launch_bounds__(kGroupWaves * 64) void gemv_mfma_group_kernel(
+    const GroupPhase *__restrict__ tab, const uint16_t *__restrict__ unit_phase, int M) {
+    __shared__ float red[kGroupWaves][MT * 4][64];
+    const int u = blockIdx.x;
+    const GroupPhase &P = tab[unit_phase[u]];
+    const int unit = u - P.unit_begin;
+    // one pass of the unit loop: the step is larger than any unit count
+    if (P.precision == NVQ_W4A8)
+        mfma_units<NVQ_W4A8, 1, MT, kGroupWaves, 2, false>(
+            P.segs, P.G, M, reinterpret_cast<const char *>(P.xq), P.xscale, unit, 1 << 30, red);
+    else
+        mfma_units<NVQ_W4A16, 1, MT, kGroupWaves, 2, false>(
+            P.segs, P.G, M, reinterpret_cast<const char *>(P.x_bf16), nullptr, unit, 1 << 30, red);
+}
+
+template <int PREC, int R, int MT, int W, int B, bool DEBUG>
 int launch_one(const GemvSegs &S, int G, int M, const void *x, const float *xscale,
                hipStream_t st) {
     const int units = (S.total_rows + 16 * R - 1) / (16 * R);
@@ -352,6 +383,18 @@ bool gemv_mfma_supported(const GemvSegs &S, int K, int M) {
     for (int i = 0; i < S.nseg; ++i)
         if (!aligned(S.sc[i], 8)) return false;
     return true;
+}
+
+int launch_gemv_mfma_group(const GroupPhase *tab, const uint16_t *unit_phase, int nunits, int M,
+                           hipStream_t st) {
+    if (nunits <= 0) return NVQ_OK;
+    const dim3 grid(nunits), block(kGroupWaves * 64);
+    if (M > 16)
+        hipLaunchKernelGGL(gemv_mfma_group_kernel<2>, grid, block, 0, st, tab, unit_phase, M);
+    else
+        hipLaunchKernelGGL(gemv_mfma_group_kernel<1>, grid, block, 0, st, tab, unit_phase, M);
+    NVQ_HIP_TRY(hipGetLastError());
+    return NVQ_OK;
 }
 
 int launch_gemv_mfma(const GemvSegs &S, int K, int precision, const void *x, const float *xscale,

@@ -55,6 +55,25 @@ bool gemv_mfma_supported(const GemvSegs &segs, int K, int M);
 int launch_gemv_mfma(const GemvSegs &segs, int K, int precision, const void *x,
                      const float *xscale, int M, hipStream_t st);
 
+// One phase of a grouped small-batch launch (lives in device memory): the
+// activation quantisation of all its tokens (W4A8) and the matrix-core product
+// of its row tiles run in grids shared with the other phases of its batch.
+struct GroupPhase {
+    GemvSegs segs;           // accumulator dumps unused
+    const uint16_t *x_bf16;  // [M][K] input
+    int8_t *xq;              // [M][K]   codes      (W4A8 phases, workspace)
+    float *xscale;           // [M]      scales
+    int32_t *xgsum;          // [M][K/32] code sums
+    int G, precision;
+    int unit_begin;          // first grid unit (16-row tile) of the phase in its batch
+};
+// jobs[j] names the phase whose M tokens grid blocks j*M .. j*M+M-1 quantise.
+int launch_quant_act_group(const GroupPhase *tab, const uint16_t *jobs, int njobs, int M,
+                           hipStream_t st);
+// unit_phase[u] names the phase of grid unit u.
+int launch_gemv_mfma_group(const GroupPhase *tab, const uint16_t *unit_phase, int nunits, int M,
+                           hipStream_t st);
+
 // ---- device helpers -------------------------------------------------------
 #if defined(__HIPCC__)
 

@@ -32,11 +32,11 @@ __device__ __forceinline__ int quant_one(float x, float s) {
     return (int)r;
 }
 
+// Token m of one [M][K] input, by one workgroup.
 template <bool PER_GROUP>
-__global__ __launch_bounds__(kQuantThreads) void quant_act_kernel(
-    const uint4 *__restrict__ x, int K, int8_t *__restrict__ xq, float *__restrict__ xscale,
-    int32_t *__restrict__ xgsum) {
-    const int m = blockIdx.x;
+__device__ __forceinline__ void quant_token(const uint4 *__restrict__ x, int K, int m,
+                                            int8_t *__restrict__ xq, float *__restrict__ xscale,
+                                            int32_t *__restrict__ xgsum) {
     const int chunks = K / 8;  // multiple of 4
     const int G = K / 32;
     const uint4 *xr = x + (int64_t)m * chunks;
@@ -91,6 +91,31 @@ __global__ __launch_bounds__(kQuantThreads) void quant_act_kernel(
         sum += __shfl_xor(sum, 2, 64);
         if ((c & 3) == 0) gs[c >> 2] = sum;
     }
+}
+
+template <bool PER_GROUP>
+__global__ __launch_bounds__(kQuantThreads) void quant_act_kernel(
+    const uint4 *__restrict__ x, int K, int8_t *__restrict__ xq, float *__restrict__ xscale,
+    int32_t *__restrict__ xgsum) {
+    quant_token<PER_GROUP>(x, K, blockIdx.x, xq, xscale, xgsum);
+}
+
+// Per-token scales, the inputs of many phases in one grid.
+__global__ __launch_bounds__(kQuantThreads) void quant_act_group_kernel(
+    const GroupPhase *__restrict__ tab, const uint16_t *__restrict__ jobs, int M) {
+    const int job = blockIdx.x / M, m = blockIdx.x - job * M;
+    const GroupPhase &P = tab[jobs[job]];
+    quant_token<false>(reinterpret_cast<const uint4 *>(P.x_bf16), P.G * 32, m, P.xq, P.xscale,
+                       P.xgsum);
+}
+
+int launch_quant_act_group(const GroupPhase *tab, const uint16_t *jobs, int njobs, int M,
+                           hipStream_t st) {
+    if (njobs <= 0) return NVQ_OK;
+    hipLaunchKernelGGL(quant_act_group_kernel, dim3(njobs * M), dim3(kQuantThreads), 0, st, tab,
+                       jobs, M);
+    NVQ_HIP_TRY(hipGetLastError());
+    return NVQ_OK;
 }
 
 int launch_quant_act(const uint16_t *x, int M, int K, int act_group, int8_t *xq, float *xscale,

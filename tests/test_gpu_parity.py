@@ -401,3 +401,64 @@ def test_streaming_plan_orders_dependent_phases():
                                               precision=i % 2)], 1)[0]
             assert np_ref.rel_l2(bufs[i + 1].float().cpu().numpy(), y_r) < 4e-3, (rep, i)
     dl.close()
+
+
+# ---- grouped small-batch walker (2..32 tokens on the matrix cores) -------------------
+@pytest.mark.parametrize("name,M,ordered", [("1b", 5, False), ("1b", 20, True), ("8b", 16, False),
+                                            ("8b", 32, False)])
+def test_grouped_plan_matches_oracle_on_repeated_runs(name, M, ordered):
+    say("grouped plan", name, M, ordered)
+    shapes, bits = STREAM_MODELS[name]
+    entries, host = model_entries(shapes, bits, M=M, seed=8300)
+    ys_ref = oracle.decode_linears(host, M, 0)
+    dl = nvq.DecodeList(entries, M, 0, ordered=ordered)
+    info = dl.plan_info()
+    say("  plan", info)
+    assert not info["streaming"]
+    # "waits" counts the batch boundaries: independent buffers make one batch of all phases
+    assert info["waits"] == (info["phases"] - 1 if ordered else 0)
+    for rep in range(3):
+        for e in entries:
+            e["y"].zero_()
+        dl.run_plan()
+        torch.cuda.synchronize()
+        for e, y_r in zip(entries, ys_ref):
+            err = np_ref.rel_l2(e["y"].cpu().numpy(), y_r)
+            assert err < TOL, (rep, err)
+            assert err < 1e-5, (rep, err)
+    # the one-call entry point takes the same path
+    for e in entries:
+        e["y"].zero_()
+    nvq.decode_linears(entries, M, 0)
+    torch.cuda.synchronize()
+    for e, y_r in zip(entries, ys_ref):
+        assert np_ref.rel_l2(e["y"].cpu().numpy(), y_r) < 1e-5
+    dl.close()
+
+
+def test_grouped_plan_orders_dependent_phases():
+    say("grouped chain")
+    # four phases, each reading the bf16 output of the one before it: four batches
+    M = 6
+    dims = [2048, 4096, 1024, 6144, 512]
+    hostW = [oracle.pack_int4(synth.make_weight(8900 + i, dims[i + 1], dims[i]).numpy())
+             for i in range(4)]
+    x0 = act(8999, M, dims[0])
+    bufs = [x0.to(DEV)] + [torch.zeros((M, d), dtype=torch.bfloat16, device=DEV) for d in dims[1:]]
+    entries = []
+    for i, (q, s) in enumerate(hostW):
+        qd, sd = to_dev_packed(q, s)
+        entries.append(dict(qweight=qd, scales=sd, x=bufs[i], y=bufs[i + 1], precision=i % 2))
+    dl = nvq.DecodeList(entries, M)
+    info = dl.plan_info()
+    assert not info["streaming"] and info["waits"] == 3      # the analysis found the chain
+    for rep in range(2):
+        for b in bufs[1:]:
+            b.zero_()
+        dl.run_plan()
+        torch.cuda.synchronize()
+        for i, (q, s) in enumerate(hostW):
+            y_r = oracle.decode_linears([dict(qweight=q, scales=s, x=u16(bufs[i]),
+                                              precision=i % 2)], M)[0]
+            assert np_ref.rel_l2(bufs[i + 1].float().cpu().numpy(), y_r) < 4e-3, (rep, i)
+    dl.close()
