@@ -263,9 +263,10 @@ GroupPlan group_plan(const nvq_linear *L, const std::vector<Phase> &phases, int 
             gp.jobs.push_back((uint16_t)p);
             ++cur.njobs;
         }
-        const int tiles = (g.segs.total_rows + 15) / 16;
-        gp.units.insert(gp.units.end(), (size_t)tiles, (uint16_t)p);
-        cur.nunits += tiles;
+        const int rows_per_unit = 16 * group_row_tiles(M);
+        const int units = (g.segs.total_rows + rows_per_unit - 1) / rows_per_unit;
+        gp.units.insert(gp.units.end(), (size_t)units, (uint16_t)p);
+        cur.nunits += units;
         gp.tab.push_back(g);
     }
     gp.batches.push_back(cur);

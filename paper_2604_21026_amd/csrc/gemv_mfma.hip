@@ -46,8 +46,23 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned uint2v __attribute__((ext_vector_type(2)));
 typedef unsigned uint4v __attribute__((ext_vector_type(4)));
 
+// Pointers that come out of a table in memory are generic to the compiler;
+// every access here is to global memory, and saying so keeps the loads off the
+// slower flat path.
+template <typename T>
+__device__ __forceinline__ const __attribute__((address_space(1))) T *as_global(const void *p) {
+    return (const __attribute__((address_space(1))) T *)p;
+}
+
+__device__ __forceinline__ void store_global(void *y, int y_dtype, int64_t idx, float v) {
+    if (y_dtype == NVQ_F32)
+        ((__attribute__((address_space(1))) float *)y)[idx] = v;
+    else
+        ((__attribute__((address_space(1))) uint16_t *)y)[idx] = float_to_bf16_bits(v);
+}
+
 __device__ __forceinline__ uint4v load_stream(const uint4 *p) {
-    return __builtin_nontemporal_load(reinterpret_cast<const uint4v *>(p));
+    return __builtin_nontemporal_load(as_global<uint4v>(p));
 }
 
 // r[j] of lane-row kb holds element (kb, j) of a 4x4 matrix of dwords (one
@@ -76,8 +91,8 @@ struct Act<NVQ_W4A8> {
     static constexpr int kRaw = 2;
     static constexpr int kLaneBytes = 32;  // byte offset of lane-row kb: kb * 32
     __device__ static void load(const char *p, uint4v (&raw)[kRaw]) {
-        raw[0] = *reinterpret_cast<const uint4v *>(p);
-        raw[1] = *reinterpret_cast<const uint4v *>(p + 16);
+        raw[0] = *as_global<uint4v>(p);
+        raw[1] = *as_global<uint4v>(p + 16);
     }
     // Operands of groups 0..3: dword kb of each half (codes 4kb..4kb+3 and
     // 16+4kb..16+4kb+3), the choice the weight operand makes.
@@ -117,7 +132,7 @@ struct Act<NVQ_W4A16> {
     static constexpr int kLaneBytes = 16;
     __device__ static void load(const char *p, uint4v (&raw)[kRaw]) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) raw[i] = *reinterpret_cast<const uint4v *>(p + 64 * i);
+        for (int i = 0; i < 4; ++i) raw[i] = *as_global<uint4v>(p + 64 * i);
     }
     // Lane-row kb needs activations 4kb..4kb+3 and 16+4kb..16+4kb+3 of a group:
     // the first or second half of piece kb/2 and of piece 2 + kb/2.  For the
@@ -205,7 +220,7 @@ __device__ __forceinline__ void mfma_units(const GemvSegs &S, int G, int M,
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
             const int m = mt * 16 + kb * 4 + jj;
-            xs[mt][jj] = (PREC == NVQ_W4A8 && m < M) ? xscale[m] : 1.0f;
+            xs[mt][jj] = (PREC == NVQ_W4A8 && m < M) ? as_global<float>(xscale)[m] : 1.0f;
         }
 
     for (int unit = unit_first; unit < units; unit += unit_step) {
@@ -234,7 +249,7 @@ __device__ __forceinline__ void mfma_units(const GemvSegs &S, int G, int M,
 #pragma unroll
                 for (int r = 0; r < R; ++r) {
                     col[b].w[r] = load_stream(rr[r].qw + 4 * cc + kb);
-                    const uint2 sc = *reinterpret_cast<const uint2 *>(rr[r].sc + 4 * cc);
+                    const uint2v sc = *as_global<uint2v>(rr[r].sc + 4 * cc);
                     // a column past the end of the row contributes zero
                     col[b].s[r] = make_uint2(ok ? sc.x : 0u, ok ? sc.y : 0u);
                 }
@@ -312,7 +327,7 @@ __device__ __forceinline__ void mfma_units(const GemvSegs &S, int G, int M,
                 const int r = reg / (MT * 4), mt = (reg >> 2) % MT, jj = reg & 3;
                 const int m = mt * 16 + kb * 4 + jj;
                 const RowRef o = locate_row(S, (unit * R + r) * 16 + n, G);
-                if (o.valid && m < M) store_out(o.y, o.y_dtype, (int64_t)m * o.N + o.n, sum);
+                if (o.valid && m < M) store_global(o.y, o.y_dtype, (int64_t)m * o.N + o.n, sum);
             }
         }
         __syncthreads();
@@ -329,19 +344,19 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(
 // Grouped launch: the row tiles of many phases in one grid, one tile per
 // workgroup.  unit_phase[u] names the phase of grid unit u.
 constexpr int kGroupWaves = 8;
-template <int MT>
+template <int MT, int R>
 __global__ __launch_bounds__(kGroupWaves * 64) void gemv_mfma_group_kernel(
     const GroupPhase *__restrict__ tab, const uint16_t *__restrict__ unit_phase, int M) {
-    __shared__ float red[kGroupWaves][MT * 4][64];
+    __shared__ float red[kGroupWaves][R * MT * 4][64];
     const int u = blockIdx.x;
     const GroupPhase &P = tab[unit_phase[u]];
     const int unit = u - P.unit_begin;
     // one pass of the unit loop: the step is larger than any unit count
     if (P.precision == NVQ_W4A8)
-        mfma_units<NVQ_W4A8, 1, MT, kGroupWaves, 2, false>(
+        mfma_units<NVQ_W4A8, R, MT, kGroupWaves, 2, false>(
             P.segs, P.G, M, reinterpret_cast<const char *>(P.xq), P.xscale, unit, 1 << 30, red);
     else
-        mfma_units<NVQ_W4A16, 1, MT, kGroupWaves, 2, false>(
+        mfma_units<NVQ_W4A16, R, MT, kGroupWaves, 2, false>(
             P.segs, P.G, M, reinterpret_cast<const char *>(P.x_bf16), nullptr, unit, 1 << 30, red);
 }
 
@@ -390,9 +405,9 @@ int launch_gemv_mfma_group(const GroupPhase *tab, const uint16_t *unit_phase, in
     if (nunits <= 0) return NVQ_OK;
     const dim3 grid(nunits), block(kGroupWaves * 64);
     if (M > 16)
-        hipLaunchKernelGGL(gemv_mfma_group_kernel<2>, grid, block, 0, st, tab, unit_phase, M);
+        hipLaunchKernelGGL((gemv_mfma_group_kernel<2, 2>), grid, block, 0, st, tab, unit_phase, M);
     else
-        hipLaunchKernelGGL(gemv_mfma_group_kernel<1>, grid, block, 0, st, tab, unit_phase, M);
+        hipLaunchKernelGGL((gemv_mfma_group_kernel<1, 2>), grid, block, 0, st, tab, unit_phase, M);
     NVQ_HIP_TRY(hipGetLastError());
     return NVQ_OK;
 }

@@ -65,12 +65,15 @@ struct GroupPhase {
     float *xscale;           // [M]      scales
     int32_t *xgsum;          // [M][K/32] code sums
     int G, precision;
-    int unit_begin;          // first grid unit (16-row tile) of the phase in its batch
+    int unit_begin;          // first grid unit of the phase in its batch
 };
 // jobs[j] names the phase whose M tokens grid blocks j*M .. j*M+M-1 quantise.
 int launch_quant_act_group(const GroupPhase *tab, const uint16_t *jobs, int njobs, int M,
                            hipStream_t st);
-// unit_phase[u] names the phase of grid unit u.
+// unit_phase[u] names the phase of grid unit u; a unit is group_row_tiles(M)
+// consecutive 16-row tiles, which share their activation operands (as many as
+// fit the registers next to one or two token tiles).
+static inline int group_row_tiles(int M) { (void)M; return 2; }
 int launch_gemv_mfma_group(const GroupPhase *tab, const uint16_t *unit_phase, int nunits, int M,
                            hipStream_t st);
 
