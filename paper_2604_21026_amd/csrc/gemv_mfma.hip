@@ -61,8 +61,12 @@ __device__ __forceinline__ void store_global(void *y, int y_dtype, int64_t idx, 
         ((__attribute__((address_space(1))) uint16_t *)y)[idx] = float_to_bf16_bits(v);
 }
 
+// Weights are loaded through the caches: a wave reads 64 bytes of each of 16
+// rows per load and its neighbours read the other halves of the same 128-byte
+// lines a little later; with non-temporal loads a third of the lines was
+// fetched from HBM twice.
 __device__ __forceinline__ uint4v load_stream(const uint4 *p) {
-    return __builtin_nontemporal_load(as_global<uint4v>(p));
+    return *as_global<uint4v>(p);
 }
 
 // r[j] of lane-row kb holds element (kb, j) of a 4x4 matrix of dwords (one
@@ -343,7 +347,7 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(
 
 // Grouped launch: the row tiles of many phases in one grid, one tile per
 // workgroup.  unit_phase[u] names the phase of grid unit u.
-constexpr int kGroupWaves = 8;
+constexpr int kGroupWaves = 4;
 template <int MT, int R>
 __global__ __launch_bounds__(kGroupWaves * 64) void gemv_mfma_group_kernel(
     const GroupPhase *__restrict__ tab, const uint16_t *__restrict__ unit_phase, int M) {
