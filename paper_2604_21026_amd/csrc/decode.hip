@@ -283,6 +283,7 @@ std::vector<StreamPhase> stream_table(const nvq_linear *L, const std::vector<Pha
     std::vector<StreamPhase> tab;
     if (M != 1 || nwg <= 0 || nwg > kMaxStreamWg) return tab;
     const int waves = nwg * kStreamWaves;
+    int rot = 0;  // first wave of the next phase's extra rows
     for (const Phase &ph : phases) {
         const nvq_linear &e0 = L[ph.first];
         const int G = e0.K / 32;
@@ -305,7 +306,10 @@ std::vector<StreamPhase> stream_table(const nvq_linear *L, const std::vector<Pha
         sp.G = G;
         sp.gpl = (G + 63) / 64;
         sp.precision = e0.precision;
-        sp.rows_per_wave = (rows + waves - 1) / waves;
+        sp.rows_base = rows / waves;
+        sp.rows_extra = rows - sp.rows_base * waves;
+        sp.rows_rot = rot;
+        rot = (rot + sp.rows_extra) % waves;
         sp.wait_phase = -1;
         sp.publish = 0;
         sp.img = nullptr;

@@ -23,7 +23,11 @@ struct StreamPhase {
     int nseg, total_rows;
     int K, G, gpl;         // G = K/32 (even), gpl = ceil(G/64) <= 7
     int precision;         // NVQ_W4A8 | NVQ_W4A16
-    int rows_per_wave;     // ceil(total_rows / (workgroups * kStreamWaves))
+    // Rows are dealt to the W = workgroups * kStreamWaves waves as evenly as whole
+    // rows allow: wave j' = (wave - rows_rot) mod W takes rows_base rows, one more
+    // if j' < rows_extra, in order of j'.  rows_rot advances from phase to phase
+    // so that the waves with the extra row change.
+    int rows_base, rows_extra, rows_rot;
     int wait_phase;        // latest earlier phase this one depends on, or -1
     int publish;           // 1 if a later phase depends on this one
     int img_chunks;        // KiB chunks of the prepared image (0 if built in the kernel)
@@ -35,6 +39,18 @@ struct StreamPhase {
 // Workgroups the streaming kernel may be launched with (all must be
 // co-resident): the number of compute units, or 0 if the kernel does not fit.
 int stream_grid_limit();
+
+#if defined(__HIPCC__)
+// First row and row count of wave `gw` (of `waves`) in a phase.
+__device__ __forceinline__ void stream_wave_rows(int rows_base, int rows_extra, int rows_rot,
+                                                 int gw, int waves, int &first, int &count) {
+    int j = gw - rows_rot;
+    j = j < 0 ? j + waves : j;
+    const int more = j < rows_extra ? j : rows_extra;
+    first = j * rows_base + more;
+    count = rows_base + (j < rows_extra ? 1 : 0);
+}
+#endif
 
 // Bytes of the activation image of a layer with K inputs, padded to whole KiB.
 static inline int stream_image_bytes(int K, int precision, int act_group) {

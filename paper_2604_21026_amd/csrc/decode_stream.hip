@@ -205,9 +205,11 @@ __device__ __forceinline__ void issue_next_run(Issue &c, CPhase *tab, int nphase
         CPhase &ph = tab[c.p];
         if (c.part == 0) {
             c.part = 1;
-            c.row = gw * ph.rows_per_wave;
-            const int stop = c.row + ph.rows_per_wave;
-            c.row_stop = stop < ph.total_rows ? stop : ph.total_rows;
+            int first, count;
+            stream_wave_rows(ph.rows_base, ph.rows_extra, ph.rows_rot, gw,
+                             (int)gridDim.x * kStreamWaves, first, count);
+            c.row = first;
+            c.row_stop = first + count;
         }
         if (c.row < c.row_stop) {
             int first = 0, end = ph.row_end[0];
@@ -703,10 +705,9 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
 
         // ---- this wave's weight rows ---------------------------------------------------
         const int gpl = ph.gpl;
-        const int r0 = gw * ph.rows_per_wave;
-        int r1 = r0 + ph.rows_per_wave;
-        r1 = r1 < ph.total_rows ? r1 : ph.total_rows;
-        const int nrows = r1 > r0 ? r1 - r0 : 0;
+        int r0, nrows;
+        stream_wave_rows(ph.rows_base, ph.rows_extra, ph.rows_rot, gw, nwg * kStreamWaves, r0, nrows);
+        const int r1 = r0 + nrows;
         const float xs =
             (w4a8 && !PER_GROUP) ? __uint_as_float(lds_read4(img + L.stok)) : 1.0f;
         const uint32_t plane = (uint32_t)G * 16u;
