@@ -273,6 +273,25 @@ GroupPlan group_plan(const nvq_linear *L, const std::vector<Phase> &phases, int 
     return gp;
 }
 
+// Start of the cyclic run of `len` entries of `load` with the smallest sum
+// (the first such run).
+int lightest_window(const std::vector<uint64_t> &load, int len) {
+    const int n = (int)load.size();
+    if (len <= 0 || len >= n) return 0;
+    uint64_t sum = 0;
+    for (int j = 0; j < len; ++j) sum += load[(size_t)j];
+    uint64_t best = sum;
+    int at = 0;
+    for (int s = 1; s < n; ++s) {
+        sum += load[(size_t)(s + len - 1) % n] - load[(size_t)s - 1];
+        if (sum < best) {
+            best = sum;
+            at = s;
+        }
+    }
+    return at;
+}
+
 // Phase table for the streaming kernel; empty if some phase does not qualify.
 // Each phase records the latest earlier phase it conflicts with (it reads what
 // that phase wrote, or writes what that phase read or wrote); with `ordered`
@@ -283,7 +302,9 @@ std::vector<StreamPhase> stream_table(const nvq_linear *L, const std::vector<Pha
     std::vector<StreamPhase> tab;
     if (M != 1 || nwg <= 0 || nwg > kMaxStreamWg) return tab;
     const int waves = nwg * kStreamWaves;
-    int rot = 0;  // first wave of the next phase's extra rows
+    // bytes of extra rows dealt to each wave so far: the extra rows of a phase
+    // go to the run of waves that has received the least
+    std::vector<uint64_t> extra_bytes((size_t)waves, 0);
     for (const Phase &ph : phases) {
         const nvq_linear &e0 = L[ph.first];
         const int G = e0.K / 32;
@@ -308,8 +329,9 @@ std::vector<StreamPhase> stream_table(const nvq_linear *L, const std::vector<Pha
         sp.precision = e0.precision;
         sp.rows_base = rows / waves;
         sp.rows_extra = rows - sp.rows_base * waves;
-        sp.rows_rot = rot;
-        rot = (rot + sp.rows_extra) % waves;
+        sp.rows_rot = lightest_window(extra_bytes, sp.rows_extra);
+        for (int j = 0; j < sp.rows_extra; ++j)
+            extra_bytes[(size_t)(sp.rows_rot + j) % waves] += (uint64_t)G * 18;
         sp.wait_phase = -1;
         sp.publish = 0;
         sp.img = nullptr;

@@ -25,8 +25,9 @@ struct StreamPhase {
     int precision;         // NVQ_W4A8 | NVQ_W4A16
     // Rows are dealt to the W = workgroups * kStreamWaves waves as evenly as whole
     // rows allow: wave j' = (wave - rows_rot) mod W takes rows_base rows, one more
-    // if j' < rows_extra, in order of j'.  rows_rot advances from phase to phase
-    // so that the waves with the extra row change.
+    // if j' < rows_extra, in order of j'.  The host chooses rows_rot per phase so
+    // that the extra rows go to the waves that have received the fewest extra
+    // bytes so far.
     int rows_base, rows_extra, rows_rot;
     int wait_phase;        // latest earlier phase this one depends on, or -1
     int publish;           // 1 if a later phase depends on this one
