@@ -566,9 +566,19 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
         // ================= loader wave =================
         // Copies prepared images into LDS ahead of the streaming waves and
         // mirrors every workgroup barrier they execute.
-        int q = 0;  // first phase whose image has not been dealt with
-        // Load the image of independent phase q (blocks until its LDS region is
-        // free: every wave has finished phase img_need).  False on abort.
+        int q = 0;         // first phase whose image has not been dealt with
+        int pending = -1;  // phase whose image has been requested but not yet announced
+        // The requested image has landed: announce it.
+        auto flush = [&]() {
+            if (pending >= 0) {
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+                if (lane == 0) lds_write4(ready_a, (uint32_t)(pending + 1));
+                pending = -1;
+            }
+        };
+        // Request the image of independent phase q (blocks until its LDS region
+        // is free: every wave has finished phase img_need) and announce the one
+        // requested before it, so that two images are in flight.  False on abort.
         auto load_image = [&]() -> bool {
             CPhase &pq = tab[q];
             const uint32_t need = (uint32_t)(pq.img_need + 1);
@@ -584,6 +594,7 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
                     m = m < a.w ? m : a.w;
                 }
                 if ((uint32_t)__builtin_amdgcn_readfirstlane((int)m) >= need) break;
+                flush();  // the waves may be waiting for exactly that image
                 if (lds_read4_uniform(abort_a)) return false;
                 if (++spins > kSpinLimit) {
                     lds_write4(abort_a, 1u);
@@ -592,19 +603,34 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
                 __builtin_amdgcn_s_sleep(2);
             }
             const uint32_t dst = (uint32_t)pq.img_lds;
-            for (int j = 0; j < pq.img_chunks; ++j)
+            const int chunks = pq.img_chunks;
+            for (int j = 0; j < chunks; ++j)
                 __builtin_amdgcn_global_load_lds(
                     (const void *)(pq.img + j * 64 + lane),
                     (lds_void_ptr)(reinterpret_cast<char *>(sh.area) + dst + j * 1024), 16, 0, 0);
-            __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+            if (pending >= 0) {
+                // loads return in order: the older image is complete when at most
+                // the `chunks` loads just issued are outstanding
+                switch (chunks) {
+#define NVQ_W(n) case n: __builtin_amdgcn_s_waitcnt(vmcnt_imm(n)); break;
+                    NVQ_W(1) NVQ_W(2) NVQ_W(3) NVQ_W(4) NVQ_W(5) NVQ_W(6) NVQ_W(7) NVQ_W(8)
+                    NVQ_W(9) NVQ_W(10) NVQ_W(11) NVQ_W(12) NVQ_W(13) NVQ_W(14) NVQ_W(15) NVQ_W(16)
+                    NVQ_W(17) NVQ_W(18) NVQ_W(19) NVQ_W(20) NVQ_W(21) NVQ_W(22) NVQ_W(23) NVQ_W(24)
+                    NVQ_W(25) NVQ_W(26) NVQ_W(27) NVQ_W(28) NVQ_W(29) NVQ_W(30) NVQ_W(31)
+#undef NVQ_W
+                    default: __builtin_amdgcn_s_waitcnt(vmcnt_imm(0)); break;
+                }
+                if (lane == 0) lds_write4(ready_a, (uint32_t)(pending + 1));
+            }
+            pending = q;
             ++q;
-            if (lane == 0) lds_write4(ready_a, (uint32_t)q);
             return true;
         };
         bool live = true;
         for (int p = 0; p < nphase && live; ++p) {
             CPhase &ph = tab[p];
             if (ph.wait_phase >= 0) {
+                flush();
                 lds_barrier();  // dependency satisfied
                 if (lds_read4_uniform(abort_a)) break;
                 const LdsWriter wr = {0};
@@ -618,8 +644,12 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
             while (live && q < nphase && q <= p + kLookahead && tab[q].wait_phase < 0 &&
                    tab[q].img_need < p)
                 live = load_image();
-            if (ph.publish && live) lds_barrier();
+            if (ph.publish && live) {
+                flush();
+                lds_barrier();
+            }
         }
+        flush();
         return;
     }
 
