@@ -24,7 +24,6 @@ namespace {
 
 size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-constexpr int kMaxStreamWg = 1024;  // flag words reserved in the workspace
 
 // Workspace layout (offsets from a 256-byte aligned base).
 struct Workspace {
@@ -32,8 +31,9 @@ struct Workspace {
     float *xscale;      // [M][maxK/32]
     int32_t *xgsum;     // [M][maxK/32]
     StreamPhase *tab;   // [n]                 phase table of the streaming kernel
-    uint32_t *flags;    // [kMaxStreamWg]      one word per workgroup
+    uint32_t *flags;    // [kStreamMaxWg]      one word per workgroup
     uint32_t *status;   // [64]                word 0: a wait timed out
+    uint32_t *imgflags; // [n]                 one word per phase (follows the status words)
     void *dummy;        // 1 KiB               target of the ring's filler loads
     char *images;       // prepared activation images of the streaming kernel
     GroupPhase *gtab;   // [n]                 phase table of the grouped small-batch launches
@@ -72,8 +72,9 @@ Workspace carve(void *base, int M, int n, const ListSizes &ls) {
     w.xscale = reinterpret_cast<float *>(take((size_t)M * G * 4));
     w.xgsum = reinterpret_cast<int32_t *>(take((size_t)M * G * 4));
     w.tab = reinterpret_cast<StreamPhase *>(take((size_t)(n > 0 ? n : 1) * sizeof(StreamPhase)));
-    w.flags = reinterpret_cast<uint32_t *>(take(kMaxStreamWg * 4));
+    w.flags = reinterpret_cast<uint32_t *>(take(kStreamMaxWg * 4));
     w.status = reinterpret_cast<uint32_t *>(take(256));
+    w.imgflags = reinterpret_cast<uint32_t *>(take((size_t)(n > 0 ? n : 1) * 4));
     w.dummy = take(1024);
     w.images = take(image_bytes);
     const size_t nn = (size_t)(n > 0 ? n : 1);
@@ -300,7 +301,7 @@ std::vector<StreamPhase> stream_table(const nvq_linear *L, const std::vector<Pha
                                       int act_group, int nwg, bool ordered, char *images,
                                       int *nimages) {
     std::vector<StreamPhase> tab;
-    if (M != 1 || nwg <= 0 || nwg > kMaxStreamWg) return tab;
+    if (M != 1 || nwg <= 0 || nwg > kStreamMaxWg) return tab;
     const int waves = nwg * kStreamWaves;
     // bytes of extra rows dealt to each wave so far: the extra rows of a phase
     // go to the run of waves that has received the least
@@ -449,8 +450,9 @@ extern "C" int nvq_plan_create(const nvq_linear *layers, int n, int M, int act_g
         hipError_t e = hipMemcpyAsync(ws.tab, tab.data(), tab.size() * sizeof(StreamPhase),
                                       hipMemcpyHostToDevice, st);
         if (e == hipSuccess) {
-            hipLaunchKernelGGL(fill_u32_kernel, dim3((kMaxStreamWg + 64 + 255) / 256), dim3(256), 0,
-                               st, ws.flags, kMaxStreamWg + 64, 0u);  // flags and status
+            const int words = kStreamImageFlags + n;  // workgroup flags, status, image flags
+            hipLaunchKernelGGL(fill_u32_kernel, dim3((words + 255) / 256), dim3(256), 0, st, ws.flags,
+                               words, 0u);
             e = hipGetLastError();
         }
         if (e != hipSuccess) {

@@ -10,6 +10,10 @@ constexpr int kStreamThreads = (kStreamWaves + 1) * 64;  // plus the loader wave
 constexpr int kStreamMaxK = 14336;     // widest input an activation image holds
 constexpr int kStreamImageMax = 31744;  // largest image, padded to whole KiB (bf16, K = 14336)
 constexpr int kStreamImageArea = 59392; // LDS bytes that hold the images of consecutive phases
+constexpr int kStreamMaxWg = 1024;      // flag words reserved for workgroups
+// Layout of the flag words: [0, kStreamMaxWg) one per workgroup, then 64 status
+// words, then one word per phase ("the prepared image of this phase is stored").
+constexpr int kStreamImageFlags = kStreamMaxWg + 64;
 
 // One phase = up to four weight matrices that read the same input vector.
 // Lives in device memory; every field is read wave-uniformly.
@@ -60,10 +64,11 @@ static inline int stream_image_bytes(int K, int precision, int act_group) {
     return (raw + 1023) / 1024 * 1024;
 }
 
-// Enqueue one walk.  `flags` holds one word per workgroup and `status` one
-// word (set to 1 if a wait timed out); both persist between runs of the same
-// table, with `flag_base` advanced by nphase + 2 per run (base + 1: images
-// ready, base + 2 + p: phase p published).  `nimages` = phases with a prepared
+// Enqueue one walk.  `flags` holds one word per workgroup, the status words
+// (`status` = flags + kStreamMaxWg; word 0 is set to 1 if a wait timed out) and
+// one word per phase; all persist between runs of the same table, with
+// `flag_base` advanced by nphase + 2 per run (image word = base + 1: the
+// phase's image is stored; workgroup word = base + 2 + p: phase p published).  `nimages` = phases with a prepared
 // image (0 skips the prologue).  `dummy` is any valid
 // 1 KiB of device memory.  `trace` is nullptr or nphase * 8 words that
 // receive workgroup 0's per-phase timestamps.

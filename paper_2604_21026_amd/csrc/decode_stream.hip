@@ -26,7 +26,8 @@
 // G x 16 bytes, plus per group the constant of the deferred offset correction
 // (-8*sum(codes) or -136*sum(x)), plus the scale(s).  For a phase that depends
 // on no earlier phase the image is built ONCE per step, in global memory, by
-// one workgroup in a prologue (instead of once per compute unit).  The loader
+// one workgroup in a prologue (instead of once per compute unit) and announced
+// through a flag word of its own; there is no grid-wide barrier.  The loader
 // wave copies images from there into a circular LDS area up to kLookahead
 // phases ahead and announces them through an LDS word; streaming waves report
 // the phases they have finished through one LDS word each, which tells the
@@ -525,33 +526,26 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
     }
 
     // ---- prologue: images of the phases that depend on no earlier phase, one
-    // ---- workgroup per phase; then everybody waits for everybody
+    // ---- workgroup per phase, each announced through the phase's flag word as
+    // ---- soon as it is stored (the loader waves wait for the images they copy,
+    // ---- nobody waits for all of them)
+    uint32_t *const img_flags = flags + kStreamImageFlags;
     if (nimages > 0) {
         for (int p = wg; p < nphase; p += nwg) {
             CPhase &ph = tab[p];
             if (ph.img) {
                 const GlobalWriter wr = {reinterpret_cast<char *>(const_cast<uint4 *>(ph.img))};
                 image_build<PER_GROUP>(wr, ph, sh, w, lane);
-                lds_barrier();  // sh.amax_part may be reused
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // this wave's image stores have completed
+                lds_barrier();                             // (and sh.amax_part may be reused)
+                if (w == 0) {
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+                    if (lane == 0)
+                        __hip_atomic_store(img_flags + p, flag_base + 1u, __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_AGENT);
+                }
             }
         }
-        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // this wave's image stores have completed
-        lds_barrier();
-        bool ok = true;
-        if (w == 0) {
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-            if (lane == 0)
-                __hip_atomic_store(flags + wg, flag_base + 1u, __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
-            ok = wait_flags(flags, nwg, flag_base + 1u, lane);
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-            if (!ok && lane == 0) {
-                lds_write4(lds_addr(&sh.abort), 1u);
-                __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-        }
-        lds_barrier();
-        if (lds_read4_uniform(lds_addr(&sh.abort))) return;
     }
     trace_mark(trace, wg, w, lane, 0, 3);  // prologue done
     const uint32_t area_base = lds_addr(sh.area);
@@ -575,6 +569,37 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
                 if (lane == 0) lds_write4(ready_a, (uint32_t)(pending + 1));
                 pending = -1;
             }
+        };
+        // Has the prologue of some workgroup stored the image of phase i yet?  The
+        // answer is needed for every image once; lane j looks at phase i + j, and
+        // everything up to the first missing image is remembered.  Blocks (bounded)
+        // until phase i itself is stored; false on abort.
+        int stored = 0;  // the images of all phases < stored are known to be stored
+        auto image_stored = [&](int i) -> bool {
+            uint32_t spins = 0;
+            while (i >= stored) {
+                flush();  // (its loads would otherwise be waited for with the flag loads)
+                const int j = stored + lane;
+                bool ok = true;
+                if (j < nphase && tab_generic[j].img != nullptr)
+                    ok = __hip_atomic_load(img_flags + j, __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_AGENT) == flag_base + 1u;
+                const uint64_t missing = ~__builtin_amdgcn_ballot_w64(ok);
+                const int run = missing ? __builtin_ctzll(missing) : 64;
+                if (run > 0) {
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+                    stored += run;
+                    continue;
+                }
+                if (lds_read4_uniform(abort_a)) return false;
+                if (++spins > kSpinLimit) {
+                    lds_write4(abort_a, 1u);
+                    __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    return false;
+                }
+                __builtin_amdgcn_s_sleep(4);
+            }
+            return true;
         };
         // Request the image of independent phase q (blocks until its LDS region
         // is free: every wave has finished phase img_need) and announce the one
@@ -602,6 +627,7 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
                 }
                 __builtin_amdgcn_s_sleep(2);
             }
+            if (!image_stored(q)) return false;
             const uint32_t dst = (uint32_t)pq.img_lds;
             const int chunks = pq.img_chunks;
             for (int j = 0; j < chunks; ++j)
