@@ -41,6 +41,8 @@ def lib():
         vp, i64, ci = C.c_void_p, C.c_int64, C.c_int
         L.orc_pack_int4.argtypes = [vp, i64, i64, vp, vp]
         L.orc_dequant_int4.argtypes = [vp, vp, i64, i64, vp]
+        L.orc_dequant_bf16.argtypes = [vp, vp, i64, i64, vp]
+        L.orc_dequant_bf16.restype = C.c_int
         L.orc_quant_act_i8.argtypes = [vp, i64, i64, ci, vp, vp, vp]
         L.orc_gemv_w4a8.argtypes = [vp, vp, i64, i64, vp, vp, ci, i64, vp, vp]
         L.orc_w4a8_acc_deferred.argtypes = [vp, i64, i64, vp, vp, i64, vp]
@@ -109,6 +111,16 @@ def dequant_int4(qweight, scales):
     Wd = np.empty((N, K), np.float64)
     _chk(lib().orc_dequant_int4(_p(q), _p(s), N, K, _p(Wd)), "dequant_int4")
     return Wd
+
+
+def dequant_bf16(qweight, scales):
+    """-> uint16 (bf16 bits) [N,K] with value bf16_rne(code * scale)."""
+    q = _arr(qweight, np.uint8, 2)
+    s = _arr(scales, np.uint16, 2)
+    N, K = q.shape[0], q.shape[1] * 2
+    out = np.empty((N, K), np.uint16)
+    _chk(lib().orc_dequant_bf16(_p(q), _p(s), N, K, _p(out)), "dequant_bf16")
+    return out
 
 
 def quant_act_i8(x_bf16, act_group=0):

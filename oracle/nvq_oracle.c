@@ -174,6 +174,25 @@ int orc_dequant_int4(const uint8_t *qweight, const uint16_t *scales,
     return ORC_OK;
 }
 
+/* Dense bf16 weights for the prefill path (paper: kernel table, the
+ * dequantisation kernel that materialises 16-bit weights for a library GEMM;
+ * here the 16-bit type is bf16).  out[n][k] = bf16_rne(code * scale); the
+ * product of a 4-bit code and an fp16 scale is exact in binary32, so the only
+ * rounding is the one to bf16. */
+int orc_dequant_bf16(const uint8_t *qweight, const uint16_t *scales,
+                     int64_t N, int64_t K, uint16_t *out) {
+    if (!qweight || !scales || !out) return ORC_ERR_ARG;
+    if (N <= 0 || K <= 0 || (K % 32) != 0) return ORC_ERR_SHAPE;
+    const int64_t G = K / 32;
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t k = 0; k < K; ++k) {
+            const double v = (double)code_at(qweight + n * (K / 2), k) *
+                             (double)orc_half_to_float(scales[n * G + k / 32]);
+            out[n * K + k] = orc_float_to_bf16((float)v);   /* (float)v is exact */
+        }
+    return ORC_OK;
+}
+
 /* ---------- a2: activation quantisation ----------------------------------- */
 /* x bf16 [M][K] -> xq int8 [M][K]; xscale fp32 [M] (act_group 0) or
  * [M][K/32] (act_group 32); xgsum int32 [M][K/32] = sum of codes per block

@@ -124,3 +124,28 @@ def test_scale_overflow_is_reported():
 def test_shape_errors():
     with pytest.raises(oracle.OracleError):
         oracle.pack_int4(np.zeros((2, 48), np.float32))
+
+
+def test_dequant_bf16_is_the_library_rounding_of_the_exact_product():
+    # code * scale is exact in binary32 (4 + 11 significand bits), so the dense bf16 weight is
+    # torch's own float32 -> bfloat16 conversion of numpy's unpacked product: a library routine,
+    # not the oracle's rounding code.  Random bytes cover every nibble (incl. code -8), scales
+    # cover subnormal, ordinary and the largest finite fp16.
+    import torch
+    rng = np.random.default_rng(31)
+    N, K = 24, 256
+    q = rng.integers(0, 256, (N, K // 2), dtype=np.uint8)
+    s = rng.integers(0x0001, 0x7c00, (N, K // 32)).astype(np.uint16)
+    s[0, 0], s[0, 1], s[0, 2] = 0x0001, 0x7bff, 0x0000
+    got = oracle.dequant_bf16(q, s)
+    exact = np_ref.unpack_codes(q).astype(np.float64) * np.repeat(s.view(np.float16).astype(np.float64), 32, axis=1)
+    assert np.array_equal(exact.astype(np.float32).astype(np.float64), exact)     # exact in fp32
+    want = torch.from_numpy(exact.astype(np.float32)).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(got, want)
+    # ties to even, by hand: code +1 times scale 1 + 2^-8 (fp16 0x3C04) lies exactly between
+    # bf16 1.0 (0x3F80) and 1 + 2^-7 (0x3F81) -> 0x3F80; scale 1 + 3 * 2^-8 (0x3C0C) lies between
+    # 0x3F81 and 0x3F82 -> 0x3F82
+    q1 = np.full((1, 16), 0x88, np.uint8)            # all codes 0
+    q1[0, 0] = 0x89                                  # element 0: code +1
+    assert oracle.dequant_bf16(q1, np.array([[0x3C04]], np.uint16))[0, 0] == 0x3F80
+    assert oracle.dequant_bf16(q1, np.array([[0x3C0C]], np.uint16))[0, 0] == 0x3F82
