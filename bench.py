@@ -225,6 +225,21 @@ def main():
                 w2, _ = time_steps(d2, max(a.steps // 2, 1), max(a.warmup // 2, 1), torch)
                 out["config"]["tokens_per_s_all_" + name] = round(M / w2, 2)
                 d2.close()
+            # prefill helper: dense bf16 weights of the largest layer (reads 0.5625, writes 2 bytes
+            # per weight)
+            big = max(layers, key=lambda L: L["spec"].N * L["spec"].K)
+            dense = nvq.dequant_bf16(big["qweight"], big["scales"])
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(20):
+                nvq.dequant_bf16_into(big["qweight"], big["scales"], dense)
+            e1.record()
+            torch.cuda.synchronize()
+            nw = big["spec"].N * big["spec"].K
+            out["config"]["dequant_bf16_gbs"] = round(nw * 2.5625 * 20 / (e0.elapsed_time(e1) * 1e-3)
+                                                      / 1e9, 1)
+            del dense
             d3 = nvq.DecodeList(entries_for(layers, bits, nvq), M, a.act_group, ordered=True)
             w3, _ = time_steps(d3, max(a.steps // 2, 1), max(a.warmup // 2, 1), torch)
             out["config"]["tokens_per_s_ordered_chain"] = round(M / w3, 2)

@@ -204,6 +204,20 @@ int nvq_plan_trace(nvq_plan *plan, uint64_t *buf, size_t bytes);
 void nvq_plan_destroy(nvq_plan *plan);
 
 /*
+ * nvq_dequant_bf16 -- dense bf16 weights for the prefill / large-batch path
+ * (paper: kernel table, the dequantisation kernel that materialises 16-bit
+ * weights for a library GEMM).  out[n][k] = bf16(code[n][k] * scale[n][k/32]),
+ * rounded to nearest even once (the product is exact in binary32).
+ *   qweight  device, [N][K/2], layout of nvq_pack_int4, 16-byte aligned
+ *   scales   device, [N][K/32] fp16 bits
+ *   out_bf16 device, [N][K] bf16 bits, 16-byte aligned, owned by the caller
+ * Enqueues on `stream`; K % 32 == 0.  Errors: NVQ_ERR_INVALID_ARG (null
+ * pointer), NVQ_ERR_SHAPE, NVQ_ERR_ALIGN, NVQ_ERR_HIP.
+ */
+int nvq_dequant_bf16(const uint8_t *qweight, const uint16_t *scales, int64_t N, int64_t K,
+                     uint16_t *out_bf16, void *stream);
+
+/*
  * nvq_precision_from_scores -- host helper: the normalise-and-assign tail of
  * the paper's Algorithm 1.  scores (host, L doubles) are min-max normalised;
  * if max - min < eps every normalised score is 0; out[i] = NVQ_W4A16 if the

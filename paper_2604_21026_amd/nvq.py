@@ -23,7 +23,7 @@ EXPORTS = (
     "nvq_gemv_w4a16", "nvq_gemv_w4a8", "nvq_decode_workspace_bytes", "nvq_decode_linears",
     "nvq_plan_create", "nvq_plan_run", "nvq_plan_info", "nvq_plan_status", "nvq_plan_trace",
     "nvq_plan_destroy",
-    "nvq_precision_from_scores", "nvq_stream_read", "nvq_stream_copy",
+    "nvq_dequant_bf16", "nvq_precision_from_scores", "nvq_stream_read", "nvq_stream_copy",
 )
 
 
@@ -59,6 +59,7 @@ def lib() -> C.CDLL:
     L.nvq_last_hip_error.restype = C.c_char_p
     L.nvq_last_hip_error.argtypes = []
     L.nvq_pack_int4.argtypes = [vp, i64, i64, ci, vp, vp, vp]
+    L.nvq_dequant_bf16.argtypes = [vp, vp, i64, i64, vp, vp]
     L.nvq_quant_act_i8.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp]
     L.nvq_gemv_w4a16.argtypes = [vp, vp, ci, ci, vp, ci, vp, ci, vp]
     L.nvq_gemv_w4a8.argtypes = [vp, vp, ci, ci, vp, vp, vp, ci, ci, vp, ci, vp, vp]
@@ -125,6 +126,23 @@ def pack_int4(W: torch.Tensor, group: int = 32):
     _check(lib().nvq_pack_int4(_dev(W, torch.float32, "W"), N, K, group, q.data_ptr(),
                                s.data_ptr(), _stream()), "nvq_pack_int4")
     return q, s
+
+
+def dequant_bf16_into(qweight: torch.Tensor, scales: torch.Tensor, out: torch.Tensor):
+    """qweight u8 [N,K/2], scales int16 (fp16 bits) [N,K/32] -> dense bf16 weights in out [N,K]."""
+    N, K = qweight.shape[0], qweight.shape[1] * 2
+    if tuple(out.shape) != (N, K):
+        raise ValueError("out: shape mismatch")
+    _check(lib().nvq_dequant_bf16(_dev(qweight, torch.uint8, "qweight"),
+                                  _dev(scales, torch.int16, "scales"), N, K,
+                                  _dev(out, torch.bfloat16, "out"), _stream()), "nvq_dequant_bf16")
+    return out
+
+
+def dequant_bf16(qweight: torch.Tensor, scales: torch.Tensor) -> torch.Tensor:
+    N, K = qweight.shape[0], qweight.shape[1] * 2
+    return dequant_bf16_into(qweight, scales,
+                             torch.empty((N, K), dtype=torch.bfloat16, device=qweight.device))
 
 
 def quant_act_i8(x: torch.Tensor, act_group: int = 0):

@@ -70,6 +70,30 @@ def test_pack_int4_edge_values():
     assert np_ref.unpack_codes(q.cpu().numpy())[0, :12].tolist() == [7, 2, 4, 0, 0, 2, -2, -4, 6, -6, 4, 6]
 
 
+# ---- prefill path: dense bf16 weights ------------------------------------------
+@pytest.mark.parametrize("N,K", [(3, 32), (70, 2048), (257, 4096), (5, 14336), (1031, 1024)])
+def test_dequant_bf16_bit_exact(N, K):
+    say("dequant", N, K)
+    _, q, s = packed(1500 + N, N, K)
+    qd, sd = to_dev_packed(q, s)
+    out = nvq.dequant_bf16(qd, sd)
+    torch.cuda.synchronize()
+    assert np.array_equal(u16(out), oracle.dequant_bf16(q, s))
+
+
+def test_dequant_bf16_every_nibble_and_extreme_scales():
+    say("dequant extremes")
+    rng = np.random.default_rng(19)
+    N, K = 33, 1024
+    q = rng.integers(0, 256, (N, K // 2), dtype=np.uint8)      # includes nibble 0 = code -8
+    s = rng.integers(0x0000, 0x7c00, (N, K // 32)).astype(np.uint16)   # subnormal .. 65504
+    s[0, :4] = [0x0000, 0x0001, 0x7bff, 0x3c04]
+    qd, sd = to_dev_packed(q, s)
+    out = nvq.dequant_bf16(qd, sd)
+    torch.cuda.synchronize()
+    assert np.array_equal(u16(out), oracle.dequant_bf16(q, s))
+
+
 # ---- a2 activation quantisation ----------------------------------------------
 @pytest.mark.parametrize("M,K,group", [(1, 32, 0), (1, 2048, 0), (3, 3072, 0), (1, 4096, 0),
                                        (2, 8192, 0), (1, 14336, 0), (32, 4096, 0),
