@@ -22,7 +22,12 @@ class OracleError(RuntimeError):
 class _Linear(C.Structure):
     _fields_ = [("qweight", C.c_void_p), ("scales", C.c_void_p),
                 ("N", C.c_int64), ("K", C.c_int64),
-                ("x", C.c_void_p), ("y", C.c_void_p), ("precision", C.c_int)]
+                ("x", C.c_void_p), ("y", C.c_void_p), ("precision", C.c_int),
+                ("in_op", C.c_int), ("x2", C.c_void_p), ("gamma", C.c_void_p),
+                ("eps", C.c_double), ("h_out", C.c_void_p), ("xt", C.c_void_p)]
+
+
+IN_PLAIN, IN_RMSNORM, IN_SILU_MUL = 0, 1, 2
 
 
 def lib():
@@ -48,6 +53,12 @@ def lib():
         L.orc_w4a8_acc_deferred.argtypes = [vp, i64, i64, vp, vp, i64, vp]
         L.orc_gemv_w4a16.argtypes = [vp, vp, i64, i64, vp, i64, vp]
         L.orc_decode_linears.argtypes = [vp, i64, i64, ci, vp, vp]
+        L.orc_double_to_bf16.restype = C.c_uint16
+        L.orc_double_to_bf16.argtypes = [C.c_double]
+        L.orc_rms_norm.argtypes = [vp, vp, vp, C.c_double, i64, i64, vp, vp]
+        L.orc_rms_norm.restype = C.c_int
+        L.orc_silu_mul.argtypes = [vp, vp, i64, i64, vp]
+        L.orc_silu_mul.restype = C.c_int
         L.orc_precision_from_scores.argtypes = [vp, i64, C.c_double, C.c_double, vp, vp]
         for f in ("orc_pack_int4", "orc_dequant_int4", "orc_quant_act_i8", "orc_gemv_w4a8",
                   "orc_w4a8_acc_deferred", "orc_gemv_w4a16", "orc_decode_linears",
@@ -174,8 +185,39 @@ def gemv_w4a16(qweight, scales, x_bf16):
     return y
 
 
+def rms_norm(x_bf16, gamma_bf16, eps, res_bf16=None):
+    """x, res u16(bf16) [M,K], gamma u16 [K] -> (out u16 [M,K], h u16 [M,K] or None):
+    out = bf16(h * gamma / sqrt(mean(h^2) + eps)), h = bf16(x + res) (or x)."""
+    x = _arr(x_bf16, np.uint16, 2)
+    g = _arr(gamma_bf16, np.uint16, 1)
+    M, K = x.shape
+    assert g.shape == (K,)
+    out = np.empty((M, K), np.uint16)
+    r = h = None
+    if res_bf16 is not None:
+        r = _arr(res_bf16, np.uint16, 2)
+        assert r.shape == (M, K)
+        h = np.empty((M, K), np.uint16)
+    _chk(lib().orc_rms_norm(_p(x), _p(r) if r is not None else None, _p(g), float(eps), M, K,
+                            _p(out), _p(h) if h is not None else None), "rms_norm")
+    return out, h
+
+
+def silu_mul(g_bf16, u_bf16):
+    """g, u u16(bf16) [M,K] -> u16 [M,K]: bf16(silu(g) * u)."""
+    g = _arr(g_bf16, np.uint16, 2)
+    u = _arr(u_bf16, np.uint16, 2)
+    assert g.shape == u.shape
+    out = np.empty(g.shape, np.uint16)
+    _chk(lib().orc_silu_mul(_p(g), _p(u), g.shape[0], g.shape[1], _p(out)), "silu_mul")
+    return out
+
+
 def decode_linears(layers, M, act_group=0):
-    """layers: list of dicts {qweight, scales, x, precision}; returns list of y float64 [M,N]."""
+    """layers: list of dicts {qweight, scales, x, precision[, in_op, x2, gamma, eps]};
+    returns list of y float64 [M,N].  With in_op the layer's input is first transformed
+    (IN_RMSNORM: rms_norm(x, gamma, eps, res=x2); IN_SILU_MUL: silu_mul(x, x2)); an entry dict
+    with in_op IN_RMSNORM and x2 receives the key "h" (u16 [M,K]) = bf16(x + x2)."""
     n = len(layers)
     arr = (_Linear * max(n, 1))()
     keep = []
@@ -191,8 +233,24 @@ def decode_linears(layers, M, act_group=0):
         keep += [q, s, x]
         ys.append(y)
         maxK = max(maxK, K)
+        op = int(L.get("in_op", 0))
+        x2 = g = h = xt = None
+        if op != 0:
+            xt = np.empty((M, K), np.uint16)
+            if L.get("x2") is not None:
+                x2 = _arr(L["x2"], np.uint16, 2)
+                assert x2.shape == (M, K)
+            if op == IN_RMSNORM:
+                g = _arr(L["gamma"], np.uint16, 1)
+                assert g.shape == (K,)
+                if x2 is not None:
+                    h = np.empty((M, K), np.uint16)
+                    L["h"] = h
+            keep += [xt, x2, g, h]
+        ptr = lambda a: a.ctypes.data if a is not None else None
         arr[i] = _Linear(q.ctypes.data, s.ctypes.data, N, K, x.ctypes.data, y.ctypes.data,
-                         int(L["precision"]))
+                         int(L["precision"]), op, ptr(x2), ptr(g), float(L.get("eps", 0.0)),
+                         ptr(h), ptr(xt))
     sq = np.empty(M * maxK, np.int8)
     ss = np.empty(M * maxK // 32, np.float32)
     _chk(lib().orc_decode_linears(C.byref(arr), n, M, act_group, _p(sq), _p(ss)), "decode_linears")

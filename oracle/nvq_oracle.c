@@ -317,6 +317,70 @@ int orc_gemv_w4a16(const uint8_t *qweight, const uint16_t *scales, int64_t N, in
     return ORC_OK;
 }
 
+/* ---------- input transforms of a linear layer (neighbouring decode kernels) -- */
+/* Round a double to bf16, to nearest, ties to even, in ONE step (going through
+ * float first could round twice).  Finite inputs in the normal bf16 range. */
+uint16_t orc_double_to_bf16(double v) {
+    uint16_t b = orc_float_to_bf16((float)v);
+    /* the right answer is b or one of its neighbours: take the nearest of the
+     * three, an exact tie goes to the even pattern */
+    uint16_t best = b;
+    double bd = fabs((double)orc_bf16_to_float(b) - v);
+    for (int d = -1; d <= 1; d += 2) {
+        uint16_t c = (uint16_t)(b + d);
+        if ((c & 0x7f80u) == 0x7f80u || ((b ^ c) & 0x8000u)) continue; /* inf/nan, sign change */
+        double cd = fabs((double)orc_bf16_to_float(c) - v);
+        if (cd < bd || (cd == bd && (c & 1u) == 0 && (best & 1u) == 1)) {
+            best = c;
+            bd = cd;
+        }
+    }
+    return best;
+}
+
+/* RMSNorm in front of a linear layer (paper: kernel table, the single-pass
+ * RMS-norm kernel; the formula is the usual one, the paper does not restate
+ * it).  Per token: h = x (+ res, rounded to bf16: the updated residual stream,
+ * stored to h_out if given); out_k = bf16(h_k * gamma_k / sqrt(mean(h^2) + eps)).
+ * x, res, out, h_out: bf16 [M][K]; gamma: bf16 [K]; res and h_out may be NULL. */
+int orc_rms_norm(const uint16_t *x, const uint16_t *res, const uint16_t *gamma, double eps,
+                 int64_t M, int64_t K, uint16_t *out, uint16_t *h_out) {
+    if (!x || !gamma || !out) return ORC_ERR_ARG;
+    if (M <= 0 || K <= 0) return ORC_ERR_SHAPE;
+    for (int64_t m = 0; m < M; ++m) {
+        double ss = 0.0;
+        for (int64_t k = 0; k < K; ++k) {
+            uint16_t hb = x[m * K + k];
+            if (res)
+                hb = orc_double_to_bf16((double)orc_bf16_to_float(hb) +
+                                        (double)orc_bf16_to_float(res[m * K + k]));
+            if (h_out) h_out[m * K + k] = hb;
+            out[m * K + k] = hb; /* parked, normalised below */
+            const double h = (double)orc_bf16_to_float(hb);
+            ss += h * h;
+        }
+        const double r = 1.0 / sqrt(ss / (double)K + eps);
+        for (int64_t k = 0; k < K; ++k) {
+            const double h = (double)orc_bf16_to_float(out[m * K + k]);
+            out[m * K + k] = orc_double_to_bf16(h * r * (double)orc_bf16_to_float(gamma[k]));
+        }
+    }
+    return ORC_OK;
+}
+
+/* SiLU(gate) * up in front of the down projection (paper: kernel table, the
+ * SiLU-multiply kernel).  out_k = bf16(g_k / (1 + exp(-g_k)) * u_k). */
+int orc_silu_mul(const uint16_t *g, const uint16_t *u, int64_t M, int64_t K, uint16_t *out) {
+    if (!g || !u || !out) return ORC_ERR_ARG;
+    if (M <= 0 || K <= 0) return ORC_ERR_SHAPE;
+    for (int64_t i = 0; i < M * K; ++i) {
+        const double gv = (double)orc_bf16_to_float(g[i]);
+        const double uv = (double)orc_bf16_to_float(u[i]);
+        out[i] = orc_double_to_bf16(gv / (1.0 + exp(-gv)) * uv);
+    }
+    return ORC_OK;
+}
+
 /* ---------- a5: walk a layer list under a precision map ------------------- */
 typedef struct {
     const uint8_t *qweight;   /* [N][K/2] */
@@ -325,6 +389,12 @@ typedef struct {
     const uint16_t *x;        /* bf16 [M][K] */
     double *y;                /* [M][N] */
     int precision;            /* 0 = W4A8, 1 = W4A16 */
+    int in_op;                /* 0 = x as it is, 1 = RMSNorm(x (+ x2)) * gamma, 2 = SiLU(x) * x2 */
+    const uint16_t *x2;       /* bf16 [M][K] or NULL */
+    const uint16_t *gamma;    /* bf16 [K] (in_op 1) */
+    double eps;               /* (in_op 1) */
+    uint16_t *h_out;          /* bf16 [M][K] or NULL: x + x2 (in_op 1 with x2) */
+    uint16_t *xt;             /* bf16 [M][K] scratch for the transformed input (in_op != 0) */
 } orc_linear;
 
 /* Entries run in order.  A W4A8 entry quantises its input first (an entry
@@ -336,10 +406,23 @@ int orc_decode_linears(const orc_linear *L, int64_t n, int64_t M, int act_group,
     if (!L || n < 0 || !scratch_q || !scratch_s) return ORC_ERR_ARG;
     for (int64_t i = 0; i < n; ++i) {
         int rc;
+        const uint16_t *x = L[i].x;
+        if (L[i].in_op == 1) {
+            rc = orc_rms_norm(L[i].x, L[i].x2, L[i].gamma, L[i].eps, M, L[i].K, L[i].xt,
+                              L[i].h_out);
+            if (rc) return rc;
+            x = L[i].xt;
+        } else if (L[i].in_op == 2) {
+            rc = orc_silu_mul(L[i].x, L[i].x2, M, L[i].K, L[i].xt);
+            if (rc) return rc;
+            x = L[i].xt;
+        } else if (L[i].in_op != 0) {
+            return ORC_ERR_ARG;
+        }
         if (L[i].precision == 1) {
-            rc = orc_gemv_w4a16(L[i].qweight, L[i].scales, L[i].N, L[i].K, L[i].x, M, L[i].y);
+            rc = orc_gemv_w4a16(L[i].qweight, L[i].scales, L[i].N, L[i].K, x, M, L[i].y);
         } else if (L[i].precision == 0) {
-            rc = orc_quant_act_i8(L[i].x, M, L[i].K, act_group, scratch_q, scratch_s, NULL);
+            rc = orc_quant_act_i8(x, M, L[i].K, act_group, scratch_q, scratch_s, NULL);
             if (rc) return rc;
             rc = orc_gemv_w4a8(L[i].qweight, L[i].scales, L[i].N, L[i].K, scratch_q,
                                scratch_s, act_group, M, L[i].y, NULL);
