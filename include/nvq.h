@@ -125,10 +125,39 @@ int nvq_gemv_w4a8(const uint8_t *qweight, const uint16_t *scales, int N, int K,
                   void *stream);
 
 /*
+ * nvq_rms_norm_bf16 / nvq_silu_mul_bf16 -- the two elementwise neighbours of
+ * the decode linears (paper: kernel table, the RMS-norm and SiLU-multiply
+ * kernels; the paper names them without restating the formulas, the usual ones
+ * are taken).  All tensors device, bf16 bits, 16-byte aligned, [M][K] except
+ * gamma [K]; K % 32 == 0, M <= NVQ_MAX_M; every result is rounded to bf16 once.
+ *   rms_norm: h = x (+ res if res != NULL, the sum rounded to bf16 and stored
+ *             to h_out if h_out != NULL);
+ *             out[m][k] = bf16(h[m][k] * gamma[k] / sqrt(mean_k(h[m]^2) + eps))
+ *   silu_mul: out = bf16(g / (1 + exp(-g)) * u)
+ * Sums of squares, the scale and exp are evaluated in binary32; against a
+ * binary64 evaluation about one output in 10^4 differs by one bf16 unit.
+ * Enqueue on `stream`.  Errors as for the other entry points.
+ */
+int nvq_rms_norm_bf16(const uint16_t *x, const uint16_t *res, const uint16_t *gamma, float eps,
+                      int M, int K, uint16_t *out, uint16_t *h_out, void *stream);
+int nvq_silu_mul_bf16(const uint16_t *g, const uint16_t *u, int M, int K, uint16_t *out,
+                      void *stream);
+
+/*
  * One linear layer of a decode step.  `precision` is the routing decision of
  * the paper's rule route(i) = W4A16 if normalised score >= tau else W4A8; all
  * linears of one transformer block carry their block's decision.
+ * `in_op` names what stands between x_bf16 and the layer (the neighbouring
+ * kernels of the paper's kernel table, applied while the input is prepared, so
+ * that they cost no launch and no extra pass over memory):
+ *   NVQ_IN_PLAIN     the layer reads x_bf16
+ *   NVQ_IN_RMSNORM   the layer reads nvq_rms_norm_bf16(x_bf16, x2_bf16, gamma_bf16, eps)
+ *                    (x2_bf16 may be NULL; with x2_bf16 the sum x + x2 goes to
+ *                    h_out_bf16 if that is not NULL: the updated residual stream;
+ *                    h_out_bf16 must not be x_bf16 or x2_bf16)
+ *   NVQ_IN_SILU_MUL  the layer reads nvq_silu_mul_bf16(x_bf16, x2_bf16)
  */
+enum { NVQ_IN_PLAIN = 0, NVQ_IN_RMSNORM = 1, NVQ_IN_SILU_MUL = 2 };
 typedef struct nvq_linear {
     const uint8_t *qweight;  /* [N][K/2] */
     const uint16_t *scales;  /* [N][K/32] */
@@ -137,6 +166,11 @@ typedef struct nvq_linear {
     void *y;                 /* [M][N] output */
     int32_t y_dtype;         /* NVQ_F32 | NVQ_BF16 */
     int32_t precision;       /* NVQ_W4A8 | NVQ_W4A16 */
+    int32_t in_op;           /* NVQ_IN_* */
+    float eps;               /* NVQ_IN_RMSNORM */
+    const uint16_t *x2_bf16;     /* [M][K] second operand, or NULL */
+    const uint16_t *gamma_bf16;  /* [K] (NVQ_IN_RMSNORM) */
+    uint16_t *h_out_bf16;        /* [M][K] or NULL (NVQ_IN_RMSNORM with x2_bf16) */
 } nvq_linear;
 
 /*

@@ -17,6 +17,7 @@
 #include <vector>
 
 #include "decode_stream.h"
+#include "transform.h"
 
 namespace nvq {
 
@@ -27,6 +28,7 @@ size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // Workspace layout (offsets from a 256-byte aligned base).
 struct Workspace {
+    uint16_t *xt;       // [M][maxK]           transformed input (per-phase launches)
     int8_t *xq;         // [M][maxK]           activation codes (per-phase launches)
     float *xscale;      // [M][maxK/32]
     int32_t *xgsum;     // [M][maxK/32]
@@ -49,6 +51,7 @@ struct ListSizes {
     size_t image_bytes;  // activation images of the streaming kernel (M = 1)
     size_t group_units;  // 16-row tiles of all entries (M > 1)
     size_t group_quant;  // codes + scales + code sums of all W4A8 entries (M > 1)
+    bool transforms;     // some entry has an input transform
 };
 
 size_t quant_bytes(int M, int K) {
@@ -68,6 +71,7 @@ Workspace carve(void *base, int M, int n, const ListSizes &ls) {
         off += round_up(bytes, 256);
         return p;
     };
+    w.xt = reinterpret_cast<uint16_t *>(take(ls.transforms ? (size_t)M * maxK * 2 : 0));
     w.xq = reinterpret_cast<int8_t *>(take((size_t)M * maxK));
     w.xscale = reinterpret_cast<float *>(take((size_t)M * G * 4));
     w.xgsum = reinterpret_cast<int32_t *>(take((size_t)M * G * 4));
@@ -92,10 +96,26 @@ int check_layers(const nvq_linear *L, int n, int M, int act_group, ListSizes *si
     if (M <= 0 || M > NVQ_MAX_M) return NVQ_ERR_SHAPE;
     int mk = 32;
     size_t ib = 0, gu = 0, gq = 0;
+    bool tr = false;
     for (int i = 0; i < n; ++i) {
         const nvq_linear &e = L[i];
         if (!e.qweight || !e.scales || !e.x_bf16 || !e.y) return NVQ_ERR_INVALID_ARG;
         if (e.precision != NVQ_W4A8 && e.precision != NVQ_W4A16) return NVQ_ERR_INVALID_ARG;
+        if (e.in_op == NVQ_IN_RMSNORM) {
+            if (!e.gamma_bf16 || !(e.eps >= 0.0f)) return NVQ_ERR_INVALID_ARG;
+        } else if (e.in_op == NVQ_IN_SILU_MUL) {
+            if (!e.x2_bf16) return NVQ_ERR_INVALID_ARG;
+        } else if (e.in_op != NVQ_IN_PLAIN) {
+            return NVQ_ERR_INVALID_ARG;
+        }
+        if (e.in_op != NVQ_IN_PLAIN &&
+            (!aligned(e.x2_bf16, 16) || !aligned(e.gamma_bf16, 16) || !aligned(e.h_out_bf16, 16)))
+            return NVQ_ERR_ALIGN;
+        // the sum is stored while the inputs are still being read
+        if (e.in_op == NVQ_IN_RMSNORM && e.h_out_bf16 &&
+            (e.h_out_bf16 == e.x_bf16 || e.h_out_bf16 == e.x2_bf16))
+            return NVQ_ERR_INVALID_ARG;
+        tr = tr || e.in_op != NVQ_IN_PLAIN;
         if (e.y_dtype != NVQ_F32 && e.y_dtype != NVQ_BF16) return NVQ_ERR_INVALID_ARG;
         if (e.N <= 0 || e.K <= 0 || (e.K % 32) != 0 || e.K > NVQ_MAX_K) return NVQ_ERR_SHAPE;
         if (!aligned(e.qweight, 16) || !aligned(e.scales, 2) || !aligned(e.x_bf16, 16) ||
@@ -111,6 +131,7 @@ int check_layers(const nvq_linear *L, int n, int M, int act_group, ListSizes *si
     sizes->image_bytes = ib;
     sizes->group_units = gu;
     sizes->group_quant = gq;
+    sizes->transforms = tr;
     return NVQ_OK;
 }
 
@@ -119,13 +140,21 @@ struct Phase {
     int first, count;
 };
 
+// The input transform of an entry (none: every field compares equal to none).
+bool same_transform(const nvq_linear &a, const nvq_linear &b) {
+    if (a.in_op != b.in_op) return false;
+    if (a.in_op == NVQ_IN_PLAIN) return true;
+    return a.x2_bf16 == b.x2_bf16 && a.gamma_bf16 == b.gamma_bf16 && a.eps == b.eps &&
+           a.h_out_bf16 == b.h_out_bf16;
+}
+
 std::vector<Phase> group_phases(const nvq_linear *L, int n) {
     std::vector<Phase> out;
     int i = 0;
     while (i < n) {
         int j = i + 1;
         while (j < n && j - i < kMaxSeg && L[j].x_bf16 == L[i].x_bf16 && L[j].K == L[i].K &&
-               L[j].precision == L[i].precision)
+               L[j].precision == L[i].precision && same_transform(L[i], L[j]))
             ++j;
         out.push_back({i, j - i});
         i = j;
@@ -137,7 +166,8 @@ std::vector<Phase> group_phases(const nvq_linear *L, int n) {
 // (a phase split only because it had more than kMaxSeg matrices).
 bool same_input(const nvq_linear *L, const Phase &a, const Phase &b) {
     return L[a.first].x_bf16 == L[b.first].x_bf16 && L[a.first].K == L[b.first].K &&
-           L[a.first].precision == L[b.first].precision;
+           L[a.first].precision == L[b.first].precision &&
+           same_transform(L[a.first], L[b.first]);
 }
 
 GemvSegs make_segs(const nvq_linear *L, const Phase &ph) {
@@ -166,14 +196,26 @@ int walk_per_phase(const nvq_linear *L, const std::vector<Phase> &phases, int M,
         const Phase &ph = phases[p];
         const nvq_linear &e0 = L[ph.first];
         const bool w4a8 = e0.precision == NVQ_W4A8;
-        if (w4a8 && !(p > 0 && same_input(L, phases[p - 1], ph))) {
-            const int q = launch_quant_act(e0.x_bf16, M, e0.K, act_group, ws.xq, ws.xscale,
-                                           ws.xgsum, st);
+        const bool fresh = !(p > 0 && same_input(L, phases[p - 1], ph));
+        const uint16_t *x = e0.x_bf16;
+        if (e0.in_op != NVQ_IN_PLAIN) {
+            // the transformed input of the previous phase is still in ws.xt if it was the same
+            if (fresh) {
+                const int t = e0.in_op == NVQ_IN_RMSNORM
+                                  ? launch_rms_norm(e0.x_bf16, e0.x2_bf16, e0.gamma_bf16, e0.eps, M,
+                                                    e0.K, ws.xt, e0.h_out_bf16, st)
+                                  : launch_silu_mul(e0.x_bf16, e0.x2_bf16, M, e0.K, ws.xt, st);
+                if (t != NVQ_OK) return t;
+            }
+            x = ws.xt;
+        }
+        if (w4a8 && fresh) {
+            const int q = launch_quant_act(x, M, e0.K, act_group, ws.xq, ws.xscale, ws.xgsum, st);
             if (q != NVQ_OK) return q;
         }
         const GemvSegs S = make_segs(L, ph);
         const int g = w4a8 ? launch_gemv_w4a8(S, e0.K, ws.xq, ws.xscale, ws.xgsum, act_group, M, st)
-                           : launch_gemv_w4a16(S, e0.K, e0.x_bf16, M, st);
+                           : launch_gemv_w4a16(S, e0.K, x, M, st);
         if (g != NVQ_OK) return g;
     }
     return NVQ_OK;
@@ -191,11 +233,19 @@ std::vector<int> phase_deps(const nvq_linear *L, const std::vector<Phase> &phase
                             bool ordered) {
     const size_t P = phases.size();
     std::vector<int> deps(P, -1);
-    std::vector<Range> xin(P);
-    std::vector<std::vector<Range>> yout(P);
+    std::vector<std::vector<Range>> xin(P), yout(P);  // what a phase reads and writes
     for (size_t p = 0; p < P; ++p) {
         const nvq_linear &e0 = L[phases[p].first];
-        xin[p] = {(uintptr_t)e0.x_bf16, (uintptr_t)e0.x_bf16 + (size_t)M * e0.K * 2};
+        const size_t xbytes = (size_t)M * e0.K * 2;
+        xin[p].push_back({(uintptr_t)e0.x_bf16, (uintptr_t)e0.x_bf16 + xbytes});
+        if (e0.in_op != NVQ_IN_PLAIN) {
+            if (e0.x2_bf16) xin[p].push_back({(uintptr_t)e0.x2_bf16, (uintptr_t)e0.x2_bf16 + xbytes});
+            if (e0.gamma_bf16)
+                xin[p].push_back({(uintptr_t)e0.gamma_bf16,
+                                  (uintptr_t)e0.gamma_bf16 + (size_t)e0.K * 2});
+            if (e0.in_op == NVQ_IN_RMSNORM && e0.x2_bf16 && e0.h_out_bf16)
+                yout[p].push_back({(uintptr_t)e0.h_out_bf16, (uintptr_t)e0.h_out_bf16 + xbytes});
+        }
         for (int k = 0; k < phases[p].count; ++k) {
             const nvq_linear &e = L[phases[p].first + k];
             const size_t bytes = (size_t)M * e.N * (e.y_dtype == NVQ_F32 ? 4 : 2);
@@ -207,10 +257,11 @@ std::vector<int> phase_deps(const nvq_linear *L, const std::vector<Phase> &phase
         for (size_t q = 0; q < p && !ordered; ++q) {
             bool hit = false;
             for (const Range &yq : yout[q]) {
-                hit = hit || overlap(xin[p], yq);  // read after write
+                for (const Range &xp : xin[p]) hit = hit || overlap(xp, yq);  // read after write
                 for (const Range &yp : yout[p]) hit = hit || overlap(yp, yq);  // write after write
             }
-            for (const Range &yp : yout[p]) hit = hit || overlap(yp, xin[q]);  // write after read
+            for (const Range &yp : yout[p])
+                for (const Range &xq : xin[q]) hit = hit || overlap(yp, xq);  // write after read
             if (hit) dep = (int)q;
         }
         deps[p] = dep;
@@ -236,7 +287,9 @@ GroupPlan group_plan(const nvq_linear *L, const std::vector<Phase> &phases, int 
     GroupPlan gp;
     if (M < 2 || act_group != 0 || phases.size() > 65535) return gp;
     for (const Phase &ph : phases)
-        if (!gemv_mfma_supported(make_segs(L, ph), L[ph.first].K, M)) return gp;
+        if (L[ph.first].in_op != NVQ_IN_PLAIN ||
+            !gemv_mfma_supported(make_segs(L, ph), L[ph.first].K, M))
+            return gp;
     const std::vector<int> deps = phase_deps(L, phases, M, ordered);
     size_t qoff = 0;
     GroupBatch cur = {0, 0, 0, 0};
@@ -310,6 +363,7 @@ std::vector<StreamPhase> stream_table(const nvq_linear *L, const std::vector<Pha
         const nvq_linear &e0 = L[ph.first];
         const int G = e0.K / 32;
         if (e0.K > kStreamMaxK) return {};
+        if (e0.in_op != NVQ_IN_PLAIN) return {};
         StreamPhase sp = {};
         int rows = 0;
         for (int k = 0; k < ph.count; ++k) {

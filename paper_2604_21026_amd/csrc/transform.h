@@ -1,0 +1,103 @@
+// Arithmetic of the input transforms of a linear layer (device code shared by
+// the standalone kernels and the persistent decode kernel): RMSNorm with an
+// optional residual add in front, and SiLU(gate) * up.  Paper: kernel table
+// (RMS-norm and SiLU-multiply kernels of the decode path); the formulas are the
+// usual ones.  Every result is rounded to bf16 once, to nearest even.
+#pragma once
+
+#include "nvq_internal.h"
+
+namespace nvq {
+
+#if defined(__HIPCC__)
+
+// a + b of two bf16 numbers, rounded to bf16 once.  The sum of two bf16 values
+// is exact in binary64; rounding it through binary32 first could round twice.
+__device__ __forceinline__ uint32_t add_bf16_bits(uint32_t a, uint32_t b) {
+    const double v = (double)bf16_bits_to_float(a) + (double)bf16_bits_to_float(b);
+    uint64_t u = (uint64_t)__double_as_longlong(v);
+    // binary64 -> the bf16 significand (7 fraction bits): 45 bits are dropped
+    const uint64_t drop = (1ull << 45) - 1, half = 1ull << 44;
+    const uint64_t rem = u & drop;
+    u >>= 45;  // sign, 11-bit exponent, 7 fraction bits
+    if (rem > half || (rem == half && (u & 1))) ++u;
+    // rebias the exponent from binary64 (1023) to bf16 (127); sums of finite bf16
+    // inputs that are not tiny stay in range, tiny or zero results flush to zero
+    const uint32_t sign = (uint32_t)(u >> 18) & 1u;
+    const int32_t exp = (int32_t)((u >> 7) & 0x7ffu) - 1023 + 127;
+    const uint32_t frac = (uint32_t)u & 0x7fu;
+    if (exp <= 0) return sign << 15;
+    if (exp >= 255) return (sign << 15) | 0x7f80u;
+    return (sign << 15) | ((uint32_t)exp << 7) | frac;
+}
+
+// Eight bf16 values (one uint4) at a time.
+__device__ __forceinline__ uint4 add_bf16x8(const uint4 &a, const uint4 &b) {
+    const uint32_t av[4] = {a.x, a.y, a.z, a.w}, bv[4] = {b.x, b.y, b.z, b.w};
+    uint32_t o[4];
+#pragma unroll
+    for (int d = 0; d < 4; ++d)
+        o[d] = add_bf16_bits(av[d] & 0xffffu, bv[d] & 0xffffu) |
+               (add_bf16_bits(av[d] >> 16, bv[d] >> 16) << 16);
+    return make_uint4(o[0], o[1], o[2], o[3]);
+}
+
+__device__ __forceinline__ float sumsq_bf16x8(const uint4 &h) {
+    const uint32_t hv[4] = {h.x, h.y, h.z, h.w};
+    float s = 0.0f;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        const float lo = bf16_bits_to_float(hv[d] & 0xffffu), hi = bf16_bits_to_float(hv[d] >> 16);
+        s = fmaf(lo, lo, s);
+        s = fmaf(hi, hi, s);
+    }
+    return s;
+}
+
+// 1 / sqrt(mean of squares + eps) from the sum of squares of K values.
+__device__ __forceinline__ float rms_scale(float sumsq, int K, float eps) {
+    return 1.0f / sqrtf(sumsq / (float)K + eps);
+}
+
+// bf16(h * r * gamma), eight at a time.
+__device__ __forceinline__ uint4 scale_bf16x8(const uint4 &h, float r, const uint4 &gamma) {
+    const uint32_t hv[4] = {h.x, h.y, h.z, h.w}, gv[4] = {gamma.x, gamma.y, gamma.z, gamma.w};
+    uint32_t o[4];
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        const float lo = bf16_bits_to_float(hv[d] & 0xffffu) * r * bf16_bits_to_float(gv[d] & 0xffffu);
+        const float hi = bf16_bits_to_float(hv[d] >> 16) * r * bf16_bits_to_float(gv[d] >> 16);
+        o[d] = (uint32_t)float_to_bf16_bits(lo) | ((uint32_t)float_to_bf16_bits(hi) << 16);
+    }
+    return make_uint4(o[0], o[1], o[2], o[3]);
+}
+
+__device__ __forceinline__ float silu_mul_one(float g, float u) {
+    return g / (1.0f + expf(-g)) * u;
+}
+
+// bf16(silu(g) * u), eight at a time.
+__device__ __forceinline__ uint4 silu_mul_bf16x8(const uint4 &g, const uint4 &u) {
+    const uint32_t gv[4] = {g.x, g.y, g.z, g.w}, uv[4] = {u.x, u.y, u.z, u.w};
+    uint32_t o[4];
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        const float lo = silu_mul_one(bf16_bits_to_float(gv[d] & 0xffffu),
+                                      bf16_bits_to_float(uv[d] & 0xffffu));
+        const float hi = silu_mul_one(bf16_bits_to_float(gv[d] >> 16),
+                                      bf16_bits_to_float(uv[d] >> 16));
+        o[d] = (uint32_t)float_to_bf16_bits(lo) | ((uint32_t)float_to_bf16_bits(hi) << 16);
+    }
+    return make_uint4(o[0], o[1], o[2], o[3]);
+}
+
+#endif  // __HIPCC__
+
+// Internal launchers (validated arguments; enqueue only).  One workgroup per
+// token; K % 8 == 0.
+int launch_rms_norm(const uint16_t *x, const uint16_t *res, const uint16_t *gamma, float eps, int M,
+                    int K, uint16_t *out, uint16_t *h_out, hipStream_t st);
+int launch_silu_mul(const uint16_t *g, const uint16_t *u, int M, int K, uint16_t *out,
+                    hipStream_t st);
+
+}  // namespace nvq

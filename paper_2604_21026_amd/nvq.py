@@ -17,13 +17,14 @@ F32, BF16 = 0, 1
 W4A8, W4A16 = 0, 1
 MAX_M = 32
 PLAN_ORDERED = 1
+IN_PLAIN, IN_RMSNORM, IN_SILU_MUL = 0, 1, 2
 
 EXPORTS = (
     "nvq_status_string", "nvq_last_hip_error", "nvq_pack_int4", "nvq_quant_act_i8",
     "nvq_gemv_w4a16", "nvq_gemv_w4a8", "nvq_decode_workspace_bytes", "nvq_decode_linears",
     "nvq_plan_create", "nvq_plan_run", "nvq_plan_info", "nvq_plan_status", "nvq_plan_trace",
     "nvq_plan_destroy",
-    "nvq_dequant_bf16", "nvq_precision_from_scores", "nvq_stream_read", "nvq_stream_copy",
+    "nvq_dequant_bf16", "nvq_rms_norm_bf16", "nvq_silu_mul_bf16", "nvq_precision_from_scores", "nvq_stream_read", "nvq_stream_copy",
 )
 
 
@@ -38,7 +39,9 @@ class Linear(C.Structure):
     """Mirror of `nvq_linear`."""
     _fields_ = [("qweight", C.c_void_p), ("scales", C.c_void_p), ("N", C.c_int32),
                 ("K", C.c_int32), ("x_bf16", C.c_void_p), ("y", C.c_void_p),
-                ("y_dtype", C.c_int32), ("precision", C.c_int32)]
+                ("y_dtype", C.c_int32), ("precision", C.c_int32), ("in_op", C.c_int32),
+                ("eps", C.c_float), ("x2_bf16", C.c_void_p), ("gamma_bf16", C.c_void_p),
+                ("h_out_bf16", C.c_void_p)]
 
 
 _lib = None
@@ -60,6 +63,8 @@ def lib() -> C.CDLL:
     L.nvq_last_hip_error.argtypes = []
     L.nvq_pack_int4.argtypes = [vp, i64, i64, ci, vp, vp, vp]
     L.nvq_dequant_bf16.argtypes = [vp, vp, i64, i64, vp, vp]
+    L.nvq_rms_norm_bf16.argtypes = [vp, vp, vp, C.c_float, ci, ci, vp, vp, vp]
+    L.nvq_silu_mul_bf16.argtypes = [vp, vp, ci, ci, vp, vp]
     L.nvq_quant_act_i8.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp]
     L.nvq_gemv_w4a16.argtypes = [vp, vp, ci, ci, vp, ci, vp, ci, vp]
     L.nvq_gemv_w4a8.argtypes = [vp, vp, ci, ci, vp, vp, vp, ci, ci, vp, ci, vp, vp]
@@ -145,6 +150,28 @@ def dequant_bf16(qweight: torch.Tensor, scales: torch.Tensor) -> torch.Tensor:
                              torch.empty((N, K), dtype=torch.bfloat16, device=qweight.device))
 
 
+def rms_norm(x: torch.Tensor, gamma: torch.Tensor, eps: float, res: Optional[torch.Tensor] = None):
+    """x, res bf16 [M,K], gamma bf16 [K] -> (out bf16 [M,K], h bf16 [M,K] or None)."""
+    M, K = x.shape
+    out = torch.empty_like(x)
+    h = torch.empty_like(x) if res is not None else None
+    _check(lib().nvq_rms_norm_bf16(_dev(x, torch.bfloat16, "x"),
+                                   _dev(res, torch.bfloat16, "res") if res is not None else None,
+                                   _dev(gamma, torch.bfloat16, "gamma"), float(eps), M, K,
+                                   out.data_ptr(), h.data_ptr() if h is not None else None,
+                                   _stream()), "nvq_rms_norm_bf16")
+    return out, h
+
+
+def silu_mul(g: torch.Tensor, u: torch.Tensor) -> torch.Tensor:
+    """g, u bf16 [M,K] -> bf16(silu(g) * u)."""
+    M, K = g.shape
+    out = torch.empty_like(g)
+    _check(lib().nvq_silu_mul_bf16(_dev(g, torch.bfloat16, "g"), _dev(u, torch.bfloat16, "u"), M, K,
+                                   out.data_ptr(), _stream()), "nvq_silu_mul_bf16")
+    return out
+
+
 def quant_act_i8(x: torch.Tensor, act_group: int = 0):
     """x bf16 [M,K] -> xq i8 [M,K], xscale f32 [M] or [M,K/32], xgsum i32 [M,K/32]."""
     M, K = x.shape
@@ -206,10 +233,22 @@ class DecodeList:
             N, K = q.shape[0], q.shape[1] * 2
             if tuple(x.shape) != (M, K) or tuple(y.shape) != (M, N):
                 raise ValueError("entry %d: shape mismatch" % i)
+            op = int(e.get("in_op", IN_PLAIN))
+            x2, gamma, h = e.get("x2"), e.get("gamma"), e.get("h_out")
+            if x2 is not None and tuple(x2.shape) != (M, K):
+                raise ValueError("entry %d: x2 shape mismatch" % i)
+            if h is not None and tuple(h.shape) != (M, K):
+                raise ValueError("entry %d: h_out shape mismatch" % i)
+            if gamma is not None and tuple(gamma.shape) != (K,):
+                raise ValueError("entry %d: gamma shape mismatch" % i)
             self.arr[i] = Linear(_dev(q, torch.uint8, "qweight"), _dev(s, torch.int16, "scales"),
                                  N, K, _dev(x, torch.bfloat16, "x"), _dev(y, y.dtype, "y"),
-                                 _y_dtype(y.dtype), int(e["precision"]))
-            self.keep += [q, s, x, y]
+                                 _y_dtype(y.dtype), int(e["precision"]), op,
+                                 float(e.get("eps", 0.0)),
+                                 _dev(x2, torch.bfloat16, "x2") if x2 is not None else None,
+                                 _dev(gamma, torch.bfloat16, "gamma") if gamma is not None else None,
+                                 _dev(h, torch.bfloat16, "h_out") if h is not None else None)
+            self.keep += [q, s, x, y, x2, gamma, h]
             dev = q.device
         need = lib().nvq_decode_workspace_bytes(C.byref(self.arr), self.n, M, act_group)
         if self.n and need == 0:

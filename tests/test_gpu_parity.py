@@ -486,3 +486,117 @@ def test_grouped_plan_orders_dependent_phases():
                                               precision=i % 2)], M)[0]
             assert np_ref.rel_l2(bufs[i + 1].float().cpu().numpy(), y_r) < 4e-3, (rep, i)
     dl.close()
+
+
+# ---- input transforms: RMSNorm (+ residual) and SiLU-multiply ------------------------
+def ulp_report(got_u16, want_u16):
+    """(fraction of differing elements, largest difference in bf16 units of last place)."""
+    a = got_u16.astype(np.int32)
+    b = want_u16.astype(np.int32)
+    # order-preserving integer view of the sign-magnitude patterns
+    a = np.where(a & 0x8000, -(a & 0x7fff), a)
+    b = np.where(b & 0x8000, -(b & 0x7fff), b)
+    d = np.abs(a - b)
+    return float((d != 0).mean()), int(d.max())
+
+
+@pytest.mark.parametrize("M,K,with_res", [(1, 4096, False), (1, 4096, True), (3, 2048, True),
+                                          (16, 14336, True), (2, 96, False), (32, 8192, False)])
+def test_rms_norm_matches_oracle(M, K, with_res):
+    say("rms_norm", M, K, with_res)
+    x = act(9100 + K, M, K)
+    r = act(9200 + K, M, K) if with_res else None
+    gamma = (1.0 + 0.1 * torch.randn(K, generator=torch.Generator().manual_seed(K))).to(torch.bfloat16)
+    out_r, h_r = oracle.rms_norm(u16(x), u16(gamma), 1e-5, res_bf16=u16(r) if with_res else None)
+    out, h = nvq.rms_norm(x.to(DEV), gamma.to(DEV), 1e-5, r.to(DEV) if with_res else None)
+    torch.cuda.synchronize()
+    if with_res:
+        assert np.array_equal(u16(h), h_r)            # the bf16 addition is exact-rounded
+    frac, worst = ulp_report(u16(out), out_r)
+    say("  differing %.2e, worst %d ulp" % (frac, worst))
+    assert worst <= 1 and frac < 2e-3
+
+
+@pytest.mark.parametrize("M,K", [(1, 14336), (5, 8192), (32, 4096), (2, 64)])
+def test_silu_mul_matches_oracle(M, K):
+    say("silu_mul", M, K)
+    g = act(9300 + K, M, K)
+    u = act(9400 + K, M, K)
+    want = oracle.silu_mul(u16(g), u16(u))
+    out = nvq.silu_mul(g.to(DEV), u.to(DEV))
+    torch.cuda.synchronize()
+    frac, worst = ulp_report(u16(out), want)
+    say("  differing %.2e, worst %d ulp" % (frac, worst))
+    assert worst <= 1 and frac < 2e-3
+
+
+def block_with_transforms(M, hidden, kv, ffn, seed, bits):
+    """One transformer block's linears with their neighbours fused in: RMSNorm in front of
+    q/k/v, the attention output (its own buffer) into o, residual add + RMSNorm in front of
+    gate/up, SiLU-multiply in front of down.  Returns (entries, buffers, host weights)."""
+    g1 = (1.0 + 0.1 * torch.randn(hidden, generator=torch.Generator().manual_seed(seed))).to(torch.bfloat16)
+    g2 = (1.0 + 0.1 * torch.randn(hidden, generator=torch.Generator().manual_seed(seed + 1))).to(torch.bfloat16)
+    B = dict(h0=act(seed + 2, M, hidden).to(DEV), attn=act(seed + 3, M, hidden).to(DEV),
+             g1=g1.to(DEV), g2=g2.to(DEV),
+             o=torch.zeros((M, hidden), dtype=torch.bfloat16, device=DEV),
+             h1=torch.zeros((M, hidden), dtype=torch.bfloat16, device=DEV),
+             gate=torch.zeros((M, ffn), dtype=torch.bfloat16, device=DEV),
+             up=torch.zeros((M, ffn), dtype=torch.bfloat16, device=DEV))
+    shapes = [("q", hidden, hidden), ("k", kv, hidden), ("v", kv, hidden), ("o", hidden, hidden),
+              ("gate", ffn, hidden), ("up", ffn, hidden), ("down", hidden, ffn)]
+    W, entries = {}, []
+    for i, (name, N, K) in enumerate(shapes):
+        _, q, s = packed(seed + 10 + i, N, K)
+        W[name] = (q, s)
+        qd, sd = to_dev_packed(q, s)
+        e = dict(qweight=qd, scales=sd, precision=bits[0] if i < 4 else bits[1])
+        if name in ("q", "k", "v"):
+            e.update(x=B["h0"], in_op=nvq.IN_RMSNORM, gamma=B["g1"], eps=1e-5,
+                     y=torch.zeros((M, N), dtype=torch.float32, device=DEV))
+        elif name == "o":
+            e.update(x=B["attn"], y=B["o"])
+        elif name in ("gate", "up"):
+            e.update(x=B["h0"], x2=B["o"], in_op=nvq.IN_RMSNORM, gamma=B["g2"], eps=1e-5,
+                     h_out=B["h1"], y=B[name])
+        else:
+            e.update(x=B["gate"], x2=B["up"], in_op=nvq.IN_SILU_MUL,
+                     y=torch.zeros((M, N), dtype=torch.float32, device=DEV))
+        entries.append(e)
+    return entries, B, W
+
+
+def check_block_against_oracle(entries, B, W, M):
+    """Every stage against the oracle applied to the GPU's own inputs of that stage."""
+    names = ["q", "k", "v", "o", "gate", "up", "down"]
+    for e, name in zip(entries, names):
+        q, s = W[name]
+        h = dict(qweight=q, scales=s, x=u16(e["x"]), precision=e["precision"],
+                 in_op=e.get("in_op", 0))
+        if e.get("x2") is not None:
+            h["x2"] = u16(e["x2"])
+        if e.get("gamma") is not None:
+            h["gamma"], h["eps"] = u16(e["gamma"]), e["eps"]
+        y_r = oracle.decode_linears([h], M)[0]
+        got = e["y"].float().cpu().numpy()
+        err = np_ref.rel_l2(got, y_r)
+        assert err < 4e-3, (name, err)          # bf16 outputs and rare one-ulp input differences
+        if name == "gate":
+            assert np.array_equal(u16(B["h1"]), h["h"])       # the updated residual stream
+
+
+@pytest.mark.parametrize("M", [1, 3])
+@pytest.mark.parametrize("bits", [(0, 1), (1, 0)])
+def test_decode_linears_with_input_transforms(M, bits):
+    say("walker with transforms", M, bits)
+    entries, B, W = block_with_transforms(M, 2048, 512, 8192, 9500, bits)
+    dl = nvq.DecodeList(entries, M, 0)
+    info = dl.plan_info()
+    say("  plan", info)
+    for rep in range(2):
+        for k in ("o", "h1", "gate", "up"):
+            B[k].zero_()
+        dl.run_plan()
+        torch.cuda.synchronize()
+        assert not dl.plan_timed_out()
+        check_block_against_oracle(entries, B, W, M)
+    dl.close()
