@@ -85,6 +85,55 @@ def entries_for(layers, bits, nvq):
     return out
 
 
+def chain_entries(layers, bits, model, torch, nvq, synth, dev):
+    """The same linears wired up as a real decode step: RMSNorm in front of q/k/v and gate/up,
+    the residual adds fused into those norms, SiLU(gate)*up in front of down, a final norm in
+    front of lm_head; bf16 activations between the layers.  Attention itself is outside the
+    path: o reads a seeded buffer of its own.  Every phase but o depends on its predecessor."""
+    nb, hidden, kv, ffn, vocab = synth.MODELS[model]
+    bf = dict(dtype=torch.bfloat16, device=dev)
+    gen = torch.Generator().manual_seed(synth.BASE_SEED + 800_000)
+    gam = lambda: (1.0 + 0.1 * torch.randn(hidden, generator=gen)).to(torch.bfloat16).to(dev)
+    h = synth.make_activation(synth.activation_seed(10_000), 1, hidden, True, device=dev)
+    down = None
+    out = []
+    by_block = {}
+    for L in layers:
+        by_block.setdefault(L["spec"].block, []).append(L)
+    for b in range(nb):
+        q, k, v, o, gate, up, dn = by_block[b]
+        prec = bits[b]
+        g1, g2 = gam(), gam()
+        h_in = torch.zeros((1, hidden), **bf) if down is not None else None
+        for L in (q, k, v):
+            e = dict(qweight=L["qweight"], scales=L["scales"], precision=prec, x=h,
+                     in_op=nvq.IN_RMSNORM, gamma=g1, eps=1e-5,
+                     y=torch.zeros((1, L["spec"].N), **bf))
+            if down is not None:
+                e.update(x2=down, h_out=h_in)
+            out.append(e)
+        if down is not None:
+            h = h_in
+        attn = synth.make_activation(synth.activation_seed(20_000 + b), 1, hidden, True, device=dev)
+        o_out = torch.zeros((1, hidden), **bf)
+        out.append(dict(qweight=o["qweight"], scales=o["scales"], precision=prec, x=attn, y=o_out))
+        h1 = torch.zeros((1, hidden), **bf)
+        gbuf, ubuf = torch.zeros((1, ffn), **bf), torch.zeros((1, ffn), **bf)
+        for L, y in ((gate, gbuf), (up, ubuf)):
+            out.append(dict(qweight=L["qweight"], scales=L["scales"], precision=prec, x=h, x2=o_out,
+                            in_op=nvq.IN_RMSNORM, gamma=g2, eps=1e-5, h_out=h1, y=y))
+        h = h1
+        down = torch.zeros((1, hidden), **bf)
+        out.append(dict(qweight=dn["qweight"], scales=dn["scales"], precision=prec, x=gbuf, x2=ubuf,
+                        in_op=nvq.IN_SILU_MUL, y=down))
+    if -1 in by_block:
+        (head,) = by_block[-1]
+        out.append(dict(qweight=head["qweight"], scales=head["scales"], precision=nvq.W4A16, x=h,
+                        x2=down, in_op=nvq.IN_RMSNORM, gamma=gam(), eps=1e-5,
+                        y=torch.zeros((1, head["spec"].N), dtype=torch.float32, device=dev)))
+    return out
+
+
 def time_steps(dl, steps, warmup, torch):
     """K walks of the prepared plan.  Returns (wall seconds per step between two device
     synchronisations, seconds per launch from HIP events on the launch stream)."""
@@ -240,6 +289,14 @@ def main():
             out["config"]["dequant_bf16_gbs"] = round(nw * 2.5625 * 20 / (e0.elapsed_time(e1) * 1e-3)
                                                       / 1e9, 1)
             del dense
+            if M == 1:
+                # the realistic dependent step: norms, residual adds and SiLU-multiply fused in
+                d4 = nvq.DecodeList(chain_entries(layers, bits, a.model, torch, nvq, synth, dev), 1,
+                                    a.act_group)
+                w4, _ = time_steps(d4, max(a.steps // 2, 1), max(a.warmup // 2, 1), torch)
+                out["config"]["tokens_per_s_block_chain"] = round(1 / w4, 2)
+                out["config"]["block_chain_plan"] = d4.plan_info()
+                d4.close()
             d3 = nvq.DecodeList(entries_for(layers, bits, nvq), M, a.act_group, ordered=True)
             w3, _ = time_steps(d3, max(a.steps // 2, 1), max(a.warmup // 2, 1), torch)
             out["config"]["tokens_per_s_ordered_chain"] = round(M / w3, 2)

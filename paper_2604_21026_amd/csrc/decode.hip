@@ -363,8 +363,12 @@ std::vector<StreamPhase> stream_table(const nvq_linear *L, const std::vector<Pha
         const nvq_linear &e0 = L[ph.first];
         const int G = e0.K / 32;
         if (e0.K > kStreamMaxK) return {};
-        if (e0.in_op != NVQ_IN_PLAIN) return {};
         StreamPhase sp = {};
+        sp.in_op = e0.in_op;
+        sp.eps = e0.eps;
+        sp.x2 = e0.in_op != NVQ_IN_PLAIN ? e0.x2_bf16 : nullptr;
+        sp.gamma = e0.in_op == NVQ_IN_RMSNORM ? e0.gamma_bf16 : nullptr;
+        sp.h_out = e0.in_op == NVQ_IN_RMSNORM && e0.x2_bf16 ? e0.h_out_bf16 : nullptr;
         int rows = 0;
         for (int k = 0; k < ph.count; ++k) {
             const nvq_linear &e = L[ph.first + k];

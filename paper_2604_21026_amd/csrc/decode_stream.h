@@ -24,6 +24,12 @@ struct StreamPhase {
     int row_end[kMaxSeg];  // first row after segment i (rows numbered across segments)
     int y_dtype[kMaxSeg];
     const uint16_t *x;     // bf16 [K]
+    // what stands between x and the layer (NVQ_IN_*): RMSNorm of x (+ x2) times
+    // gamma, with the sum stored to h_out, or SiLU(x) * x2
+    const uint16_t *x2, *gamma;
+    uint16_t *h_out;
+    int in_op;
+    float eps;
     int nseg, total_rows;
     int K, G, gpl;         // G = K/32 (even), gpl = ceil(G/64) <= 7
     int precision;         // NVQ_W4A8 | NVQ_W4A16

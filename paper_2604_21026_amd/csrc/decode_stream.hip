@@ -56,6 +56,7 @@
 #include <type_traits>
 
 #include "decode_stream.h"
+#include "transform.h"
 
 namespace nvq {
 
@@ -87,6 +88,7 @@ struct Shared {
     uint32_t sring[kStreamWaves][kSlots][64];  // one dword per lane: zero-extended fp16 scale
     uint4 area[kStreamImageArea / 16];  // activation images of consecutive phases (circular)
     float amax_part[kStreamWaves];
+    float sumsq_part[kStreamWaves];
     uint32_t progress[kStreamWaves];  // phases finished by each streaming wave
     uint32_t img_ready;               // images of phases < img_ready are in LDS
     int abort;
@@ -409,13 +411,19 @@ __device__ __forceinline__ void image_put(const Writer &wr, const ImgLayout<PER_
 }
 
 // Build the image of phase `ph` from its raw input, all waves of the workgroup
-// together: wave w handles the 512-value pieces w, w + waves, ...  The caller
-// guarantees that nobody still reads the destination and that sh.amax_part is
-// free; one barrier is used inside (absmax exchange, W4A8 per-token only).
+// together: wave w handles the 512-value pieces w, w + waves, ...  The phase's
+// input transform (RMSNorm with residual add, SiLU-multiply; paper: kernel
+// table) is applied on the way, so it costs no launch and no pass over memory;
+// `store_h` says whether this workgroup stores the residual sum.  The caller
+// guarantees that nobody still reads the destination and that sh.amax_part and
+// sh.sumsq_part are free; up to two barriers are used inside (sum of squares
+// for RMSNorm; absmax exchange for W4A8 with a per-token scale).
 template <bool PER_GROUP, class Writer>
 __device__ __forceinline__ void image_build(const Writer &wr, CPhase &ph, Shared &sh, int w,
-                                            int lane) {
+                                            int lane, bool store_h) {
+    const int in_op = ph.in_op;
     if (w >= kStreamWaves) {  // the loader wave only keeps the barrier count
+        if (in_op == NVQ_IN_RMSNORM) lds_barrier();
         if (ph.precision == NVQ_W4A8 && !PER_GROUP) lds_barrier();
         return;
     }
@@ -424,17 +432,52 @@ __device__ __forceinline__ void image_build(const Writer &wr, CPhase &ph, Shared
     const ImgLayout<PER_GROUP> L(w4a8, G);
     const int nxc = (K + kXChunkElems - 1) / kXChunkElems;
     const uint4 *x = reinterpret_cast<const uint4 *>(ph.x);
+    const uint4 *x2 = reinterpret_cast<const uint4 *>(ph.x2);
     uint4 xsh[kMaxXShare];
-    float amax = 0.0f;
+    float ss = 0.0f;
 #pragma unroll
     for (int k = 0; k < kMaxXShare; ++k) {
         const int j = w + k * kStreamWaves;
+        const int idx = j * 64 + lane;
         xsh[k] = make_uint4(0, 0, 0, 0);
-        if (j < nxc) {
-            if (j * 64 + lane < K / 8) xsh[k] = x[j * 64 + lane];
-            amax = fmaxf(amax, chunk_absmax(xsh[k]));
+        if (j < nxc && idx < K / 8) {
+            xsh[k] = x[idx];
+            if (in_op == NVQ_IN_SILU_MUL) {
+                xsh[k] = silu_mul_bf16x8(xsh[k], x2[idx]);
+            } else if (in_op == NVQ_IN_RMSNORM) {
+                if (x2) {
+                    xsh[k] = add_bf16x8(xsh[k], x2[idx]);
+                    if (store_h && ph.h_out) reinterpret_cast<uint4 *>(ph.h_out)[idx] = xsh[k];
+                }
+                ss += sumsq_bf16x8(xsh[k]);
+            }
         }
     }
+    if (in_op == NVQ_IN_RMSNORM) {
+        ss = wave_sum_to_lane63(ss);
+        if (lane == 63) lds_write4(lds_addr(&sh.sumsq_part[w]), __float_as_uint(ss));
+        lds_barrier();
+        float tot = 0.0f;
+#pragma unroll
+        for (int k = 0; k < kStreamWaves; k += 4) {
+            const uint4 a = lds_read16(lds_addr(&sh.sumsq_part[k]));
+            tot += __uint_as_float(a.x);
+            tot += __uint_as_float(a.y);
+            tot += __uint_as_float(a.z);
+            tot += __uint_as_float(a.w);
+        }
+        const float r = rms_scale(tot, K, ph.eps);
+        const uint4 *gamma = reinterpret_cast<const uint4 *>(ph.gamma);
+#pragma unroll
+        for (int k = 0; k < kMaxXShare; ++k) {
+            const int j = w + k * kStreamWaves;
+            const int idx = j * 64 + lane;
+            if (j < nxc && idx < K / 8) xsh[k] = scale_bf16x8(xsh[k], r, gamma[idx]);
+        }
+    }
+    float amax = 0.0f;
+#pragma unroll
+    for (int k = 0; k < kMaxXShare; ++k) amax = fmaxf(amax, chunk_absmax(xsh[k]));
     float s_tok = 0.0f;
     if (w4a8 && !PER_GROUP) {
         amax = wave_max_to_lane63(amax);
@@ -535,7 +578,7 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
             CPhase &ph = tab[p];
             if (ph.img) {
                 const GlobalWriter wr = {reinterpret_cast<char *>(const_cast<uint4 *>(ph.img))};
-                image_build<PER_GROUP>(wr, ph, sh, w, lane);
+                image_build<PER_GROUP>(wr, ph, sh, w, lane, true);
                 __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // this wave's image stores have completed
                 lds_barrier();                             // (and sh.amax_part may be reused)
                 if (w == 0) {
@@ -660,7 +703,7 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
                 lds_barrier();  // dependency satisfied
                 if (lds_read4_uniform(abort_a)) break;
                 const LdsWriter wr = {0};
-                image_build<PER_GROUP>(wr, ph, sh, w, lane);  // barrier count only
+                image_build<PER_GROUP>(wr, ph, sh, w, lane, false);  // barrier count only
                 lds_barrier();  // image complete
                 q = p + 1;
             }
@@ -727,7 +770,7 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
             if (lds_read4_uniform(abort_a)) break;
             trace_mark(trace, wg, w, lane, p, 1);
             const LdsWriter wr = {img};
-            image_build<PER_GROUP>(wr, ph, sh, w, lane);
+            image_build<PER_GROUP>(wr, ph, sh, w, lane, wg == 0);
             trace_mark(trace, wg, w, lane, p, 2);
             lds_barrier();  // the image is complete
         } else {

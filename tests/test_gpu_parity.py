@@ -592,6 +592,9 @@ def test_decode_linears_with_input_transforms(M, bits):
     dl = nvq.DecodeList(entries, M, 0)
     info = dl.plan_info()
     say("  plan", info)
+    if M == 1:
+        # one launch; gate/up wait for o (their residual operand), down waits for gate/up
+        assert info["streaming"] and info["phases"] == 4 and info["waits"] == 2
     for rep in range(2):
         for k in ("o", "h1", "gate", "up"):
             B[k].zero_()
@@ -599,4 +602,37 @@ def test_decode_linears_with_input_transforms(M, bits):
         torch.cuda.synchronize()
         assert not dl.plan_timed_out()
         check_block_against_oracle(entries, B, W, M)
+    dl.close()
+
+
+def test_chain_of_blocks_with_transforms_in_one_launch():
+    say("block chain with transforms")
+    # two blocks at the 1B shapes, the second fed by the first (the residual add of the first
+    # block's down projection happens in front of the second block's q/k/v), W4A8 then W4A16
+    M, hidden, kv, ffn = 1, 2048, 512, 8192
+    e0, B0, W0 = block_with_transforms(M, hidden, kv, ffn, 9600, (0, 0))
+    e1, B1, W1 = block_with_transforms(M, hidden, kv, ffn, 9700, (1, 1))
+    down0 = torch.zeros((M, hidden), dtype=torch.bfloat16, device=DEV)
+    e0[6]["y"] = down0
+    h2 = torch.zeros((M, hidden), dtype=torch.bfloat16, device=DEV)
+    for e in e1[:3]:                      # q/k/v of block 1: RMSNorm(h1 + down0), sum -> h2
+        e.update(x=B0["h1"], x2=down0, h_out=h2)
+    for e in e1[4:6]:                     # gate/up of block 1: RMSNorm(h2 + o1), sum -> h1'
+        e.update(x=h2)
+    entries = e0 + e1
+    dl = nvq.DecodeList(entries, M, 0)
+    info = dl.plan_info()
+    say("  plan", info)
+    assert info["streaming"] and info["phases"] == 8 and info["waits"] == 5
+    for rep in range(3):
+        for t in (B0["o"], B0["h1"], B0["gate"], B0["up"], down0, h2, B1["o"], B1["h1"],
+                  B1["gate"], B1["up"]):
+            t.zero_()
+        dl.run_plan()
+        torch.cuda.synchronize()
+        assert not dl.plan_timed_out()
+        check_block_against_oracle(e0, B0, W0, M)
+        check_block_against_oracle(e1, B1, W1, M)
+        # the residual stream entering block 1 is the exact bf16 sum
+        assert torch.equal(h2, B0["h1"] + down0)
     dl.close()
