@@ -2,14 +2,16 @@
 """Benchmark of the decode-linear hot path on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--model llama-8b]
-                    [--map mixed|w4a8|w4a16] [--leg all|step|cpu] [--extra]
+                    [--map mixed|w4a8|w4a16] [--leg all|step|cpu|calib] [--extra]
+                    [--batch M] [--act-group 0|32]
 
 A step is one walk (one run of a prepared nvq plan = one launch of the
 persistent streaming kernel) over every linear layer of one decode step at
 batch 1 of the named Llama-shaped model: activation quantisation for the W4A8
 layers, all GEMVs, lm_head (W4A16) where the model has one.  All weights and
 activations are resident in HBM before the timed region; every layer reads its
-own seeded input buffer.  Prints one JSON line; the design doc explains the fields.
+own seeded input buffer.  Prints one JSON line (metric, value, roofline of the
+persistent kernel from HIP events, cpu_baseline = the CPU oracle on a bounded sample).
 """
 import argparse
 import json
