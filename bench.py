@@ -26,6 +26,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 STREAM_KERNEL = "nvq::decode_stream_kernel<false>"
+GROUP_KERNEL = "nvq::gemv_mfma_group_kernel (+ nvq::quant_act_group_kernel)"
 
 
 def parse():
@@ -158,10 +159,12 @@ def time_steps(dl, steps, warmup, torch):
     return wall, e0.elapsed_time(e1) * 1e-3 / steps
 
 
-def traffic_from_profile(model, which):
-    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by a
+def traffic_from_profile(model, which, batch):
+    """HBM bytes per step measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by a
     copy kernel of known size); read from the committed summary, None if it is not there."""
-    path = os.path.join(ROOT, "profiles", "decode_stream_%s_%s_pmc.md" % (model, which))
+    name = ("decode_stream_%s_%s_pmc.md" % (model, which) if batch == 1 else
+            "gemv_mfma_group_%s_%s_batch%d_pmc.md" % (model, which, batch))
+    path = os.path.join(ROOT, "profiles", name)
     try:
         m = re.search(r"traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read())
         return float(m.group(1)) if m else None
@@ -264,8 +267,10 @@ def main():
         gbs = step_bytes / per_launch / 1e9
         out["roofline"] = {
             "bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": traffic_from_profile(a.model, a.map),
-            "kernel": STREAM_KERNEL if info["streaming"] else "per-phase launches",
+            "frac": round(gbs / HBM_PEAK_GBS, 4),
+            "traffic": traffic_from_profile(a.model, a.map, M),
+            "kernel": (STREAM_KERNEL if info["streaming"] else
+                       GROUP_KERNEL if info["grouped"] else "per-phase launches"),
             "launches": a.steps, "avg_launch_us": round(per_launch * 1e6, 2),  # per step
             "bytes_per_launch": step_bytes}
         dl.close()

@@ -575,7 +575,7 @@ extern "C" int nvq_plan_run(nvq_plan *pl, void *stream) {
 
 extern "C" int nvq_plan_info(const nvq_plan *pl, int *streaming, int *phases, int *waits) {
     if (!pl) return NVQ_ERR_INVALID_ARG;
-    if (streaming) *streaming = pl->nwg > 0 ? 1 : 0;
+    if (streaming) *streaming = pl->nwg > 0 ? 1 : pl->batches.empty() ? 0 : 2;
     if (phases) *phases = (int)pl->phases.size();
     if (waits) *waits = pl->nwaits;
     return NVQ_OK;
