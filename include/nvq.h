@@ -238,6 +238,22 @@ int nvq_plan_run(nvq_plan *plan, void *stream);
 int nvq_plan_info(const nvq_plan *plan, int *streaming, int *phases, int *waits);
 int nvq_plan_status(nvq_plan *plan, void *stream, int *timed_out);
 int nvq_plan_trace(nvq_plan *plan, uint64_t *buf, size_t bytes);
+/*
+ * nvq_plan_describe -- the host-side planning of a walk, without touching a
+ * device (for inspection and tests; the pointers in `layers` are only compared
+ * and checked for alignment, never followed).  `workgroups` = compute units the
+ * persistent kernel would use.  out (host, out_words int32): [0] phases,
+ * [1] the number of streaming waves the rows are dealt to if the list
+ * qualifies for the persistent kernel, else 0; then 12 words per
+ * phase: first entry, entries, the latest earlier phase it must wait for (-1:
+ * none), and for the persistent kernel: published (someone waits for it),
+ * rows, rows per wave, waves with one more row, the wave that gets the first
+ * of those, offset of the activation image in the LDS image area, the latest
+ * phase whose image it overwrites there (-1: none), image bytes, 1 if the
+ * image is prepared in the prologue.  NVQ_ERR_WORKSPACE if out is too small.
+ */
+int nvq_plan_describe(const nvq_linear *layers, int n, int M, int act_group, int flags,
+                      int workgroups, int32_t *out, int out_words);
 void nvq_plan_destroy(nvq_plan *plan);
 
 /*

@@ -435,6 +435,10 @@ std::vector<StreamPhase> stream_table(const nvq_linear *L, const std::vector<Pha
         live.swap(keep);
         live.push_back({(int)p, cursor, cursor + bytes});
         tab[p].img_lds = cursor;
+        // Images are loaded in phase order, so what an earlier image had to wait
+        // for has been waited for: the requirement is a running maximum (a region
+        // dropped from `live` above may still be partly in use).
+        if (p > 0 && tab[p - 1].img_need > need) need = tab[p - 1].img_need;
         tab[p].img_need = need;
         cursor += bytes;
     }
@@ -450,6 +454,10 @@ __global__ void fill_u32_kernel(uint32_t *p, int n, uint32_t v) {
 }  // namespace
 
 }  // namespace nvq
+
+namespace nvq {
+constexpr int kDescribeWords = 12;  // words per phase written by nvq_plan_describe
+}
 
 struct nvq_plan {
     std::vector<nvq_linear> layers;
@@ -578,6 +586,47 @@ extern "C" int nvq_plan_info(const nvq_plan *pl, int *streaming, int *phases, in
     if (streaming) *streaming = pl->nwg > 0 ? 1 : pl->batches.empty() ? 0 : 2;
     if (phases) *phases = (int)pl->phases.size();
     if (waits) *waits = pl->nwaits;
+    return NVQ_OK;
+}
+
+extern "C" int nvq_plan_describe(const nvq_linear *layers, int n, int M, int act_group, int flags,
+                                 int workgroups, int32_t *out, int out_words) {
+    using namespace nvq;
+    if (!out || out_words < 0 || workgroups <= 0 || (flags & ~NVQ_PLAN_ORDERED))
+        return NVQ_ERR_INVALID_ARG;
+    ListSizes ls;
+    const int rc = check_layers(layers, n, M, act_group, &ls);
+    if (rc != NVQ_OK) return rc;
+    const std::vector<Phase> phases = group_phases(layers, n);
+    const bool ordered = (flags & NVQ_PLAN_ORDERED) != 0;
+    int nimages = 0;
+    const std::vector<StreamPhase> tab =
+        stream_table(layers, phases, M, act_group, workgroups, ordered,
+                     reinterpret_cast<char *>(uintptr_t(4096)) /* never followed */, &nimages);
+    const std::vector<int> deps = phase_deps(layers, phases, M, ordered);
+    const int need = 2 + (int)phases.size() * kDescribeWords;
+    if (out_words < need) return NVQ_ERR_WORKSPACE;
+    out[0] = (int32_t)phases.size();
+    out[1] = tab.empty() ? 0 : workgroups * kStreamWaves;
+    for (size_t p = 0; p < phases.size(); ++p) {
+        int32_t *o = out + 2 + p * kDescribeWords;
+        o[0] = phases[p].first;
+        o[1] = phases[p].count;
+        o[2] = deps[p];
+        for (int k = 3; k < kDescribeWords; ++k) o[k] = 0;
+        if (!tab.empty()) {
+            const StreamPhase &sp = tab[p];
+            o[3] = sp.publish;
+            o[4] = sp.total_rows;
+            o[5] = sp.rows_base;
+            o[6] = sp.rows_extra;
+            o[7] = sp.rows_rot;
+            o[8] = sp.img_lds;
+            o[9] = sp.img_need;
+            o[10] = stream_image_bytes(sp.K, sp.precision, act_group);
+            o[11] = sp.img ? 1 : 0;
+        }
+    }
     return NVQ_OK;
 }
 

@@ -23,7 +23,7 @@ EXPORTS = (
     "nvq_status_string", "nvq_last_hip_error", "nvq_pack_int4", "nvq_quant_act_i8",
     "nvq_gemv_w4a16", "nvq_gemv_w4a8", "nvq_decode_workspace_bytes", "nvq_decode_linears",
     "nvq_plan_create", "nvq_plan_run", "nvq_plan_info", "nvq_plan_status", "nvq_plan_trace",
-    "nvq_plan_destroy",
+    "nvq_plan_destroy", "nvq_plan_describe",
     "nvq_dequant_bf16", "nvq_rms_norm_bf16", "nvq_silu_mul_bf16", "nvq_precision_from_scores", "nvq_stream_read", "nvq_stream_copy",
 )
 
@@ -77,6 +77,7 @@ def lib() -> C.CDLL:
     L.nvq_plan_status.argtypes = [vp, vp, C.POINTER(ci)]
     L.nvq_plan_trace.argtypes = [vp, vp, sz]
     L.nvq_plan_destroy.argtypes = [vp]
+    L.nvq_plan_describe.argtypes = [vp, ci, ci, ci, ci, ci, vp, ci]
     L.nvq_plan_destroy.restype = None
     L.nvq_precision_from_scores.argtypes = [vp, ci, C.c_double, C.c_double, vp]
     L.nvq_stream_read.argtypes = [vp, sz, vp, vp]
@@ -303,6 +304,25 @@ class DecodeList:
             self.close()
         except Exception:
             pass
+
+
+DESCRIBE_FIELDS = ("first", "count", "wait", "publish", "rows", "rows_base", "rows_extra",
+                   "rows_rot", "img_lds", "img_need", "img_bytes", "img_prepared")
+
+
+def plan_describe(linears: Sequence[Linear], M: int, act_group: int = 0, ordered: bool = False,
+                  workgroups: int = 256):
+    """Host-side planning of a walk (no device needed): (streaming waves or 0, [dict per
+    phase]).  `linears` are `Linear` structs; their pointers are compared, never followed."""
+    n = len(linears)
+    arr = (Linear * max(n, 1))(*linears)
+    words = 2 + n * len(DESCRIBE_FIELDS)
+    out = (C.c_int32 * words)()
+    _check(lib().nvq_plan_describe(C.byref(arr), n, M, act_group, PLAN_ORDERED if ordered else 0,
+                                   workgroups, out, words), "nvq_plan_describe")
+    k = len(DESCRIBE_FIELDS)
+    return int(out[1]), [dict(zip(DESCRIBE_FIELDS, out[2 + p * k:2 + (p + 1) * k]))
+                          for p in range(out[0])]
 
 
 def decode_linears(entries: Sequence[dict], M: int, act_group: int = 0) -> DecodeList:

@@ -1,0 +1,137 @@
+"""Host-side planning of the decode walk, checked without a GPU through
+nvq_plan_describe: phase grouping, dependency analysis, the dealing of rows to the
+streaming waves and the placement of activation images in the circular LDS area.
+The pointers in the layer list are made up (they are compared, never followed)."""
+import numpy as np
+import pytest
+
+from paper_2604_21026_amd import nvq, synth
+
+AREA = 59392          # bytes of the LDS image area (decode_stream.h)
+
+
+class Arena:
+    """Hands out made-up, 256-byte aligned device addresses."""
+
+    def __init__(self):
+        self.at = 1 << 20
+
+    def take(self, nbytes):
+        p = self.at
+        self.at += (int(nbytes) + 255) // 256 * 256
+        return p
+
+
+def linear(a, N, K, x, y=None, prec=0, y_f32=True, M=1, **kw):
+    y = y if y is not None else a.take(M * N * 4)
+    return nvq.Linear(a.take(N * K // 2), a.take(N * (K // 32) * 2), N, K, x, y,
+                      nvq.F32 if y_f32 else nvq.BF16, prec, kw.get("in_op", 0),
+                      kw.get("eps", 0.0), kw.get("x2"), kw.get("gamma"), kw.get("h_out"))
+
+
+def model_list(model, bits):
+    a = Arena()
+    xs, out = {}, []
+    for sp in synth.model_linears(model):
+        if sp.phase not in xs:
+            xs[sp.phase] = a.take(sp.K * 2)
+        out.append(linear(a, sp.N, sp.K, xs[sp.phase], prec=1 if sp.block < 0 else bits[sp.block]))
+    return out
+
+
+def rows_of_wave(ph, j, waves):
+    """First row and row count of wave j as the kernel computes them."""
+    k = (j - ph["rows_rot"]) % waves
+    more = min(k, ph["rows_extra"])
+    return k * ph["rows_base"] + more, ph["rows_base"] + (1 if k < ph["rows_extra"] else 0)
+
+
+@pytest.mark.parametrize("model", ["llama-1b", "llama-3b", "llama-8b"])
+def test_rows_are_dealt_once_each_and_evenly(model):
+    nb = synth.MODELS[model][0]
+    layers = model_list(model, synth.make_precision_map(nb, nb // 2))
+    waves, phases = nvq.plan_describe(layers, 1)
+    assert waves == 256 * 12
+    specs = synth.model_linears(model)
+    assert len(phases) == len({s.phase for s in specs})
+    load = np.zeros(waves)
+    for ph in phases:
+        assert ph["wait"] == -1 and ph["publish"] == 0          # every phase reads its own buffer
+        assert ph["rows_base"] * waves + ph["rows_extra"] == ph["rows"]
+        assert 0 <= ph["rows_rot"] < waves
+        K = layers[ph["first"]].K
+        covered = np.zeros(ph["rows"], np.int32)
+        for j in range(waves):
+            first, count = rows_of_wave(ph, j, waves)
+            covered[first:first + count] += 1
+            load[j] += count * (K // 32) * 18
+        assert covered.min() == 1 and covered.max() == 1         # every row exactly once
+    # no wave carries more than one of the largest rows more than another
+    biggest_row = max(l.K for l in layers) // 32 * 18
+    assert load.max() - load.min() <= biggest_row
+
+
+def test_image_regions_never_overwrite_an_image_that_may_still_be_read():
+    layers = model_list("llama-8b", synth.make_precision_map(32, 16))
+    _, phases = nvq.plan_describe(layers, 1)
+    for p, ph in enumerate(phases):
+        lo, hi = ph["img_lds"], ph["img_lds"] + ph["img_bytes"]
+        assert 0 <= lo and hi <= AREA and ph["img_bytes"] % 1024 == 0 and ph["img_prepared"] == 1
+        assert ph["img_need"] < p
+        assert p == 0 or ph["img_need"] >= phases[p - 1]["img_need"]     # images load in order
+        # the image may be loaded once every wave has finished phase img_need: the image of
+        # every later phase (img_need < q < p) may still be read and must be disjoint from it
+        for q in range(ph["img_need"] + 1, p):
+            qlo, qhi = phases[q]["img_lds"], phases[q]["img_lds"] + phases[q]["img_bytes"]
+            assert qhi <= lo or hi <= qlo, (p, q)
+    # the area is really reused (the requirement is not vacuous) and the loader can run ahead
+    assert max(ph["img_need"] for ph in phases) > 100
+    assert all(p - ph["img_need"] >= 2 for p, ph in enumerate(phases) if ph["img_need"] >= 0)
+
+
+def test_dependencies_follow_the_buffers():
+    a = Arena()
+    K = 2048
+    x0, y0, y1 = a.take(K * 2), a.take(K * 2), a.take(K * 2)
+    other, other2 = a.take(K * 2), a.take(K * 2)
+    layers = [
+        linear(a, K, K, x0, y0, y_f32=False),        # 0
+        linear(a, K, K, y0, y1, y_f32=False),        # 1 reads what 0 wrote
+        linear(a, K, K, other),                      # 2 independent
+        linear(a, K, K, other2, y0, y_f32=False),    # 3 writes what 1 read and 0 wrote
+        linear(a, K, K, x0, in_op=nvq.IN_RMSNORM, x2=y1, gamma=a.take(K * 2), eps=1e-5,
+               h_out=a.take(K * 2)),                 # 4 reads y1 through its second operand
+    ]
+    waves, phases = nvq.plan_describe(layers, 1)
+    assert waves and [ph["wait"] for ph in phases] == [-1, 0, -1, 1, 1]
+    assert [ph["publish"] for ph in phases] == [1, 1, 0, 0, 0]
+    # a phase whose input must be rebuilt after a wait has no prepared image
+    assert [ph["img_prepared"] for ph in phases] == [1, 0, 1, 0, 0]
+    # forced ordering: everybody waits for the one before
+    _, ordered = nvq.plan_describe(layers, 1, ordered=True)
+    assert [ph["wait"] for ph in ordered] == [-1, 0, 1, 2, 3]
+
+
+def test_grouping_needs_the_same_input_precision_and_transform():
+    a = Arena()
+    K = 1024
+    x, g = a.take(K * 2), a.take(K * 2)
+    layers = [linear(a, 64, K, x), linear(a, 64, K, x), linear(a, 64, K, x, prec=1),
+              linear(a, 64, K, x, prec=1, in_op=nvq.IN_RMSNORM, gamma=g, eps=1e-5),
+              linear(a, 64, K, x, prec=1, in_op=nvq.IN_RMSNORM, gamma=g, eps=1e-5),
+              linear(a, 64, K, x, prec=1, in_op=nvq.IN_RMSNORM, gamma=g, eps=1e-6)]
+    _, phases = nvq.plan_describe(layers, 1)
+    assert [(ph["first"], ph["count"]) for ph in phases] == [(0, 2), (2, 1), (3, 2), (5, 1)]
+    # at most four matrices per phase
+    many = [linear(a, 64, K, x) for _ in range(6)]
+    _, phases = nvq.plan_describe(many, 1)
+    assert [(ph["first"], ph["count"]) for ph in phases] == [(0, 4), (4, 2)]
+
+
+def test_lists_the_persistent_kernel_does_not_take():
+    a = Arena()
+    big = [linear(a, 8, 16384, a.take(16384 * 2))]           # wider than an image holds
+    waves, phases = nvq.plan_describe(big, 1)
+    assert waves == 0 and len(phases) == 1 and phases[0]["wait"] == -1
+    waves, _ = nvq.plan_describe(model_list("llama-1b", [0] * 16), 4)   # batch 4: not batch 1
+    assert waves == 0
