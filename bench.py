@@ -27,6 +27,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 STREAM_KERNEL = "nvq::decode_stream_kernel<false>"
 GROUP_KERNEL = "nvq::gemv_mfma_group_kernel (+ nvq::quant_act_group_kernel)"
+RING_KERNEL = "nvq::gemv_mfma_ring_kernel (+ nvq::quant_act_group_kernel)"
 
 
 def parse():
@@ -159,11 +160,11 @@ def time_steps(dl, steps, warmup, torch):
     return wall, e0.elapsed_time(e1) * 1e-3 / steps
 
 
-def traffic_from_profile(model, which, batch):
+def traffic_from_profile(model, which, batch, kind="group"):
     """HBM bytes per step measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by a
     copy kernel of known size); read from the committed summary, None if it is not there."""
     name = ("decode_stream_%s_%s_pmc.md" % (model, which) if batch == 1 else
-            "gemv_mfma_group_%s_%s_batch%d_pmc.md" % (model, which, batch))
+            "gemv_mfma_%s_%s_%s_batch%d_pmc.md" % (kind, model, which, batch))
     path = os.path.join(ROOT, "profiles", name)
     try:
         m = re.search(r"traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read())
@@ -268,8 +269,10 @@ def main():
         out["roofline"] = {
             "bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": round(gbs / HBM_PEAK_GBS, 4),
-            "traffic": traffic_from_profile(a.model, a.map, M),
+            "traffic": traffic_from_profile(a.model, a.map, M,
+                                            "ring" if info["persistent_grouped"] else "group"),
             "kernel": (STREAM_KERNEL if info["streaming"] else
+                       RING_KERNEL if info["persistent_grouped"] else
                        GROUP_KERNEL if info["grouped"] else "per-phase launches"),
             "launches": a.steps, "avg_launch_us": round(per_launch * 1e6, 2),  # per step
             "bytes_per_launch": step_bytes}

@@ -213,13 +213,16 @@ int nvq_decode_linears(const nvq_linear *layers, int n, int M, int act_group,
  *                    before it even when they share no buffer (the timing of
  *                    a fully dependent chain on independent inputs)
  *   nvq_plan_run     enqueues one walk on `stream`
- *   nvq_plan_info    streaming = 1 if the persistent kernel is used, 2 if the
- *                    walk is issued as grouped small-batch launches (two per
- *                    batch of independent phases), 0 for launches per phase;
+ *   nvq_plan_info    streaming = 1 if the persistent kernel is used, 2 or 3 if
+ *                    the walk is issued as grouped small-batch launches (two
+ *                    per batch of independent phases; 3: the product runs as
+ *                    a persistent grid fed through LDS rings, which needs
+ *                    M <= 16, every K a multiple of 512 and 16-byte aligned
+ *                    scale rows), 0 for launches per phase;
  *                    waits = number of phases that wait for an earlier phase
  *                    (grouped launches: number of batch boundaries)
  *   nvq_plan_status  synchronises `stream` and reports whether a wait inside
- *                    the persistent kernel gave up (its spins are bounded so
+ *                    a persistent kernel gave up (its spins are bounded so
  *                    that a grid that cannot be co-resident ends with an
  *                    error instead of a hang); outputs are invalid then
  *   nvq_plan_trace   diagnostic: give a device buffer of phases * 8 uint64

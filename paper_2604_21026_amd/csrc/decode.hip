@@ -41,6 +41,7 @@ struct Workspace {
     GroupPhase *gtab;   // [n]                 phase table of the grouped small-batch launches
     uint16_t *gjobs;    // [n]                 W4A8 phases, batch after batch
     uint16_t *gunits;   // [group_units]       phase of every 16-row tile, batch after batch
+    uint32_t *gteams;   // [n][2][kRingMaxTeams + 1]  per batch: unit ranges of the ring kernel's teams
     char *gquant;       // per-phase activation codes, scales and code sums
     size_t bytes;
 };
@@ -85,6 +86,7 @@ Workspace carve(void *base, int M, int n, const ListSizes &ls) {
     w.gtab = reinterpret_cast<GroupPhase *>(take(M > 1 ? nn * sizeof(GroupPhase) : 0));
     w.gjobs = reinterpret_cast<uint16_t *>(take(M > 1 ? nn * 2 : 0));
     w.gunits = reinterpret_cast<uint16_t *>(take(M > 1 ? ls.group_units * 2 : 0));
+    w.gteams = reinterpret_cast<uint32_t *>(take(M > 1 ? nn * 2 * (kRingMaxTeams + 1) * 4 : 0));
     w.gquant = take(M > 1 ? ls.group_quant : 0);
     w.bytes = off;
     return w;
@@ -276,12 +278,43 @@ std::vector<int> phase_deps(const nvq_linear *L, const std::vector<Phase> &phase
 struct GroupBatch {
     int job_first, njobs;    // range in the job list
     int unit_first, nunits;  // range in the unit list
+    int team_first, nteams;  // the batch's table in the team list (2 * (nteams + 1) words)
 };
 struct GroupPlan {
     std::vector<GroupPhase> tab;
     std::vector<uint16_t> jobs, units;
+    std::vector<uint32_t> teams;  // per batch: nteams + 1 unit cuts, then the phases at the cuts
     std::vector<GroupBatch> batches;
 };
+
+// Cut the units of a batch into `want` contiguous ranges of (nearly) equal
+// weight bytes for the persistent kernel's teams; a unit of phase p weighs G_p.
+void cut_batch(GroupPlan &gp, GroupBatch &b, int want) {
+    const int nteams = b.nunits < want ? b.nunits : want;
+    b.team_first = (int)gp.teams.size();
+    b.nteams = nteams;
+    if (nteams <= 0) return;
+    uint64_t total = 0;
+    for (int u = 0; u < b.nunits; ++u) total += (uint64_t)gp.tab[gp.units[(size_t)b.unit_first + u]].G;
+    std::vector<uint32_t> cut((size_t)nteams + 1), phase((size_t)nteams + 1);
+    uint64_t before = 0;  // weight of the units before u
+    int t = 0;
+    for (int u = 0; u < b.nunits; ++u) {
+        // team t starts at the first unit whose predecessors weigh t / nteams of the batch
+        while (t < nteams && before * (uint64_t)nteams >= (uint64_t)t * total) {
+            cut[(size_t)t] = (uint32_t)u;
+            phase[(size_t)t] = gp.units[(size_t)b.unit_first + u];
+            ++t;
+        }
+        before += (uint64_t)gp.tab[gp.units[(size_t)b.unit_first + u]].G;
+    }
+    for (; t <= nteams; ++t) {
+        cut[(size_t)t] = (uint32_t)b.nunits;
+        phase[(size_t)t] = gp.units[(size_t)b.unit_first + b.nunits - 1];
+    }
+    gp.teams.insert(gp.teams.end(), cut.begin(), cut.end());
+    gp.teams.insert(gp.teams.end(), phase.begin(), phase.end());
+}
 GroupPlan group_plan(const nvq_linear *L, const std::vector<Phase> &phases, int M, int act_group,
                      bool ordered, const Workspace &ws) {
     GroupPlan gp;
@@ -291,14 +324,16 @@ GroupPlan group_plan(const nvq_linear *L, const std::vector<Phase> &phases, int 
             !gemv_mfma_supported(make_segs(L, ph), L[ph.first].K, M))
             return gp;
     const std::vector<int> deps = phase_deps(L, phases, M, ordered);
+    const int want_teams = ring_team_count(M);
     size_t qoff = 0;
-    GroupBatch cur = {0, 0, 0, 0};
+    GroupBatch cur = {0, 0, 0, 0, 0, 0};
     int batch_first = 0;
     for (size_t p = 0; p < phases.size(); ++p) {
         const nvq_linear &e0 = L[phases[p].first];
         if (deps[p] >= batch_first) {  // depends on a phase of the open batch: close it
+            cut_batch(gp, cur, want_teams);
             gp.batches.push_back(cur);
-            cur = {(int)gp.jobs.size(), 0, (int)gp.units.size(), 0};
+            cur = {(int)gp.jobs.size(), 0, (int)gp.units.size(), 0, 0, 0};
             batch_first = (int)p;
         }
         GroupPhase g = {};
@@ -319,10 +354,12 @@ GroupPlan group_plan(const nvq_linear *L, const std::vector<Phase> &phases, int 
         }
         const int rows_per_unit = 16 * group_row_tiles(M);
         const int units = (g.segs.total_rows + rows_per_unit - 1) / rows_per_unit;
+        g.unit_count = units;
         gp.units.insert(gp.units.end(), (size_t)units, (uint16_t)p);
         cur.nunits += units;
         gp.tab.push_back(g);
     }
+    cut_batch(gp, cur, want_teams);
     gp.batches.push_back(cur);
     return gp;
 }
@@ -469,6 +506,7 @@ struct nvq_plan {
     int nwaits;        // phases that wait for an earlier phase (streaming kernel)
     int nimages;       // phases whose activation image is prepared in the prologue
     std::vector<nvq::GroupBatch> batches;  // grouped small-batch launches (empty: not used)
+    bool ring;         // grouped launches use the persistent ring kernel
     uint32_t runs;     // walks issued so far (advances the flag base)
     unsigned long long *trace;  // device buffer for per-phase timestamps, or nullptr
 };
@@ -505,6 +543,7 @@ extern "C" int nvq_plan_create(const nvq_linear *layers, int n, int M, int act_g
     pl->nphase = 0;
     pl->nwaits = 0;
     pl->nimages = 0;
+    pl->ring = false;
     hipStream_t st = (hipStream_t)stream;
     const int nwg = n > 0 ? stream_grid_limit() : 0;
     int nimages = 0;
@@ -543,6 +582,13 @@ extern "C" int nvq_plan_create(const nvq_linear *layers, int n, int M, int act_g
             if (e == hipSuccess)
                 e = hipMemcpyAsync(ws.gunits, gp.units.data(), gp.units.size() * 2,
                                    hipMemcpyHostToDevice, st);
+            if (e == hipSuccess && !gp.teams.empty())
+                e = hipMemcpyAsync(ws.gteams, gp.teams.data(), gp.teams.size() * 4,
+                                   hipMemcpyHostToDevice, st);
+            if (e == hipSuccess) {
+                hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, st, ws.status, 1, 0u);
+                e = hipGetLastError();
+            }
             if (e != hipSuccess) {
                 set_hip_error(e, "nvq_plan_create");
                 delete pl;
@@ -550,6 +596,11 @@ extern "C" int nvq_plan_create(const nvq_linear *layers, int n, int M, int act_g
             }
             pl->batches = gp.batches;
             pl->nwaits = (int)gp.batches.size() - 1;
+            // beyond 16 tokens the per-tile grid is still the faster one
+            pl->ring = M <= 16;
+            for (const Phase &ph : pl->phases)
+                pl->ring = pl->ring && gemv_mfma_ring_supported(make_segs(pl->layers.data(), ph),
+                                                                pl->layers[ph.first].K);
         }
     }
     *plan_out = pl;
@@ -572,8 +623,10 @@ extern "C" int nvq_plan_run(nvq_plan *pl, void *stream) {
             int rc = launch_quant_act_group(pl->ws.gtab, pl->ws.gjobs + b.job_first, b.njobs, pl->M,
                                             st);
             if (rc != NVQ_OK) return rc;
-            rc = launch_gemv_mfma_group(pl->ws.gtab, pl->ws.gunits + b.unit_first, b.nunits, pl->M,
-                                        st);
+            rc = pl->ring ? launch_gemv_mfma_ring(pl->ws.gtab, pl->ws.gteams + b.team_first, b.nteams,
+                                                  pl->M, pl->ws.status, st)
+                          : launch_gemv_mfma_group(pl->ws.gtab, pl->ws.gunits + b.unit_first,
+                                                   b.nunits, pl->M, st);
             if (rc != NVQ_OK) return rc;
         }
         return NVQ_OK;
@@ -583,7 +636,7 @@ extern "C" int nvq_plan_run(nvq_plan *pl, void *stream) {
 
 extern "C" int nvq_plan_info(const nvq_plan *pl, int *streaming, int *phases, int *waits) {
     if (!pl) return NVQ_ERR_INVALID_ARG;
-    if (streaming) *streaming = pl->nwg > 0 ? 1 : pl->batches.empty() ? 0 : 2;
+    if (streaming) *streaming = pl->nwg > 0 ? 1 : pl->batches.empty() ? 0 : pl->ring ? 3 : 2;
     if (phases) *phases = (int)pl->phases.size();
     if (waits) *waits = pl->nwaits;
     return NVQ_OK;
@@ -641,7 +694,7 @@ extern "C" int nvq_plan_trace(nvq_plan *pl, uint64_t *buf, size_t bytes) {
 extern "C" int nvq_plan_status(nvq_plan *pl, void *stream, int *timed_out) {
     if (!pl || !timed_out) return NVQ_ERR_INVALID_ARG;
     uint32_t v = 0;
-    if (pl->nwg > 0) {
+    if (pl->nwg > 0 || pl->ring) {
         NVQ_HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
         NVQ_HIP_TRY(hipMemcpy(&v, pl->ws.status, 4, hipMemcpyDeviceToHost));
     }

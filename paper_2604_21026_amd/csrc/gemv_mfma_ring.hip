@@ -1,0 +1,520 @@
+// Small-batch (2 <= M <= 32 tokens) products on the matrix cores, as one
+// persistent grid per batch of independent phases.  Paper: the W4A8 / W4A16
+// kernel descriptions; the arithmetic is that of the per-tile kernel
+// (gemv_mfma.hip), what differs is how the weights reach the waves.
+//
+// A short-lived workgroup per row tile loads, waits, computes and reduces, and
+// the few of them that fit a compute unit do not cover the memory latency.
+// Here the waves stay: a team (a loader wave and W consumer waves) walks a
+// contiguous range of the batch's units (a unit = R consecutive 16-row tiles
+// of some phase); the host cuts the batch into ranges of equal weight bytes,
+// so a team reads a table entry only when its range crosses into the next
+// phase.  A team splits into
+//   * one loader wave that copies the weights and scales of the units, column
+//     by column (a column = four groups = 64 bytes of each of the 16 rows of a
+//     tile), straight from global memory into LDS rings, one ring per consumer
+//     wave, running ahead across unit boundaries as far as the rings allow;
+//   * W = 4 consumer waves; a step is four consecutive columns of the unit,
+//     one per wave (K is a multiple of 512), so the waves advance together.
+//     Wave w reads column 4i + w of step i from its ring, loads the
+//     activations of the column itself (they come from the L2 cache, and the
+//     request for the next column is made before the current one is
+//     multiplied), feeds the MFMAs and, at the end of a unit, adds the W
+//     partial tiles through LDS in wave order.
+// Per step the loader issues 2 x 4 weight loads of 1 KiB (16 rows x 64 bytes)
+// and one scale load (32 rows x 32 bytes: the 16 scales of the step's four
+// columns).  Its loads are the only ones it has in flight and complete in
+// order, so "the oldest step not yet announced has arrived" is an exact vmcnt
+// wait; while the ring is full it announces step after step (`landed`), and a
+// consumer advances its `consumed` count once a step is in its registers; the
+// loader reuses a slot when every wave has consumed it.  All waits are bounded: a wave that gives up sets the abort
+// word, every wave then runs to the end without waiting, and the host finds
+// the status word set.
+#include "gemv_tile.h"
+#include "mfma_act.h"
+
+namespace nvq {
+
+namespace {
+
+typedef __attribute__((address_space(3))) void *lds_void_ptr;
+// The tables do not change during the kernel; read through the constant
+// address space they become scalar loads, which the loader needs: a vector
+// load would join its queue of ring loads and be waited for with vmcnt(0).
+typedef const __attribute__((address_space(4))) GroupPhase CGroup;
+typedef const __attribute__((address_space(4))) uint32_t CWord;
+
+constexpr int kRingWaves = 4;    // consumer waves per team (W)
+constexpr int kRingBundle = 3;   // units whose row tiles share the activation operands
+constexpr int kRingSteps = 4;    // ring capacity in steps (all may be in flight)
+constexpr int kTeamThreads = (kRingWaves + 1) * 64;  // a team: the consumers and their loader
+constexpr int kRingR = 2;        // row tiles per unit (the scale load fills 64 lanes)
+constexpr uint32_t kRingSpinLimit = 1u << 24;
+
+constexpr int ring_vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0f70; }
+
+template <int MT>
+struct RingShared {
+    uint4 ring[kRingWaves][kRingSteps][kRingR][64];  // lane (n, kb): group 4c + kb of row n
+    uint4 sring[kRingSteps][64];  // lane (r, n, half): scales of columns 4i+2half, 4i+2half+1
+    float red[2][kRingWaves][kRingR * MT * 4][64];   // partial tiles, by unit parity
+    alignas(16) uint32_t consumed[kRingWaves];  // steps each wave has copied into registers
+    uint32_t landed;                // steps that have arrived in the rings
+    uint32_t done;                  // partial tiles written so far (all units)
+    uint32_t abort;
+};
+
+// LDS words the waves signal through, as instructions: the compiler must not
+// cache them, and in the loader it would guard each access with vmcnt(0).
+__device__ __forceinline__ uint32_t ring_lds_addr(const void *p) { return (uint32_t)(uintptr_t)p; }
+__device__ __forceinline__ uint32_t ring_read_word(uint32_t addr) {
+    uint32_t v;
+    asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(addr) : "memory");
+    return (uint32_t)__builtin_amdgcn_readfirstlane((int)v);
+}
+typedef uint32_t ring_u32x4 __attribute__((ext_vector_type(4)));
+// the smallest of four consecutive words (16-byte aligned), wave-uniform
+__device__ __forceinline__ uint32_t ring_read_min4(uint32_t addr) {
+    ring_u32x4 v;
+    asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(addr) : "memory");
+    const uint32_t a = v.x < v.y ? v.x : v.y, b = v.z < v.w ? v.z : v.w;
+    return (uint32_t)__builtin_amdgcn_readfirstlane((int)(a < b ? a : b));
+}
+__device__ __forceinline__ void ring_write_word(uint32_t addr, uint32_t v) {
+    asm volatile("ds_write_b32 %0, %1" : : "v"(addr), "v"(v) : "memory");
+}
+__device__ __forceinline__ void ring_add_word(uint32_t addr, uint32_t v) {
+    asm volatile("ds_add_u32 %0, %1" : : "v"(addr), "v"(v) : "memory");
+}
+
+// Wait until the word at `addr` has reached `want` (counts only grow) and
+// return what it holds.  Gives up after kRingSpinLimit polls or when another
+// wave has given up.
+__device__ __forceinline__ uint32_t ring_wait(uint32_t addr, uint32_t want, uint32_t abort_addr,
+                                              bool &dead) {
+    if (dead) return want;
+    uint32_t spins = 0, seen;
+    while ((int32_t)((seen = ring_read_word(addr)) - want) < 0) {
+        __builtin_amdgcn_s_sleep(1);
+        if ((++spins & 1023u) == 0 && (ring_read_word(abort_addr) != 0 || spins >= kRingSpinLimit)) {
+            ring_write_word(abort_addr, 1u);
+            dead = true;
+            return want;
+        }
+    }
+    return seen;
+}
+
+// ---- the loader wave --------------------------------------------------------
+// The loader's loads are the only ones it has in flight and they complete in
+// order: with `outstanding` steps of OPS loads each not yet announced, the
+// oldest has arrived when at most (outstanding - 1) * OPS loads are pending.
+template <int OPS>
+__device__ __forceinline__ void ring_wait_oldest(uint32_t outstanding) {
+    if (outstanding >= 4)
+        __builtin_amdgcn_s_waitcnt(ring_vmcnt_imm(3 * OPS));
+    else if (outstanding == 3)
+        __builtin_amdgcn_s_waitcnt(ring_vmcnt_imm(2 * OPS));
+    else if (outstanding == 2)
+        __builtin_amdgcn_s_waitcnt(ring_vmcnt_imm(OPS));
+    else
+        __builtin_amdgcn_s_waitcnt(ring_vmcnt_imm(0));
+}
+
+// Units a team works on together: up to U consecutive units of one phase, so
+// that the activation operands of a column serve U * R row tiles.
+template <int U>
+__device__ __forceinline__ int bundle_units(int u, int u_end, int phase_end) {
+    int cnt = u_end - u;
+    cnt = cnt < phase_end - u ? cnt : phase_end - u;
+    return cnt < U ? cnt : U;
+}
+
+template <int MT, int U>
+__device__ __forceinline__ void ring_loader(CGroup *tab, int u, int u_end, int p,
+                                            RingShared<MT> &sh, int lane, bool &dead) {
+    constexpr int W = kRingWaves, S = kRingSteps, R = kRingR;
+    constexpr int kOps = R * W + 1;  // loads per step
+    static_assert(W == 4, "one 16-byte read fetches every wave's count");
+    static_assert(S == 4 && kOps * (S - 1) < 64, "ring_wait_oldest covers up to four steps");
+    const int n = lane & 15, kb = lane >> 4;
+    const int sr = lane >> 5, sn = (lane >> 1) & 15, shalf = lane & 1;
+    const uint32_t abort_addr = ring_lds_addr(&sh.abort);
+    const uint32_t landed_addr = ring_lds_addr(&sh.landed);
+    const uint32_t consumed_addr = ring_lds_addr(&sh.consumed[0]);
+    uint32_t T = 0;         // steps issued
+    uint32_t published = 0; // steps announced to the consumers
+    uint32_t cons_min = 0;  // a lower bound of every wave's consumed count
+
+    while (u < u_end) {
+        while (u >= tab[p].unit_begin + tab[p].unit_count) ++p;  // phases have at least one unit
+        CGroup &P = tab[p];
+        const int G = P.G, steps = G >> 4;
+        const int cnt = bundle_units<U>(u, u_end, P.unit_begin + P.unit_count);
+        const uint4 *gq[U][R], *gs[U];
+#pragma unroll
+        for (int j = 0; j < U; ++j) {
+            const int unit = u - P.unit_begin + (j < cnt ? j : 0);
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                gq[j][r] = locate_row(P.segs, (unit * R + r) * 16 + n, G).qw + kb;
+            // 16 bytes = the 8 scales of two columns
+            gs[j] = reinterpret_cast<const uint4 *>(
+                        locate_row(P.segs, (unit * R + sr) * 16 + sn, G).sc) +
+                    shalf;
+        }
+        for (int i = 0; i < steps; ++i) {
+#pragma unroll
+            for (int j = 0; j < U; ++j) {
+                if (j >= cnt) continue;
+                // No free slot: announce what has arrived in the meantime (the
+                // oldest load first; the wait returns at once if it is there),
+                // then watch the consumers.
+                uint32_t spins = 0;
+                while (T - cons_min >= (uint32_t)S && !dead) {
+                    if (published < T) {
+                        ring_wait_oldest<kOps>(T - published);
+                        ring_write_word(landed_addr, ++published);
+                        cons_min = ring_read_min4(consumed_addr);
+                        continue;
+                    }
+                    cons_min = ring_read_min4(consumed_addr);
+                    if (T - cons_min < (uint32_t)S) break;
+                    __builtin_amdgcn_s_sleep(1);
+                    if ((++spins & 1023u) == 0 &&
+                        (ring_read_word(abort_addr) != 0 || spins >= kRingSpinLimit)) {
+                        ring_write_word(abort_addr, 1u);
+                        dead = true;
+                    }
+                }
+                if (!dead) {  // else no further loads; the consumers no longer wait
+                    const int slot = (int)(T % S);
+#pragma unroll
+                    for (int w = 0; w < W; ++w)
+#pragma unroll
+                        for (int r = 0; r < R; ++r)
+                            __builtin_amdgcn_global_load_lds(
+                                (const void *)(gq[j][r] + 16 * i + 4 * w),
+                                (lds_void_ptr)&sh.ring[w][slot][r][0], 16, 0, 0);
+                    __builtin_amdgcn_global_load_lds((const void *)(gs[j] + 2 * i),
+                                                     (lds_void_ptr)&sh.sring[slot][0], 16, 0, 0);
+                }
+                ++T;
+            }
+        }
+        u += cnt;
+    }
+    // what is still in flight
+    __builtin_amdgcn_s_waitcnt(ring_vmcnt_imm(0));
+    ring_write_word(landed_addr, T);
+}
+
+// ---- the consumer waves -----------------------------------------------------
+// What a consumer needs of a unit (wave-uniform).
+struct RingUnit {
+    int phase, unit, G, C4, precision;
+    const char *xin;
+};
+
+__device__ __forceinline__ RingUnit ring_unit(CGroup *tab, int p, int u) {
+    RingUnit d;
+    CGroup &P = tab[p];
+    d.phase = p;
+    d.unit = u - P.unit_begin;
+    d.G = P.G;
+    d.C4 = d.G >> 2;
+    d.precision = P.precision;
+    d.xin = d.precision == NVQ_W4A8 ? reinterpret_cast<const char *>(P.xq)
+                                    : reinterpret_cast<const char *>(P.x_bf16);
+    return d;
+}
+
+// Request the activations of column c of unit d: for every token tile the
+// lane's 16-byte pieces (two for int8 codes, four for bf16).  Tokens past M
+// read token 0; their results are never stored.
+template <int MT>
+__device__ __forceinline__ void ring_request_a(const RingUnit &d, int c, int M, int n, int kb,
+                                               uint4v (&raw)[MT][4]) {
+    if (d.precision == NVQ_W4A8) {
+        const uint32_t row_bytes = (uint32_t)d.G * 32;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            const int m = mt * 16 + n;
+            const char *p = d.xin + (size_t)c * 128 + (m < M ? m : 0) * row_bytes + kb * 32;
+            raw[mt][0] = *as_global<uint4v>(p);
+            raw[mt][1] = *as_global<uint4v>(p + 16);
+        }
+    } else {
+        const uint32_t row_bytes = (uint32_t)d.G * 64;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            const int m = mt * 16 + n;
+            const char *p = d.xin + (size_t)c * 256 + (m < M ? m : 0) * row_bytes + kb * 16;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) raw[mt][i] = *as_global<uint4v>(p + 64 * i);
+        }
+    }
+}
+
+// The columns of a bundle of `cnt` units that belong to this wave.  `raw` holds
+// the activations of the first of them on entry and of the first column of the
+// next bundle on exit.
+template <int PREC, int MT, int U>
+__device__ __forceinline__ void ring_bundle_columns(const RingUnit &d, int cnt, const RingUnit &nxt,
+                                                    bool has_next, uint32_t &k,
+                                                    uint32_t &landed, int M,
+                                                    RingShared<MT> &sh, int w, int lane,
+                                                    bool &dead, uint4v (&raw)[MT][4],
+                                                    float (&f)[U][kRingR][MT][4]) {
+    typedef Act<PREC> A;
+    constexpr int W = kRingWaves, S = kRingSteps, R = kRingR;
+    const int n = lane & 15, kb = lane >> 4;
+    const uint32_t abort_addr = ring_lds_addr(&sh.abort);
+    const uint32_t landed_addr = ring_lds_addr(&sh.landed);
+    const uint32_t consumed_addr = ring_lds_addr(&sh.consumed[w]);
+
+    for (int c = w; c < d.C4; c += W) {
+        // operands of this column, then the request for the following one
+        typename A::operand act[MT][4];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) A::operands(raw[mt], act[mt]);
+        if (c + W < d.C4)
+            ring_request_a<MT>(d, c + W, M, n, kb, raw);
+        else if (has_next)
+            ring_request_a<MT>(nxt, w, M, n, kb, raw);
+#pragma unroll
+        for (int j = 0; j < U; ++j) {
+            if (j >= cnt) continue;
+            // the loader is usually ahead: ask again only past what was seen
+            if ((int32_t)(landed - (k + 1)) < 0)
+                landed = ring_wait(landed_addr, k + 1, abort_addr, dead);
+            const int slot = (int)(k % S);
+            uint4 wv[R];
+            uint2 sc[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                wv[r] = sh.ring[w][slot][r][lane];
+                // the wave's column is the first or second half of 16-byte piece w / 2
+                sc[r] = reinterpret_cast<const uint2 *>(
+                    &sh.sring[slot][(r * 16 + n) * 2 + (w >> 1)])[w & 1];
+            }
+            // the slot is free once these reads have been carried out; LDS serves
+            // a wave's requests in order, so the write below comes after them
+            asm volatile("" ::: "memory");
+            ++k;
+            if (lane == 0) ring_write_word(consumed_addr, k);
+
+            uint32_t q[R][4];
+            float sw[R][4];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                q[r][0] = wv[r].x;
+                q[r][1] = wv[r].y;
+                q[r][2] = wv[r].z;
+                q[r][3] = wv[r].w;
+                transpose_rows(q[r]);
+                sw[r][0] = half_bits_to_float((uint16_t)(sc[r].x & 0xffffu));
+                sw[r][1] = half_bits_to_float((uint16_t)(sc[r].x >> 16));
+                sw[r][2] = half_bits_to_float((uint16_t)(sc[r].y & 0xffffu));
+                sw[r][3] = half_bits_to_float((uint16_t)(sc[r].y >> 16));
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    // the correction term, recomputed per unit: an MFMA is cheaper
+                    // than the registers that would keep it
+                    const typename A::offset_t off = A::offset(act[mt][i]);
+#pragma unroll
+                    for (int r = 0; r < R; ++r) {
+                        int4v acc;
+                        const float4v p = A::product(act[mt][i], A::weights(q[r][i]), off, acc);
+                        f[j][r][mt][0] = fmaf(sw[r][i], p.x, f[j][r][mt][0]);
+                        f[j][r][mt][1] = fmaf(sw[r][i], p.y, f[j][r][mt][1]);
+                        f[j][r][mt][2] = fmaf(sw[r][i], p.z, f[j][r][mt][2]);
+                        f[j][r][mt][3] = fmaf(sw[r][i], p.w, f[j][r][mt][3]);
+                    }
+                }
+            }
+        }
+    }
+}
+
+template <int MT, int U>
+__device__ __forceinline__ void ring_consumer(CGroup *tab, int u, int u_end, int p, int M,
+                                              RingShared<MT> &sh, int w, int lane, bool &dead) {
+    constexpr int W = kRingWaves, R = kRingR;
+    constexpr int kTile = R * MT * 4;
+    const int n = lane & 15, kb = lane >> 4;
+    const uint32_t abort_addr = ring_lds_addr(&sh.abort);
+    const uint32_t done_addr = ring_lds_addr(&sh.done);
+    if (u >= u_end) return;
+
+    uint32_t k = 0;       // steps this wave has consumed
+    uint32_t landed = 0;  // steps known to have arrived
+    uint32_t units_done = 0;
+    while (u >= tab[p].unit_begin + tab[p].unit_count) ++p;
+    RingUnit cur = ring_unit(tab, p, u);
+    int phase_end = tab[p].unit_begin + tab[p].unit_count;
+    uint4v raw[MT][4];
+    ring_request_a<MT>(cur, w, M, n, kb, raw);
+    float xs[MT][4];  // per-token activation scale of the lane's result registers (W4A8)
+    bool fresh = true;
+
+    while (u < u_end) {
+        const int cnt = bundle_units<U>(u, u_end, phase_end);
+        const bool has_next = u + cnt < u_end;
+        RingUnit nxt = cur;
+        nxt.unit = cur.unit + cnt;
+        int phase_end_next = phase_end;
+        if (has_next && u + cnt >= phase_end) {  // the next bundle opens the next phase
+            nxt = ring_unit(tab, cur.phase + 1, u + cnt);
+            phase_end_next = tab[nxt.phase].unit_begin + tab[nxt.phase].unit_count;
+        }
+        CGroup &P = tab[cur.phase];
+        if (fresh) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) {
+                    const int m = mt * 16 + kb * 4 + jj;
+                    xs[mt][jj] = (cur.precision == NVQ_W4A8 && m < M)
+                                     ? as_global<float>(P.xscale)[m]
+                                     : 1.0f;
+                }
+        }
+
+        float f[U][R][MT][4];
+#pragma unroll
+        for (int j = 0; j < U; ++j)
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj) f[j][r][mt][jj] = 0.0f;
+
+        if (cur.precision == NVQ_W4A8)
+            ring_bundle_columns<NVQ_W4A8, MT, U>(cur, cnt, nxt, has_next, k, landed, M, sh, w, lane, dead,
+                                                 raw, f);
+        else
+            ring_bundle_columns<NVQ_W4A16, MT, U>(cur, cnt, nxt, has_next, k, landed, M, sh, w, lane, dead,
+                                                  raw, f);
+
+        // unit by unit, add the K slices of the waves in wave order
+#pragma unroll
+        for (int j = 0; j < U; ++j) {
+            if (j >= cnt) continue;
+            const int par = (int)(units_done & 1u);
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj)
+                        sh.red[par][w][(r * MT + mt) * 4 + jj][lane] = f[j][r][mt][jj] * xs[mt][jj];
+            asm volatile("" ::: "memory");
+            if (lane == 0) ring_add_word(done_addr, 1u);
+            ++units_done;
+            ring_wait(done_addr, units_done * (uint32_t)W, abort_addr, dead);
+            if (!dead) {
+#pragma unroll
+                for (int pass = 0; pass < (kTile + W - 1) / W; ++pass) {
+                    const int reg = pass * W + w;
+                    if (reg < kTile) {
+                        float sum = 0.0f;
+#pragma unroll
+                        for (int i = 0; i < W; ++i) sum += sh.red[par][i][reg][lane];
+                        const int r = reg / (MT * 4), mt = (reg >> 2) % MT, jj = reg & 3;
+                        const int m = mt * 16 + kb * 4 + jj;
+                        const RowRef o =
+                            locate_row(P.segs, ((cur.unit + j) * R + r) * 16 + n, cur.G);
+                        if (o.valid && m < M)
+                            store_global(o.y, o.y_dtype, (int64_t)m * o.N + o.n, sum);
+                    }
+                }
+            }
+        }
+        fresh = nxt.phase != cur.phase;
+        cur = nxt;
+        phase_end = phase_end_next;
+        u += cnt;
+    }
+}
+
+// TEAMS teams share a workgroup (and nothing else): one workgroup per compute
+// unit holds all the LDS, which several smaller workgroups could not divide
+// among themselves as well.  Team j = g * TEAMS + t walks the units
+// team_tab[j] .. team_tab[j + 1] - 1; team_tab[nteams + 1 + j] is the phase of
+// its first unit.
+template <int MT, int TEAMS, int U>
+__global__ __launch_bounds__(TEAMS *kTeamThreads) void gemv_mfma_ring_kernel(
+    const GroupPhase *__restrict__ tab_, const uint32_t *__restrict__ team_tab_, int nteams, int M,
+    uint32_t *__restrict__ status) {
+    __shared__ RingShared<MT> shared[TEAMS];
+    CGroup *tab = (CGroup *)tab_;
+    CWord *team_tab = (CWord *)team_tab_;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int t = wave / (kRingWaves + 1), w = wave - t * (kRingWaves + 1);
+    RingShared<MT> &sh = shared[t];
+    if (w == 0 && lane < kRingWaves) sh.consumed[lane] = 0;
+    if (w == 0 && lane == 0) {
+        sh.landed = 0;
+        sh.done = 0;
+        sh.abort = 0;
+    }
+    __syncthreads();
+    const int team = (int)blockIdx.x * TEAMS + t;
+    int u = 0, u_end = 0, p = 0;
+    if (team < nteams) {
+        u = (int)team_tab[team];
+        u_end = (int)team_tab[team + 1];
+        p = (int)team_tab[nteams + 1 + team];
+    }
+    bool dead = false;
+    if (w == kRingWaves) __builtin_amdgcn_s_setprio(3);  // the loader's few instructions go first
+    if (w == kRingWaves)
+        ring_loader<MT, U>(tab, u, u_end, p, sh, lane, dead);
+    else
+        ring_consumer<MT, U>(tab, u, u_end, p, M, sh, w, lane, dead);
+    if (dead && lane == 0) __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+}  // namespace
+
+// A step is four columns (512 inputs), and the scale load moves 16 bytes per lane.
+bool gemv_mfma_ring_supported(const GemvSegs &S, int K) {
+    if (K % (128 * kRingWaves) != 0) return false;
+    for (int i = 0; i < S.nseg; ++i)
+        if (!aligned(S.sc[i], 16)) return false;
+    return true;
+}
+
+int ring_teams_per_workgroup(int M) { return M > 16 ? 2 : 3; }
+
+// One workgroup per compute unit: three teams (52 KiB of LDS each) up to 16
+// tokens, two (68 KiB each) beyond.
+int ring_team_count(int M) {
+    const int t = device_cu_count() * ring_teams_per_workgroup(M);
+    return t < kRingMaxTeams ? t : kRingMaxTeams;
+}
+
+// team_tab: nteams + 1 unit indices (the cuts of the batch), then nteams + 1
+// phase indices (the phase of each cut's unit), in device memory.
+int launch_gemv_mfma_ring(const GroupPhase *tab, const uint32_t *team_tab, int nteams, int M,
+                          uint32_t *status, hipStream_t st) {
+    if (nteams <= 0) return NVQ_OK;
+    const int tpw = ring_teams_per_workgroup(M);
+    const dim3 grid((nteams + tpw - 1) / tpw), block(tpw * kTeamThreads);
+    if (M > 16)
+        hipLaunchKernelGGL((gemv_mfma_ring_kernel<2, 2, 1>), grid, block, 0, st, tab, team_tab, nteams,
+                           M, status);
+    else
+        hipLaunchKernelGGL((gemv_mfma_ring_kernel<1, 3, kRingBundle>), grid, block, 0, st, tab, team_tab, nteams,
+                           M, status);
+    NVQ_HIP_TRY(hipGetLastError());
+    return NVQ_OK;
+}
+
+}  // namespace nvq

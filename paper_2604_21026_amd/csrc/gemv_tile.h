@@ -25,8 +25,10 @@ struct RowRef {
 };
 
 // Map a global row number to its segment.  Rows past the end are clamped to
-// the last row so that loads stay in bounds; `valid` masks the stores.
-__device__ __forceinline__ RowRef locate_row(const GemvSegs &S, int row, int G) {
+// the last row so that loads stay in bounds; `valid` masks the stores.  SEGS is
+// a (possibly address-space qualified) GemvSegs.
+template <typename SEGS>
+__device__ __forceinline__ RowRef locate_row(SEGS &S, int row, int G) {
     RowRef r;
     r.valid = row < S.total_rows;
     if (!r.valid) row = S.total_rows - 1;

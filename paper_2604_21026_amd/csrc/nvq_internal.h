@@ -66,6 +66,7 @@ struct GroupPhase {
     int32_t *xgsum;          // [M][K/32] code sums
     int G, precision;
     int unit_begin;          // first grid unit of the phase in its batch
+    int unit_count;          // its units
 };
 // jobs[j] names the phase whose M tokens grid blocks j*M .. j*M+M-1 quantise.
 int launch_quant_act_group(const GroupPhase *tab, const uint16_t *jobs, int njobs, int M,
@@ -76,6 +77,17 @@ int launch_quant_act_group(const GroupPhase *tab, const uint16_t *jobs, int njob
 static inline int group_row_tiles(int M) { (void)M; return 2; }
 int launch_gemv_mfma_group(const GroupPhase *tab, const uint16_t *unit_phase, int nunits, int M,
                            hipStream_t st);
+// The same work as one persistent grid of teams (a loader wave feeding four
+// consumer waves through LDS rings), each walking a contiguous range of the
+// batch's units; needs K % 512 == 0 and 16-byte aligned scale rows in every
+// phase.  team_tab (device memory): nteams + 1 unit indices, the cuts of the
+// batch, then nteams + 1 phase indices, the phase of the unit at each cut.  A
+// wait inside the kernel that gives up sets *status.
+constexpr int kRingMaxTeams = 1024;
+bool gemv_mfma_ring_supported(const GemvSegs &segs, int K);
+int ring_team_count(int M);
+int launch_gemv_mfma_ring(const GroupPhase *tab, const uint32_t *team_tab, int nteams, int M,
+                          uint32_t *status, hipStream_t st);
 
 // ---- device helpers -------------------------------------------------------
 #if defined(__HIPCC__)

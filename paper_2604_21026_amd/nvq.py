@@ -280,8 +280,8 @@ class DecodeList:
         s, p, w = C.c_int(), C.c_int(), C.c_int()
         _check(lib().nvq_plan_info(self.plan(), C.byref(s), C.byref(p), C.byref(w)),
                "nvq_plan_info")
-        return {"streaming": s.value == 1, "grouped": s.value == 2, "phases": p.value,
-                "waits": w.value}
+        return {"streaming": s.value == 1, "grouped": s.value in (2, 3),
+                "persistent_grouped": s.value == 3, "phases": p.value, "waits": w.value}
 
     def plan_timed_out(self) -> bool:
         t = C.c_int()

@@ -439,6 +439,7 @@ def test_grouped_plan_matches_oracle_on_repeated_runs(name, M, ordered):
     info = dl.plan_info()
     say("  plan", info)
     assert not info["streaming"]
+    assert info["persistent_grouped"] == (M <= 16)
     # "waits" counts the batch boundaries: independent buffers make one batch of all phases
     assert info["waits"] == (info["phases"] - 1 if ordered else 0)
     for rep in range(3):
@@ -446,6 +447,7 @@ def test_grouped_plan_matches_oracle_on_repeated_runs(name, M, ordered):
             e["y"].zero_()
         dl.run_plan()
         torch.cuda.synchronize()
+        assert not dl.plan_timed_out()
         for e, y_r in zip(entries, ys_ref):
             err = np_ref.rel_l2(e["y"].cpu().numpy(), y_r)
             assert err < TOL, (rep, err)
@@ -454,6 +456,51 @@ def test_grouped_plan_matches_oracle_on_repeated_runs(name, M, ordered):
     for e in entries:
         e["y"].zero_()
     nvq.decode_linears(entries, M, 0)
+    torch.cuda.synchronize()
+    for e, y_r in zip(entries, ys_ref):
+        assert np_ref.rel_l2(e["y"].cpu().numpy(), y_r) < 1e-5
+    dl.close()
+
+
+# The persistent small-batch kernel (loader wave + LDS rings) serves lists with M <= 16 and
+# every K a multiple of 512; these shapes exercise what its bookkeeping has to get right:
+# row counts that end inside a unit of 32 rows and inside a 16-row tile, phases of several
+# matrices whose boundaries fall inside a unit, a phase with fewer units than teams next to
+# long ones (team ranges that cross phases), K from one step (512) to 28 steps, both
+# precisions, and token counts from 2 to 16.
+RING_SHAPES = [(1000, 1536, 0), (37, 1536, 0), (3, 1536, 1), (2500, 3072, 2), (777, 3072, 2),
+               (64, 14336, 3), (48, 512, 4), (4100, 512, 4), (16, 1024, 5)]
+
+
+@pytest.mark.parametrize("M,bits", [(2, (0, 1)), (7, (1, 0)), (16, (0, 1, 1))])
+def test_ring_plan_matches_oracle(M, bits):
+    say("ring plan", M, bits)
+    entries, host = model_entries(RING_SHAPES, bits, M=M, seed=8600)
+    ys_ref = oracle.decode_linears(host, M, 0)
+    dl = nvq.DecodeList(entries, M, 0)
+    info = dl.plan_info()
+    say("  plan", info)
+    assert info["grouped"] and info["persistent_grouped"]
+    for rep in range(3):
+        for e in entries:
+            e["y"].zero_()
+        dl.run_plan()
+        torch.cuda.synchronize()
+        assert not dl.plan_timed_out()
+        for e, y_r in zip(entries, ys_ref):
+            assert np_ref.rel_l2(e["y"].cpu().numpy(), y_r) < 1e-5, rep
+    dl.close()
+
+
+def test_ring_plan_needs_k_multiple_of_512():
+    say("ring plan fallback")
+    M = 4
+    entries, host = model_entries([(96, 1536, 0), (200, 640, 1)], (0, 1), M=M, seed=8700)
+    ys_ref = oracle.decode_linears(host, M, 0)
+    dl = nvq.DecodeList(entries, M, 0)
+    info = dl.plan_info()
+    assert info["grouped"] and not info["persistent_grouped"]   # K = 640: the per-tile grid
+    dl.run_plan()
     torch.cuda.synchronize()
     for e, y_r in zip(entries, ys_ref):
         assert np_ref.rel_l2(e["y"].cpu().numpy(), y_r) < 1e-5
