@@ -55,6 +55,12 @@ struct ListSizes {
     bool transforms;     // some entry has an input transform
 };
 
+// Activations of a phase in the order the persistent small-batch kernel loads
+// them: token tiles of 16, whole KiB per (tile, 128-input column, piece).
+size_t operand_image_bytes(int M, int K, int precision) {
+    return (size_t)((M + 15) / 16) * 16 * K * (precision == NVQ_W4A8 ? 1 : 2);
+}
+
 size_t quant_bytes(int M, int K) {
     return round_up((size_t)M * K, 256) + round_up((size_t)M * 4, 256) +
            round_up((size_t)M * (K / 32) * 4, 256);
@@ -127,7 +133,11 @@ int check_layers(const nvq_linear *L, int n, int M, int act_group, ListSizes *si
         // upper bound: every entry its own phase with a prepared image
         if (e.K <= kStreamMaxK) ib += (size_t)stream_image_bytes(e.K, e.precision, act_group);
         gu += (size_t)(e.N + 15) / 16 + 1;
-        if (e.precision == NVQ_W4A8) gq += quant_bytes(M, e.K);
+        // codes, scales and code sums (W4A8), or the operand image of the
+        // persistent small-batch kernel (either precision)
+        const size_t image = operand_image_bytes(M, e.K, e.precision) + round_up((size_t)M * 4, 256);
+        const size_t plain = e.precision == NVQ_W4A8 ? quant_bytes(M, e.K) : 0;
+        gq += image > plain ? image : plain;
     }
     sizes->maxK = mk;
     sizes->image_bytes = ib;
@@ -281,6 +291,7 @@ struct GroupBatch {
     int team_first, nteams;  // the batch's table in the team list (2 * (nteams + 1) words)
 };
 struct GroupPlan {
+    bool ring;  // the persistent kernel serves the list: every phase has a job and an operand image
     std::vector<GroupPhase> tab;
     std::vector<uint16_t> jobs, units;
     std::vector<uint32_t> teams;  // per batch: nteams + 1 unit cuts, then the phases at the cuts
@@ -318,11 +329,16 @@ void cut_batch(GroupPlan &gp, GroupBatch &b, int want) {
 GroupPlan group_plan(const nvq_linear *L, const std::vector<Phase> &phases, int M, int act_group,
                      bool ordered, const Workspace &ws) {
     GroupPlan gp;
+    gp.ring = false;
     if (M < 2 || act_group != 0 || phases.size() > 65535) return gp;
     for (const Phase &ph : phases)
         if (L[ph.first].in_op != NVQ_IN_PLAIN ||
             !gemv_mfma_supported(make_segs(L, ph), L[ph.first].K, M))
             return gp;
+    // beyond 16 tokens the per-tile grid is still the faster one
+    gp.ring = M <= 16;
+    for (const Phase &ph : phases)
+        gp.ring = gp.ring && gemv_mfma_ring_supported(make_segs(L, ph), L[ph.first].K);
     const std::vector<int> deps = phase_deps(L, phases, M, ordered);
     const int want_teams = ring_team_count(M);
     size_t qoff = 0;
@@ -342,7 +358,14 @@ GroupPlan group_plan(const nvq_linear *L, const std::vector<Phase> &phases, int 
         g.G = e0.K / 32;
         g.precision = e0.precision;
         g.unit_begin = cur.nunits;
-        if (e0.precision == NVQ_W4A8) {
+        if (gp.ring) {
+            char *b = ws.gquant + qoff;
+            g.xa = b;
+            g.xscale = reinterpret_cast<float *>(b + operand_image_bytes(M, e0.K, e0.precision));
+            qoff += operand_image_bytes(M, e0.K, e0.precision) + round_up((size_t)M * 4, 256);
+            gp.jobs.push_back((uint16_t)p);
+            ++cur.njobs;
+        } else if (e0.precision == NVQ_W4A8) {
             char *b = ws.gquant + qoff;
             g.xq = reinterpret_cast<int8_t *>(b);
             g.xscale = reinterpret_cast<float *>(b + round_up((size_t)M * e0.K, 256));
@@ -596,11 +619,7 @@ extern "C" int nvq_plan_create(const nvq_linear *layers, int n, int M, int act_g
             }
             pl->batches = gp.batches;
             pl->nwaits = (int)gp.batches.size() - 1;
-            // beyond 16 tokens the per-tile grid is still the faster one
-            pl->ring = M <= 16;
-            for (const Phase &ph : pl->phases)
-                pl->ring = pl->ring && gemv_mfma_ring_supported(make_segs(pl->layers.data(), ph),
-                                                                pl->layers[ph.first].K);
+            pl->ring = gp.ring;
         }
     }
     *plan_out = pl;
@@ -621,7 +640,7 @@ extern "C" int nvq_plan_run(nvq_plan *pl, void *stream) {
     if (!pl->batches.empty()) {
         for (const GroupBatch &b : pl->batches) {
             int rc = launch_quant_act_group(pl->ws.gtab, pl->ws.gjobs + b.job_first, b.njobs, pl->M,
-                                            st);
+                                            pl->ring, st);
             if (rc != NVQ_OK) return rc;
             rc = pl->ring ? launch_gemv_mfma_ring(pl->ws.gtab, pl->ws.gteams + b.team_first, b.nteams,
                                                   pl->M, pl->ws.status, st)

@@ -55,7 +55,7 @@ constexpr int ring_vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0f7
 
 template <int MT>
 struct RingShared {
-    uint4 ring[kRingWaves][kRingSteps][kRingR][64];  // lane (n, kb): group 4c + kb of row n
+    uint4 ring[kRingWaves][kRingSteps][kRingR][64];  // [4n + (kb + n/4) % 4]: group 4c + kb of row n
     uint4 sring[kRingSteps][64];  // lane (r, n, half): scales of columns 4i+2half, 4i+2half+1
     float red[2][kRingWaves][kRingR * MT * 4][64];   // partial tiles, by unit parity
     alignas(16) uint32_t consumed[kRingWaves];  // steps each wave has copied into registers
@@ -137,7 +137,12 @@ __device__ __forceinline__ void ring_loader(CGroup *tab, int u, int u_end, int p
     constexpr int kOps = R * W + 1;  // loads per step
     static_assert(W == 4, "one 16-byte read fetches every wave's count");
     static_assert(S == 4 && kOps * (S - 1) < 64, "ring_wait_oldest covers up to four steps");
-    const int n = lane & 15, kb = lane >> 4;
+    // Loader lane 4q + j fetches a 16-byte piece of row q, so that four
+    // neighbouring lanes read 64 contiguous bytes (one request to the cache;
+    // with the MFMA's lane order, rows fastest, every lane would be a request of
+    // its own).  Which piece: (j - q / 4) mod 4, a rotation that lets the 16
+    // consumer lanes of one piece read 16 different bank groups.
+    const int n = lane >> 2, kb = ((lane & 3) - (lane >> 4)) & 3;
     const int sr = lane >> 5, sn = (lane >> 1) & 15, shalf = lane & 1;
     const uint32_t abort_addr = ring_lds_addr(&sh.abort);
     const uint32_t landed_addr = ring_lds_addr(&sh.landed);
@@ -224,34 +229,38 @@ __device__ __forceinline__ RingUnit ring_unit(CGroup *tab, int p, int u) {
     d.G = P.G;
     d.C4 = d.G >> 2;
     d.precision = P.precision;
-    d.xin = d.precision == NVQ_W4A8 ? reinterpret_cast<const char *>(P.xq)
-                                    : reinterpret_cast<const char *>(P.x_bf16);
+    d.xin = P.xa;
     return d;
 }
 
-// Request the activations of column c of unit d: for every token tile the
-// lane's 16-byte pieces (two for int8 codes, four for bf16).  Tokens past M
-// read token 0; their results are never stored.
+// Request the activations of column c from a phase's operand image: per token
+// tile the lane's 16 bytes of each KiB piece (two for int8 codes, four for
+// bf16), 64 lanes x 16 contiguous bytes per load.  lane_off is the lane's byte
+// offset in a piece (ring_lane_offset).
+// Lane (n, kb) = (lane % 16, lane / 16) holds token n of a tile.  With fewer
+// than 16 tokens the lanes of the missing ones read the slot of token
+// n mod 2^ceil(log2 M) instead (an MFMA keeps tokens apart and their results
+// are never stored), so that a load touches M / 16 of a piece only.
+__device__ __forceinline__ int ring_lane_offset(int lane, int M) {
+    int mask = 15;
+    if (M <= 8) mask = 7;
+    if (M <= 4) mask = 3;
+    if (M <= 2) mask = 1;
+    return ((lane >> 4) * 16 + (lane & 15 & mask)) * 16;
+}
+
 template <int MT>
-__device__ __forceinline__ void ring_request_a(const RingUnit &d, int c, int M, int n, int kb,
-                                               uint4v (&raw)[MT][4]) {
-    if (d.precision == NVQ_W4A8) {
-        const uint32_t row_bytes = (uint32_t)d.G * 32;
+__device__ __forceinline__ void ring_request_a(const char *xin, int C4, int precision, int c,
+                                               int lane_off, uint4v (&raw)[MT][4]) {
+    const int pieces = precision == NVQ_W4A8 ? 2 : 4;
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            const int m = mt * 16 + n;
-            const char *p = d.xin + (size_t)c * 128 + (m < M ? m : 0) * row_bytes + kb * 32;
-            raw[mt][0] = *as_global<uint4v>(p);
-            raw[mt][1] = *as_global<uint4v>(p + 16);
-        }
-    } else {
-        const uint32_t row_bytes = (uint32_t)d.G * 64;
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            const int m = mt * 16 + n;
-            const char *p = d.xin + (size_t)c * 256 + (m < M ? m : 0) * row_bytes + kb * 16;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) raw[mt][i] = *as_global<uint4v>(p + 64 * i);
+    for (int mt = 0; mt < MT; ++mt) {
+        const char *p = xin + ((size_t)(mt * C4 + c) * pieces) * 1024 + lane_off;
+        raw[mt][0] = *as_global<uint4v>(p);
+        raw[mt][1] = *as_global<uint4v>(p + 1024);
+        if (pieces == 4) {
+            raw[mt][2] = *as_global<uint4v>(p + 2048);
+            raw[mt][3] = *as_global<uint4v>(p + 3072);
         }
     }
 }
@@ -264,7 +273,8 @@ __device__ __forceinline__ void ring_bundle_columns(const RingUnit &d, int cnt, 
                                                     bool has_next, uint32_t &k,
                                                     uint32_t &landed, int M,
                                                     RingShared<MT> &sh, int w, int lane,
-                                                    bool &dead, uint4v (&raw)[MT][4],
+                                                    int lane_off, bool &dead,
+                                                    uint4v (&raw)[MT][4],
                                                     float (&f)[U][kRingR][MT][4]) {
     typedef Act<PREC> A;
     constexpr int W = kRingWaves, S = kRingSteps, R = kRingR;
@@ -278,10 +288,16 @@ __device__ __forceinline__ void ring_bundle_columns(const RingUnit &d, int cnt, 
         typename A::operand act[MT][4];
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) A::operands(raw[mt], act[mt]);
-        if (c + W < d.C4)
-            ring_request_a<MT>(d, c + W, M, n, kb, raw);
-        else if (has_next)
-            ring_request_a<MT>(nxt, w, M, n, kb, raw);
+        // one request site for "the next column of this bundle" and "the first
+        // column of the next bundle": loads issued on two paths into the same
+        // registers would be waited for where the paths join
+        {
+            const bool more = c + W < d.C4;
+            const char *xin = more ? d.xin : nxt.xin;
+            const int c4 = more ? d.C4 : nxt.C4, prec = more ? d.precision : nxt.precision;
+            const int cn = more ? c + W : w;
+            if (more || has_next) ring_request_a<MT>(xin, c4, prec, cn, lane_off, raw);
+        }
 #pragma unroll
         for (int j = 0; j < U; ++j) {
             if (j >= cnt) continue;
@@ -293,7 +309,7 @@ __device__ __forceinline__ void ring_bundle_columns(const RingUnit &d, int cnt, 
             uint2 sc[R];
 #pragma unroll
             for (int r = 0; r < R; ++r) {
-                wv[r] = sh.ring[w][slot][r][lane];
+                wv[r] = sh.ring[w][slot][r][4 * n + ((kb + (n >> 2)) & 3)];
                 // the wave's column is the first or second half of 16-byte piece w / 2
                 sc[r] = reinterpret_cast<const uint2 *>(
                     &sh.sring[slot][(r * 16 + n) * 2 + (w >> 1)])[w & 1];
@@ -357,7 +373,8 @@ __device__ __forceinline__ void ring_consumer(CGroup *tab, int u, int u_end, int
     RingUnit cur = ring_unit(tab, p, u);
     int phase_end = tab[p].unit_begin + tab[p].unit_count;
     uint4v raw[MT][4];
-    ring_request_a<MT>(cur, w, M, n, kb, raw);
+    const int lane_off = ring_lane_offset(lane, M);
+    ring_request_a<MT>(cur.xin, cur.C4, cur.precision, w, lane_off, raw);
     float xs[MT][4];  // per-token activation scale of the lane's result registers (W4A8)
     bool fresh = true;
 
@@ -395,10 +412,10 @@ __device__ __forceinline__ void ring_consumer(CGroup *tab, int u, int u_end, int
                     for (int jj = 0; jj < 4; ++jj) f[j][r][mt][jj] = 0.0f;
 
         if (cur.precision == NVQ_W4A8)
-            ring_bundle_columns<NVQ_W4A8, MT, U>(cur, cnt, nxt, has_next, k, landed, M, sh, w, lane, dead,
+            ring_bundle_columns<NVQ_W4A8, MT, U>(cur, cnt, nxt, has_next, k, landed, M, sh, w, lane, lane_off, dead,
                                                  raw, f);
         else
-            ring_bundle_columns<NVQ_W4A16, MT, U>(cur, cnt, nxt, has_next, k, landed, M, sh, w, lane, dead,
+            ring_bundle_columns<NVQ_W4A16, MT, U>(cur, cnt, nxt, has_next, k, landed, M, sh, w, lane, lane_off, dead,
                                                   raw, f);
 
         // unit by unit, add the K slices of the waves in wave order

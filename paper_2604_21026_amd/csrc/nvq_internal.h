@@ -64,13 +64,20 @@ struct GroupPhase {
     int8_t *xq;              // [M][K]   codes      (W4A8 phases, workspace)
     float *xscale;           // [M]      scales
     int32_t *xgsum;          // [M][K/32] code sums
+    char *xa;                // operand image of the persistent kernel (either precision, workspace)
     int G, precision;
     int unit_begin;          // first grid unit of the phase in its batch
     int unit_count;          // its units
 };
 // jobs[j] names the phase whose M tokens grid blocks j*M .. j*M+M-1 quantise.
+// With `image` set, every job writes its phase's operand image `xa` instead:
+// per tile of 16 tokens, 128-input column c and piece i one KiB whose 16 bytes
+// number 16 * kb + n are, for token n of the tile, the int8 codes
+// 32 * kb + 16 * i .. + 15 of the column (W4A8, two pieces; xscale as before,
+// no code sums) or the bf16 inputs 32 * i + 8 * kb .. + 7 of the column, copied
+// (W4A16, four pieces).  Token slots past M are left as they are.
 int launch_quant_act_group(const GroupPhase *tab, const uint16_t *jobs, int njobs, int M,
-                           hipStream_t st);
+                           bool image, hipStream_t st);
 // unit_phase[u] names the phase of grid unit u; a unit is group_row_tiles(M)
 // consecutive 16-row tiles, which share their activation operands (as many as
 // fit the registers next to one or two token tiles).

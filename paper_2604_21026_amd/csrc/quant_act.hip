@@ -32,16 +32,31 @@ __device__ __forceinline__ int quant_one(float x, float s) {
     return (int)r;
 }
 
-// Token m of one [M][K] input, by one workgroup.
-template <bool PER_GROUP>
+// Byte offset, in the operand image of the persistent small-batch kernel, of
+// the 16-byte piece that holds input e (a multiple of 8) of token m: KiB blocks
+// per (token tile, 128-input column, piece), 16 bytes per (kb, token) in them.
+// PIECES = 2 for int8 codes (piece = a half of group kb of the column), 4 for
+// bf16 (piece i = inputs 32 i .. 32 i + 31, split over kb by eights).
+template <int PIECES>
+__device__ __forceinline__ size_t image_offset(int K, int m, int e) {
+    const int c = e >> 7, off = e & 127;
+    const int kb = PIECES == 2 ? off >> 5 : (off & 31) >> 3;
+    const int piece = PIECES == 2 ? (off & 31) >> 4 : off >> 5;
+    const size_t block = ((size_t)(m >> 4) * (K >> 7) + c) * PIECES + piece;
+    return block * 1024 + (size_t)(kb * 16 + (m & 15)) * 16 + (PIECES == 2 ? (off & 8) : 0);
+}
+
+// Token m of one [M][K] input, by one workgroup.  IMAGE: the codes go to the
+// operand image `xq` instead of the [M][K] matrix, and no code sums are kept.
+template <bool PER_GROUP, bool IMAGE = false>
 __device__ __forceinline__ void quant_token(const uint4 *__restrict__ x, int K, int m,
                                             int8_t *__restrict__ xq, float *__restrict__ xscale,
                                             int32_t *__restrict__ xgsum) {
     const int chunks = K / 8;  // multiple of 4
     const int G = K / 32;
     const uint4 *xr = x + (int64_t)m * chunks;
-    uint2 *qr = reinterpret_cast<uint2 *>(xq + (int64_t)m * K);
-    int32_t *gs = xgsum + (int64_t)m * G;
+    uint2 *qr = reinterpret_cast<uint2 *>(xq + (IMAGE ? 0 : (int64_t)m * K));
+    int32_t *gs = IMAGE ? nullptr : xgsum + (int64_t)m * G;
 
     float s_tok = 0.0f;
     if (!PER_GROUP) {
@@ -86,6 +101,10 @@ __device__ __forceinline__ void quant_token(const uint4 *__restrict__ x, int K, 
                 ((uint32_t)(q[2] & 0xff) << 16) | ((uint32_t)(q[3] & 0xff) << 24);
         out.y = (uint32_t)(q[4] & 0xff) | ((uint32_t)(q[5] & 0xff) << 8) |
                 ((uint32_t)(q[6] & 0xff) << 16) | ((uint32_t)(q[7] & 0xff) << 24);
+        if (IMAGE) {
+            *reinterpret_cast<uint2 *>(xq + image_offset<2>(K, m, 8 * c)) = out;
+            continue;
+        }
         qr[c] = out;
         sum += __shfl_xor(sum, 1, 64);
         sum += __shfl_xor(sum, 2, 64);
@@ -109,11 +128,32 @@ __global__ __launch_bounds__(kQuantThreads) void quant_act_group_kernel(
                        P.xgsum);
 }
 
+// Operand images of many phases in one grid: quantised codes (W4A8) or a
+// rearranged copy of the bf16 inputs (W4A16).
+__global__ __launch_bounds__(kQuantThreads) void operand_image_group_kernel(
+    const GroupPhase *__restrict__ tab, const uint16_t *__restrict__ jobs, int M) {
+    const int job = blockIdx.x / M, m = blockIdx.x - job * M;
+    const GroupPhase &P = tab[jobs[job]];
+    const int K = P.G * 32;
+    const uint4 *x = reinterpret_cast<const uint4 *>(P.x_bf16);
+    if (P.precision == NVQ_W4A8) {
+        quant_token<false, true>(x, K, m, reinterpret_cast<int8_t *>(P.xa), P.xscale, nullptr);
+    } else {
+        const uint4 *xr = x + (int64_t)m * (K / 8);
+        for (int c = threadIdx.x; c < K / 8; c += kQuantThreads)
+            *reinterpret_cast<uint4 *>(P.xa + image_offset<4>(K, m, 8 * c)) = xr[c];
+    }
+}
+
 int launch_quant_act_group(const GroupPhase *tab, const uint16_t *jobs, int njobs, int M,
-                           hipStream_t st) {
+                           bool image, hipStream_t st) {
     if (njobs <= 0) return NVQ_OK;
-    hipLaunchKernelGGL(quant_act_group_kernel, dim3(njobs * M), dim3(kQuantThreads), 0, st, tab,
-                       jobs, M);
+    if (image)
+        hipLaunchKernelGGL(operand_image_group_kernel, dim3(njobs * M), dim3(kQuantThreads), 0, st,
+                           tab, jobs, M);
+    else
+        hipLaunchKernelGGL(quant_act_group_kernel, dim3(njobs * M), dim3(kQuantThreads), 0, st,
+                           tab, jobs, M);
     NVQ_HIP_TRY(hipGetLastError());
     return NVQ_OK;
 }
