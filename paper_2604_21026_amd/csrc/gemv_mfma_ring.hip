@@ -21,7 +21,7 @@
 //     request for the next column is made before the current one is
 //     multiplied), feeds the MFMAs and, at the end of a unit, adds the W
 //     partial tiles through LDS in wave order.
-// Per step the loader issues 2 x 4 weight loads of 1 KiB (16 rows x 64 bytes)
+// Per step the loader issues 2 x 4 weight loads of 1 KiB (8 rows x 128 bytes)
 // and one scale load (32 rows x 32 bytes: the 16 scales of the step's four
 // columns).  Its loads are the only ones it has in flight and complete in
 // order, so "the oldest step not yet announced has arrived" is an exact vmcnt
@@ -55,7 +55,9 @@ constexpr int ring_vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0f7
 
 template <int MT>
 struct RingShared {
-    uint4 ring[kRingWaves][kRingSteps][kRingR][64];  // [4n + (kb + n/4) % 4]: group 4c + kb of row n
+    // [step][row tile][column pair][row half]: 8 rows x 128 bytes (two columns)
+    // per KiB, in the lane order of the loader (ring_lane_of)
+    uint4 ring[kRingSteps][kRingR][2][2][64];
     uint4 sring[kRingSteps][64];  // lane (r, n, half): scales of columns 4i+2half, 4i+2half+1
     float red[2][kRingWaves][kRingR * MT * 4][64];   // partial tiles, by unit parity
     alignas(16) uint32_t consumed[kRingWaves];  // steps each wave has copied into registers
@@ -106,6 +108,16 @@ __device__ __forceinline__ uint32_t ring_wait(uint32_t addr, uint32_t want, uint
 }
 
 // ---- the loader wave --------------------------------------------------------
+// Where piece `piece` (16 bytes, 0..7) of row n (0..15) of a two-column block
+// lies in its KiB: the loader's lane order.  Rows are rotated against each
+// other by one piece and neighbouring rows swapped in the second row half, so
+// that the 16 lanes that read the same piece of the 16 rows hit 16 different
+// groups of LDS banks.
+__device__ __forceinline__ int ring_lane_of(int n, int piece) {
+    const int q = n & 7, h = n >> 3;
+    return 8 * (q ^ h) + ((piece + q) & 7);
+}
+
 // The loader's loads are the only ones it has in flight and they complete in
 // order: with `outstanding` steps of OPS loads each not yet announced, the
 // oldest has arrived when at most (outstanding - 1) * OPS loads are pending.
@@ -137,12 +149,14 @@ __device__ __forceinline__ void ring_loader(CGroup *tab, int u, int u_end, int p
     constexpr int kOps = R * W + 1;  // loads per step
     static_assert(W == 4, "one 16-byte read fetches every wave's count");
     static_assert(S == 4 && kOps * (S - 1) < 64, "ring_wait_oldest covers up to four steps");
-    // Loader lane 4q + j fetches a 16-byte piece of row q, so that four
-    // neighbouring lanes read 64 contiguous bytes (one request to the cache;
-    // with the MFMA's lane order, rows fastest, every lane would be a request of
-    // its own).  Which piece: (j - q / 4) mod 4, a rotation that lets the 16
-    // consumer lanes of one piece read 16 different bank groups.
-    const int n = lane >> 2, kb = ((lane & 3) - (lane >> 4)) & 3;
+    // A load moves whole 128-byte lines: eight rows x two columns, the eight
+    // lanes 8q .. 8q + 7 one line.  (64-byte halves of a line fetched by two
+    // loads a little apart came from HBM twice too often: rows a power of two
+    // bytes apart fall into few sets of the first-level cache, and the line was
+    // gone before its second half was asked for.)  Lane 8l + j of the load for
+    // row half h holds row 8h + q, q = l xor h, and of it piece (j - q) mod 8;
+    // see ring_lane_of.
+    const int lq = lane >> 3;
     const int sr = lane >> 5, sn = (lane >> 1) & 15, shalf = lane & 1;
     const uint32_t abort_addr = ring_lds_addr(&sh.abort);
     const uint32_t landed_addr = ring_lds_addr(&sh.landed);
@@ -156,13 +170,16 @@ __device__ __forceinline__ void ring_loader(CGroup *tab, int u, int u_end, int p
         CGroup &P = tab[p];
         const int G = P.G, steps = G >> 4;
         const int cnt = bundle_units<U>(u, u_end, P.unit_begin + P.unit_count);
-        const uint4 *gq[U][R], *gs[U];
+        const uint4 *gq[U][R][2], *gs[U];
 #pragma unroll
         for (int j = 0; j < U; ++j) {
             const int unit = u - P.unit_begin + (j < cnt ? j : 0);
 #pragma unroll
             for (int r = 0; r < R; ++r)
-                gq[j][r] = locate_row(P.segs, (unit * R + r) * 16 + n, G).qw + kb;
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+                    gq[j][r][h] = locate_row(P.segs, (unit * R + r) * 16 + 8 * h + (lq ^ h), G).qw +
+                                  (((lane & 7) - (lq ^ h)) & 7);
             // 16 bytes = the 8 scales of two columns
             gs[j] = reinterpret_cast<const uint4 *>(
                         locate_row(P.segs, (unit * R + sr) * 16 + sn, G).sc) +
@@ -195,12 +212,14 @@ __device__ __forceinline__ void ring_loader(CGroup *tab, int u, int u_end, int p
                 if (!dead) {  // else no further loads; the consumers no longer wait
                     const int slot = (int)(T % S);
 #pragma unroll
-                    for (int w = 0; w < W; ++w)
+                    for (int r = 0; r < R; ++r)
 #pragma unroll
-                        for (int r = 0; r < R; ++r)
-                            __builtin_amdgcn_global_load_lds(
-                                (const void *)(gq[j][r] + 16 * i + 4 * w),
-                                (lds_void_ptr)&sh.ring[w][slot][r][0], 16, 0, 0);
+                        for (int cp = 0; cp < 2; ++cp)
+#pragma unroll
+                            for (int h = 0; h < 2; ++h)
+                                __builtin_amdgcn_global_load_lds(
+                                    (const void *)(gq[j][r][h] + 16 * i + 8 * cp),
+                                    (lds_void_ptr)&sh.ring[slot][r][cp][h][0], 16, 0, 2);
                     __builtin_amdgcn_global_load_lds((const void *)(gs[j] + 2 * i),
                                                      (lds_void_ptr)&sh.sring[slot][0], 16, 0, 0);
                 }
@@ -309,7 +328,7 @@ __device__ __forceinline__ void ring_bundle_columns(const RingUnit &d, int cnt, 
             uint2 sc[R];
 #pragma unroll
             for (int r = 0; r < R; ++r) {
-                wv[r] = sh.ring[w][slot][r][4 * n + ((kb + (n >> 2)) & 3)];
+                wv[r] = sh.ring[slot][r][w >> 1][n >> 3][ring_lane_of(n, 4 * (w & 1) + kb)];
                 // the wave's column is the first or second half of 16-byte piece w / 2
                 sc[r] = reinterpret_cast<const uint2 *>(
                     &sh.sring[slot][(r * 16 + n) * 2 + (w >> 1)])[w & 1];
