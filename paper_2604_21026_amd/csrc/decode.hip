@@ -41,7 +41,7 @@ struct Workspace {
     GroupPhase *gtab;   // [n]                 phase table of the grouped small-batch launches
     uint16_t *gjobs;    // [n]                 W4A8 phases, batch after batch
     uint16_t *gunits;   // [group_units]       phase of every 16-row tile, batch after batch
-    uint32_t *gteams;   // [n][2][kRingMaxTeams + 1]  per batch: unit ranges of the ring kernel's teams
+    uint32_t *gteams;   // [n][2][kRingMaxParts + 1]  per batch: the parts of the ring kernel's XCDs
     char *gquant;       // per-phase activation codes, scales and code sums
     size_t bytes;
 };
@@ -92,7 +92,7 @@ Workspace carve(void *base, int M, int n, const ListSizes &ls) {
     w.gtab = reinterpret_cast<GroupPhase *>(take(M > 1 ? nn * sizeof(GroupPhase) : 0));
     w.gjobs = reinterpret_cast<uint16_t *>(take(M > 1 ? nn * 2 : 0));
     w.gunits = reinterpret_cast<uint16_t *>(take(M > 1 ? ls.group_units * 2 : 0));
-    w.gteams = reinterpret_cast<uint32_t *>(take(M > 1 ? nn * 2 * (kRingMaxTeams + 1) * 4 : 0));
+    w.gteams = reinterpret_cast<uint32_t *>(take(M > 1 ? nn * 2 * (kRingMaxParts + 1) * 4 : 0));
     w.gquant = take(M > 1 ? ls.group_quant : 0);
     w.bytes = off;
     return w;
@@ -288,44 +288,48 @@ std::vector<int> phase_deps(const nvq_linear *L, const std::vector<Phase> &phase
 struct GroupBatch {
     int job_first, njobs;    // range in the job list
     int unit_first, nunits;  // range in the unit list
-    int team_first, nteams;  // the batch's table in the team list (2 * (nteams + 1) words)
+    int part_first, nparts;  // the batch's table in the part list (2 * (nparts + 1) words)
+    int grid;                // workgroups of the persistent kernel
 };
 struct GroupPlan {
     bool ring;  // the persistent kernel serves the list: every phase has a job and an operand image
     std::vector<GroupPhase> tab;
     std::vector<uint16_t> jobs, units;
-    std::vector<uint32_t> teams;  // per batch: nteams + 1 unit cuts, then the phases at the cuts
+    std::vector<uint32_t> parts;  // per batch: nparts + 1 unit cuts, then the phases at the cuts
     std::vector<GroupBatch> batches;
 };
 
-// Cut the units of a batch into `want` contiguous ranges of (nearly) equal
-// weight bytes for the persistent kernel's teams; a unit of phase p weighs G_p.
-void cut_batch(GroupPlan &gp, GroupBatch &b, int want) {
-    const int nteams = b.nunits < want ? b.nunits : want;
-    b.team_first = (int)gp.teams.size();
-    b.nteams = nteams;
-    if (nteams <= 0) return;
+// Cut the units of a batch into contiguous parts of (nearly) equal weight
+// bytes, one per XCD of the persistent kernel's grid; a unit of phase p weighs
+// G_p.
+void cut_batch(GroupPlan &gp, GroupBatch &b, int M) {
+    b.grid = ring_grid(M, b.nunits);
+    const int nparts = ring_parts(b.grid);
+    b.part_first = (int)gp.parts.size();
+    b.nparts = nparts;
+    if (nparts <= 0) return;
     uint64_t total = 0;
     for (int u = 0; u < b.nunits; ++u) total += (uint64_t)gp.tab[gp.units[(size_t)b.unit_first + u]].G;
-    std::vector<uint32_t> cut((size_t)nteams + 1), phase((size_t)nteams + 1);
+    std::vector<uint32_t> cut((size_t)nparts + 1), phase((size_t)nparts + 1);
     uint64_t before = 0;  // weight of the units before u
     int t = 0;
     for (int u = 0; u < b.nunits; ++u) {
-        // team t starts at the first unit whose predecessors weigh t / nteams of the batch
-        while (t < nteams && before * (uint64_t)nteams >= (uint64_t)t * total) {
+        // part t starts at the first unit whose predecessors weigh t / nparts of the batch
+        while (t < nparts && before * (uint64_t)nparts >= (uint64_t)t * total) {
             cut[(size_t)t] = (uint32_t)u;
             phase[(size_t)t] = gp.units[(size_t)b.unit_first + u];
             ++t;
         }
         before += (uint64_t)gp.tab[gp.units[(size_t)b.unit_first + u]].G;
     }
-    for (; t <= nteams; ++t) {
+    for (; t <= nparts; ++t) {
         cut[(size_t)t] = (uint32_t)b.nunits;
         phase[(size_t)t] = gp.units[(size_t)b.unit_first + b.nunits - 1];
     }
-    gp.teams.insert(gp.teams.end(), cut.begin(), cut.end());
-    gp.teams.insert(gp.teams.end(), phase.begin(), phase.end());
+    gp.parts.insert(gp.parts.end(), cut.begin(), cut.end());
+    gp.parts.insert(gp.parts.end(), phase.begin(), phase.end());
 }
+
 GroupPlan group_plan(const nvq_linear *L, const std::vector<Phase> &phases, int M, int act_group,
                      bool ordered, const Workspace &ws) {
     GroupPlan gp;
@@ -340,16 +344,15 @@ GroupPlan group_plan(const nvq_linear *L, const std::vector<Phase> &phases, int 
     for (const Phase &ph : phases)
         gp.ring = gp.ring && gemv_mfma_ring_supported(make_segs(L, ph), L[ph.first].K);
     const std::vector<int> deps = phase_deps(L, phases, M, ordered);
-    const int want_teams = ring_team_count(M);
     size_t qoff = 0;
-    GroupBatch cur = {0, 0, 0, 0, 0, 0};
+    GroupBatch cur = {0, 0, 0, 0, 0, 0, 0};
     int batch_first = 0;
     for (size_t p = 0; p < phases.size(); ++p) {
         const nvq_linear &e0 = L[phases[p].first];
         if (deps[p] >= batch_first) {  // depends on a phase of the open batch: close it
-            cut_batch(gp, cur, want_teams);
+            cut_batch(gp, cur, M);
             gp.batches.push_back(cur);
-            cur = {(int)gp.jobs.size(), 0, (int)gp.units.size(), 0, 0, 0};
+            cur = {(int)gp.jobs.size(), 0, (int)gp.units.size(), 0, 0, 0, 0};
             batch_first = (int)p;
         }
         GroupPhase g = {};
@@ -382,7 +385,7 @@ GroupPlan group_plan(const nvq_linear *L, const std::vector<Phase> &phases, int 
         cur.nunits += units;
         gp.tab.push_back(g);
     }
-    cut_batch(gp, cur, want_teams);
+    cut_batch(gp, cur, M);
     gp.batches.push_back(cur);
     return gp;
 }
@@ -605,8 +608,8 @@ extern "C" int nvq_plan_create(const nvq_linear *layers, int n, int M, int act_g
             if (e == hipSuccess)
                 e = hipMemcpyAsync(ws.gunits, gp.units.data(), gp.units.size() * 2,
                                    hipMemcpyHostToDevice, st);
-            if (e == hipSuccess && !gp.teams.empty())
-                e = hipMemcpyAsync(ws.gteams, gp.teams.data(), gp.teams.size() * 4,
+            if (e == hipSuccess && !gp.parts.empty())
+                e = hipMemcpyAsync(ws.gteams, gp.parts.data(), gp.parts.size() * 4,
                                    hipMemcpyHostToDevice, st);
             if (e == hipSuccess) {
                 hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, st, ws.status, 1, 0u);
@@ -642,8 +645,8 @@ extern "C" int nvq_plan_run(nvq_plan *pl, void *stream) {
             int rc = launch_quant_act_group(pl->ws.gtab, pl->ws.gjobs + b.job_first, b.njobs, pl->M,
                                             pl->ring, st);
             if (rc != NVQ_OK) return rc;
-            rc = pl->ring ? launch_gemv_mfma_ring(pl->ws.gtab, pl->ws.gteams + b.team_first, b.nteams,
-                                                  pl->M, pl->ws.status, st)
+            rc = pl->ring ? launch_gemv_mfma_ring(pl->ws.gtab, pl->ws.gteams + b.part_first, b.nparts,
+                                                  b.grid, pl->M, pl->ws.status, st)
                           : launch_gemv_mfma_group(pl->ws.gtab, pl->ws.gunits + b.unit_first,
                                                    b.nunits, pl->M, st);
             if (rc != NVQ_OK) return rc;

@@ -5,11 +5,10 @@
 //
 // A short-lived workgroup per row tile loads, waits, computes and reduces, and
 // the few of them that fit a compute unit do not cover the memory latency.
-// Here the waves stay: a team (a loader wave and W consumer waves) walks a
-// contiguous range of the batch's units (a unit = R consecutive 16-row tiles
-// of some phase); the host cuts the batch into ranges of equal weight bytes,
-// so a team reads a table entry only when its range crosses into the next
-// phase.  A team splits into
+// Here the waves stay: a team (a loader wave and W consumer waves) works off
+// groups of consecutive units of the batch (a unit = R consecutive 16-row
+// tiles of some phase), dealt so that the teams of an XCD advance through the
+// phases together (RingWalk).  A team splits into
 //   * one loader wave that copies the weights and scales of the units, column
 //     by column (a column = four groups = 64 bytes of each of the 16 rows of a
 //     tile), straight from global memory into LDS rings, one ring per consumer
@@ -133,6 +132,49 @@ __device__ __forceinline__ void ring_wait_oldest(uint32_t outstanding) {
         __builtin_amdgcn_s_waitcnt(ring_vmcnt_imm(0));
 }
 
+// A team's way through its part of the batch.  The batch is cut into parts
+// of equal weight bytes, one per XCD (workgroup g runs on XCD g mod 8: the
+// compute units of an XCD share an L2 cache), and the teams of an XCD take the
+// part's groups of U units in turn: team q the groups q, q + teams, ...  So
+// the teams of an XCD advance through the phases together and the operand
+// image they all read is one phase's, which stays in their L2; a group that
+// crosses a phase boundary is worked off as two bundles.
+struct RingWalk {
+    int a;       // first unit of the current group
+    int u;       // next unit to work on
+    int u_end;   // end of the current group
+    int p;       // phase of unit u (when u < u_end)
+    int part_end, stride;
+};
+
+template <int U>
+__device__ __forceinline__ void ring_walk_settle(RingWalk &wk, CGroup *tab) {
+    if (wk.u >= wk.u_end) {
+        wk.a += wk.stride;
+        wk.u = wk.a;
+        const int e = wk.a + U;
+        wk.u_end = e < wk.part_end ? e : wk.part_end;
+    }
+    if (wk.u < wk.u_end)
+        while (wk.u >= tab[wk.p].unit_begin + tab[wk.p].unit_count) ++wk.p;  // phases have units
+}
+
+template <int U>
+__device__ __forceinline__ RingWalk ring_walk_begin(CGroup *tab, int part_begin, int part_end,
+                                                    int p, int q, int teams) {
+    RingWalk wk;
+    wk.part_end = part_end;
+    wk.stride = teams * U;
+    wk.a = part_begin + q * U;
+    wk.u = wk.a;
+    const int e = wk.a + U;
+    wk.u_end = e < part_end ? e : part_end;
+    wk.p = p;
+    if (wk.u < wk.u_end)
+        while (wk.u >= tab[wk.p].unit_begin + tab[wk.p].unit_count) ++wk.p;
+    return wk;
+}
+
 // Units a team works on together: up to U consecutive units of one phase, so
 // that the activation operands of a column serve U * R row tiles.
 template <int U>
@@ -143,8 +185,8 @@ __device__ __forceinline__ int bundle_units(int u, int u_end, int phase_end) {
 }
 
 template <int MT, int U>
-__device__ __forceinline__ void ring_loader(CGroup *tab, int u, int u_end, int p,
-                                            RingShared<MT> &sh, int lane, bool &dead) {
+__device__ __forceinline__ void ring_loader(CGroup *tab, RingWalk wk, RingShared<MT> &sh,
+                                            int lane, bool &dead) {
     constexpr int W = kRingWaves, S = kRingSteps, R = kRingR;
     constexpr int kOps = R * W + 1;  // loads per step
     static_assert(W == 4, "one 16-byte read fetches every wave's count");
@@ -165,11 +207,11 @@ __device__ __forceinline__ void ring_loader(CGroup *tab, int u, int u_end, int p
     uint32_t published = 0; // steps announced to the consumers
     uint32_t cons_min = 0;  // a lower bound of every wave's consumed count
 
-    while (u < u_end) {
-        while (u >= tab[p].unit_begin + tab[p].unit_count) ++p;  // phases have at least one unit
-        CGroup &P = tab[p];
+    while (wk.u < wk.u_end) {
+        CGroup &P = tab[wk.p];
+        const int u = wk.u;
         const int G = P.G, steps = G >> 4;
-        const int cnt = bundle_units<U>(u, u_end, P.unit_begin + P.unit_count);
+        const int cnt = bundle_units<U>(u, wk.u_end, P.unit_begin + P.unit_count);
         const uint4 *gq[U][R][2], *gs[U];
 #pragma unroll
         for (int j = 0; j < U; ++j) {
@@ -226,7 +268,8 @@ __device__ __forceinline__ void ring_loader(CGroup *tab, int u, int u_end, int p
                 ++T;
             }
         }
-        u += cnt;
+        wk.u += cnt;
+        ring_walk_settle<U>(wk, tab);
     }
     // what is still in flight
     __builtin_amdgcn_s_waitcnt(ring_vmcnt_imm(0));
@@ -376,38 +419,39 @@ __device__ __forceinline__ void ring_bundle_columns(const RingUnit &d, int cnt, 
 }
 
 template <int MT, int U>
-__device__ __forceinline__ void ring_consumer(CGroup *tab, int u, int u_end, int p, int M,
+__device__ __forceinline__ void ring_consumer(CGroup *tab, RingWalk wk, int M,
                                               RingShared<MT> &sh, int w, int lane, bool &dead) {
     constexpr int W = kRingWaves, R = kRingR;
     constexpr int kTile = R * MT * 4;
     const int n = lane & 15, kb = lane >> 4;
     const uint32_t abort_addr = ring_lds_addr(&sh.abort);
     const uint32_t done_addr = ring_lds_addr(&sh.done);
-    if (u >= u_end) return;
+    if (wk.u >= wk.u_end) return;
 
     uint32_t k = 0;       // steps this wave has consumed
     uint32_t landed = 0;  // steps known to have arrived
     uint32_t units_done = 0;
-    while (u >= tab[p].unit_begin + tab[p].unit_count) ++p;
-    RingUnit cur = ring_unit(tab, p, u);
-    int phase_end = tab[p].unit_begin + tab[p].unit_count;
+    RingUnit cur = ring_unit(tab, wk.p, wk.u);
     uint4v raw[MT][4];
     const int lane_off = ring_lane_offset(lane, M);
     ring_request_a<MT>(cur.xin, cur.C4, cur.precision, w, lane_off, raw);
     float xs[MT][4];  // per-token activation scale of the lane's result registers (W4A8)
     bool fresh = true;
 
-    while (u < u_end) {
-        const int cnt = bundle_units<U>(u, u_end, phase_end);
-        const bool has_next = u + cnt < u_end;
-        RingUnit nxt = cur;
-        nxt.unit = cur.unit + cnt;
-        int phase_end_next = phase_end;
-        if (has_next && u + cnt >= phase_end) {  // the next bundle opens the next phase
-            nxt = ring_unit(tab, cur.phase + 1, u + cnt);
-            phase_end_next = tab[nxt.phase].unit_begin + tab[nxt.phase].unit_count;
-        }
+    while (wk.u < wk.u_end) {
         CGroup &P = tab[cur.phase];
+        const int cnt = bundle_units<U>(wk.u, wk.u_end, P.unit_begin + P.unit_count);
+        RingWalk nw = wk;
+        nw.u += cnt;
+        ring_walk_settle<U>(nw, tab);
+        const bool has_next = nw.u < nw.u_end;
+        RingUnit nxt = cur;
+        if (has_next) {
+            if (nw.p == cur.phase)
+                nxt.unit = nw.u - P.unit_begin;
+            else
+                nxt = ring_unit(tab, nw.p, nw.u);
+        }
         if (fresh) {
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
@@ -473,23 +517,22 @@ __device__ __forceinline__ void ring_consumer(CGroup *tab, int u, int u_end, int
         }
         fresh = nxt.phase != cur.phase;
         cur = nxt;
-        phase_end = phase_end_next;
-        u += cnt;
+        wk = nw;
     }
 }
 
 // TEAMS teams share a workgroup (and nothing else): one workgroup per compute
 // unit holds all the LDS, which several smaller workgroups could not divide
-// among themselves as well.  Team j = g * TEAMS + t walks the units
-// team_tab[j] .. team_tab[j + 1] - 1; team_tab[nteams + 1 + j] is the phase of
-// its first unit.
+// among themselves as well.  part_tab holds nparts + 1 unit indices, the cuts
+// of the batch into parts, then nparts + 1 phase indices, the phase of the unit
+// at each cut; workgroup g serves part g mod nparts (see RingWalk).
 template <int MT, int TEAMS, int U>
 __global__ __launch_bounds__(TEAMS *kTeamThreads) void gemv_mfma_ring_kernel(
-    const GroupPhase *__restrict__ tab_, const uint32_t *__restrict__ team_tab_, int nteams, int M,
+    const GroupPhase *__restrict__ tab_, const uint32_t *__restrict__ part_tab_, int nparts, int M,
     uint32_t *__restrict__ status) {
     __shared__ RingShared<MT> shared[TEAMS];
     CGroup *tab = (CGroup *)tab_;
-    CWord *team_tab = (CWord *)team_tab_;
+    CWord *part_tab = (CWord *)part_tab_;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int t = wave / (kRingWaves + 1), w = wave - t * (kRingWaves + 1);
@@ -501,19 +544,18 @@ __global__ __launch_bounds__(TEAMS *kTeamThreads) void gemv_mfma_ring_kernel(
         sh.abort = 0;
     }
     __syncthreads();
-    const int team = (int)blockIdx.x * TEAMS + t;
-    int u = 0, u_end = 0, p = 0;
-    if (team < nteams) {
-        u = (int)team_tab[team];
-        u_end = (int)team_tab[team + 1];
-        p = (int)team_tab[nteams + 1 + team];
-    }
+    const int part = (int)blockIdx.x % nparts;
+    // workgroups of this part: those g < grid with g mod nparts == part
+    const int part_wgs = ((int)gridDim.x - 1 - part) / nparts + 1;
+    const RingWalk wk = ring_walk_begin<U>(tab, (int)part_tab[part], (int)part_tab[part + 1],
+                                           (int)part_tab[nparts + 1 + part],
+                                           ((int)blockIdx.x / nparts) * TEAMS + t, part_wgs * TEAMS);
     bool dead = false;
     if (w == kRingWaves) __builtin_amdgcn_s_setprio(3);  // the loader's few instructions go first
     if (w == kRingWaves)
-        ring_loader<MT, U>(tab, u, u_end, p, sh, lane, dead);
+        ring_loader<MT, U>(tab, wk, sh, lane, dead);
     else
-        ring_consumer<MT, U>(tab, u, u_end, p, M, sh, w, lane, dead);
+        ring_consumer<MT, U>(tab, wk, M, sh, w, lane, dead);
     if (dead && lane == 0) __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
@@ -528,27 +570,33 @@ bool gemv_mfma_ring_supported(const GemvSegs &S, int K) {
 }
 
 int ring_teams_per_workgroup(int M) { return M > 16 ? 2 : 3; }
+int ring_bundle_units(int M) { return M > 16 ? 1 : kRingBundle; }
 
-// One workgroup per compute unit: three teams (52 KiB of LDS each) up to 16
-// tokens, two (68 KiB each) beyond.
-int ring_team_count(int M) {
-    const int t = device_cu_count() * ring_teams_per_workgroup(M);
-    return t < kRingMaxTeams ? t : kRingMaxTeams;
+// One workgroup per compute unit at most: three teams (52 KiB of LDS each) up
+// to 16 tokens, two (68 KiB each) beyond; fewer workgroups if the batch has
+// fewer groups of units than that many teams.
+int ring_grid(int M, int nunits) {
+    const int per_wg = ring_teams_per_workgroup(M) * ring_bundle_units(M);
+    const int want = (nunits + per_wg - 1) / per_wg, cap = device_cu_count();
+    return want < cap ? want : cap;
 }
+// Parts the batch is cut into: one per XCD (eight; workgroups go to the XCDs in
+// turn), fewer for a grid of fewer workgroups.
+int ring_parts(int grid) { return grid < 8 ? grid : 8; }
 
-// team_tab: nteams + 1 unit indices (the cuts of the batch), then nteams + 1
+// part_tab: nparts + 1 unit indices (the cuts of the batch), then nparts + 1
 // phase indices (the phase of each cut's unit), in device memory.
-int launch_gemv_mfma_ring(const GroupPhase *tab, const uint32_t *team_tab, int nteams, int M,
-                          uint32_t *status, hipStream_t st) {
-    if (nteams <= 0) return NVQ_OK;
+int launch_gemv_mfma_ring(const GroupPhase *tab, const uint32_t *part_tab, int nparts, int grid,
+                          int M, uint32_t *status, hipStream_t st) {
+    if (nparts <= 0 || grid <= 0) return NVQ_OK;
     const int tpw = ring_teams_per_workgroup(M);
-    const dim3 grid((nteams + tpw - 1) / tpw), block(tpw * kTeamThreads);
+    const dim3 g(grid), block(tpw * kTeamThreads);
     if (M > 16)
-        hipLaunchKernelGGL((gemv_mfma_ring_kernel<2, 2, 1>), grid, block, 0, st, tab, team_tab, nteams,
+        hipLaunchKernelGGL((gemv_mfma_ring_kernel<2, 2, 1>), g, block, 0, st, tab, part_tab, nparts,
                            M, status);
     else
-        hipLaunchKernelGGL((gemv_mfma_ring_kernel<1, 3, kRingBundle>), grid, block, 0, st, tab, team_tab, nteams,
-                           M, status);
+        hipLaunchKernelGGL((gemv_mfma_ring_kernel<1, 3, kRingBundle>), g, block, 0, st, tab,
+                           part_tab, nparts, M, status);
     NVQ_HIP_TRY(hipGetLastError());
     return NVQ_OK;
 }

@@ -85,16 +85,19 @@ static inline int group_row_tiles(int M) { (void)M; return 2; }
 int launch_gemv_mfma_group(const GroupPhase *tab, const uint16_t *unit_phase, int nunits, int M,
                            hipStream_t st);
 // The same work as one persistent grid of teams (a loader wave feeding four
-// consumer waves through LDS rings), each walking a contiguous range of the
-// batch's units; needs K % 512 == 0 and 16-byte aligned scale rows in every
-// phase.  team_tab (device memory): nteams + 1 unit indices, the cuts of the
-// batch, then nteams + 1 phase indices, the phase of the unit at each cut.  A
-// wait inside the kernel that gives up sets *status.
-constexpr int kRingMaxTeams = 1024;
+// consumer waves through LDS rings); needs K % 512 == 0 and 16-byte aligned
+// scale rows in every phase, and the operand images of launch_quant_act_group.
+// The batch is cut into `nparts` = ring_parts(grid) parts of equal weight bytes
+// that the workgroups of one XCD each work off together; part_tab (device
+// memory): nparts + 1 unit indices, the cuts, then nparts + 1 phase indices,
+// the phase of the unit at each cut.  A wait inside the kernel that gives up
+// sets *status.
+constexpr int kRingMaxParts = 8;
 bool gemv_mfma_ring_supported(const GemvSegs &segs, int K);
-int ring_team_count(int M);
-int launch_gemv_mfma_ring(const GroupPhase *tab, const uint32_t *team_tab, int nteams, int M,
-                          uint32_t *status, hipStream_t st);
+int ring_grid(int M, int nunits);
+int ring_parts(int grid);
+int launch_gemv_mfma_ring(const GroupPhase *tab, const uint32_t *part_tab, int nparts, int grid,
+                          int M, uint32_t *status, hipStream_t st);
 
 // ---- device helpers -------------------------------------------------------
 #if defined(__HIPCC__)
