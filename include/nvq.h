@@ -257,6 +257,18 @@ int nvq_plan_trace(nvq_plan *plan, uint64_t *buf, size_t bytes);
  */
 int nvq_plan_describe(const nvq_linear *layers, int n, int M, int act_group, int flags,
                       int workgroups, int32_t *out, int out_words);
+/*
+ * nvq_plan_describe_batches -- likewise for the grouped small-batch launches
+ * (M > 1): out[0] = batches of mutually independent phases (0 if the list does
+ * not qualify for the matrix-core kernels), out[1] = 1 if the persistent kernel
+ * serves them; then 24 words per batch: first and last phase, units (pairs of
+ * 16-row tiles), input jobs, workgroups and parts of the persistent kernel,
+ * 9 words unit index at which each part begins (the last one = units; unused:
+ * -1), 9 words phase of the unit at each cut.  The grid assumes the current
+ * device's compute units (256 without a device).
+ */
+int nvq_plan_describe_batches(const nvq_linear *layers, int n, int M, int act_group, int flags,
+                              int32_t *out, int out_words);
 void nvq_plan_destroy(nvq_plan *plan);
 
 /*

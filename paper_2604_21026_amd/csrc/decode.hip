@@ -705,6 +705,40 @@ extern "C" int nvq_plan_describe(const nvq_linear *layers, int n, int M, int act
     return NVQ_OK;
 }
 
+extern "C" int nvq_plan_describe_batches(const nvq_linear *layers, int n, int M, int act_group,
+                                         int flags, int32_t *out, int out_words) {
+    using namespace nvq;
+    if (!out || out_words < 2 || (flags & ~NVQ_PLAN_ORDERED)) return NVQ_ERR_INVALID_ARG;
+    ListSizes ls;
+    const int rc = check_layers(layers, n, M, act_group, &ls);
+    if (rc != NVQ_OK) return rc;
+    const std::vector<Phase> phases = group_phases(layers, n);
+    Workspace none = {};  // pointers into it are computed, never followed
+    const GroupPlan gp = group_plan(layers, phases, M, act_group, (flags & NVQ_PLAN_ORDERED) != 0,
+                                    none);
+    out[0] = gp.tab.empty() ? 0 : (int32_t)gp.batches.size();
+    out[1] = gp.ring ? 1 : 0;
+    if (gp.tab.empty()) return NVQ_OK;
+    constexpr int kWords = 6 + 2 * (kRingMaxParts + 1);
+    if (out_words < 2 + (int)gp.batches.size() * kWords) return NVQ_ERR_WORKSPACE;
+    for (size_t b = 0; b < gp.batches.size(); ++b) {
+        const GroupBatch &gb = gp.batches[b];
+        int32_t *o = out + 2 + b * kWords;
+        for (int k = 0; k < kWords; ++k) o[k] = -1;
+        o[0] = gb.nunits > 0 ? gp.units[(size_t)gb.unit_first] : -1;
+        o[1] = gb.nunits > 0 ? gp.units[(size_t)gb.unit_first + gb.nunits - 1] : -1;
+        o[2] = gb.nunits;
+        o[3] = gb.njobs;
+        o[4] = gb.grid;
+        o[5] = gb.nparts;
+        for (int k = 0; k <= gb.nparts && gb.nparts > 0; ++k) {
+            o[6 + k] = (int32_t)gp.parts[(size_t)gb.part_first + k];
+            o[6 + kRingMaxParts + 1 + k] = (int32_t)gp.parts[(size_t)gb.part_first + gb.nparts + 1 + k];
+        }
+    }
+    return NVQ_OK;
+}
+
 extern "C" int nvq_plan_trace(nvq_plan *pl, uint64_t *buf, size_t bytes) {
     if (!pl) return NVQ_ERR_INVALID_ARG;
     if (buf && (bytes < (size_t)pl->nphase * nvq::kStreamTraceSlots * 8 || !nvq::aligned(buf, 8)))

@@ -23,7 +23,7 @@ EXPORTS = (
     "nvq_status_string", "nvq_last_hip_error", "nvq_pack_int4", "nvq_quant_act_i8",
     "nvq_gemv_w4a16", "nvq_gemv_w4a8", "nvq_decode_workspace_bytes", "nvq_decode_linears",
     "nvq_plan_create", "nvq_plan_run", "nvq_plan_info", "nvq_plan_status", "nvq_plan_trace",
-    "nvq_plan_destroy", "nvq_plan_describe",
+    "nvq_plan_destroy", "nvq_plan_describe", "nvq_plan_describe_batches",
     "nvq_dequant_bf16", "nvq_rms_norm_bf16", "nvq_silu_mul_bf16", "nvq_precision_from_scores", "nvq_stream_read", "nvq_stream_copy",
 )
 
@@ -78,6 +78,7 @@ def lib() -> C.CDLL:
     L.nvq_plan_trace.argtypes = [vp, vp, sz]
     L.nvq_plan_destroy.argtypes = [vp]
     L.nvq_plan_describe.argtypes = [vp, ci, ci, ci, ci, ci, vp, ci]
+    L.nvq_plan_describe_batches.argtypes = [vp, ci, ci, ci, ci, vp, ci]
     L.nvq_plan_destroy.restype = None
     L.nvq_precision_from_scores.argtypes = [vp, ci, C.c_double, C.c_double, vp]
     L.nvq_stream_read.argtypes = [vp, sz, vp, vp]
@@ -304,6 +305,26 @@ class DecodeList:
             self.close()
         except Exception:
             pass
+
+
+def plan_describe_batches(linears: Sequence[Linear], M: int, ordered: bool = False):
+    """Host-side planning of the grouped small-batch launches (no device needed):
+    (persistent kernel used, [dict per batch])."""
+    n = len(linears)
+    arr = (Linear * max(n, 1))(*linears)
+    per = 6 + 2 * 9
+    words = 2 + max(n, 1) * per
+    out = (C.c_int32 * words)()
+    _check(lib().nvq_plan_describe_batches(C.byref(arr), n, M, 0, PLAN_ORDERED if ordered else 0,
+                                           out, words), "nvq_plan_describe_batches")
+    res = []
+    for b in range(out[0]):
+        o = out[2 + b * per:2 + (b + 1) * per]
+        nparts = o[5]
+        res.append(dict(first_phase=o[0], last_phase=o[1], units=o[2], jobs=o[3], grid=o[4],
+                        parts=nparts, cuts=list(o[6:6 + nparts + 1]),
+                        cut_phases=list(o[15:15 + nparts + 1])))
+    return bool(out[1]), res
 
 
 DESCRIBE_FIELDS = ("first", "count", "wait", "publish", "rows", "rows_base", "rows_extra",

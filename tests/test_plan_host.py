@@ -135,3 +135,72 @@ def test_lists_the_persistent_kernel_does_not_take():
     assert waves == 0 and len(phases) == 1 and phases[0]["wait"] == -1
     waves, _ = nvq.plan_describe(model_list("llama-1b", [0] * 16), 4)   # batch 4: not batch 1
     assert waves == 0
+
+
+# ---- grouped small-batch launches: batches and the parts of the persistent kernel ----
+def model_list_m(model, bits, M):
+    a = Arena()
+    xs, out = {}, []
+    for sp in synth.model_linears(model):
+        if sp.phase not in xs:
+            xs[sp.phase] = a.take(M * sp.K * 2)
+        out.append(linear(a, sp.N, sp.K, xs[sp.phase], prec=1 if sp.block < 0 else bits[sp.block],
+                          M=M))
+    return out
+
+
+@pytest.mark.parametrize("model,M", [("llama-1b", 4), ("llama-8b", 16)])
+def test_parts_of_a_batch_cover_its_units_with_equal_weight(model, M):
+    nb = synth.MODELS[model][0]
+    layers = model_list_m(model, synth.make_precision_map(nb, nb // 2), M)
+    _, phases = nvq.plan_describe(layers, M)
+    ring, batches = nvq.plan_describe_batches(layers, M)
+    assert ring and len(batches) == 1              # independent inputs: one batch of all phases
+    b = batches[0]
+    assert (b["first_phase"], b["last_phase"]) == (0, len(phases) - 1)
+    assert b["jobs"] == len(phases)                # every phase gets an operand image
+    # units: pairs of 16-row tiles, phase after phase; a unit of a phase weighs its K
+    unit_phase, weight = [], []
+    for p, ph in enumerate(phases):
+        first = layers[ph["first"]]
+        rows = sum(layers[ph["first"] + i].N for i in range(ph["count"]))
+        unit_phase += [p] * ((rows + 31) // 32)
+        weight += [first.K] * ((rows + 31) // 32)
+    assert b["units"] == len(unit_phase)
+    assert b["grid"] == 256 and b["parts"] == 8    # one workgroup per compute unit, 8 XCDs
+    cuts = b["cuts"]
+    assert cuts[0] == 0 and cuts[-1] == b["units"] and cuts == sorted(cuts)
+    for c, p in zip(cuts[:-1], b["cut_phases"][:-1]):
+        assert p == unit_phase[c]                  # where a team starts looking for its phase
+    w = np.array(weight, dtype=np.int64)
+    part_weight = [int(w[cuts[i]:cuts[i + 1]].sum()) for i in range(8)]
+    assert max(part_weight) - min(part_weight) <= 2 * int(w.max())
+
+
+def test_a_chain_makes_one_batch_per_phase_and_small_batches_few_workgroups():
+    a = Arena()
+    M = 6
+    dims = [2048, 4096, 1024, 6144, 512]
+    bufs = [a.take(M * d * 2) for d in dims]
+    layers = [linear(a, dims[i + 1], dims[i], bufs[i], y=bufs[i + 1], prec=i % 2, y_f32=False, M=M)
+              for i in range(4)]
+    ring, batches = nvq.plan_describe_batches(layers, M)
+    assert ring and len(batches) == 4
+    for i, b in enumerate(batches):
+        units = (dims[i + 1] + 31) // 32
+        assert (b["first_phase"], b["last_phase"], b["units"], b["jobs"]) == (i, i, units, 1)
+        assert b["grid"] == min(256, (units + 8) // 9)       # 3 teams x bundles of 3 units
+        assert b["parts"] == min(8, b["grid"])
+        assert b["cuts"][0] == 0 and b["cuts"][-1] == units
+        assert all(p == i for p in b["cut_phases"])
+
+
+def test_lists_the_persistent_small_batch_kernel_does_not_take():
+    a = Arena()
+    x = a.take(32 * 4096 * 2)
+    ring, batches = nvq.plan_describe_batches([linear(a, 128, 4096, x, M=32)], 32)
+    assert not ring and len(batches) == 1          # more than 16 tokens: per-tile grid
+    ring, batches = nvq.plan_describe_batches([linear(a, 128, 640, x, M=4)], 4)
+    assert not ring and len(batches) == 1          # K is no multiple of 512
+    ring, batches = nvq.plan_describe_batches([linear(a, 128, 4128, x, M=4)], 4)
+    assert not ring and batches == []              # K % 128 != 0: launches per phase
