@@ -217,8 +217,8 @@ int nvq_decode_linears(const nvq_linear *layers, int n, int M, int act_group,
  *                    the walk is issued as grouped small-batch launches (two
  *                    per batch of independent phases; 3: the product runs as
  *                    a persistent grid fed through LDS rings, which needs
- *                    M <= 16, every K a multiple of 512 and 16-byte aligned
- *                    scale rows), 0 for launches per phase;
+ *                    every K a multiple of 512 and 16-byte aligned scale
+ *                    rows), 0 for launches per phase;
  *                    waits = number of phases that wait for an earlier phase
  *                    (grouped launches: number of batch boundaries)
  *   nvq_plan_status  synchronises `stream` and reports whether a wait inside

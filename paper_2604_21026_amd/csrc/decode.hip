@@ -339,8 +339,7 @@ GroupPlan group_plan(const nvq_linear *L, const std::vector<Phase> &phases, int 
         if (L[ph.first].in_op != NVQ_IN_PLAIN ||
             !gemv_mfma_supported(make_segs(L, ph), L[ph.first].K, M))
             return gp;
-    // beyond 16 tokens the per-tile grid is still the faster one
-    gp.ring = M <= 16;
+    gp.ring = true;
     for (const Phase &ph : phases)
         gp.ring = gp.ring && gemv_mfma_ring_supported(make_segs(L, ph), L[ph.first].K);
     const std::vector<int> deps = phase_deps(L, phases, M, ordered);

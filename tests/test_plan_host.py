@@ -199,7 +199,7 @@ def test_lists_the_persistent_small_batch_kernel_does_not_take():
     a = Arena()
     x = a.take(32 * 4096 * 2)
     ring, batches = nvq.plan_describe_batches([linear(a, 128, 4096, x, M=32)], 32)
-    assert not ring and len(batches) == 1          # more than 16 tokens: per-tile grid
+    assert ring and batches[0]["grid"] == 2        # 4 units, two teams per workgroup beyond 16 tokens
     ring, batches = nvq.plan_describe_batches([linear(a, 128, 640, x, M=4)], 4)
     assert not ring and len(batches) == 1          # K is no multiple of 512
     ring, batches = nvq.plan_describe_batches([linear(a, 128, 4128, x, M=4)], 4)
