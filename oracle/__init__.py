@@ -134,6 +134,16 @@ def dequant_bf16(qweight, scales):
     return out
 
 
+def gemm_w4a16_dense(qweight, scales, x_bf16):
+    """Prefill / large-batch product (paper: kernel table, the weights are dequantised to 16-bit
+    values and a dense GEMM follows): Y = X * Wd^T with Wd the bf16 weights of dequant_bf16 and
+    X the bf16 activations [M,K]; every product is exact in float64, the sum is float64.
+    -> float64 [M,N]."""
+    wd = dequant_bf16(qweight, scales).astype(np.uint32) << 16
+    x = _arr(x_bf16, np.uint16, 2).astype(np.uint32) << 16
+    return x.view(np.float32).astype(np.float64) @ wd.view(np.float32).astype(np.float64).T
+
+
 def quant_act_i8(x_bf16, act_group=0):
     """x u16(bf16 bits) [M,K] -> (xq i8 [M,K], xscale f32 [M] or [M,K/32], xgsum i32 [M,K/32])."""
     x = _arr(x_bf16, np.uint16, 2)
