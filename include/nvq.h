@@ -286,6 +286,26 @@ int nvq_dequant_bf16(const uint8_t *qweight, const uint16_t *scales, int64_t N, 
                      uint16_t *out_bf16, void *stream);
 
 /*
+ * nvq_gemm_w4a16 -- the prefill / large-batch product (paper: kernel table,
+ * dequantise to 16-bit weights, then a dense GEMM; limitations: large batches
+ * are bound by compute).  y[m][n] = sum_k x[m][k] * wd[n][k] with wd the bf16
+ * weights nvq_dequant_bf16 would store, bf16 x bf16 products accumulated in
+ * fp32 on the matrix cores (the summation order is the kernel's); the dense
+ * weights are never written to memory.  For any M >= 1; meant for M of a few
+ * hundred and more (below that the batch-1 and small-batch paths read the
+ * weights once and are faster).  Note that the weights are rounded to bf16
+ * here, as in the paper's prefill path, and are not in nvq_gemv_w4a16.
+ *   qweight  device, [N][K/2], layout of nvq_pack_int4, 16-byte aligned
+ *   scales   device, [N][K/32] fp16 bits
+ *   x_bf16   device, [M][K] bf16 bits, 16-byte aligned
+ *   y        device, [M][N] f32 or bf16 (y_dtype), owned by the caller
+ * Enqueues on `stream`; K % 32 == 0.  Errors: NVQ_ERR_INVALID_ARG (null
+ * pointer, y_dtype), NVQ_ERR_SHAPE, NVQ_ERR_ALIGN, NVQ_ERR_HIP.
+ */
+int nvq_gemm_w4a16(const uint8_t *qweight, const uint16_t *scales, int64_t N, int64_t K,
+                   const uint16_t *x_bf16, int64_t M, void *y, int y_dtype, void *stream);
+
+/*
  * nvq_precision_from_scores -- host helper: the normalise-and-assign tail of
  * the paper's Algorithm 1.  scores (host, L doubles) are min-max normalised;
  * if max - min < eps every normalised score is 0; out[i] = NVQ_W4A16 if the

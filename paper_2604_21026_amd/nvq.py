@@ -24,7 +24,7 @@ EXPORTS = (
     "nvq_gemv_w4a16", "nvq_gemv_w4a8", "nvq_decode_workspace_bytes", "nvq_decode_linears",
     "nvq_plan_create", "nvq_plan_run", "nvq_plan_info", "nvq_plan_status", "nvq_plan_trace",
     "nvq_plan_destroy", "nvq_plan_describe", "nvq_plan_describe_batches",
-    "nvq_dequant_bf16", "nvq_rms_norm_bf16", "nvq_silu_mul_bf16", "nvq_precision_from_scores", "nvq_stream_read", "nvq_stream_copy",
+    "nvq_dequant_bf16", "nvq_gemm_w4a16", "nvq_rms_norm_bf16", "nvq_silu_mul_bf16", "nvq_precision_from_scores", "nvq_stream_read", "nvq_stream_copy",
 )
 
 
@@ -63,6 +63,7 @@ def lib() -> C.CDLL:
     L.nvq_last_hip_error.argtypes = []
     L.nvq_pack_int4.argtypes = [vp, i64, i64, ci, vp, vp, vp]
     L.nvq_dequant_bf16.argtypes = [vp, vp, i64, i64, vp, vp]
+    L.nvq_gemm_w4a16.argtypes = [vp, vp, i64, i64, vp, i64, vp, ci, vp]
     L.nvq_rms_norm_bf16.argtypes = [vp, vp, vp, C.c_float, ci, ci, vp, vp, vp]
     L.nvq_silu_mul_bf16.argtypes = [vp, vp, ci, ci, vp, vp]
     L.nvq_quant_act_i8.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp]
@@ -196,6 +197,20 @@ def gemv_w4a16(qweight, scales, x, out_dtype=torch.float32, out: Optional[torch.
                                 _dev(scales, torch.int16, "scales"), N, K,
                                 _dev(x, torch.bfloat16, "x"), M, _dev(y, y.dtype, "y"),
                                 _y_dtype(y.dtype), _stream()), "nvq_gemv_w4a16")
+    return y
+
+
+def gemm_w4a16(qweight, scales, x, out_dtype=torch.float32, out: Optional[torch.Tensor] = None):
+    """Prefill / large-batch product: x bf16 [M,K] -> y [M,N] (weights rounded to bf16)."""
+    N, K = qweight.shape[0], qweight.shape[1] * 2
+    M = x.shape[0]
+    if x.shape[1] != K or tuple(scales.shape) != (N, K // 32):
+        raise ValueError("shape mismatch")
+    y = out if out is not None else torch.empty((M, N), dtype=out_dtype, device=x.device)
+    _check(lib().nvq_gemm_w4a16(_dev(qweight, torch.uint8, "qweight"),
+                                _dev(scales, torch.int16, "scales"), N, K,
+                                _dev(x, torch.bfloat16, "x"), M, _dev(y, y.dtype, "y"),
+                                _y_dtype(y.dtype), _stream()), "nvq_gemm_w4a16")
     return y
 
 

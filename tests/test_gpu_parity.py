@@ -684,3 +684,38 @@ def test_chain_of_blocks_with_transforms_in_one_launch():
         # the residual stream entering block 1 is the exact bf16 sum
         assert torch.equal(h2, B0["h1"] + down0)
     dl.close()
+
+
+# ---- prefill / large-batch product on the matrix cores --------------------------------
+# Shapes: one tile, ragged tokens and rows inside a 256 x 128 workgroup tile and inside the
+# 32 x 32 MFMA tiles, several workgroups in both directions, K from one group to many.
+@pytest.mark.parametrize("M,N,K", [(32, 32, 32), (256, 128, 64), (77, 45, 96), (300, 200, 256),
+                                   (513, 257, 2048), (1, 1, 32), (1024, 384, 4096)])
+def test_gemm_w4a16_matches_oracle(M, N, K):
+    say("gemm", M, N, K)
+    _, q, s = packed(9100 + M + N, N, K)
+    xh = act(9200 + K, M, K)
+    want = oracle.gemm_w4a16_dense(q, s, u16(xh))
+    qd, sd = to_dev_packed(q, s)
+    y = nvq.gemm_w4a16(qd, sd, xh.to(DEV))
+    torch.cuda.synchronize()
+    err = np_ref.rel_l2(y.cpu().numpy(), want)
+    say("  rel l2", err)
+    assert err < 1e-5
+    yb = nvq.gemm_w4a16(qd, sd, xh.to(DEV), out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    assert np_ref.rel_l2(yb.float().cpu().numpy(), want) < 4e-3
+
+
+def test_gemm_w4a16_takes_every_code():
+    say("gemm codes")
+    rng = np.random.default_rng(9300)
+    M, N, K = 96, 64, 128
+    q = rng.integers(0, 256, (N, K // 2)).astype(np.uint8)          # code -8 included
+    s = (rng.random((N, K // 32)).astype(np.float32) * 0.1 + 0.01).astype(np.float16).view(np.uint16)
+    xh = act(9301, M, K)
+    want = oracle.gemm_w4a16_dense(q, s, u16(xh))
+    qd, sd = to_dev_packed(q, s)
+    y = nvq.gemm_w4a16(qd, sd, xh.to(DEV))
+    torch.cuda.synchronize()
+    assert np_ref.rel_l2(y.cpu().numpy(), want) < 1e-5
