@@ -2,8 +2,8 @@
 """Benchmark of the decode-linear hot path on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--model llama-8b]
-                    [--map mixed|w4a8|w4a16] [--leg all|step|cpu|calib] [--extra]
-                    [--batch M] [--act-group 0|32]
+                    [--map mixed|w4a8|w4a16] [--leg all|step|cpu|calib|prefill] [--extra]
+                    [--batch M] [--act-group 0|32] [--prefill-tokens T]
 
 A step is one walk (one run of a prepared nvq plan = one launch of the
 persistent streaming kernel) over every linear layer of one decode step at
@@ -12,6 +12,10 @@ layers, all GEMVs, lm_head (W4A16) where the model has one.  All weights and
 activations are resident in HBM before the timed region; every layer reads its
 own seeded input buffer.  Prints one JSON line (metric, value, roofline of the
 persistent kernel from HIP events, cpu_baseline = the CPU oracle on a bounded sample).
+
+--leg prefill is a separate measurement outside the headline metric: the seven linears of one
+transformer block of the model for T tokens at once through nvq_gemm_w4a16 (dequantisation
+fused into a bf16 matrix-core GEMM), reported in TFLOP/s against the dense bf16 MFMA peak.
 """
 import argparse
 import json
@@ -37,7 +41,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--model", default="llama-8b", choices=["llama-1b", "llama-3b", "llama-8b"])
     ap.add_argument("--map", default="mixed", choices=["mixed", "w4a8", "w4a16"])
-    ap.add_argument("--leg", default="all", choices=["all", "step", "cpu", "calib"],
+    ap.add_argument("--prefill-tokens", type=int, default=4096)
+    ap.add_argument("--leg", default="all", choices=["all", "step", "cpu", "calib", "prefill"],
                     help="calib: run only the plain copy kernel (1 GiB, for scaling profiler "
                          "byte counters)")
     ap.add_argument("--act-group", type=int, default=0, choices=[0, 32])
@@ -210,6 +215,58 @@ def cpu_leg(model, bits, M, synth, budget_s=20.0):
             "gbs": round(total_w * 0.5625 / step_s / 1e9, 2)}
 
 
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def prefill_leg(a, torch, nvq, synth):
+    """One block's linears for T tokens through the fused-dequantisation GEMM."""
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    T = a.prefill_tokens
+    specs = [sp for sp in synth.model_linears(a.model) if sp.block == 0]
+    mats, xs = [], {}
+    for sp in specs:
+        W = synth.make_weight(synth.tensor_seed(0, sp.slot), sp.N, sp.K, device=dev)
+        q, s = nvq.pack_int4(W)
+        del W
+        if sp.phase not in xs:
+            xs[sp.phase] = synth.make_activation(synth.activation_seed(sp.phase), T, sp.K, True,
+                                                 device=dev)
+        mats.append((q, s, xs[sp.phase], torch.empty((T, sp.N), dtype=torch.bfloat16, device=dev)))
+    flops = sum(2.0 * T * sp.N * sp.K for sp in specs)
+
+    def block():
+        for q, s, x, y in mats:
+            nvq.gemm_w4a16(q, s, x, out=y)
+
+    for _ in range(a.warmup // 10 + 2):
+        block()
+    torch.cuda.synchronize()
+    reps = max(a.steps // 10, 5)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(reps):
+        block()
+    e1.record()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) / reps
+    dev_s = e0.elapsed_time(e1) * 1e-3 / reps
+    tf = flops / dev_s / 1e12
+    print(json.dumps({
+        "metric": "prefill linear-layer throughput, one %s block, %d tokens" % (a.model, T),
+        "value": round(T / wall, 1), "unit": "tokens/s (one block's seven linears)", "n_gpus": 1,
+        "steps": reps, "warmup": a.warmup // 10 + 2, "ms_per_step": round(wall * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 x bf16(int4 * fp16 scale) -> f32", "data": "synthetic",
+        "config": {"workload": "%s block 0: q, k, v, o, gate, up, down as %d-token GEMMs with the "
+                               "dequantisation fused in" % (a.model, T), "flop_per_step": flops},
+        "roofline": {"bound": "mfma", "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
+                     "traffic": None, "kernel": "nvq::gemm_w4a16_kernel", "launches": reps * len(mats),
+                     "avg_launch_us": round(dev_s * 1e6 / len(mats), 2)}}))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -229,6 +286,9 @@ def main():
         print(json.dumps({"calib": "nvq::stream_copy_kernel", "bytes_read": 1 << 30,
                           "bytes_written": 1 << 30, "launches": 5}))
         return
+    if a.leg == "prefill":
+        prefill_leg(a, torch, nvq, synth)
+        return
     M = a.batch
     if not 1 <= M <= 32:
         print("bench.py: --batch must be 1..32", file=sys.stderr)
@@ -246,7 +306,7 @@ def main():
         "config": {"workload": "%s-shaped decode step, batch %d, %d linears in %s, precision map "
                                "%s (%d of %d blocks W4A16%s), own input buffer per layer" %
                                (a.model, M, len(specs),
-                                "one launch" if M == 1 else "one launch per phase", a.map,
+                                "one launch" if M == 1 else "two launches", a.map,
                                 sum(bits), len(bits),
                                 ", lm_head W4A16" if specs[-1].block < 0 else ""),
                    "act_group": a.act_group, "weight_bytes_per_step": step_bytes},
