@@ -51,6 +51,13 @@ def test_argument_validation_happens_before_any_launch():
     assert L.nvq_gemv_w4a8(a, a, 8, 64, a, a, None, 0, 1, a, 0, None, None) == 1
     assert L.nvq_gemv_w4a8(a, a, 0, 64, a, a, a, 0, 1, a, 0, None, None) == 2
     assert L.nvq_stream_read(a, 24, a, None) == 2
+    assert L.nvq_gemm_w4a16(a, a, 8, 64, None, 4, a, 0, None) == 1
+    assert L.nvq_gemm_w4a16(a, a, 8, 64, a, 4, a, 3, None) == 1
+    assert L.nvq_gemm_w4a16(a, a, 8, 48, a, 4, a, 0, None) == 2
+    assert L.nvq_gemm_w4a16(a, a, 8, 64, a, 0, a, 0, None) == 2
+    assert L.nvq_gemm_w4a16(a + 8, a, 8, 64, a, 4, a, 0, None) == 3
+    assert L.nvq_dequant_bf16(a, a, 8, 40, a, None) == 2
+    assert L.nvq_dequant_bf16(a, None, 8, 64, a, None) == 1
 
 
 def test_decode_list_validation_and_workspace_size():
