@@ -31,7 +31,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 STREAM_KERNEL = "nvq::decode_stream_kernel<false>"
 GROUP_KERNEL = "nvq::gemv_mfma_group_kernel (+ nvq::quant_act_group_kernel)"
-RING_KERNEL = "nvq::gemv_mfma_ring_kernel (+ nvq::quant_act_group_kernel)"
+RING_KERNEL = ("nvq::gemv_mfma_ring_kernel (+ nvq::token_scale_group_kernel, "
+               "nvq::operand_image_group_kernel)")
 
 
 def parse():
@@ -306,7 +307,7 @@ def main():
         "config": {"workload": "%s-shaped decode step, batch %d, %d linears in %s, precision map "
                                "%s (%d of %d blocks W4A16%s), own input buffer per layer" %
                                (a.model, M, len(specs),
-                                "one launch" if M == 1 else "two launches", a.map,
+                                "one launch" if M == 1 else "three launches", a.map,
                                 sum(bits), len(bits),
                                 ", lm_head W4A16" if specs[-1].block < 0 else ""),
                    "act_group": a.act_group, "weight_bytes_per_step": step_bytes},

@@ -42,6 +42,7 @@ struct Workspace {
     uint16_t *gjobs;    // [n]                 W4A8 phases, batch after batch
     uint16_t *gunits;   // [group_units]       phase of every 16-row tile, batch after batch
     uint32_t *gteams;   // [n][2][kRingMaxParts + 1]  per batch: the parts of the ring kernel's XCDs
+    uint16_t *gimgs;    // [group_images]      phase of every operand image unit, batch after batch
     char *gquant;       // per-phase activation codes, scales and code sums
     size_t bytes;
 };
@@ -52,6 +53,7 @@ struct ListSizes {
     size_t image_bytes;  // activation images of the streaming kernel (M = 1)
     size_t group_units;  // 16-row tiles of all entries (M > 1)
     size_t group_quant;  // codes + scales + code sums of all W4A8 entries (M > 1)
+    size_t group_images; // operand image units of all entries (M > 1)
     bool transforms;     // some entry has an input transform
 };
 
@@ -93,6 +95,7 @@ Workspace carve(void *base, int M, int n, const ListSizes &ls) {
     w.gjobs = reinterpret_cast<uint16_t *>(take(M > 1 ? nn * 2 : 0));
     w.gunits = reinterpret_cast<uint16_t *>(take(M > 1 ? ls.group_units * 2 : 0));
     w.gteams = reinterpret_cast<uint32_t *>(take(M > 1 ? nn * 2 * (kRingMaxParts + 1) * 4 : 0));
+    w.gimgs = reinterpret_cast<uint16_t *>(take(M > 1 ? ls.group_images * 2 : 0));
     w.gquant = take(M > 1 ? ls.group_quant : 0);
     w.bytes = off;
     return w;
@@ -103,7 +106,7 @@ int check_layers(const nvq_linear *L, int n, int M, int act_group, ListSizes *si
     if (act_group != 0 && act_group != 32) return NVQ_ERR_INVALID_ARG;
     if (M <= 0 || M > NVQ_MAX_M) return NVQ_ERR_SHAPE;
     int mk = 32;
-    size_t ib = 0, gu = 0, gq = 0;
+    size_t ib = 0, gu = 0, gq = 0, gi = 0;
     bool tr = false;
     for (int i = 0; i < n; ++i) {
         const nvq_linear &e = L[i];
@@ -138,11 +141,13 @@ int check_layers(const nvq_linear *L, int n, int M, int act_group, ListSizes *si
         const size_t image = operand_image_bytes(M, e.K, e.precision) + round_up((size_t)M * 4, 256);
         const size_t plain = e.precision == NVQ_W4A8 ? quant_bytes(M, e.K) : 0;
         gq += image > plain ? image : plain;
+        gi += (size_t)image_units(M, e.K);
     }
     sizes->maxK = mk;
     sizes->image_bytes = ib;
     sizes->group_units = gu;
     sizes->group_quant = gq;
+    sizes->group_images = gi;
     sizes->transforms = tr;
     return NVQ_OK;
 }
@@ -288,13 +293,14 @@ std::vector<int> phase_deps(const nvq_linear *L, const std::vector<Phase> &phase
 struct GroupBatch {
     int job_first, njobs;    // range in the job list
     int unit_first, nunits;  // range in the unit list
+    int img_first, nimg;     // range in the image unit list
     int part_first, nparts;  // the batch's table in the part list (2 * (nparts + 1) words)
     int grid;                // workgroups of the persistent kernel
 };
 struct GroupPlan {
     bool ring;  // the persistent kernel serves the list: every phase has a job and an operand image
     std::vector<GroupPhase> tab;
-    std::vector<uint16_t> jobs, units;
+    std::vector<uint16_t> jobs, units, imgs;
     std::vector<uint32_t> parts;  // per batch: nparts + 1 unit cuts, then the phases at the cuts
     std::vector<GroupBatch> batches;
 };
@@ -344,14 +350,14 @@ GroupPlan group_plan(const nvq_linear *L, const std::vector<Phase> &phases, int 
         gp.ring = gp.ring && gemv_mfma_ring_supported(make_segs(L, ph), L[ph.first].K);
     const std::vector<int> deps = phase_deps(L, phases, M, ordered);
     size_t qoff = 0;
-    GroupBatch cur = {0, 0, 0, 0, 0, 0, 0};
+    GroupBatch cur = {0, 0, 0, 0, 0, 0, 0, 0, 0};
     int batch_first = 0;
     for (size_t p = 0; p < phases.size(); ++p) {
         const nvq_linear &e0 = L[phases[p].first];
         if (deps[p] >= batch_first) {  // depends on a phase of the open batch: close it
             cut_batch(gp, cur, M);
             gp.batches.push_back(cur);
-            cur = {(int)gp.jobs.size(), 0, (int)gp.units.size(), 0, 0, 0, 0};
+            cur = {(int)gp.jobs.size(), 0, (int)gp.units.size(), 0, (int)gp.imgs.size(), 0, 0, 0, 0};
             batch_first = (int)p;
         }
         GroupPhase g = {};
@@ -367,6 +373,10 @@ GroupPlan group_plan(const nvq_linear *L, const std::vector<Phase> &phases, int 
             qoff += operand_image_bytes(M, e0.K, e0.precision) + round_up((size_t)M * 4, 256);
             gp.jobs.push_back((uint16_t)p);
             ++cur.njobs;
+            g.img_begin = cur.nimg;
+            const int iu = image_units(M, e0.K);
+            gp.imgs.insert(gp.imgs.end(), (size_t)iu, (uint16_t)p);
+            cur.nimg += iu;
         } else if (e0.precision == NVQ_W4A8) {
             char *b = ws.gquant + qoff;
             g.xq = reinterpret_cast<int8_t *>(b);
@@ -607,6 +617,9 @@ extern "C" int nvq_plan_create(const nvq_linear *layers, int n, int M, int act_g
             if (e == hipSuccess)
                 e = hipMemcpyAsync(ws.gunits, gp.units.data(), gp.units.size() * 2,
                                    hipMemcpyHostToDevice, st);
+            if (e == hipSuccess && !gp.imgs.empty())
+                e = hipMemcpyAsync(ws.gimgs, gp.imgs.data(), gp.imgs.size() * 2,
+                                   hipMemcpyHostToDevice, st);
             if (e == hipSuccess && !gp.parts.empty())
                 e = hipMemcpyAsync(ws.gteams, gp.parts.data(), gp.parts.size() * 4,
                                    hipMemcpyHostToDevice, st);
@@ -641,8 +654,10 @@ extern "C" int nvq_plan_run(nvq_plan *pl, void *stream) {
     }
     if (!pl->batches.empty()) {
         for (const GroupBatch &b : pl->batches) {
-            int rc = launch_quant_act_group(pl->ws.gtab, pl->ws.gjobs + b.job_first, b.njobs, pl->M,
-                                            pl->ring, st);
+            int rc = pl->ring ? launch_operand_images(pl->ws.gtab, pl->ws.gjobs + b.job_first, b.njobs,
+                                                      pl->ws.gimgs + b.img_first, b.nimg, pl->M, st)
+                              : launch_quant_act_group(pl->ws.gtab, pl->ws.gjobs + b.job_first,
+                                                       b.njobs, pl->M, st);
             if (rc != NVQ_OK) return rc;
             rc = pl->ring ? launch_gemv_mfma_ring(pl->ws.gtab, pl->ws.gteams + b.part_first, b.nparts,
                                                   b.grid, pl->M, pl->ws.status, st)

@@ -68,16 +68,23 @@ struct GroupPhase {
     int G, precision;
     int unit_begin;          // first grid unit of the phase in its batch
     int unit_count;          // its units
+    int img_begin;           // first image unit of the phase in its batch (launch_operand_images)
 };
 // jobs[j] names the phase whose M tokens grid blocks j*M .. j*M+M-1 quantise.
-// With `image` set, every job writes its phase's operand image `xa` instead:
-// per tile of 16 tokens, 128-input column c and piece i one KiB whose 16 bytes
-// number 16 * kb + n are, for token n of the tile, the int8 codes
-// 32 * kb + 16 * i .. + 15 of the column (W4A8, two pieces; xscale as before,
-// no code sums) or the bf16 inputs 32 * i + 8 * kb .. + 7 of the column, copied
-// (W4A16, four pieces).  Token slots past M are left as they are.
 int launch_quant_act_group(const GroupPhase *tab, const uint16_t *jobs, int njobs, int M,
-                           bool image, hipStream_t st);
+                           hipStream_t st);
+// The operand images `xa` of the phases named in `jobs` (per-token scales of
+// the W4A8 ones first, then the images: img_units[u] names the phase of image
+// unit u, a token tile times eight 128-input columns; image_units(M, K) of
+// them per phase, numbered from GroupPhase::img_begin).  Per tile of 16
+// tokens, column c and piece i one KiB whose 16 bytes number 16 * kb + n are,
+// for token n of the tile, the int8 codes 32 * kb + 16 * i .. + 15 of the
+// column (W4A8, two pieces; xscale as in launch_quant_act_group, no code sums)
+// or the bf16 inputs 32 * i + 8 * kb .. + 7 of the column, copied (W4A16, four
+// pieces).  Token slots past M are left as they are.
+int image_units(int M, int K);
+int launch_operand_images(const GroupPhase *tab, const uint16_t *jobs, int njobs,
+                          const uint16_t *img_units, int nimg, int M, hipStream_t st);
 // unit_phase[u] names the phase of grid unit u; a unit is group_row_tiles(M)
 // consecutive 16-row tiles, which share their activation operands (as many as
 // fit the registers next to one or two token tiles).

@@ -32,31 +32,16 @@ __device__ __forceinline__ int quant_one(float x, float s) {
     return (int)r;
 }
 
-// Byte offset, in the operand image of the persistent small-batch kernel, of
-// the 16-byte piece that holds input e (a multiple of 8) of token m: KiB blocks
-// per (token tile, 128-input column, piece), 16 bytes per (kb, token) in them.
-// PIECES = 2 for int8 codes (piece = a half of group kb of the column), 4 for
-// bf16 (piece i = inputs 32 i .. 32 i + 31, split over kb by eights).
-template <int PIECES>
-__device__ __forceinline__ size_t image_offset(int K, int m, int e) {
-    const int c = e >> 7, off = e & 127;
-    const int kb = PIECES == 2 ? off >> 5 : (off & 31) >> 3;
-    const int piece = PIECES == 2 ? (off & 31) >> 4 : off >> 5;
-    const size_t block = ((size_t)(m >> 4) * (K >> 7) + c) * PIECES + piece;
-    return block * 1024 + (size_t)(kb * 16 + (m & 15)) * 16 + (PIECES == 2 ? (off & 8) : 0);
-}
-
-// Token m of one [M][K] input, by one workgroup.  IMAGE: the codes go to the
-// operand image `xq` instead of the [M][K] matrix, and no code sums are kept.
-template <bool PER_GROUP, bool IMAGE = false>
+// Token m of one [M][K] input, by one workgroup.
+template <bool PER_GROUP>
 __device__ __forceinline__ void quant_token(const uint4 *__restrict__ x, int K, int m,
                                             int8_t *__restrict__ xq, float *__restrict__ xscale,
                                             int32_t *__restrict__ xgsum) {
     const int chunks = K / 8;  // multiple of 4
     const int G = K / 32;
     const uint4 *xr = x + (int64_t)m * chunks;
-    uint2 *qr = reinterpret_cast<uint2 *>(xq + (IMAGE ? 0 : (int64_t)m * K));
-    int32_t *gs = IMAGE ? nullptr : xgsum + (int64_t)m * G;
+    uint2 *qr = reinterpret_cast<uint2 *>(xq + (int64_t)m * K);
+    int32_t *gs = xgsum + (int64_t)m * G;
 
     float s_tok = 0.0f;
     if (!PER_GROUP) {
@@ -101,10 +86,6 @@ __device__ __forceinline__ void quant_token(const uint4 *__restrict__ x, int K, 
                 ((uint32_t)(q[2] & 0xff) << 16) | ((uint32_t)(q[3] & 0xff) << 24);
         out.y = (uint32_t)(q[4] & 0xff) | ((uint32_t)(q[5] & 0xff) << 8) |
                 ((uint32_t)(q[6] & 0xff) << 16) | ((uint32_t)(q[7] & 0xff) << 24);
-        if (IMAGE) {
-            *reinterpret_cast<uint2 *>(xq + image_offset<2>(K, m, 8 * c)) = out;
-            continue;
-        }
         qr[c] = out;
         sum += __shfl_xor(sum, 1, 64);
         sum += __shfl_xor(sum, 2, 64);
@@ -128,32 +109,107 @@ __global__ __launch_bounds__(kQuantThreads) void quant_act_group_kernel(
                        P.xgsum);
 }
 
-// Operand images of many phases in one grid: quantised codes (W4A8) or a
-// rearranged copy of the bf16 inputs (W4A16).
-__global__ __launch_bounds__(kQuantThreads) void operand_image_group_kernel(
+// ---- operand images of the persistent small-batch kernel ---------------------
+// Per tile of 16 tokens, 128-input column c and piece i one KiB whose 16 bytes
+// number 16 * kb + n are, for token n of the tile, the int8 codes 32 * kb +
+// 16 * i .. + 15 of the column (W4A8, two pieces) or the bf16 inputs 32 * i +
+// 8 * kb .. + 7 of the column (W4A16, four pieces): the order in which a wave
+// of the matrix-core kernel loads its activation operands.  Two grids: the
+// per-token scales of the W4A8 phases first, then the images, a wave writing
+// whole KiB pieces (one workgroup per token, as for the [M][K] codes, would
+// write 8 or 16 bytes here and there into lines shared with 15 other
+// workgroups).
+
+// Per-token scale of token m of every W4A8 job (the other jobs' workgroups leave).
+__global__ __launch_bounds__(kQuantThreads) void token_scale_group_kernel(
     const GroupPhase *__restrict__ tab, const uint16_t *__restrict__ jobs, int M) {
     const int job = blockIdx.x / M, m = blockIdx.x - job * M;
     const GroupPhase &P = tab[jobs[job]];
-    const int K = P.G * 32;
-    const uint4 *x = reinterpret_cast<const uint4 *>(P.x_bf16);
-    if (P.precision == NVQ_W4A8) {
-        quant_token<false, true>(x, K, m, reinterpret_cast<int8_t *>(P.xa), P.xscale, nullptr);
-    } else {
-        const uint4 *xr = x + (int64_t)m * (K / 8);
-        for (int c = threadIdx.x; c < K / 8; c += kQuantThreads)
-            *reinterpret_cast<uint4 *>(P.xa + image_offset<4>(K, m, 8 * c)) = xr[c];
+    if (P.precision != NVQ_W4A8) return;
+    __shared__ float red[kQuantThreads / 64];
+    const int chunks = P.G * 4;
+    const uint4 *xr = reinterpret_cast<const uint4 *>(P.x_bf16) + (int64_t)m * chunks;
+    float a = 0.0f;
+    for (int c = threadIdx.x; c < chunks; c += kQuantThreads) a = fmaxf(a, chunk_absmax(xr[c]));
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) a = fmaxf(a, __shfl_xor(a, off, 64));
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = a;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        a = red[0];
+#pragma unroll
+        for (int i = 1; i < kQuantThreads / 64; ++i) a = fmaxf(a, red[i]);
+        P.xscale[m] = a / 127.0f;
     }
 }
 
+constexpr int kImageColumns = 8;  // columns of 128 inputs per workgroup (two per wave)
+
+__device__ __forceinline__ uint32_t quant_pack4(uint32_t w0, uint32_t w1, float s) {
+    const int q0 = (s != 0.0f) ? quant_one(bf16_bits_to_float(w0 & 0xffffu), s) : 0;
+    const int q1 = (s != 0.0f) ? quant_one(bf16_bits_to_float(w0 >> 16), s) : 0;
+    const int q2 = (s != 0.0f) ? quant_one(bf16_bits_to_float(w1 & 0xffffu), s) : 0;
+    const int q3 = (s != 0.0f) ? quant_one(bf16_bits_to_float(w1 >> 16), s) : 0;
+    return (uint32_t)(q0 & 0xff) | ((uint32_t)(q1 & 0xff) << 8) | ((uint32_t)(q2 & 0xff) << 16) |
+           ((uint32_t)(q3 & 0xff) << 24);
+}
+
+// img_units[u] names the phase of grid unit u; a unit is a token tile times
+// kImageColumns columns of that phase.  Token slots past M are left as they are.
+__global__ __launch_bounds__(kQuantThreads) void operand_image_group_kernel(
+    const GroupPhase *__restrict__ tab, const uint16_t *__restrict__ img_units, int M) {
+    const GroupPhase &P = tab[img_units[blockIdx.x]];
+    const int local = blockIdx.x - P.img_begin;
+    const int C4 = P.G >> 2, cblocks = (C4 + kImageColumns - 1) / kImageColumns;
+    const int mt = local / cblocks, cb = local - mt * cblocks;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = lane & 15, kb = lane >> 4;
+    const int m = mt * 16 + n;
+    if (m >= M) return;
+    const uint16_t *xr = P.x_bf16 + (int64_t)m * (P.G * 32);
+    if (P.precision == NVQ_W4A8) {
+        const float s = P.xscale[m];
+        for (int c = cb * kImageColumns + wave; c < C4 && c < (cb + 1) * kImageColumns; c += 4) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const uint4 *src = reinterpret_cast<const uint4 *>(xr + c * 128 + 32 * kb + 16 * i);
+                const uint4 v0 = src[0], v1 = src[1];
+                const uint4 out = make_uint4(quant_pack4(v0.x, v0.y, s), quant_pack4(v0.z, v0.w, s),
+                                             quant_pack4(v1.x, v1.y, s), quant_pack4(v1.z, v1.w, s));
+                *reinterpret_cast<uint4 *>(P.xa + ((size_t)(mt * C4 + c) * 2 + i) * 1024 +
+                                           lane * 16) = out;
+            }
+        }
+    } else {
+        for (int c = cb * kImageColumns + wave; c < C4 && c < (cb + 1) * kImageColumns; c += 4) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                *reinterpret_cast<uint4 *>(P.xa + ((size_t)(mt * C4 + c) * 4 + i) * 1024 +
+                                           lane * 16) =
+                    *reinterpret_cast<const uint4 *>(xr + c * 128 + 32 * i + 8 * kb);
+        }
+    }
+}
+
+int image_units(int M, int K) { return ((M + 15) / 16) * ((K / 128 + kImageColumns - 1) / kImageColumns); }
+
+int launch_operand_images(const GroupPhase *tab, const uint16_t *jobs, int njobs,
+                          const uint16_t *img_units, int nimg, int M, hipStream_t st) {
+    if (njobs <= 0 || nimg <= 0) return NVQ_OK;
+    hipLaunchKernelGGL(token_scale_group_kernel, dim3(njobs * M), dim3(kQuantThreads), 0, st, tab,
+                       jobs, M);
+    NVQ_HIP_TRY(hipGetLastError());
+    hipLaunchKernelGGL(operand_image_group_kernel, dim3(nimg), dim3(kQuantThreads), 0, st, tab,
+                       img_units, M);
+    NVQ_HIP_TRY(hipGetLastError());
+    return NVQ_OK;
+}
+
 int launch_quant_act_group(const GroupPhase *tab, const uint16_t *jobs, int njobs, int M,
-                           bool image, hipStream_t st) {
+                           hipStream_t st) {
     if (njobs <= 0) return NVQ_OK;
-    if (image)
-        hipLaunchKernelGGL(operand_image_group_kernel, dim3(njobs * M), dim3(kQuantThreads), 0, st,
-                           tab, jobs, M);
-    else
-        hipLaunchKernelGGL(quant_act_group_kernel, dim3(njobs * M), dim3(kQuantThreads), 0, st,
-                           tab, jobs, M);
+    hipLaunchKernelGGL(quant_act_group_kernel, dim3(njobs * M), dim3(kQuantThreads), 0, st, tab, jobs,
+                       M);
     NVQ_HIP_TRY(hipGetLastError());
     return NVQ_OK;
 }
