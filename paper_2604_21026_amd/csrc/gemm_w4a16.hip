@@ -8,23 +8,24 @@
 //
 // v_mfma_f32_32x32x16_bf16: operand A = 32 tokens x 16 inputs, operand B = 16
 // inputs x 32 weight rows, lane (i, b) = (lane % 32, lane / 32) supplies eight
-// inputs of token / row i.  Which eight is free as long as both operands agree:
-// for step s of a quantisation group lane (i, b) takes inputs 16 s + 8 b ..
-// + 7, that is 16 contiguous bytes of the activations and, of the group's 16
-// packed bytes, the low (s = 0) or high (s = 1) nibbles of bytes 8 b .. 8 b + 7:
-// one 8-byte load per lane, row and group.  Nibble -> fp32 (byte convert),
-// one FMA with the group's scale ((n - 8) * s is exact), round to bf16.
+// inputs of token / row i.  Which eight is free as long as both operands agree,
+// and since the scale is folded into the bf16 weight an MFMA may mix two
+// quantisation groups: the kernel advances by pairs of groups (64 inputs), lane
+// (i, b) takes its eight inputs from group 2 p + b of pair p, inputs 8 s .. 8 s
+// + 7 of that group in MFMA step s = 0..3.  For the activations that is 16
+// contiguous bytes; for the weights the lane loads the group's 16 packed bytes
+// once (adjacent to the other lane's group: 32 contiguous bytes per row) and
+// step s uses the low (s < 2) or high nibbles of bytes 8 (s % 2) .. + 7.
+// Nibble -> fp32 (byte convert), one FMA with the group's scale ((n - 8) * s is
+// exact), round to bf16.
 //
 // A workgroup of four waves owns 256 tokens x 128 weight rows, a wave 128 x 64
 // (4 x 2 MFMA tiles, 128 accumulator registers); a wave's dequantised operand
-// serves its four token tiles.  Activations and packed weights pass through
-// LDS (rows padded to 80 bytes: 16 lanes reading 16 bytes each then cover all
-// 64 banks), both double buffered, the activations group by group, the weights
-// four groups at a time (64 contiguous bytes per row and load).  A wave holds
-// the operands of the group it multiplies in registers and, while the matrix
-// core works, reads the next group's activations from LDS and dequantises the
-// next group's weights; memory is asked for a group's activations three groups
-// ahead.  One barrier per group of 32 inputs.
+// serves its four token tiles.  Activations pass through LDS (rows of 128 bytes
+// padded to 144: 16 lanes reading 16 bytes each then cover all 64 banks),
+// double buffered, eight neighbouring threads staging a token's 128 bytes; one
+// barrier per pair of groups.  The next pair's activations and packed weights
+// are requested before the current pair is multiplied.
 #include "nvq_internal.h"
 
 namespace nvq {
@@ -39,8 +40,7 @@ typedef float floatx2 __attribute__((ext_vector_type(2)));
 constexpr int kGemmTokens = 256;  // per workgroup
 constexpr int kGemmRows = 128;
 constexpr int kGemmThreads = 256;
-constexpr int kXRowBytes = 80;  // 32 bf16 + 16 bytes of padding
-constexpr int kWRowBytes = 80;  // four groups of 16 packed bytes + 16 bytes of padding
+constexpr int kXRowBytes = 144;  // 64 bf16 + 16 bytes of padding
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
     const floatx2 f = {a, b};
@@ -64,39 +64,34 @@ __device__ __forceinline__ bf16x8 dequant8(uint32_t n0, uint32_t n1, float s, fl
 template <bool F32>
 __global__ __launch_bounds__(kGemmThreads) void gemm_w4a16_kernel(
     const uint4 *__restrict__ qw, const uint16_t *__restrict__ sc, int N, int G,
-    const uint4 *__restrict__ x, int M, void *__restrict__ y, int scales_by_four) {
+    const uint4 *__restrict__ x, int M, void *__restrict__ y) {
     __shared__ __attribute__((aligned(16))) unsigned char xs[2][kGemmTokens * kXRowBytes];
-    __shared__ __attribute__((aligned(16))) unsigned char wq[2][kGemmRows * kWRowBytes];
-    __shared__ __attribute__((aligned(8))) uint16_t ws[2][kGemmRows][4];
 
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int li = lane & 31, lb = lane >> 5;
     const int m0 = blockIdx.y * kGemmTokens, n0 = blockIdx.x * kGemmRows;
+    const int P = (G + 1) >> 1;  // pairs of groups
 
-    // Staging, activations: four neighbouring threads copy the 64 bytes of a
-    // token and group (one request to the cache per token and load), thread t
-    // those of tokens m0 + t / 4 + 64 i (the last token again past the end: those
-    // results are not stored).
-    const uint4 *xrow[4];
+    // Staging: eight neighbouring threads copy the 128 bytes of a token and
+    // pair (one cache line), thread t those of tokens m0 + t / 8 + 32 i (the
+    // last token again past the end: those results are not stored).
+    const uint4 *xrow[8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int m = m0 + (t >> 2) + 64 * i;
-        xrow[i] = x + (size_t)(m < M ? m : M - 1) * (size_t)(G * 4) + (t & 3);
+    for (int i = 0; i < 8; ++i) {
+        const int m = m0 + (t >> 3) + 32 * i;
+        xrow[i] = x + (size_t)(m < M ? m : M - 1) * (size_t)(G * 4);
     }
-    // Staging, weights: four groups (128 inputs) at a time, so that four
-    // neighbouring threads copy 64 contiguous bytes of a row (a load per lane,
-    // row and group asks the cache for a line per 8 bytes and was what bound the
-    // kernel); thread t the 16 bytes of group 4 j + t % 4 of rows t / 4 and
-    // t / 4 + 64, and thread t < 128 the four scales of row t.
-    const uint4 *wrow[2];
+    // The lane's weight rows, one per row tile (the last row again past the end).
+    const uint4 *qrow[2];
+    const uint16_t *srow[2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int n = n0 + (t >> 2) + 64 * i;
-        wrow[i] = qw + (size_t)(n < N ? n : N - 1) * (size_t)G;
+    for (int rt = 0; rt < 2; ++rt) {
+        const int n = n0 + wn * 64 + rt * 32 + li;
+        const int nc = n < N ? n : N - 1;
+        qrow[rt] = qw + (size_t)nc * (size_t)G;
+        srow[rt] = sc + (size_t)nc * (size_t)G;
     }
-    const int ns = n0 + (t & 127);
-    const uint16_t *srow = sc + (size_t)(ns < N ? ns : N - 1) * (size_t)G;
 
     floatx16 acc[4][2];
 #pragma unroll
@@ -106,137 +101,94 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_w4a16_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[tt][rt][r] = 0.0f;
 
-    // In flight: the activations of the group after next and the weights of the
-    // four groups after the next four, in registers until they are staged.
-    uint4 xn0, xn1, xn2, xn3, wq0, wq1;
-    uint2 wsc;
-#define NVQ_REQUEST_X(g_)          \
-    do {                           \
-        xn0 = xrow[0][4 * (g_)];   \
-        xn1 = xrow[1][4 * (g_)];   \
-        xn2 = xrow[2][4 * (g_)];   \
-        xn3 = xrow[3][4 * (g_)];   \
+    // In flight between pairs: the activations and the packed weights of the
+    // next pair.  An odd number of groups: the missing group of the last pair is
+    // the last group again, with scale 0 (all its weights 0).
+    uint4 xn0, xn1, xn2, xn3, xn4, xn5, xn6, xn7, wn0, wn1;
+    uint32_t hn0, hn1;
+#define NVQ_REQUEST(p_)                                                              \
+    do {                                                                             \
+        {                                                                            \
+            const int gx_ = 2 * (p_) + ((t >> 2) & 1);                               \
+            const int cx_ = 4 * (gx_ < G ? gx_ : G - 1) + (t & 3);                   \
+            xn0 = xrow[0][cx_];                                                      \
+            xn1 = xrow[1][cx_];                                                      \
+            xn2 = xrow[2][cx_];                                                      \
+            xn3 = xrow[3][cx_];                                                      \
+            xn4 = xrow[4][cx_];                                                      \
+            xn5 = xrow[5][cx_];                                                      \
+            xn6 = xrow[6][cx_];                                                      \
+            xn7 = xrow[7][cx_];                                                      \
+        }                                                                            \
+        const int gw_ = 2 * (p_) + lb;                                               \
+        const int gc_ = gw_ < G ? gw_ : G - 1;                                       \
+        wn0 = qrow[0][gc_];                                                          \
+        wn1 = qrow[1][gc_];                                                          \
+        hn0 = gw_ < G ? (uint32_t)srow[0][gc_] : 0u;                                 \
+        hn1 = gw_ < G ? (uint32_t)srow[1][gc_] : 0u;                                 \
     } while (0)
 #define NVQ_STAGE_X(buf_)                                                            \
     do {                                                                             \
-        unsigned char *dst_ = &xs[(buf_)][(t >> 2) * kXRowBytes + 16 * (t & 3)];     \
+        unsigned char *dst_ = &xs[(buf_)][(t >> 3) * kXRowBytes + 16 * (t & 7)];     \
         *reinterpret_cast<uint4 *>(dst_) = xn0;                                      \
-        *reinterpret_cast<uint4 *>(dst_ + 64 * kXRowBytes) = xn1;                    \
-        *reinterpret_cast<uint4 *>(dst_ + 128 * kXRowBytes) = xn2;                   \
-        *reinterpret_cast<uint4 *>(dst_ + 192 * kXRowBytes) = xn3;                   \
-    } while (0)
-    // groups past the end are clamped to the last one (their products are not formed)
-#define NVQ_REQUEST_W(j_)                                                            \
-    do {                                                                             \
-        const int gq_ = 4 * (j_) + (t & 3) < G ? 4 * (j_) + (t & 3) : G - 1;         \
-        wq0 = wrow[0][gq_];                                                          \
-        wq1 = wrow[1][gq_];                                                          \
-        if (t < 128) {                                                               \
-            if (scales_by_four) {                                                    \
-                const int gs_ = 4 * (j_) < G ? 4 * (j_) : G - 4;                     \
-                wsc = *reinterpret_cast<const uint2 *>(srow + gs_);                  \
-            } else {                                                                 \
-                uint32_t h_[4];                                                      \
-                _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_)                     \
-                    h_[i_] = srow[4 * (j_) + i_ < G ? 4 * (j_) + i_ : G - 1];        \
-                wsc = make_uint2(h_[0] | (h_[1] << 16), h_[2] | (h_[3] << 16));      \
-            }                                                                        \
-        }                                                                            \
-    } while (0)
-#define NVQ_STAGE_W(buf_)                                                            \
-    do {                                                                             \
-        unsigned char *dst_ = &wq[(buf_)][(t >> 2) * kWRowBytes + 16 * (t & 3)];     \
-        *reinterpret_cast<uint4 *>(dst_) = wq0;                                      \
-        *reinterpret_cast<uint4 *>(dst_ + 64 * kWRowBytes) = wq1;                    \
-        if (t < 128) *reinterpret_cast<uint2 *>(&ws[(buf_)][t][0]) = wsc;            \
-    } while (0)
-    // operand A of one group: [token tile][step], from LDS buffer buf_
-#define NVQ_READ_A(a_, buf_)                                                                       \
-    do {                                                                                           \
-        _Pragma("unroll") for (int tt = 0; tt < 4; ++tt) {                                         \
-            const unsigned char *row_ =                                                            \
-                &xs[(buf_)][(wm * 128 + tt * 32 + li) * kXRowBytes + 16 * lb];                     \
-            a_[tt][0] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(row_));        \
-            a_[tt][1] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(row_ + 32));   \
-        }                                                                                          \
-    } while (0)
-    // operand B of group g_: [row tile][step], from the staged words and scales
-#define NVQ_DEQUANT(b_, g_)                                                                        \
-    do {                                                                                           \
-        const int wb_ = ((g_) >> 2) & 1, gi_ = (g_) & 3;                                           \
-        _Pragma("unroll") for (int rt = 0; rt < 2; ++rt) {                                         \
-            const int r_ = wn * 64 + rt * 32 + li;                                                 \
-            const uint2 w_ =                                                                       \
-                *reinterpret_cast<const uint2 *>(&wq[wb_][r_ * kWRowBytes + 16 * gi_ + 8 * lb]);   \
-            const float s_ = half_bits_to_float(ws[wb_][r_][gi_]);                                 \
-            const float m_ = -8.0f * s_;                                                           \
-            b_[rt][0] = dequant8(w_.x & 0x0f0f0f0fu, w_.y & 0x0f0f0f0fu, s_, m_);                  \
-            b_[rt][1] = dequant8((w_.x >> 4) & 0x0f0f0f0fu, (w_.y >> 4) & 0x0f0f0f0fu, s_, m_);    \
-        }                                                                                          \
+        *reinterpret_cast<uint4 *>(dst_ + 32 * kXRowBytes) = xn1;                    \
+        *reinterpret_cast<uint4 *>(dst_ + 64 * kXRowBytes) = xn2;                    \
+        *reinterpret_cast<uint4 *>(dst_ + 96 * kXRowBytes) = xn3;                    \
+        *reinterpret_cast<uint4 *>(dst_ + 128 * kXRowBytes) = xn4;                   \
+        *reinterpret_cast<uint4 *>(dst_ + 160 * kXRowBytes) = xn5;                   \
+        *reinterpret_cast<uint4 *>(dst_ + 192 * kXRowBytes) = xn6;                   \
+        *reinterpret_cast<uint4 *>(dst_ + 224 * kXRowBytes) = xn7;                   \
     } while (0)
 
-    // One group of 32 inputs.  The MFMAs of group g take their operands from
-    // registers (ac_, bc_); while the matrix core works, the wave fetches the
-    // activations of group g + 1 from LDS (an_) and dequantises its weights
-    // (bn_).  Before that the activations of group g + 2 go to the LDS buffer
-    // that group g's were read from during the group before (buffer g % 2 holds
-    // group g) and memory is asked for group g + 3; every fourth group the
-    // weights of the next four groups are staged the same way (buffer
-    // (g / 4) % 2; group g + 1's were staged at least one group ago).
-#define NVQ_GROUP(g_, ac_, bc_, an_, bn_)                                                          \
-    do {                                                                                           \
-        const int cur_ = (g_) & 1;                                                                 \
-        NVQ_STAGE_X(cur_);                                                                         \
-        {                                                                                          \
-            const int g3_ = (g_) + 3 < G ? (g_) + 3 : G - 1;                                       \
-            NVQ_REQUEST_X(g3_);                                                                    \
-        }                                                                                          \
-        if (((g_) & 3) == 0) {                                                                     \
-            NVQ_STAGE_W((((g_) >> 2) + 1) & 1);                                                    \
-            NVQ_REQUEST_W(((g_) >> 2) + 2);                                                        \
-        }                                                                                          \
-        /* the two MFMAs into one accumulator are eight MFMAs apart */                            \
-        _Pragma("unroll") for (int st = 0; st < 2; ++st)                                           \
-            _Pragma("unroll") for (int tt = 0; tt < 4; ++tt)                                       \
-                _Pragma("unroll") for (int rt = 0; rt < 2; ++rt)                                   \
-            acc[tt][rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ac_[tt][st], bc_[rt][st],        \
-                                                                  acc[tt][rt], 0, 0, 0);           \
-        NVQ_READ_A(an_, cur_ ^ 1);                                                                 \
-        NVQ_DEQUANT(bn_, ((g_) + 1 < G ? (g_) + 1 : G - 1));                                       \
-        __syncthreads();                                                                           \
-    } while (0)
+    NVQ_REQUEST(0);
+    NVQ_STAGE_X(0);
+    uint4 wc0 = wn0, wc1 = wn1;
+    uint32_t hc0 = hn0, hc1 = hn1;
+    NVQ_REQUEST((P > 1 ? 1 : 0));
+    __syncthreads();
 
-    bf16x8 aA[4][2], aB[4][2], bA[2][2], bB[2][2];
-    {
-        const int g1 = G > 1 ? 1 : G - 1, g2 = G > 2 ? 2 : G - 1;
-        NVQ_REQUEST_X(0);
-        NVQ_REQUEST_W(0);
-        NVQ_STAGE_X(0);
-        NVQ_STAGE_W(0);
-        NVQ_REQUEST_X(g1);
-        NVQ_REQUEST_W(1);
-        __syncthreads();
-        NVQ_READ_A(aA, 0);
-        NVQ_DEQUANT(bA, 0);
-        NVQ_STAGE_X(1);
-        NVQ_REQUEST_X(g2);
+    for (int p = 0; p < P; ++p) {
+        const int cur = p & 1;
+        // next pair: stage what was requested during the pair before, ask for the one after
+        const uint4 wnext0 = wn0, wnext1 = wn1;
+        const uint32_t hnext0 = hn0, hnext1 = hn1;
+        NVQ_STAGE_X(cur ^ 1);  // everyone left this buffer before the last barrier
+        {
+            const int p2 = p + 2 < P ? p + 2 : P - 1;
+            NVQ_REQUEST(p2);
+        }
+        const uint4 wc[2] = {wc0, wc1};
+        const float sv[2] = {half_bits_to_float((uint16_t)hc0), half_bits_to_float((uint16_t)hc1)};
+        const float m8[2] = {-8.0f * sv[0], -8.0f * sv[1]};
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+            bf16x8 b[2];
+#pragma unroll
+            for (int rt = 0; rt < 2; ++rt) {
+                const uint32_t d0 = (st & 1) ? wc[rt].z : wc[rt].x, d1 = (st & 1) ? wc[rt].w : wc[rt].y;
+                b[rt] = (st < 2) ? dequant8(d0 & 0x0f0f0f0fu, d1 & 0x0f0f0f0fu, sv[rt], m8[rt])
+                                 : dequant8((d0 >> 4) & 0x0f0f0f0fu, (d1 >> 4) & 0x0f0f0f0fu, sv[rt],
+                                            m8[rt]);
+            }
+#pragma unroll
+            for (int tt = 0; tt < 4; ++tt) {
+                const unsigned char *row =
+                    &xs[cur][(wm * 128 + tt * 32 + li) * kXRowBytes + 64 * lb + 16 * st];
+                const bf16x8 a = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(row));
+#pragma unroll
+                for (int rt = 0; rt < 2; ++rt)
+                    acc[tt][rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b[rt], acc[tt][rt], 0, 0, 0);
+            }
+        }
+        wc0 = wnext0;
+        wc1 = wnext1;
+        hc0 = hnext0;
+        hc1 = hnext1;
         __syncthreads();
     }
-    // here: aA, bA = group 0; LDS: activations of group 1, weights of groups
-    // 0..3; registers: activations of group 2, weights of groups 4..7
 
-    for (int g = 0; g < G; g += 2) {
-        NVQ_GROUP(g, aA, bA, aB, bB);
-        if (g + 1 < G) NVQ_GROUP(g + 1, aB, bB, aA, bA);
-    }
-
-#undef NVQ_GROUP
-#undef NVQ_DEQUANT
-#undef NVQ_READ_A
-#undef NVQ_REQUEST_X
-#undef NVQ_REQUEST_W
+#undef NVQ_REQUEST
 #undef NVQ_STAGE_X
-#undef NVQ_STAGE_W
 
     // result tile: lane (j, b) holds weight row j; register r holds token
     // 8 * (r / 4) + 4 * b + r % 4
@@ -280,15 +232,13 @@ extern "C" int nvq_gemm_w4a16(const uint8_t *qweight, const uint16_t *scales, in
         block(kGemmThreads);
     if (grid.y > 65535u) return NVQ_ERR_SHAPE;
     const uint4 *qw = reinterpret_cast<const uint4 *>(qweight);
-    // four scales of a row in one 8-byte load
-    const int by_four = (K % 128) == 0 && aligned(scales, 8) ? 1 : 0;
     const uint4 *x = reinterpret_cast<const uint4 *>(x_bf16);
     if (y_dtype == NVQ_F32)
         hipLaunchKernelGGL(gemm_w4a16_kernel<true>, grid, block, 0, (hipStream_t)stream, qw, scales,
-                           (int)N, (int)(K / 32), x, (int)M, y, by_four);
+                           (int)N, (int)(K / 32), x, (int)M, y);
     else
         hipLaunchKernelGGL(gemm_w4a16_kernel<false>, grid, block, 0, (hipStream_t)stream, qw, scales,
-                           (int)N, (int)(K / 32), x, (int)M, y, by_four);
+                           (int)N, (int)(K / 32), x, (int)M, y);
     NVQ_HIP_TRY(hipGetLastError());
     return NVQ_OK;
 }
