@@ -689,8 +689,10 @@ def test_chain_of_blocks_with_transforms_in_one_launch():
 # ---- prefill / large-batch product on the matrix cores --------------------------------
 # Shapes: one tile, ragged tokens and rows inside a 256 x 128 workgroup tile and inside the
 # 32 x 32 MFMA tiles, several workgroups in both directions, K from one group to many.
+# The last two: many workgroups in both directions, ragged at both ends.
 @pytest.mark.parametrize("M,N,K", [(32, 32, 32), (256, 128, 64), (77, 45, 96), (300, 200, 256),
-                                   (513, 257, 2048), (1, 1, 32), (1024, 384, 4096)])
+                                   (513, 257, 2048), (1, 1, 32), (1024, 384, 4096),
+                                   (4096, 4096, 64), (4000, 4300, 96)])
 def test_gemm_w4a16_matches_oracle(M, N, K):
     say("gemm", M, N, K)
     _, q, s = packed(9100 + M + N, N, K)
