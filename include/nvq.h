@@ -192,7 +192,10 @@ typedef struct nvq_linear {
  *              bytes, 256-byte aligned; its contents are scratch.
  * At M = 1 the whole list runs as ONE persistent kernel that keeps streaming
  * the weights of coming phases while a phase is being set up (needs every
- * K <= 14336); otherwise one or two launches per phase are enqueued.  Both give the same results.
+ * K <= 14336).  At 2 <= M <= 32 with per-token activation scales and every
+ * K a multiple of 128, phases that do not depend on each other share two or
+ * three launches on the matrix cores.  Otherwise one or two launches per phase
+ * are enqueued.  All give the same results (up to the fp32 summation order).
  * nvq_decode_linears copies its phase table to the device on every call
  * (a blocking copy of a few KiB); a plan does that once.
  * nvq_decode_workspace_bytes returns 0 for invalid arguments.
