@@ -60,6 +60,10 @@ def lib():
         L.orc_silu_mul.argtypes = [vp, vp, i64, i64, vp]
         L.orc_silu_mul.restype = C.c_int
         L.orc_precision_from_scores.argtypes = [vp, i64, C.c_double, C.c_double, vp, vp]
+        L.orc_token_norms.argtypes = [vp, i64, vp, i64, i64, ci, vp]
+        L.orc_token_norms.restype = C.c_int
+        L.orc_mcap_scores.argtypes = [vp, vp, vp, i64, i64, vp]
+        L.orc_mcap_scores.restype = C.c_int
         for f in ("orc_pack_int4", "orc_dequant_int4", "orc_quant_act_i8", "orc_gemv_w4a8",
                   "orc_w4a8_acc_deferred", "orc_gemv_w4a16", "orc_decode_linears",
                   "orc_precision_from_scores"):
@@ -265,6 +269,33 @@ def decode_linears(layers, M, act_group=0):
     ss = np.empty(M * maxK // 32, np.float32)
     _chk(lib().orc_decode_linears(C.byref(arr), n, M, act_group, _p(sq), _p(ss)), "decode_linears")
     return ys
+
+
+def token_norms(a, b=None):
+    """Per-token Euclidean norm of the rows of a [M,Na] (float32, or uint16 = bf16 bits), with
+    the rows of b [M,Nb] appended if given (Algorithm 1's magnitudes).  -> float64 [M]."""
+    dt = 1 if np.asarray(a).dtype == np.uint16 else 0
+    a = _arr(a, np.uint16 if dt else np.float32, 2)
+    M, Na = a.shape
+    Nb = 0
+    if b is not None:
+        b = _arr(b, np.uint16 if dt else np.float32, 2)
+        Nb = b.shape[1]
+    out = np.empty(M, np.float64)
+    _chk(lib().orc_token_norms(_p(a), Na, _p(b) if b is not None else None, Nb, M, dt, _p(out)),
+         "token_norms")
+    return out
+
+
+def mcap_scores(a_attn, a_ffn, prompt_len):
+    """Algorithm 1's score line.  a_attn, a_ffn float64 [L,T], prompt_len ints summing to T."""
+    aa = _arr(a_attn, np.float64, 2)
+    af = _arr(a_ffn, np.float64, 2)
+    pl = _arr(prompt_len, np.int64, 1)
+    s = np.empty(aa.shape[0], np.float64)
+    _chk(lib().orc_mcap_scores(_p(aa), _p(af), _p(pl), pl.shape[0], aa.shape[0], _p(s)),
+         "mcap_scores")
+    return s
 
 
 def precision_from_scores(scores, tau=0.7, eps=1e-12):

@@ -434,6 +434,63 @@ int orc_decode_linears(const orc_linear *L, int64_t n, int64_t M, int act_group,
     return ORC_OK;
 }
 
+/* ---------- activation magnitudes and scores (Algorithm 1) ----------------- */
+/* The two magnitudes Algorithm 1 takes per layer and token are Euclidean norms
+ * of output vectors: of the query and value projections side by side (the
+ * attention proxy) and of the feed-forward block's output.  out[m] =
+ * sqrt(sum_n a[m][n]^2 + sum_n b[m][n]^2); b may be NULL (Nb = 0).
+ * dtype 0: float32, 1: bf16 bits. */
+static double elem_at(const void *p, int dtype, int64_t i) {
+    return dtype == 0 ? (double)((const float *)p)[i]
+                      : (double)orc_bf16_to_float(((const uint16_t *)p)[i]);
+}
+int orc_token_norms(const void *a, int64_t Na, const void *b, int64_t Nb, int64_t M, int dtype,
+                    double *out) {
+    if (!a || !out || (Nb > 0 && !b)) return ORC_ERR_ARG;
+    if (Na <= 0 || Nb < 0 || M <= 0 || (dtype != 0 && dtype != 1)) return ORC_ERR_SHAPE;
+    for (int64_t m = 0; m < M; ++m) {
+        double sum = 0.0;
+        for (int64_t n = 0; n < Na; ++n) {
+            const double v = elem_at(a, dtype, m * Na + n);
+            sum += v * v;
+        }
+        for (int64_t n = 0; n < Nb; ++n) {
+            const double v = elem_at(b, dtype, m * Nb + n);
+            sum += v * v;
+        }
+        out[m] = sqrt(sum);
+    }
+    return ORC_OK;
+}
+
+/* The score line of Algorithm 1: per layer the mean over the prompts of the
+ * mean over a prompt's tokens of (attention proxy + feed-forward magnitude).
+ * a_attn, a_ffn: [L][T] with the tokens of the k prompts one after the other,
+ * T = sum of prompt_len. */
+int orc_mcap_scores(const double *a_attn, const double *a_ffn, const int64_t *prompt_len,
+                    int64_t k, int64_t L, double *s) {
+    if (!a_attn || !a_ffn || !prompt_len || !s) return ORC_ERR_ARG;
+    if (k <= 0 || L <= 0) return ORC_ERR_SHAPE;
+    int64_t T = 0;
+    for (int64_t j = 0; j < k; ++j) {
+        if (prompt_len[j] <= 0) return ORC_ERR_SHAPE;
+        T += prompt_len[j];
+    }
+    for (int64_t i = 0; i < L; ++i) {
+        double over_prompts = 0.0;
+        int64_t t0 = 0;
+        for (int64_t j = 0; j < k; ++j) {
+            double over_tokens = 0.0;
+            for (int64_t t = t0; t < t0 + prompt_len[j]; ++t)
+                over_tokens += a_attn[i * T + t] + a_ffn[i * T + t];
+            over_prompts += over_tokens / (double)prompt_len[j];
+            t0 += prompt_len[j];
+        }
+        s[i] = over_prompts / (double)k;
+    }
+    return ORC_OK;
+}
+
 /* ---------- routing rule (Algorithm 1, normalise + assign) ---------------- */
 /* scores s[L] -> out[L]: 1 = W4A16 (normalised score >= tau), 0 = W4A8.
  * If max - min < eps every normalised score is 0. */
