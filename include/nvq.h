@@ -309,6 +309,31 @@ int nvq_gemm_w4a16(const uint8_t *qweight, const uint16_t *scales, int64_t N, in
                    const uint16_t *x_bf16, int64_t M, void *y, int y_dtype, void *stream);
 
 /*
+ * Calibration statistics of the paper's Algorithm 1 (Monte Carlo activation
+ * profiling), run once per model over a few prompts, not per decoded token.
+ *
+ * nvq_token_norms -- the magnitude Algorithm 1 takes per layer and token:
+ * out[m] = sqrt(sum_n a[m][n]^2 + sum_n b[m][n]^2), the Euclidean norm of the
+ * rows of a and b side by side (query and value projection outputs for the
+ * attention proxy; the feed-forward output alone, b = NULL, Nb = 0, for the
+ * other).  a [M][Na], b [M][Nb]: device, f32 or bf16 (dtype, the y_dtype
+ * constants), e.g. the y buffers of a decode list; out: device, M floats.
+ * Sums in fp32.  Enqueues on `stream`.
+ *
+ * nvq_mcap_scores -- host code: the score line.  a_attn, a_ffn (host, [L][T]):
+ * the magnitudes of the L layers for the tokens of k prompts one after the
+ * other, prompt_len[j] tokens each (T their sum); scores[i] = mean over the
+ * prompts of the mean over a prompt's tokens of (a_attn + a_ffn).  Its output
+ * feeds nvq_precision_from_scores.
+ * Errors: NVQ_ERR_INVALID_ARG (null pointer, dtype), NVQ_ERR_SHAPE (sizes or a
+ * prompt length <= 0), NVQ_ERR_ALIGN, NVQ_ERR_HIP.
+ */
+int nvq_token_norms(const void *a, int Na, const void *b, int Nb, int M, int dtype, float *out,
+                    void *stream);
+int nvq_mcap_scores(const float *a_attn, const float *a_ffn, const int *prompt_len, int k, int L,
+                    double *scores);
+
+/*
  * nvq_precision_from_scores -- host helper: the normalise-and-assign tail of
  * the paper's Algorithm 1.  scores (host, L doubles) are min-max normalised;
  * if max - min < eps every normalised score is 0; out[i] = NVQ_W4A16 if the

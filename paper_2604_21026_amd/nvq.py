@@ -24,7 +24,7 @@ EXPORTS = (
     "nvq_gemv_w4a16", "nvq_gemv_w4a8", "nvq_decode_workspace_bytes", "nvq_decode_linears",
     "nvq_plan_create", "nvq_plan_run", "nvq_plan_info", "nvq_plan_status", "nvq_plan_trace",
     "nvq_plan_destroy", "nvq_plan_describe", "nvq_plan_describe_batches",
-    "nvq_dequant_bf16", "nvq_gemm_w4a16", "nvq_rms_norm_bf16", "nvq_silu_mul_bf16", "nvq_precision_from_scores", "nvq_stream_read", "nvq_stream_copy",
+    "nvq_dequant_bf16", "nvq_gemm_w4a16", "nvq_rms_norm_bf16", "nvq_silu_mul_bf16", "nvq_precision_from_scores", "nvq_token_norms", "nvq_mcap_scores", "nvq_stream_read", "nvq_stream_copy",
 )
 
 
@@ -82,6 +82,8 @@ def lib() -> C.CDLL:
     L.nvq_plan_describe_batches.argtypes = [vp, ci, ci, ci, ci, vp, ci]
     L.nvq_plan_destroy.restype = None
     L.nvq_precision_from_scores.argtypes = [vp, ci, C.c_double, C.c_double, vp]
+    L.nvq_token_norms.argtypes = [vp, ci, vp, ci, ci, ci, vp, vp]
+    L.nvq_mcap_scores.argtypes = [vp, vp, vp, ci, ci, vp]
     L.nvq_stream_read.argtypes = [vp, sz, vp, vp]
     L.nvq_stream_copy.argtypes = [vp, vp, sz, vp]
     for f in ("nvq_pack_int4", "nvq_quant_act_i8", "nvq_gemv_w4a16", "nvq_gemv_w4a8",
@@ -366,6 +368,34 @@ def decode_linears(entries: Sequence[dict], M: int, act_group: int = 0) -> Decod
     dl = DecodeList(entries, M, act_group)
     dl.run()
     return dl
+
+
+def token_norms(a: torch.Tensor, b: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Per-token Euclidean norm of the rows of a (and b side by side): f32 [M]."""
+    M, Na = a.shape
+    Nb = 0 if b is None else b.shape[1]
+    if b is not None and (b.shape[0] != M or b.dtype != a.dtype):
+        raise ValueError("b: shape or dtype mismatch")
+    out = torch.empty(M, dtype=torch.float32, device=a.device)
+    _check(lib().nvq_token_norms(_dev(a, a.dtype, "a"), Na,
+                                 _dev(b, a.dtype, "b") if b is not None else None, Nb, M,
+                                 _y_dtype(a.dtype), _dev(out, torch.float32, "out"), _stream()),
+           "nvq_token_norms")
+    return out
+
+
+def mcap_scores(a_attn, a_ffn, prompt_len: Sequence[int]):
+    """Algorithm 1's score line (host): a_attn, a_ffn float32 [L][T] -> list of L scores."""
+    import numpy as np
+    aa = np.ascontiguousarray(a_attn, dtype=np.float32)
+    af = np.ascontiguousarray(a_ffn, dtype=np.float32)
+    if aa.ndim != 2 or aa.shape != af.shape or sum(prompt_len) != aa.shape[1]:
+        raise ValueError("shape mismatch")
+    pl = (C.c_int * len(prompt_len))(*[int(v) for v in prompt_len])
+    out = (C.c_double * aa.shape[0])()
+    _check(lib().nvq_mcap_scores(aa.ctypes.data, af.ctypes.data, pl, len(prompt_len), aa.shape[0],
+                                 out), "nvq_mcap_scores")
+    return list(out)
 
 
 def precision_from_scores(scores: Sequence[float], tau: float = 0.7, eps: float = 1e-12):

@@ -88,6 +88,28 @@ def test_precision_from_scores_follows_the_papers_table():
     assert nvq.precision_from_scores([61.0, 101.5, 142.0], 0.5) == [0, 1, 1]
 
 
+def test_mcap_scores_follow_the_oracle():
+    import numpy as np
+    import oracle
+    rng = np.random.default_rng(11)
+    L, lens = 5, [3, 1, 7, 2]
+    attn = rng.random((L, sum(lens))).astype(np.float32) * 10
+    ffn = rng.random((L, sum(lens))).astype(np.float32) * 3
+    got = nvq.mcap_scores(attn, ffn, lens)
+    want = oracle.mcap_scores(attn.astype(np.float64), ffn.astype(np.float64), lens)
+    assert np.allclose(got, want, rtol=1e-14, atol=0)
+    lib = nvq.lib()
+    a = attn.ctypes.data
+    assert lib.nvq_mcap_scores(a, a, None, 1, 1, a) == 1
+    bad = (C.c_int * 2)(3, 0)
+    out = (C.c_double * 5)()
+    assert lib.nvq_mcap_scores(a, a, bad, 2, 5, out) == 2
+    assert lib.nvq_token_norms(None, 4, None, 0, 1, 0, a, None) == 1
+    assert lib.nvq_token_norms(a, 4, None, 3, 1, 0, a, None) == 1
+    assert lib.nvq_token_norms(a, 0, None, 0, 1, 0, a, None) == 2
+    assert lib.nvq_token_norms(a, 4, None, 0, 1, 9, a, None) == 1
+
+
 def test_binding_refuses_host_tensors():
     import torch
     with pytest.raises(ValueError):

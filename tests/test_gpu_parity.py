@@ -721,3 +721,22 @@ def test_gemm_w4a16_takes_every_code():
     y = nvq.gemm_w4a16(qd, sd, xh.to(DEV))
     torch.cuda.synchronize()
     assert np_ref.rel_l2(y.cpu().numpy(), want) < 1e-5
+
+
+# ---- calibration statistics (Algorithm 1) ----------------------------------------------
+@pytest.mark.parametrize("M,Na,Nb,bf16", [(1, 5, 0, False), (7, 4096, 1024, False),
+                                          (33, 4096, 0, True), (3, 1000, 37, True)])
+def test_token_norms_match_oracle(M, Na, Nb, bf16):
+    say("token norms", M, Na, Nb, bf16)
+    g = torch.Generator().manual_seed(9400 + M)
+    a = torch.randn((M, Na), generator=g) * 3
+    b = torch.randn((M, Nb), generator=g) if Nb else None
+    if bf16:
+        a = a.to(torch.bfloat16)
+        b = b.to(torch.bfloat16) if b is not None else None
+        want = oracle.token_norms(u16(a), u16(b) if b is not None else None)
+    else:
+        want = oracle.token_norms(a.numpy(), b.numpy() if b is not None else None)
+    got = nvq.token_norms(a.to(DEV), b.to(DEV) if b is not None else None)
+    torch.cuda.synchronize()
+    assert np.allclose(got.cpu().numpy(), want, rtol=2e-6, atol=0)
