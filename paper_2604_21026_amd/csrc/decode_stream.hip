@@ -554,6 +554,9 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
     const int gw = wg * kStreamWaves + w;
     if (threadIdx.x == 0) lds_write4(lds_addr(&sh.abort), 0u);
     trace_mark(trace, wg, w, lane, 0, 5);  // kernel entered
+#ifdef NVQ_TRACE_ENDS
+    if (trace && lane == 0) trace[nphase * kTraceSlots + 16 * (nwg + wg) + w] = wall_clock64();
+#endif
 
     // The streaming waves request their first chunks at once: weights depend on
     // nothing, so the ring fills while the prologue below prepares the images.
@@ -914,30 +917,48 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
             case 3: rows_in_registers(std::integral_constant<int, 3>()); break;
             case 4: rows_in_registers(std::integral_constant<int, 4>()); break;
             default: {
-                // longer rows: activations out of the image for every chunk
-                int i = 0;
-                int row = r0;
-                float sum = 0.0f;
-                const int nchunks = nrows * gpl;
-                for (int c = 0; c < nchunks; ++c) {
-                    u32x4_t x[4];
-                    x[2] = x[3] = u32x4_t{0, 0, 0, 0};
-                    uint32_t aux, sgbits = 0;
-                    bool ok;
-                    request_x(i, x, aux, sgbits, ok);
-                    uint32_t sbits;
-                    const uint4 wq = pop_chunk(sbits);  // its lgkmcnt(0) also covers the reads above
-                    // nothing below may be scheduled (or copied) before that wait
+                // longer rows: the first kHeldGpl groups of the lane stay in
+                // registers as above, the others come out of the image for every
+                // chunk (the registers of a wave hold no more)
+                constexpr int kHeldGpl = 3;
+                u32x4_t hx[kHeldGpl][4];
+                uint32_t haux[kHeldGpl], hsgb[kHeldGpl];
+                bool hok[kHeldGpl];
+#pragma unroll
+                for (int i = 0; i < kHeldGpl; ++i) {
+                    hx[i][2] = hx[i][3] = u32x4_t{0, 0, 0, 0};
+                    hsgb[i] = 0;
+                    request_x(i, hx[i], haux[i], hsgb[i], hok[i]);
+                }
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+                for (int i = 0; i < kHeldGpl; ++i)
                     asm volatile(""
-                                 : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(aux),
-                                   "+v"(sgbits));
-                    sum = chunk_term(sum, wq, sbits, x, aux, sgbits, ok);
-                    if (++i == gpl) {
-                        i = 0;
-                        finish_row(row, sum);
-                        sum = 0.0f;
-                        ++row;
+                                 : "+v"(hx[i][0]), "+v"(hx[i][1]), "+v"(hx[i][2]), "+v"(hx[i][3]),
+                                   "+v"(haux[i]), "+v"(hsgb[i]));
+                for (int row = r0; row < r1; ++row) {
+                    float sum = 0.0f;
+#pragma unroll
+                    for (int i = 0; i < kHeldGpl; ++i) {
+                        uint32_t sbits;
+                        const uint4 wq = pop_chunk(sbits);
+                        sum = chunk_term(sum, wq, sbits, hx[i], haux[i], hsgb[i], hok[i]);
                     }
+                    for (int i = kHeldGpl; i < gpl; ++i) {
+                        u32x4_t x[4];
+                        x[2] = x[3] = u32x4_t{0, 0, 0, 0};
+                        uint32_t aux, sgbits = 0;
+                        bool ok;
+                        request_x(i, x, aux, sgbits, ok);
+                        uint32_t sbits;
+                        const uint4 wq = pop_chunk(sbits);  // its lgkmcnt(0) also covers the reads above
+                        // nothing below may be scheduled (or copied) before that wait
+                        asm volatile(""
+                                     : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(aux),
+                                       "+v"(sgbits));
+                        sum = chunk_term(sum, wq, sbits, x, aux, sgbits, ok);
+                    }
+                    finish_row(row, sum);
                 }
             }
         }
@@ -960,6 +981,11 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
             }
         }
     }
+#ifdef NVQ_TRACE_ENDS
+    if (trace && lane == 0) {
+        trace[nphase * kTraceSlots + 16 * wg + w] = wall_clock64();
+    }
+#endif
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // no load may outlive the wave
 }
 
