@@ -434,13 +434,18 @@ __device__ __forceinline__ void image_build(const Writer &wr, CPhase &ph, Shared
     const uint4 *x = reinterpret_cast<const uint4 *>(ph.x);
     const uint4 *x2 = reinterpret_cast<const uint4 *>(ph.x2);
     uint4 xsh[kMaxXShare];
+    // the norm weights depend on nothing: they are requested with the input, not
+    // after the sum of squares has gone round the workgroup
+    uint4 gsh[kMaxXShare];
     float ss = 0.0f;
 #pragma unroll
     for (int k = 0; k < kMaxXShare; ++k) {
         const int j = w + k * kStreamWaves;
         const int idx = j * 64 + lane;
         xsh[k] = make_uint4(0, 0, 0, 0);
+        gsh[k] = make_uint4(0, 0, 0, 0);
         if (j < nxc && idx < K / 8) {
+            if (in_op == NVQ_IN_RMSNORM) gsh[k] = reinterpret_cast<const uint4 *>(ph.gamma)[idx];
             xsh[k] = x[idx];
             if (in_op == NVQ_IN_SILU_MUL) {
                 xsh[k] = silu_mul_bf16x8(xsh[k], x2[idx]);
@@ -467,12 +472,11 @@ __device__ __forceinline__ void image_build(const Writer &wr, CPhase &ph, Shared
             tot += __uint_as_float(a.w);
         }
         const float r = rms_scale(tot, K, ph.eps);
-        const uint4 *gamma = reinterpret_cast<const uint4 *>(ph.gamma);
 #pragma unroll
         for (int k = 0; k < kMaxXShare; ++k) {
             const int j = w + k * kStreamWaves;
             const int idx = j * 64 + lane;
-            if (j < nxc && idx < K / 8) xsh[k] = scale_bf16x8(xsh[k], r, gamma[idx]);
+            if (j < nxc && idx < K / 8) xsh[k] = scale_bf16x8(xsh[k], r, gsh[k]);
         }
     }
     float amax = 0.0f;
