@@ -755,8 +755,12 @@ extern "C" int nvq_plan_describe_batches(const nvq_linear *layers, int n, int M,
 
 extern "C" int nvq_plan_trace(nvq_plan *pl, uint64_t *buf, size_t bytes) {
     if (!pl) return NVQ_ERR_INVALID_ARG;
-    if (buf && (bytes < (size_t)pl->nphase * nvq::kStreamTraceSlots * 8 || !nvq::aligned(buf, 8)))
-        return NVQ_ERR_WORKSPACE;
+    size_t need = (size_t)pl->nphase * nvq::kStreamTraceSlots * 8;
+#ifdef NVQ_TRACE_ENDS
+    // working builds with per-wave entry and end times: 16 words per workgroup, twice
+    need += (size_t)32 * (pl->nwg > 0 ? pl->nwg : 0) * 8;
+#endif
+    if (buf && (bytes < need || !nvq::aligned(buf, 8))) return NVQ_ERR_WORKSPACE;
     pl->trace = reinterpret_cast<unsigned long long *>(buf);
     return NVQ_OK;
 }

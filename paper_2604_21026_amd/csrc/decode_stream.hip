@@ -77,7 +77,7 @@ constexpr int kXChunkElems = 512;          // bf16 values per input chunk
 constexpr int kMaxXShare = (kStreamMaxK / kXChunkElems + kStreamWaves - 1) / kStreamWaves;  // 4
 
 constexpr uint32_t kSpinLimit = 4u << 20;  // polls before a wait gives up (seconds)
-constexpr int kLookahead = 3;              // phases the loader wave may run ahead
+constexpr int kLookahead = 3;              // phases the loader wave may run ahead (6 and 12: no faster)
 
 // s_waitcnt immediate that waits for vmcnt <= n only (gfx9 encoding:
 // vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] at [15:14]).
@@ -753,6 +753,8 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
     };
 
     bool aborted = false;
+    uint32_t ready_seen = 0;     // sh.img_ready as requested on entering an independent phase
+    bool ready_pending = false;  // ... and not yet looked at
     for (int p = 0; p < nphase && !aborted; ++p) {
         CPhase &ph = tab[p];
         const int G = ph.G;
@@ -780,25 +782,15 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
             image_build<PER_GROUP>(wr, ph, sh, w, lane, wg == 0);
             trace_mark(trace, wg, w, lane, p, 2);
             lds_barrier();  // the image is complete
+            ready_pending = false;
         } else {
-            // ---- independent phase: the loader wave announces the image
+            // ---- independent phase: the loader wave announces the image.  The word is
+            // ---- only requested here; it is looked at after the wait that the wave's
+            // ---- first reads of the image need anyway (LDS serves a wave's requests
+            // ---- in order, so reads issued after it saw the image if it says so)
             trace_mark(trace, wg, w, lane, p, 1);
-            uint32_t spins = 0;
-            while (lds_read4_uniform(ready_a) < (uint32_t)(p + 1)) {
-                if (lds_read4_uniform(abort_a) || ++spins > kSpinLimit) {
-                    aborted = true;
-                    break;
-                }
-                __builtin_amdgcn_s_sleep(1);
-            }
-            if (aborted) {
-                if (lane == 0) {
-                    lds_write4(abort_a, 1u);
-                    __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                }
-                break;
-            }
-            trace_mark(trace, wg, w, lane, p, 2);
+            asm volatile("ds_read_b32 %0, %1" : "=v"(ready_seen) : "v"(ready_a) : "memory");
+            ready_pending = true;
         }
         trace_mark(trace, wg, w, lane, p, 6);
         // Waves w, w + 4, w + 8 share a SIMD; rotate their priorities so that none
@@ -814,9 +806,35 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
         int r0, nrows;
         stream_wave_rows(ph.rows_base, ph.rows_extra, ph.rows_rot, gw, nwg * kStreamWaves, r0, nrows);
         const int r1 = r0 + nrows;
-        const float xs =
-            (w4a8 && !PER_GROUP) ? __uint_as_float(lds_read4(img + L.stok)) : 1.0f;
+        uint32_t xs_bits = 0x3f800000u;  // per-token activation scale (W4A8), else 1
         const uint32_t plane = (uint32_t)G * 16u;
+        // Requested with the first activations, valid after the wait that follows them.
+        auto request_xs = [&]() {
+            if (w4a8 && !PER_GROUP)
+                asm volatile("ds_read_b32 %0, %1" : "=v"(xs_bits) : "v"(img + L.stok) : "memory");
+        };
+        // After that wait: did the word requested on entering the phase say that the
+        // image is there?  If not, waits for it (bounded) and returns false once: the
+        // reads have to be issued again.  On abort `aborted` is set (and true returned).
+        auto image_ready = [&]() -> bool {
+            if (!ready_pending) return true;
+            ready_pending = false;
+            if ((uint32_t)__builtin_amdgcn_readfirstlane((int)ready_seen) >= (uint32_t)(p + 1))
+                return true;
+            uint32_t spins = 0;
+            while (lds_read4_uniform(ready_a) < (uint32_t)(p + 1)) {
+                if (lds_read4_uniform(abort_a) || ++spins > kSpinLimit) {
+                    aborted = true;
+                    if (lane == 0) {
+                        lds_write4(abort_a, 1u);
+                        __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                    return true;
+                }
+                __builtin_amdgcn_s_sleep(1);
+            }
+            return false;
+        };
         float yv = 0.0f;  // results of up to 64 rows, one per lane, until they are stored
 
         // The lane's activations of group g = i * 64 + lane (clamped to a valid group)
@@ -864,7 +882,7 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
                 float,
                 __builtin_amdgcn_readlane(__builtin_bit_cast(int, wave_sum_to_lane63(sum)), 63));
             const int k = row - r0;
-            if (lane == (k & 63)) yv = tot * xs;
+            if (lane == (k & 63)) yv = tot * __uint_as_float(xs_bits);
             if ((k & 63) == 63 || row == r1 - 1) {
                 const int r = row - (k & 63) + lane;
                 if (r <= row) {
@@ -892,18 +910,24 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
             u32x4_t x[GPL][4];
             uint32_t aux[GPL], sgb[GPL];
             bool ok[GPL];
+            do {
+                request_xs();
 #pragma unroll
-            for (int i = 0; i < GPL; ++i) {
-                x[i][2] = x[i][3] = u32x4_t{0, 0, 0, 0};
-                sgb[i] = 0;
-                request_x(i, x[i], aux[i], sgb[i], ok[i]);
-            }
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                for (int i = 0; i < GPL; ++i) {
+                    x[i][2] = x[i][3] = u32x4_t{0, 0, 0, 0};
+                    sgb[i] = 0;
+                    request_x(i, x[i], aux[i], sgb[i], ok[i]);
+                }
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                asm volatile("" : "+v"(xs_bits), "+v"(ready_seen));
 #pragma unroll
-            for (int i = 0; i < GPL; ++i)  // nothing may be scheduled (or copied) before that wait
-                asm volatile(""
-                             : "+v"(x[i][0]), "+v"(x[i][1]), "+v"(x[i][2]), "+v"(x[i][3]),
-                               "+v"(aux[i]), "+v"(sgb[i]));
+                for (int i = 0; i < GPL; ++i)  // nothing may be scheduled (or copied) before that wait
+                    asm volatile(""
+                                 : "+v"(x[i][0]), "+v"(x[i][1]), "+v"(x[i][2]), "+v"(x[i][3]),
+                                   "+v"(aux[i]), "+v"(sgb[i]));
+            } while (!image_ready());
+            if (ph.wait_phase < 0) trace_mark(trace, wg, w, lane, p, 2);
+            if (aborted) return;
             for (int row = r0; row < r0 + nrows; ++row) {
                 float sum = 0.0f;
 #pragma unroll
@@ -915,7 +939,8 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
                 finish_row(row, sum);
             }
         };
-        switch (gpl) {
+        // (a wave without rows in this phase never looks at the image)
+        if (nrows > 0) switch (gpl) {
             case 1: rows_in_registers(std::integral_constant<int, 1>()); break;
             case 2: rows_in_registers(std::integral_constant<int, 2>()); break;
             case 3: rows_in_registers(std::integral_constant<int, 3>()); break;
@@ -928,18 +953,24 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
                 u32x4_t hx[kHeldGpl][4];
                 uint32_t haux[kHeldGpl], hsgb[kHeldGpl];
                 bool hok[kHeldGpl];
+                do {
+                    request_xs();
 #pragma unroll
-                for (int i = 0; i < kHeldGpl; ++i) {
-                    hx[i][2] = hx[i][3] = u32x4_t{0, 0, 0, 0};
-                    hsgb[i] = 0;
-                    request_x(i, hx[i], haux[i], hsgb[i], hok[i]);
-                }
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                    for (int i = 0; i < kHeldGpl; ++i) {
+                        hx[i][2] = hx[i][3] = u32x4_t{0, 0, 0, 0};
+                        hsgb[i] = 0;
+                        request_x(i, hx[i], haux[i], hsgb[i], hok[i]);
+                    }
+                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                    asm volatile("" : "+v"(xs_bits), "+v"(ready_seen));
 #pragma unroll
-                for (int i = 0; i < kHeldGpl; ++i)
-                    asm volatile(""
-                                 : "+v"(hx[i][0]), "+v"(hx[i][1]), "+v"(hx[i][2]), "+v"(hx[i][3]),
-                                   "+v"(haux[i]), "+v"(hsgb[i]));
+                    for (int i = 0; i < kHeldGpl; ++i)
+                        asm volatile(""
+                                     : "+v"(hx[i][0]), "+v"(hx[i][1]), "+v"(hx[i][2]),
+                                       "+v"(hx[i][3]), "+v"(haux[i]), "+v"(hsgb[i]));
+                } while (!image_ready());
+                if (ph.wait_phase < 0) trace_mark(trace, wg, w, lane, p, 2);
+                if (aborted) break;
                 for (int row = r0; row < r1; ++row) {
                     float sum = 0.0f;
 #pragma unroll
@@ -966,6 +997,7 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
                 }
             }
         }
+        if (aborted) break;
         // this wave no longer reads the phase's image
         if (lane == 0) lds_write4(progress_a + w * 4, (uint32_t)(p + 1));
         trace_mark(trace, wg, w, lane, p, 7);
