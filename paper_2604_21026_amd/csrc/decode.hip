@@ -458,11 +458,18 @@ std::vector<StreamPhase> stream_table(const nvq_linear *L, const std::vector<Pha
         sp.G = G;
         sp.gpl = (G + 63) / 64;
         sp.precision = e0.precision;
-        sp.rows_base = rows / waves;
-        sp.rows_extra = rows - sp.rows_base * waves;
+        sp.row_unit = 1;
+        if (G == kStreamPairG && act_group != 32) {
+            bool even = true;
+            for (int k = 0; k < ph.count; ++k) even = even && L[ph.first + k].N % 2 == 0;
+            if (even) sp.row_unit = 2;
+        }
+        const int units = rows / sp.row_unit;
+        sp.rows_base = units / waves;
+        sp.rows_extra = units - sp.rows_base * waves;
         sp.rows_rot = lightest_window(extra_bytes, sp.rows_extra);
         for (int j = 0; j < sp.rows_extra; ++j)
-            extra_bytes[(size_t)(sp.rows_rot + j) % waves] += (uint64_t)G * 18;
+            extra_bytes[(size_t)(sp.rows_rot + j) % waves] += (uint64_t)G * 18 * sp.row_unit;
         sp.wait_phase = -1;
         sp.publish = 0;
         sp.img = nullptr;
@@ -528,7 +535,7 @@ __global__ void fill_u32_kernel(uint32_t *p, int n, uint32_t v) {
 }  // namespace nvq
 
 namespace nvq {
-constexpr int kDescribeWords = 12;  // words per phase written by nvq_plan_describe
+constexpr int kDescribeWords = 13;  // words per phase written by nvq_plan_describe
 }
 
 struct nvq_plan {
@@ -543,6 +550,7 @@ struct nvq_plan {
     std::vector<nvq::GroupBatch> batches;  // grouped small-batch launches (empty: not used)
     bool ring;         // grouped launches use the persistent ring kernel
     uint32_t runs;     // walks issued so far (advances the flag base)
+    bool pairs;        // some phase of the streaming table deals its rows in pairs
     unsigned long long *trace;  // device buffer for per-phase timestamps, or nullptr
 };
 
@@ -573,6 +581,7 @@ extern "C" int nvq_plan_create(const nvq_linear *layers, int n, int M, int act_g
     pl->M = M;
     pl->act_group = act_group;
     pl->runs = 0;
+    pl->pairs = false;
     pl->trace = nullptr;
     pl->nwg = 0;
     pl->nphase = 0;
@@ -586,6 +595,7 @@ extern "C" int nvq_plan_create(const nvq_linear *layers, int n, int M, int act_g
         stream_table(pl->layers.data(), pl->phases, M, act_group, nwg,
                      (flags & NVQ_PLAN_ORDERED) != 0, ws.images, &nimages);
     if (!tab.empty()) {
+        for (const StreamPhase &sp : tab) pl->pairs = pl->pairs || sp.row_unit == 2;
         // pageable source: the copy has left the host buffer when the call returns
         hipError_t e = hipMemcpyAsync(ws.tab, tab.data(), tab.size() * sizeof(StreamPhase),
                                       hipMemcpyHostToDevice, st);
@@ -649,8 +659,9 @@ extern "C" int nvq_plan_run(nvq_plan *pl, void *stream) {
     if (pl->nwg > 0) {
         const uint32_t base = pl->runs * (uint32_t)(pl->nphase + 2);
         ++pl->runs;
-        return launch_decode_stream(pl->ws.tab, pl->nphase, pl->nimages, pl->act_group, pl->ws.flags,
-                                    pl->ws.status, base, pl->ws.dummy, pl->nwg, pl->trace, st);
+        return launch_decode_stream(pl->ws.tab, pl->nphase, pl->nimages, pl->act_group, pl->pairs,
+                                    pl->ws.flags, pl->ws.status, base, pl->ws.dummy, pl->nwg,
+                                    pl->trace, st);
     }
     if (!pl->batches.empty()) {
         for (const GroupBatch &b : pl->batches) {
@@ -714,6 +725,7 @@ extern "C" int nvq_plan_describe(const nvq_linear *layers, int n, int M, int act
             o[9] = sp.img_need;
             o[10] = stream_image_bytes(sp.K, sp.precision, act_group);
             o[11] = sp.img ? 1 : 0;
+            o[12] = sp.row_unit;
         }
     }
     return NVQ_OK;

@@ -14,6 +14,7 @@ constexpr int kStreamMaxWg = 1024;      // flag words reserved for workgroups
 // Layout of the flag words: [0, kStreamMaxWg) one per workgroup, then 64 status
 // words, then one word per phase ("the prepared image of this phase is stored").
 constexpr int kStreamImageFlags = kStreamMaxWg + 64;
+constexpr int kStreamPairG = 96;  // groups per row for which rows are streamed in pairs
 
 // One phase = up to four weight matrices that read the same input vector.
 // Lives in device memory; every field is read wave-uniformly.
@@ -39,6 +40,12 @@ struct StreamPhase {
     // that the extra rows go to the waves that have received the fewest extra
     // bytes so far.
     int rows_base, rows_extra, rows_rot;
+    // 1, or 2: rows are dealt in pairs of neighbours (rows_base and rows_extra then
+    // count pairs, and row 2i goes with row 2i + 1).  With G = 96 a row is one and
+    // a half chunks; a pair is streamed as three full chunks, the middle one half
+    // of each row, instead of four chunks of which two are half empty.  Needs an
+    // even number of rows in every segment and per-token activation scales.
+    int row_unit;
     int wait_phase;        // latest earlier phase this one depends on, or -1
     int publish;           // 1 if a later phase depends on this one
     int img_chunks;        // KiB chunks of the prepared image (0 if built in the kernel)
@@ -61,6 +68,7 @@ __device__ __forceinline__ void stream_wave_rows(int rows_base, int rows_extra, 
     first = j * rows_base + more;
     count = rows_base + (j < rows_extra ? 1 : 0);
 }
+
 #endif
 
 // Bytes of the activation image of a layer with K inputs, padded to whole KiB.
@@ -77,10 +85,12 @@ static inline int stream_image_bytes(int K, int precision, int act_group) {
 // phase's image is stored; workgroup word = base + 2 + p: phase p published).  `nimages` = phases with a prepared
 // image (0 skips the prologue).  `dummy` is any valid
 // 1 KiB of device memory.  `trace` is nullptr or nphase * 8 words that
-// receive workgroup 0's per-phase timestamps.
+// receive workgroup 0's per-phase timestamps.  `pairs` says that some phase of
+// the table deals its rows in pairs (row_unit == 2): the kernel variant that has
+// that path is launched.
 int launch_decode_stream(const StreamPhase *tab_dev, int nphase, int nimages, int act_group,
-                         uint32_t *flags, uint32_t *status, uint32_t flag_base, const void *dummy,
-                         int nwg, unsigned long long *trace, hipStream_t st);
+                         bool pairs, uint32_t *flags, uint32_t *status, uint32_t flag_base,
+                         const void *dummy, int nwg, unsigned long long *trace, hipStream_t st);
 
 // Timestamps written per phase when a trace buffer is given (see the kernel).
 constexpr int kStreamTraceSlots = 8;

@@ -211,8 +211,8 @@ __device__ __forceinline__ void issue_next_run(Issue &c, CPhase *tab, int nphase
             int first, count;
             stream_wave_rows(ph.rows_base, ph.rows_extra, ph.rows_rot, gw,
                              (int)gridDim.x * kStreamWaves, first, count);
-            c.row = first;
-            c.row_stop = first + count;
+            c.row = first * ph.row_unit;
+            c.row_stop = c.row + count * ph.row_unit;
         }
         if (c.row < c.row_stop) {
             int first = 0, end = ph.row_end[0];
@@ -226,14 +226,17 @@ __device__ __forceinline__ void issue_next_run(Issue &c, CPhase *tab, int nphase
                     q = ph.qw[k];
                     s = ph.sc[k];
                 }
-            const bool ragged = (ph.G & 63) != 0;
+            // rows in pairs: an even number of rows of 96 groups is a whole number
+            // of chunks (segments hold an even number of rows, so does the range)
+            const bool pairs = ph.row_unit == 2;
+            const bool ragged = (ph.G & 63) != 0 && !pairs;
             int rows = (c.row_stop < end ? c.row_stop : end) - c.row;
             if (ragged) rows = 1;
             const int64_t off = (int64_t)(c.row - first) * ph.G;
             c.q = q + off;
             c.s = s + off;
             c.qstep = c.sstep = 64;
-            c.left = rows * ph.gpl;
+            c.left = pairs ? rows / 2 * (2 * kStreamPairG / 64) : rows * ph.gpl;
             c.tail = ragged ? ph.G - (ph.gpl - 1) * 64 : 64;
             c.row += rows;
             return;
@@ -543,7 +546,11 @@ __device__ __forceinline__ bool wait_flags(const uint32_t *flags, int nwg, uint3
     }
 }
 
-template <bool PER_GROUP>
+// PAIRS: the table has phases whose rows are dealt in pairs (row_unit == 2).  A
+// kernel of its own, because the mere presence of that path costs the others
+// some 7 % on lists of many short phases (the compiler's register assignment
+// for the code they share).
+template <bool PER_GROUP, bool PAIRS>
 __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
     const StreamPhase *__restrict__ tab_generic, int nphase, int nimages,
     uint32_t *__restrict__ flags, uint32_t *__restrict__ status, uint32_t flag_base,
@@ -805,6 +812,8 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
         const int gpl = ph.gpl;
         int r0, nrows;
         stream_wave_rows(ph.rows_base, ph.rows_extra, ph.rows_rot, gw, nwg * kStreamWaves, r0, nrows);
+        r0 *= ph.row_unit;
+        nrows *= ph.row_unit;
         const int r1 = r0 + nrows;
         uint32_t xs_bits = 0x3f800000u;  // per-token activation scale (W4A8), else 1
         const uint32_t plane = (uint32_t)G * 16u;
@@ -839,8 +848,7 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
 
         // The lane's activations of group g = i * 64 + lane (clamped to a valid group)
         // out of the LDS image; nothing is waited for.
-        auto request_x = [&](int i, u32x4_t(&x)[4], uint32_t &aux, uint32_t &sgbits, bool &ok) {
-            const int g = i * 64 + lane;
+        auto request_group = [&](int g, u32x4_t(&x)[4], uint32_t &aux, uint32_t &sgbits, bool &ok) {
             ok = g < G;
             const uint32_t ga = img + (ok ? g : 0) * 16;
             const uint32_t aux_a = img + L.aux + (ok ? g : 0) * 4;
@@ -862,6 +870,9 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
                                "v"(aux_a)
                              : "memory");
             }
+        };
+        auto request_x = [&](int i, u32x4_t(&x)[4], uint32_t &aux, uint32_t &sgbits, bool &ok) {
+            request_group(i * 64 + lane, x, aux, sgbits, ok);
         };
         // One chunk against the lane's activations of its group, added to `sum`.
         auto chunk_term = [&](float sum, const uint4 &wq, uint32_t sbits, const u32x4_t(&x)[4],
@@ -939,14 +950,59 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
                 finish_row(row, sum);
             }
         };
+        // Rows of 96 groups in pairs (A, B): three chunks, the lanes of the first hold
+        // groups 0..63 of A, those of the second groups 64..95 of A and 0..31 of B,
+        // those of the third groups 32..95 of B; the lane's three groups stay in
+        // registers for the phase.
+        auto row_pairs = [&]() {
+            u32x4_t x[3][4];
+            uint32_t aux[3], sgb[3];
+            bool ok[3];
+            const bool first_half = lane < 32;
+            do {
+                request_xs();
+#pragma unroll
+                for (int i = 0; i < 3; ++i) {
+                    x[i][2] = x[i][3] = u32x4_t{0, 0, 0, 0};
+                    sgb[i] = 0;
+                    const int g = i == 0 ? lane : i == 1 ? (first_half ? 64 + lane : lane - 32) : 32 + lane;
+                    request_group(g, x[i], aux[i], sgb[i], ok[i]);
+                }
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                asm volatile("" : "+v"(xs_bits), "+v"(ready_seen));
+#pragma unroll
+                for (int i = 0; i < 3; ++i)
+                    asm volatile(""
+                                 : "+v"(x[i][0]), "+v"(x[i][1]), "+v"(x[i][2]), "+v"(x[i][3]),
+                                   "+v"(aux[i]), "+v"(sgb[i]));
+            } while (!image_ready());
+            if (ph.wait_phase < 0) trace_mark(trace, wg, w, lane, p, 2);
+            if (aborted) return;
+            for (int row = r0; row < r1; row += 2) {
+                uint32_t sbits;
+                uint4 wq = pop_chunk(sbits);
+                float sum_a = chunk_term(0.0f, wq, sbits, x[0], aux[0], sgb[0], true);
+                wq = pop_chunk(sbits);
+                const float mid = chunk_term(0.0f, wq, sbits, x[1], aux[1], sgb[1], true);
+                sum_a += first_half ? mid : 0.0f;
+                float sum_b = first_half ? 0.0f : mid;
+                wq = pop_chunk(sbits);
+                sum_b = chunk_term(sum_b, wq, sbits, x[2], aux[2], sgb[2], true);
+                finish_row(row, sum_a);
+                finish_row(row + 1, sum_b);
+            }
+        };
         // (a wave without rows in this phase never looks at the image)
-        if (nrows > 0) switch (gpl) {
+        if (nrows > 0 && ph.row_unit == 2) {
+            // (the host pairs rows only with per-token activation scales: with a
+            // scale per group the wave's registers do not hold this path as well)
+            if constexpr (!PER_GROUP && PAIRS) row_pairs();
+        } else if (nrows > 0) switch (gpl) {
             case 1: rows_in_registers(std::integral_constant<int, 1>()); break;
             case 2: rows_in_registers(std::integral_constant<int, 2>()); break;
-            case 3: rows_in_registers(std::integral_constant<int, 3>()); break;
             case 4: rows_in_registers(std::integral_constant<int, 4>()); break;
             default: {
-                // longer rows: the first kHeldGpl groups of the lane stay in
+                // rows of three chunks, and longer ones: the first kHeldGpl groups of the lane stay in
                 // registers as above, the others come out of the image for every
                 // chunk (the registers of a wave hold no more)
                 constexpr int kHeldGpl = 3;
@@ -1031,7 +1087,7 @@ int stream_grid_limit() {
     static int cached = -1;
     if (cached < 0) {
         int per_cu = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_stream_kernel<false>,
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_stream_kernel<false, false>,
                                                          kStreamThreads, 0) != hipSuccess)
             per_cu = 0;
         cached = per_cu >= 1 ? device_cu_count() : 0;
@@ -1040,16 +1096,21 @@ int stream_grid_limit() {
 }
 
 int launch_decode_stream(const StreamPhase *tab_dev, int nphase, int nimages, int act_group,
-                         uint32_t *flags, uint32_t *status, uint32_t flag_base, const void *dummy,
-                         int nwg, unsigned long long *trace, hipStream_t st) {
+                         bool pairs, uint32_t *flags, uint32_t *status, uint32_t flag_base,
+                         const void *dummy, int nwg, unsigned long long *trace, hipStream_t st) {
     const dim3 grid(nwg), block(kStreamThreads);
-    if (act_group == 32)
-        hipLaunchKernelGGL(decode_stream_kernel<true>, grid, block, 0, st, tab_dev, nphase, nimages,
-                           flags, status, flag_base, reinterpret_cast<const uint4 *>(dummy), trace);
-    else
-        hipLaunchKernelGGL(decode_stream_kernel<false>, grid, block, 0, st, tab_dev, nphase,
-                           nimages, flags, status, flag_base,
-                           reinterpret_cast<const uint4 *>(dummy), trace);
+    const uint4 *d = reinterpret_cast<const uint4 *>(dummy);
+    if (act_group == 32) {
+        if (pairs) return NVQ_ERR_INVALID_ARG;  // rows are not paired with per-group scales
+        hipLaunchKernelGGL((decode_stream_kernel<true, false>), grid, block, 0, st, tab_dev, nphase,
+                           nimages, flags, status, flag_base, d, trace);
+    } else if (pairs) {
+        hipLaunchKernelGGL((decode_stream_kernel<false, true>), grid, block, 0, st, tab_dev, nphase,
+                           nimages, flags, status, flag_base, d, trace);
+    } else {
+        hipLaunchKernelGGL((decode_stream_kernel<false, false>), grid, block, 0, st, tab_dev,
+                           nphase, nimages, flags, status, flag_base, d, trace);
+    }
     NVQ_HIP_TRY(hipGetLastError());
     return NVQ_OK;
 }

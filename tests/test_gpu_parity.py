@@ -369,13 +369,21 @@ STREAM_MODELS = {
     # 8b block shapes, one W4A8 block
     "8b": ([(4096, 4096, 0), (1024, 4096, 0), (1024, 4096, 0), (4096, 4096, 1),
             (14336, 4096, 2), (14336, 4096, 2), (4096, 14336, 3)], (0,)),
+    # llama-3b block shapes (rows of 96 groups go to the waves in pairs), one block of
+    # each precision; in the third, layers with an odd number of rows (no pairs there)
+    "3b": ([(3072, 3072, 0), (1024, 3072, 0), (1024, 3072, 0), (3072, 3072, 1),
+            (8192, 3072, 2), (8192, 3072, 2), (3072, 8192, 3)], (0, 1)),
+    "3b odd": ([(3071, 3072, 0), (1024, 3072, 0), (8190, 3072, 1), (12294, 3072, 1),
+                (2, 3072, 2)], (1, 0)),
 }
 
 
 @pytest.mark.parametrize("name,group,ordered", [("1b", 0, False), ("1b", 0, True),
                                                 ("ragged", 0, False), ("ragged", 32, True),
                                                 ("8b", 0, False), ("8b", 32, False),
-                                                ("8b", 0, True)])
+                                                ("8b", 0, True),
+                                                ("3b", 0, False), ("3b", 0, True),
+                                                ("3b", 32, False), ("3b odd", 0, False)])
 def test_streaming_plan_matches_oracle_on_repeated_runs(name, group, ordered):
     say("stream plan", name, group, ordered)
     shapes, bits = STREAM_MODELS[name]

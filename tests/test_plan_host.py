@@ -43,7 +43,8 @@ def rows_of_wave(ph, j, waves):
     """First row and row count of wave j as the kernel computes them."""
     k = (j - ph["rows_rot"]) % waves
     more = min(k, ph["rows_extra"])
-    return k * ph["rows_base"] + more, ph["rows_base"] + (1 if k < ph["rows_extra"] else 0)
+    u = ph["row_unit"]
+    return u * (k * ph["rows_base"] + more), u * (ph["rows_base"] + (1 if k < ph["rows_extra"] else 0))
 
 
 @pytest.mark.parametrize("model", ["llama-1b", "llama-3b", "llama-8b"])
@@ -57,7 +58,10 @@ def test_rows_are_dealt_once_each_and_evenly(model):
     load = np.zeros(waves)
     for ph in phases:
         assert ph["wait"] == -1 and ph["publish"] == 0          # every phase reads its own buffer
-        assert ph["rows_base"] * waves + ph["rows_extra"] == ph["rows"]
+        K = layers[ph["first"]].K
+        # rows of 96 groups (K = 3072) are dealt in pairs, all others one by one
+        assert ph["row_unit"] == (2 if K == 3072 else 1)
+        assert (ph["rows_base"] * waves + ph["rows_extra"]) * ph["row_unit"] == ph["rows"]
         assert 0 <= ph["rows_rot"] < waves
         K = layers[ph["first"]].K
         covered = np.zeros(ph["rows"], np.int32)
