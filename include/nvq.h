@@ -250,15 +250,17 @@ int nvq_plan_trace(nvq_plan *plan, uint64_t *buf, size_t bytes);
  * and checked for alignment, never followed).  `workgroups` = compute units the
  * persistent kernel would use.  out (host, out_words int32): [0] phases,
  * [1] the number of streaming waves the rows are dealt to if the list
- * qualifies for the persistent kernel, else 0; then 13 words per
+ * qualifies for the persistent kernel, else 0; then 14 words per
  * phase: first entry, entries, the latest earlier phase it must wait for (-1:
  * none), and for the persistent kernel: published (someone waits for it),
  * rows, rows per wave, waves with one more row, the wave that gets the first
  * of those, offset of the activation image in the LDS image area, the latest
  * phase whose image it overwrites there (-1: none), image bytes, 1 if the
- * image is prepared in the prologue, and the unit the rows are dealt in: 1, or 2
- * (K = 3072, an even number of rows in every layer of the phase: neighbouring
- * rows go to the same wave in pairs, and the two counts before count pairs).
+ * image is prepared in the prologue, the unit the rows are dealt in (that many
+ * neighbouring rows go to the same wave, and the two counts before count units:
+ * more than 1 where an independent phase has too few rows to give every wave a
+ * few KiB), and 2 if neighbouring rows are streamed in pairs (K = 3072 with an
+ * even number of rows in every layer of the phase), else 0.
  * NVQ_ERR_WORKSPACE if out is too small.
  */
 int nvq_plan_describe(const nvq_linear *layers, int n, int M, int act_group, int flags,

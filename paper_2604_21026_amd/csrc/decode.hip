@@ -13,6 +13,7 @@
 // quantisation launch per W4A8 phase and one fused GEMV launch), or, for 2..32
 // tokens of shapes the matrix-core kernel takes, as two launches per batch of
 // mutually independent phases (one grid quantises, one multiplies).
+#include <algorithm>
 #include <new>
 #include <vector>
 
@@ -431,7 +432,13 @@ std::vector<StreamPhase> stream_table(const nvq_linear *L, const std::vector<Pha
     // bytes of extra rows dealt to each wave so far: the extra rows of a phase
     // go to the run of waves that has received the least
     std::vector<uint64_t> extra_bytes((size_t)waves, 0);
+    const std::vector<int> deps = phase_deps(L, phases, M, ordered);
+    std::vector<char> published(phases.size(), 0);
+    for (size_t p = 1; p < phases.size(); ++p)
+        if (deps[p] >= 0) published[(size_t)deps[p]] = 1;
+    size_t pi = 0;
     for (const Phase &ph : phases) {
+        const size_t p_index = pi++;
         const nvq_linear &e0 = L[ph.first];
         const int G = e0.K / 32;
         if (e0.K > kStreamMaxK) return {};
@@ -459,17 +466,28 @@ std::vector<StreamPhase> stream_table(const nvq_linear *L, const std::vector<Pha
         sp.gpl = (G + 63) / 64;
         sp.precision = e0.precision;
         sp.row_unit = 1;
+        sp.pair_stream = 0;
         if (G == kStreamPairG && act_group != 32) {
             bool even = true;
             for (int k = 0; k < ph.count; ++k) even = even && L[ph.first + k].N % 2 == 0;
-            if (even) sp.row_unit = 2;
+            if (even) sp.row_unit = sp.pair_stream = 2;
         }
-        const int units = rows / sp.row_unit;
+        // A phase with fewer rows than would give every wave kStreamThinChunks
+        // chunks deals them in larger units to fewer waves: what a wave spends per
+        // phase it takes part in (descriptor, image, addresses of its run, the row
+        // sums) is then spent once per that many chunks, and the other waves pass.
+        // Only where nobody waits for the phase and it waits for nobody: there the
+        // waves are free to drift apart and the bytes even out over the phases.
+        if (deps[p_index] < 0 && !published[p_index]) {
+            const int half_chunks_per_row = sp.pair_stream ? 3 : 2 * sp.gpl;  // in half chunks
+            int unit = sp.row_unit;
+            while (unit * half_chunks_per_row < 2 * kStreamThinChunks) unit += sp.row_unit;
+            if (unit > sp.row_unit && (int64_t)rows < (int64_t)unit * waves) sp.row_unit = unit;
+        }
+        const int units = (rows + sp.row_unit - 1) / sp.row_unit;  // the last one may be short
         sp.rows_base = units / waves;
         sp.rows_extra = units - sp.rows_base * waves;
-        sp.rows_rot = lightest_window(extra_bytes, sp.rows_extra);
-        for (int j = 0; j < sp.rows_extra; ++j)
-            extra_bytes[(size_t)(sp.rows_rot + j) % waves] += (uint64_t)G * 18 * sp.row_unit;
+        sp.rows_rot = 0;  // set below
         sp.wait_phase = -1;
         sp.publish = 0;
         sp.img = nullptr;
@@ -477,7 +495,31 @@ std::vector<StreamPhase> stream_table(const nvq_linear *L, const std::vector<Pha
         tab.push_back(sp);
     }
     const size_t P = tab.size();
-    const std::vector<int> deps = phase_deps(L, phases, M, ordered);
+    // Which waves get a phase's extra units (a cyclic run of waves, rows_rot its
+    // start).  Two ways, the one that leaves the heaviest wave lighter wins: the run
+    // that has received the fewest bytes so far, or simply the run after the
+    // previous phase's.
+    {
+        std::vector<int> rot[2];
+        uint64_t heaviest[2];
+        for (int way = 0; way < 2; ++way) {
+            std::fill(extra_bytes.begin(), extra_bytes.end(), 0);
+            rot[way].resize(P);
+            int next = 0;
+            for (size_t p = 0; p < P; ++p) {
+                const int extra = tab[p].rows_extra;
+                const int at = way == 0 ? lightest_window(extra_bytes, extra) : next;
+                if (extra > 0) next = (next + extra) % waves;
+                rot[way][p] = at;
+                for (int j = 0; j < extra; ++j)
+                    extra_bytes[(size_t)(at + j) % waves] +=
+                        (uint64_t)tab[p].G * 18 * tab[p].row_unit;
+            }
+            heaviest[way] = *std::max_element(extra_bytes.begin(), extra_bytes.end());
+        }
+        const int way = heaviest[1] < heaviest[0] ? 1 : 0;
+        for (size_t p = 0; p < P; ++p) tab[p].rows_rot = rot[way][p];
+    }
     for (size_t p = 1; p < P; ++p) {
         tab[p].wait_phase = deps[p];
         if (deps[p] >= 0) tab[deps[p]].publish = 1;
@@ -535,7 +577,7 @@ __global__ void fill_u32_kernel(uint32_t *p, int n, uint32_t v) {
 }  // namespace nvq
 
 namespace nvq {
-constexpr int kDescribeWords = 13;  // words per phase written by nvq_plan_describe
+constexpr int kDescribeWords = 14;  // words per phase written by nvq_plan_describe
 }
 
 struct nvq_plan {
@@ -595,7 +637,7 @@ extern "C" int nvq_plan_create(const nvq_linear *layers, int n, int M, int act_g
         stream_table(pl->layers.data(), pl->phases, M, act_group, nwg,
                      (flags & NVQ_PLAN_ORDERED) != 0, ws.images, &nimages);
     if (!tab.empty()) {
-        for (const StreamPhase &sp : tab) pl->pairs = pl->pairs || sp.row_unit == 2;
+        for (const StreamPhase &sp : tab) pl->pairs = pl->pairs || sp.pair_stream != 0;
         // pageable source: the copy has left the host buffer when the call returns
         hipError_t e = hipMemcpyAsync(ws.tab, tab.data(), tab.size() * sizeof(StreamPhase),
                                       hipMemcpyHostToDevice, st);
@@ -726,6 +768,7 @@ extern "C" int nvq_plan_describe(const nvq_linear *layers, int n, int M, int act
             o[10] = stream_image_bytes(sp.K, sp.precision, act_group);
             o[11] = sp.img ? 1 : 0;
             o[12] = sp.row_unit;
+            o[13] = sp.pair_stream;
         }
     }
     return NVQ_OK;

@@ -15,6 +15,9 @@ constexpr int kStreamMaxWg = 1024;      // flag words reserved for workgroups
 // words, then one word per phase ("the prepared image of this phase is stored").
 constexpr int kStreamImageFlags = kStreamMaxWg + 64;
 constexpr int kStreamPairG = 96;  // groups per row for which rows are streamed in pairs
+// Chunks a wave should at least get from a phase it works on (measured on 1B-, 3B-
+// and 8B-shaped steps: 4 -> 8 -> 16 gains at every step, 24 and more lose again).
+constexpr int kStreamThinChunks = 16;
 
 // One phase = up to four weight matrices that read the same input vector.
 // Lives in device memory; every field is read wave-uniformly.
@@ -40,12 +43,13 @@ struct StreamPhase {
     // that the extra rows go to the waves that have received the fewest extra
     // bytes so far.
     int rows_base, rows_extra, rows_rot;
-    // 1, or 2: rows are dealt in pairs of neighbours (rows_base and rows_extra then
-    // count pairs, and row 2i goes with row 2i + 1).  With G = 96 a row is one and
-    // a half chunks; a pair is streamed as three full chunks, the middle one half
-    // of each row, instead of four chunks of which two are half empty.  Needs an
-    // even number of rows in every segment and per-token activation scales.
-    int row_unit;
+    // Rows are dealt in units of row_unit neighbours (rows_base and rows_extra
+    // count units; the last unit of the phase may be short).  pair_stream = 2 with G = 96, where a row is one and a half
+    // chunks: rows 2i and 2i + 1 are streamed as three full chunks, the middle one
+    // half of each row, instead of four chunks of which two are half empty; it
+    // needs an even number of rows in every segment, per-token activation scales
+    // and an even row_unit.  Otherwise 0.
+    int row_unit, pair_stream;
     int wait_phase;        // latest earlier phase this one depends on, or -1
     int publish;           // 1 if a later phase depends on this one
     int img_chunks;        // KiB chunks of the prepared image (0 if built in the kernel)
@@ -86,7 +90,7 @@ static inline int stream_image_bytes(int K, int precision, int act_group) {
 // image (0 skips the prologue).  `dummy` is any valid
 // 1 KiB of device memory.  `trace` is nullptr or nphase * 8 words that
 // receive workgroup 0's per-phase timestamps.  `pairs` says that some phase of
-// the table deals its rows in pairs (row_unit == 2): the kernel variant that has
+// the table streams its rows in pairs (pair_stream): the kernel variant that has
 // that path is launched.
 int launch_decode_stream(const StreamPhase *tab_dev, int nphase, int nimages, int act_group,
                          bool pairs, uint32_t *flags, uint32_t *status, uint32_t flag_base,

@@ -212,7 +212,8 @@ __device__ __forceinline__ void issue_next_run(Issue &c, CPhase *tab, int nphase
             stream_wave_rows(ph.rows_base, ph.rows_extra, ph.rows_rot, gw,
                              (int)gridDim.x * kStreamWaves, first, count);
             c.row = first * ph.row_unit;
-            c.row_stop = c.row + count * ph.row_unit;
+            c.row_stop = c.row + count * ph.row_unit;  // (the last unit of a phase may be short)
+            c.row_stop = c.row_stop < ph.total_rows ? c.row_stop : ph.total_rows;
         }
         if (c.row < c.row_stop) {
             int first = 0, end = ph.row_end[0];
@@ -228,7 +229,7 @@ __device__ __forceinline__ void issue_next_run(Issue &c, CPhase *tab, int nphase
                 }
             // rows in pairs: an even number of rows of 96 groups is a whole number
             // of chunks (segments hold an even number of rows, so does the range)
-            const bool pairs = ph.row_unit == 2;
+            const bool pairs = ph.pair_stream != 0;
             const bool ragged = (ph.G & 63) != 0 && !pairs;
             int rows = (c.row_stop < end ? c.row_stop : end) - c.row;
             if (ragged) rows = 1;
@@ -546,7 +547,7 @@ __device__ __forceinline__ bool wait_flags(const uint32_t *flags, int nwg, uint3
     }
 }
 
-// PAIRS: the table has phases whose rows are dealt in pairs (row_unit == 2).  A
+// PAIRS: the table has phases whose rows are streamed in pairs (pair_stream).  A
 // kernel of its own, because the mere presence of that path costs the others
 // some 7 % on lists of many short phases (the compiler's register assignment
 // for the code they share).
@@ -814,6 +815,7 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
         stream_wave_rows(ph.rows_base, ph.rows_extra, ph.rows_rot, gw, nwg * kStreamWaves, r0, nrows);
         r0 *= ph.row_unit;
         nrows *= ph.row_unit;
+        if (r0 + nrows > ph.total_rows) nrows = ph.total_rows - r0;  // a short last unit
         const int r1 = r0 + nrows;
         uint32_t xs_bits = 0x3f800000u;  // per-token activation scale (W4A8), else 1
         const uint32_t plane = (uint32_t)G * 16u;
@@ -993,7 +995,7 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
             }
         };
         // (a wave without rows in this phase never looks at the image)
-        if (nrows > 0 && ph.row_unit == 2) {
+        if (nrows > 0 && ph.pair_stream != 0) {
             // (the host pairs rows only with per-token activation scales: with a
             // scale per group the wave's registers do not hold this path as well)
             if constexpr (!PER_GROUP && PAIRS) row_pairs();
