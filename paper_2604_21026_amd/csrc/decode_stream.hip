@@ -183,9 +183,9 @@ __device__ __forceinline__ float quad_max(float v) {
 // pointer stride: consecutive weight rows inside one matrix (a single row
 // when K is no multiple of 2048).
 struct Issue {
-    const uint4 *q;     // next chunk: 64 x 16 bytes
-    const uint16_t *s;  // its 64 scales
-    int qstep, sstep;   // pointer advance per chunk, in elements
+    const char *q;      // next chunk: 64 x 16 bytes
+    const char *s;      // its 64 scales (2 bytes each)
+    uint32_t qstep, sstep;  // pointer advance per chunk, in bytes (unsigned: two scalar adds)
     int left;           // chunks left in the run
     int tail;           // valid lanes in the run's last chunk (64 = all)
     int p;              // phase of the run
@@ -198,8 +198,8 @@ __device__ __forceinline__ void issue_next_run(Issue &c, CPhase *tab, int nphase
     for (;;) {
         if (c.p >= nphase) {
             // past the last phase: dummy chunks keep the load count constant
-            c.q = dummy;
-            c.s = reinterpret_cast<const uint16_t *>(dummy);
+            c.q = reinterpret_cast<const char *>(dummy);
+            c.s = reinterpret_cast<const char *>(dummy);
             c.qstep = c.sstep = 0;
             c.left = 1 << 30;
             c.tail = 64;
@@ -234,9 +234,10 @@ __device__ __forceinline__ void issue_next_run(Issue &c, CPhase *tab, int nphase
             int rows = (c.row_stop < end ? c.row_stop : end) - c.row;
             if (ragged) rows = 1;
             const int64_t off = (int64_t)(c.row - first) * ph.G;
-            c.q = q + off;
-            c.s = s + off;
-            c.qstep = c.sstep = 64;
+            c.q = reinterpret_cast<const char *>(q + off);
+            c.s = reinterpret_cast<const char *>(s + off);
+            c.qstep = 64 * 16;
+            c.sstep = 64 * 2;
             c.left = pairs ? rows / 2 * (2 * kStreamPairG / 64) : rows * ph.gpl;
             c.tail = ragged ? ph.G - (ph.gpl - 1) * 64 : 64;
             c.row += rows;
@@ -253,18 +254,18 @@ __device__ __forceinline__ void issue_chunk(Issue &c, CPhase *tab, int nphase,
                                             const uint4 *dummy) {
     const int valid = c.left == 1 ? c.tail : 64;
     if (valid >= 64) {
-        __builtin_amdgcn_global_load_lds((const void *)(c.s + lane),
+        __builtin_amdgcn_global_load_lds((const void *)(c.s + lane * 2),
                                          (lds_void_ptr)&sh.sring[w][slot][0], 2, 0, 2);
-        __builtin_amdgcn_global_load_lds((const void *)(c.q + lane),
+        __builtin_amdgcn_global_load_lds((const void *)(c.q + lane * 16),
                                          (lds_void_ptr)&sh.ring[w][slot][0], 16, 0, 2);
     } else {
         // lanes past the end issue nothing; lane 0 is always valid, so both
         // loads are issued and the load count stays exact
         if (lane < valid)
-            __builtin_amdgcn_global_load_lds((const void *)(c.s + lane),
+            __builtin_amdgcn_global_load_lds((const void *)(c.s + lane * 2),
                                              (lds_void_ptr)&sh.sring[w][slot][0], 2, 0, 2);
         if (lane < valid)
-            __builtin_amdgcn_global_load_lds((const void *)(c.q + lane),
+            __builtin_amdgcn_global_load_lds((const void *)(c.q + lane * 16),
                                              (lds_void_ptr)&sh.ring[w][slot][0], 16, 0, 2);
     }
     c.q += c.qstep;
@@ -438,18 +439,14 @@ __device__ __forceinline__ void image_build(const Writer &wr, CPhase &ph, Shared
     const uint4 *x = reinterpret_cast<const uint4 *>(ph.x);
     const uint4 *x2 = reinterpret_cast<const uint4 *>(ph.x2);
     uint4 xsh[kMaxXShare];
-    // the norm weights depend on nothing: they are requested with the input, not
-    // after the sum of squares has gone round the workgroup
-    uint4 gsh[kMaxXShare];
     float ss = 0.0f;
 #pragma unroll
     for (int k = 0; k < kMaxXShare; ++k) {
         const int j = w + k * kStreamWaves;
-        const int idx = j * 64 + lane;
+        int idx = j * 64 + lane;
+        asm volatile("" : "+v"(idx));  // computed here, not kept through the kernel
         xsh[k] = make_uint4(0, 0, 0, 0);
-        gsh[k] = make_uint4(0, 0, 0, 0);
         if (j < nxc && idx < K / 8) {
-            if (in_op == NVQ_IN_RMSNORM) gsh[k] = reinterpret_cast<const uint4 *>(ph.gamma)[idx];
             xsh[k] = x[idx];
             if (in_op == NVQ_IN_SILU_MUL) {
                 xsh[k] = silu_mul_bf16x8(xsh[k], x2[idx]);
@@ -476,11 +473,14 @@ __device__ __forceinline__ void image_build(const Writer &wr, CPhase &ph, Shared
             tot += __uint_as_float(a.w);
         }
         const float r = rms_scale(tot, K, ph.eps);
+        // (requesting the norm weights together with the input instead: 16 more live
+        // registers here and no gain, they come out of the L2)
+        const uint4 *gamma = reinterpret_cast<const uint4 *>(ph.gamma);
 #pragma unroll
         for (int k = 0; k < kMaxXShare; ++k) {
             const int j = w + k * kStreamWaves;
             const int idx = j * 64 + lane;
-            if (j < nxc && idx < K / 8) xsh[k] = scale_bf16x8(xsh[k], r, gsh[k]);
+            if (j < nxc && idx < K / 8) xsh[k] = scale_bf16x8(xsh[k], r, gamma[idx]);
         }
     }
     float amax = 0.0f;
@@ -533,7 +533,10 @@ __device__ __forceinline__ bool wait_flags(const uint32_t *flags, int nwg, uint3
             uint32_t v[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const int f = f0 + j * 64 + lane;
+                int f = f0 + j * 64 + lane;
+                // (opaque, so that the four addresses are computed here and not kept in
+                // registers through the whole kernel)
+                asm volatile("" : "+v"(f));
                 v[j] = f < nwg ? __hip_atomic_load(flags + f, __ATOMIC_RELAXED,
                                                    __HIP_MEMORY_SCOPE_AGENT)
                                : target;
