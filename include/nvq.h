@@ -250,7 +250,7 @@ int nvq_plan_trace(nvq_plan *plan, uint64_t *buf, size_t bytes);
  * and checked for alignment, never followed).  `workgroups` = compute units the
  * persistent kernel would use.  out (host, out_words int32): [0] phases,
  * [1] the number of streaming waves the rows are dealt to if the list
- * qualifies for the persistent kernel, else 0; then 14 words per
+ * qualifies for the persistent kernel, else 0; then 15 words per
  * phase: first entry, entries, the latest earlier phase it must wait for (-1:
  * none), and for the persistent kernel: published (someone waits for it),
  * rows, rows per wave, waves with one more row, the wave that gets the first
@@ -260,7 +260,9 @@ int nvq_plan_trace(nvq_plan *plan, uint64_t *buf, size_t bytes);
  * neighbouring rows go to the same wave, and the two counts before count units:
  * more than 1 where an independent phase has too few rows to give every wave a
  * few KiB), and 2 if neighbouring rows are streamed in pairs (K = 3072 with an
- * even number of rows in every layer of the phase), else 0.
+ * even number of rows in every layer of the phase), else 0, and 1 if the order
+ * the waves are dealt rows in runs over the workgroups first (phases that wait
+ * or are waited for), 0 if over the waves of a workgroup first.
  * NVQ_ERR_WORKSPACE if out is too small.
  */
 int nvq_plan_describe(const nvq_linear *layers, int n, int M, int act_group, int flags,

@@ -467,6 +467,7 @@ std::vector<StreamPhase> stream_table(const nvq_linear *L, const std::vector<Pha
         sp.precision = e0.precision;
         sp.row_unit = 1;
         sp.pair_stream = 0;
+        sp.spread = deps[p_index] >= 0 || published[p_index];
         if (G == kStreamPairG && act_group != 32) {
             bool even = true;
             for (int k = 0; k < ph.count; ++k) even = even && L[ph.first + k].N % 2 == 0;
@@ -506,13 +507,24 @@ std::vector<StreamPhase> stream_table(const nvq_linear *L, const std::vector<Pha
             std::fill(extra_bytes.begin(), extra_bytes.end(), 0);
             rot[way].resize(P);
             int next = 0;
+            std::vector<uint64_t> view((size_t)waves);
             for (size_t p = 0; p < P; ++p) {
                 const int extra = tab[p].rows_extra;
-                const int at = way == 0 ? lightest_window(extra_bytes, extra) : next;
+                // extra_bytes is indexed workgroup * kStreamWaves + wave; position j of
+                // the phase's dealing order is that wave:
+                auto wave_at = [&](int j) {
+                    return tab[p].spread ? (size_t)(j % nwg) * kStreamWaves + (size_t)(j / nwg)
+                                         : (size_t)j;
+                };
+                int at = next;
+                if (way == 0) {
+                    for (int j = 0; j < waves; ++j) view[(size_t)j] = extra_bytes[wave_at(j)];
+                    at = lightest_window(view, extra);
+                }
                 if (extra > 0) next = (next + extra) % waves;
                 rot[way][p] = at;
                 for (int j = 0; j < extra; ++j)
-                    extra_bytes[(size_t)(at + j) % waves] +=
+                    extra_bytes[wave_at((at + j) % waves)] +=
                         (uint64_t)tab[p].G * 18 * tab[p].row_unit;
             }
             heaviest[way] = *std::max_element(extra_bytes.begin(), extra_bytes.end());
@@ -577,7 +589,7 @@ __global__ void fill_u32_kernel(uint32_t *p, int n, uint32_t v) {
 }  // namespace nvq
 
 namespace nvq {
-constexpr int kDescribeWords = 14;  // words per phase written by nvq_plan_describe
+constexpr int kDescribeWords = 15;  // words per phase written by nvq_plan_describe
 }
 
 struct nvq_plan {
@@ -769,6 +781,7 @@ extern "C" int nvq_plan_describe(const nvq_linear *layers, int n, int M, int act
             o[11] = sp.img ? 1 : 0;
             o[12] = sp.row_unit;
             o[13] = sp.pair_stream;
+            o[14] = sp.spread;
         }
     }
     return NVQ_OK;

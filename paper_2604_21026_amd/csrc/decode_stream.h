@@ -38,7 +38,13 @@ struct StreamPhase {
     int K, G, gpl;         // G = K/32 (even), gpl = ceil(G/64) <= 7
     int precision;         // NVQ_W4A8 | NVQ_W4A16
     // Rows are dealt to the W = workgroups * kStreamWaves waves as evenly as whole
-    // rows allow: wave j' = (wave - rows_rot) mod W takes rows_base rows, one more
+    // rows allow.  wave = workgroup * kStreamWaves + wave in the workgroup, or, with
+    // spread = 1, wave in the workgroup * workgroups + workgroup: then neighbours sit
+    // on different compute units and the waves that get a phase's extra rows are
+    // spread evenly over them, which a phase that others wait for needs (it ends with
+    // its busiest compute unit; 18 % of the step time of a dependent chain), while
+    // independent phases stream faster (5 %) with a compute unit's waves on
+    // neighbouring rows.  Wave j' = (wave - rows_rot) mod W takes rows_base rows, one more
     // if j' < rows_extra, in order of j'.  The host chooses rows_rot per phase so
     // that the extra rows go to the waves that have received the fewest extra
     // bytes so far.
@@ -50,6 +56,7 @@ struct StreamPhase {
     // needs an even number of rows in every segment, per-token activation scales
     // and an even row_unit.  Otherwise 0.
     int row_unit, pair_stream;
+    int spread;
     int wait_phase;        // latest earlier phase this one depends on, or -1
     int publish;           // 1 if a later phase depends on this one
     int img_chunks;        // KiB chunks of the prepared image (0 if built in the kernel)

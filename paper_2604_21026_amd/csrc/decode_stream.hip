@@ -209,7 +209,8 @@ __device__ __forceinline__ void issue_next_run(Issue &c, CPhase *tab, int nphase
         if (c.part == 0) {
             c.part = 1;
             int first, count;
-            stream_wave_rows(ph.rows_base, ph.rows_extra, ph.rows_rot, gw,
+            stream_wave_rows(ph.rows_base, ph.rows_extra, ph.rows_rot,
+                             ph.spread ? w * (int)gridDim.x + (int)blockIdx.x : gw,
                              (int)gridDim.x * kStreamWaves, first, count);
             c.row = first * ph.row_unit;
             c.row_stop = c.row + count * ph.row_unit;  // (the last unit of a phase may be short)
@@ -566,7 +567,9 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
     const int lane = threadIdx.x & 63;
     const int wg = blockIdx.x;
     const int nwg = gridDim.x;
+    // The wave's place in the two orders rows are dealt in (StreamPhase::spread).
     const int gw = wg * kStreamWaves + w;
+    const int gw_spread = w * nwg + wg;
     if (threadIdx.x == 0) lds_write4(lds_addr(&sh.abort), 0u);
     trace_mark(trace, wg, w, lane, 0, 5);  // kernel entered
 #ifdef NVQ_TRACE_ENDS
@@ -815,7 +818,8 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
         // ---- this wave's weight rows ---------------------------------------------------
         const int gpl = ph.gpl;
         int r0, nrows;
-        stream_wave_rows(ph.rows_base, ph.rows_extra, ph.rows_rot, gw, nwg * kStreamWaves, r0, nrows);
+        stream_wave_rows(ph.rows_base, ph.rows_extra, ph.rows_rot, ph.spread ? gw_spread : gw,
+                         nwg * kStreamWaves, r0, nrows);
         r0 *= ph.row_unit;
         nrows *= ph.row_unit;
         if (r0 + nrows > ph.total_rows) nrows = ph.total_rows - r0;  // a short last unit

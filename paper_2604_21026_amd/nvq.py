@@ -346,7 +346,7 @@ def plan_describe_batches(linears: Sequence[Linear], M: int, ordered: bool = Fal
 
 DESCRIBE_FIELDS = ("first", "count", "wait", "publish", "rows", "rows_base", "rows_extra",
                    "rows_rot", "img_lds", "img_need", "img_bytes", "img_prepared", "row_unit",
-                   "pair_stream")
+                   "pair_stream", "spread")
 
 
 def plan_describe(linears: Sequence[Linear], M: int, act_group: int = 0, ordered: bool = False,
