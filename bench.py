@@ -29,7 +29,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-STREAM_KERNEL = "nvq::decode_stream_kernel<false>"
+STREAM_KERNEL = "nvq::decode_stream_kernel"  # <per-group scales, paired rows>: one of three
 GROUP_KERNEL = "nvq::gemv_mfma_group_kernel (+ nvq::quant_act_group_kernel)"
 RING_KERNEL = ("nvq::gemv_mfma_ring_kernel (+ nvq::token_scale_group_kernel, "
                "nvq::operand_image_group_kernel)")
