@@ -298,8 +298,8 @@ def main():
     specs = synth.model_linears(a.model)
     step_bytes = sum(synth.weight_bytes(s.N, s.K) for s in specs)
     out = {
-        "metric": "decode linear-layer tokens/s + achieved HBM GB/s (%% of peak), 8B shapes, "
-                  "batch %d" % M,
+        "metric": "decode linear-layer tokens/s + achieved HBM GB/s (%% of peak), %s shapes, "
+                  "batch %d" % (a.model.split("-")[1].upper(), M),
         "value": None, "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": None, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int4 weights; int8 x int4 -> int32 (W4A8) and bf16 x int4 -> f32 (W4A16)",

@@ -39,6 +39,7 @@ struct Workspace {
     uint32_t *imgflags; // [n]                 one word per phase (follows the status words)
     void *dummy;        // 1 KiB               target of the ring's filler loads
     char *images;       // prepared activation images of the streaming kernel
+    uint8_t *skips;     // skip table of the streaming kernel (M = 1): a row per streaming wave
     GroupPhase *gtab;   // [n]                 phase table of the grouped small-batch launches
     uint16_t *gjobs;    // [n]                 W4A8 phases, batch after batch
     uint16_t *gunits;   // [group_units]       phase of every 16-row tile, batch after batch
@@ -91,6 +92,8 @@ Workspace carve(void *base, int M, int n, const ListSizes &ls) {
     w.imgflags = reinterpret_cast<uint32_t *>(take((size_t)(n > 0 ? n : 1) * 4));
     w.dummy = take(1024);
     w.images = take(image_bytes);
+    w.skips = reinterpret_cast<uint8_t *>(
+        take(M == 1 ? (size_t)kStreamMaxWg * kStreamWaves * (size_t)stream_skip_stride(n) : 0));
     const size_t nn = (size_t)(n > 0 ? n : 1);
     w.gtab = reinterpret_cast<GroupPhase *>(take(M > 1 ? nn * sizeof(GroupPhase) : 0));
     w.gjobs = reinterpret_cast<uint16_t *>(take(M > 1 ? nn * 2 : 0));
@@ -425,7 +428,7 @@ int lightest_window(const std::vector<uint64_t> &load, int len) {
 // every phase is made to depend on its predecessor.
 std::vector<StreamPhase> stream_table(const nvq_linear *L, const std::vector<Phase> &phases, int M,
                                       int act_group, int nwg, bool ordered, char *images,
-                                      int *nimages) {
+                                      int *nimages, std::vector<uint8_t> *skips = nullptr) {
     std::vector<StreamPhase> tab;
     if (M != 1 || nwg <= 0 || nwg > kStreamMaxWg) return tab;
     const int waves = nwg * kStreamWaves;
@@ -536,6 +539,33 @@ std::vector<StreamPhase> stream_table(const nvq_linear *L, const std::vector<Pha
         tab[p].wait_phase = deps[p];
         if (deps[p] >= 0) tab[deps[p]].publish = 1;
     }
+    // The skip table: a wave passes, without looking at them, the phases that give it
+    // no rows and have no barrier (nobody waits for them, they wait for nobody).
+    if (skips) {
+        const int stride = stream_skip_stride((int)P);
+        skips->assign((size_t)waves * stride, 0);
+        std::vector<uint8_t> active((size_t)waves);
+        for (size_t pp = P; pp-- > 0;) {
+            const StreamPhase &sp = tab[pp];
+            const bool skippable = sp.wait_phase < 0 && !sp.publish;
+            for (int j = 0; j < waves; ++j) {
+                int jj = j - sp.rows_rot;
+                jj = jj < 0 ? jj + waves : jj;
+                const size_t g = sp.spread ? (size_t)(j % nwg) * kStreamWaves + (size_t)(j / nwg)
+                                           : (size_t)j;
+                active[g] = !skippable || sp.rows_base > 0 || jj < sp.rows_extra;
+            }
+            for (int g = 0; g < waves; ++g) {
+                uint8_t *row = skips->data() + (size_t)g * stride;
+                if (active[(size_t)g]) {
+                    row[pp] = 0;
+                } else {
+                    const int next = pp + 1 < P ? row[pp + 1] : 0;
+                    row[pp] = (uint8_t)(next >= 255 ? 255 : next + 1);
+                }
+            }
+        }
+    }
     // Activation images.  A phase that waits for nothing gets its image
     // prepared in global memory.  In LDS the images of consecutive phases are
     // laid out one after the other in a circular area; img_need names the
@@ -645,14 +675,17 @@ extern "C" int nvq_plan_create(const nvq_linear *layers, int n, int M, int act_g
     hipStream_t st = (hipStream_t)stream;
     const int nwg = n > 0 ? stream_grid_limit() : 0;
     int nimages = 0;
+    std::vector<uint8_t> skips;
     const std::vector<StreamPhase> tab =
         stream_table(pl->layers.data(), pl->phases, M, act_group, nwg,
-                     (flags & NVQ_PLAN_ORDERED) != 0, ws.images, &nimages);
+                     (flags & NVQ_PLAN_ORDERED) != 0, ws.images, &nimages, &skips);
     if (!tab.empty()) {
         for (const StreamPhase &sp : tab) pl->pairs = pl->pairs || sp.pair_stream != 0;
         // pageable source: the copy has left the host buffer when the call returns
         hipError_t e = hipMemcpyAsync(ws.tab, tab.data(), tab.size() * sizeof(StreamPhase),
                                       hipMemcpyHostToDevice, st);
+        if (e == hipSuccess)
+            e = hipMemcpyAsync(ws.skips, skips.data(), skips.size(), hipMemcpyHostToDevice, st);
         if (e == hipSuccess) {
             const int words = kStreamImageFlags + n;  // workgroup flags, status, image flags
             hipLaunchKernelGGL(fill_u32_kernel, dim3((words + 255) / 256), dim3(256), 0, st, ws.flags,
@@ -713,7 +746,8 @@ extern "C" int nvq_plan_run(nvq_plan *pl, void *stream) {
     if (pl->nwg > 0) {
         const uint32_t base = pl->runs * (uint32_t)(pl->nphase + 2);
         ++pl->runs;
-        return launch_decode_stream(pl->ws.tab, pl->nphase, pl->nimages, pl->act_group, pl->pairs,
+        return launch_decode_stream(pl->ws.tab, pl->ws.skips, pl->nphase, pl->nimages, pl->act_group,
+                                    pl->pairs,
                                     pl->ws.flags, pl->ws.status, base, pl->ws.dummy, pl->nwg,
                                     pl->trace, st);
     }

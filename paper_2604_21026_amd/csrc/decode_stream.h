@@ -14,10 +14,15 @@ constexpr int kStreamMaxWg = 1024;      // flag words reserved for workgroups
 // Layout of the flag words: [0, kStreamMaxWg) one per workgroup, then 64 status
 // words, then one word per phase ("the prepared image of this phase is stored").
 constexpr int kStreamImageFlags = kStreamMaxWg + 64;
+// Skip table: one row of skip_stride(phases) bytes per streaming wave (workgroup *
+// kStreamWaves + wave); byte p = how many phases from p on the wave may pass
+// without a look (it has no rows in them and they have no barriers), at most 255.
+constexpr int stream_skip_stride(int nphase) { return (nphase + 4 + 3) / 4 * 4; }
 constexpr int kStreamPairG = 96;  // groups per row for which rows are streamed in pairs
 // Chunks a wave should at least get from a phase it works on (measured on 1B-, 3B-
-// and 8B-shaped steps: 4 -> 8 -> 16 gains at every step, 24 and more lose again).
-constexpr int kStreamThinChunks = 16;
+// and 8B-shaped steps: 4 -> 8 -> 12 gains at every step, flat from 12 to 16, 24 and
+// more lose again).
+constexpr int kStreamThinChunks = 12;
 
 // One phase = up to four weight matrices that read the same input vector.
 // Lives in device memory; every field is read wave-uniformly.
@@ -96,12 +101,14 @@ static inline int stream_image_bytes(int K, int precision, int act_group) {
 // phase's image is stored; workgroup word = base + 2 + p: phase p published).  `nimages` = phases with a prepared
 // image (0 skips the prologue).  `dummy` is any valid
 // 1 KiB of device memory.  `trace` is nullptr or nphase * 8 words that
-// receive workgroup 0's per-phase timestamps.  `pairs` says that some phase of
+// receive workgroup 0's per-phase timestamps (of the phases its first wave does
+// not pass).  `skips`: the skip table, nwg * kStreamWaves rows.  `pairs` says that some phase of
 // the table streams its rows in pairs (pair_stream): the kernel variant that has
 // that path is launched.
-int launch_decode_stream(const StreamPhase *tab_dev, int nphase, int nimages, int act_group,
-                         bool pairs, uint32_t *flags, uint32_t *status, uint32_t flag_base,
-                         const void *dummy, int nwg, unsigned long long *trace, hipStream_t st);
+int launch_decode_stream(const StreamPhase *tab_dev, const uint8_t *skips, int nphase, int nimages,
+                         int act_group, bool pairs, uint32_t *flags, uint32_t *status,
+                         uint32_t flag_base, const void *dummy, int nwg,
+                         unsigned long long *trace, hipStream_t st);
 
 // Timestamps written per phase when a trace buffer is given (see the kernel).
 constexpr int kStreamTraceSlots = 8;

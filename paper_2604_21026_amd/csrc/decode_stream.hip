@@ -178,6 +178,12 @@ __device__ __forceinline__ float quad_max(float v) {
     return v;
 }
 
+// Byte p of the wave's row of the skip table, as a scalar load.
+typedef const __attribute__((address_space(4))) uint32_t CSkipWord;
+__device__ __forceinline__ int phase_skip(CSkipWord *row, int p) {
+    return (int)((row[p >> 2] >> ((p & 3) * 8)) & 0xffu);
+}
+
 // ---- the issue side: where the wave's next chunk comes from -------------------
 // All fields are wave-uniform.  A run is a sequence of chunks at a constant
 // pointer stride: consecutive weight rows inside one matrix (a single row
@@ -193,8 +199,8 @@ struct Issue {
     int row, row_stop;  // weight rows of phase p not yet turned into runs
 };
 
-__device__ __forceinline__ void issue_next_run(Issue &c, CPhase *tab, int nphase, int w,
-                                               int gw, const uint4 *dummy) {
+__device__ __forceinline__ void issue_next_run(Issue &c, CPhase *tab, CSkipWord *skips, int nphase,
+                                               int w, int gw, const uint4 *dummy) {
     for (;;) {
         if (c.p >= nphase) {
             // past the last phase: dummy chunks keep the load count constant
@@ -245,12 +251,13 @@ __device__ __forceinline__ void issue_next_run(Issue &c, CPhase *tab, int nphase
             return;
         }
         ++c.p;
+        if (c.p < nphase) c.p += phase_skip(skips, c.p);  // phases without rows for this wave
         c.part = 0;
     }
 }
 
 // Issue the two loads of the next chunk into ring slot `slot`.
-__device__ __forceinline__ void issue_chunk(Issue &c, CPhase *tab, int nphase,
+__device__ __forceinline__ void issue_chunk(Issue &c, CPhase *tab, CSkipWord *skips, int nphase,
                                             Shared &sh, int w, int gw, int slot, int lane,
                                             const uint4 *dummy) {
     const int valid = c.left == 1 ? c.tail : 64;
@@ -271,7 +278,7 @@ __device__ __forceinline__ void issue_chunk(Issue &c, CPhase *tab, int nphase,
     }
     c.q += c.qstep;
     c.s += c.sstep;
-    if (--c.left == 0) issue_next_run(c, tab, nphase, w, gw, dummy);
+    if (--c.left == 0) issue_next_run(c, tab, skips, nphase, w, gw, dummy);
 }
 
 // ---- arithmetic of one chunk ----------------------------------------------------
@@ -557,8 +564,8 @@ __device__ __forceinline__ bool wait_flags(const uint32_t *flags, int nwg, uint3
 // for the code they share).
 template <bool PER_GROUP, bool PAIRS>
 __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
-    const StreamPhase *__restrict__ tab_generic, int nphase, int nimages,
-    uint32_t *__restrict__ flags, uint32_t *__restrict__ status, uint32_t flag_base,
+    const StreamPhase *__restrict__ tab_generic, const uint8_t *__restrict__ skips_generic,
+    int nphase, int nimages, uint32_t *__restrict__ flags, uint32_t *__restrict__ status, uint32_t flag_base,
     const uint4 *__restrict__ dummy, unsigned long long *__restrict__ trace) {
     __shared__ Shared sh;
     CPhase *tab = (CPhase *)tab_generic;
@@ -578,15 +585,19 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
 
     // The streaming waves request their first chunks at once: weights depend on
     // nothing, so the ring fills while the prologue below prepares the images.
+    // this wave's row of the skip table (the loader wave has none and looks at every phase)
+    CSkipWord *skips = (CSkipWord *)(skips_generic + (size_t)(w < kStreamWaves ? gw : 0) *
+                                                         (size_t)stream_skip_stride(nphase));
     Stream st;
     st.ic.p = 0;
     st.ic.part = 0;
     st.ic.left = 0;
     st.slot = 0;
     if (w < kStreamWaves) {
-        issue_next_run(st.ic, tab, nphase, w, gw, dummy);
+        st.ic.p = phase_skip(skips, 0);
+        issue_next_run(st.ic, tab, skips, nphase, w, gw, dummy);
         for (int u = 0; u < kSlots; ++u)  // fill the ring
-            issue_chunk(st.ic, tab, nphase, sh, w, gw, u, lane, dummy);
+            issue_chunk(st.ic, tab, skips, nphase, sh, w, gw, u, lane, dummy);
     }
 
     // ---- prologue: images of the phases that depend on no earlier phase, one
@@ -761,7 +772,7 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
                      : "v"(ring_base + st.slot * 1024u), "v"(sring_base + st.slot * 256u)
                      : "memory");
         scale_bits = sb;
-        issue_chunk(st.ic, tab, nphase, sh, w, gw, (int)st.slot, lane, dummy);
+        issue_chunk(st.ic, tab, skips, nphase, sh, w, gw, (int)st.slot, lane, dummy);
         st.slot = st.slot + 1 == kSlots ? 0 : st.slot + 1;
         return make_uint4(v.x, v.y, v.z, v.w);
     };
@@ -770,6 +781,16 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
     uint32_t ready_seen = 0;     // sh.img_ready as requested on entering an independent phase
     bool ready_pending = false;  // ... and not yet looked at
     for (int p = 0; p < nphase && !aborted; ++p) {
+        {
+            // phases in which this wave has no rows and nobody meets at a barrier are
+            // passed without a look; the loader learns that they are done with
+            const int pass = phase_skip(skips, p);
+            if (pass > 0) {
+                p += pass;
+                if (lane == 0) lds_write4(progress_a + w * 4, (uint32_t)(p < nphase ? p : nphase));
+                if (p >= nphase) break;
+            }
+        }
         CPhase &ph = tab[p];
         const int G = ph.G;
         const bool w4a8 = ph.precision == NVQ_W4A8;
@@ -1104,20 +1125,21 @@ int stream_grid_limit() {
     return cached;
 }
 
-int launch_decode_stream(const StreamPhase *tab_dev, int nphase, int nimages, int act_group,
-                         bool pairs, uint32_t *flags, uint32_t *status, uint32_t flag_base,
-                         const void *dummy, int nwg, unsigned long long *trace, hipStream_t st) {
+int launch_decode_stream(const StreamPhase *tab_dev, const uint8_t *skips, int nphase, int nimages,
+                         int act_group, bool pairs, uint32_t *flags, uint32_t *status,
+                         uint32_t flag_base, const void *dummy, int nwg,
+                         unsigned long long *trace, hipStream_t st) {
     const dim3 grid(nwg), block(kStreamThreads);
     const uint4 *d = reinterpret_cast<const uint4 *>(dummy);
     if (act_group == 32) {
         if (pairs) return NVQ_ERR_INVALID_ARG;  // rows are not paired with per-group scales
-        hipLaunchKernelGGL((decode_stream_kernel<true, false>), grid, block, 0, st, tab_dev, nphase,
-                           nimages, flags, status, flag_base, d, trace);
+        hipLaunchKernelGGL((decode_stream_kernel<true, false>), grid, block, 0, st, tab_dev, skips,
+                           nphase, nimages, flags, status, flag_base, d, trace);
     } else if (pairs) {
-        hipLaunchKernelGGL((decode_stream_kernel<false, true>), grid, block, 0, st, tab_dev, nphase,
-                           nimages, flags, status, flag_base, d, trace);
+        hipLaunchKernelGGL((decode_stream_kernel<false, true>), grid, block, 0, st, tab_dev, skips,
+                           nphase, nimages, flags, status, flag_base, d, trace);
     } else {
-        hipLaunchKernelGGL((decode_stream_kernel<false, false>), grid, block, 0, st, tab_dev,
+        hipLaunchKernelGGL((decode_stream_kernel<false, false>), grid, block, 0, st, tab_dev, skips,
                            nphase, nimages, flags, status, flag_base, d, trace);
     }
     NVQ_HIP_TRY(hipGetLastError());

@@ -62,13 +62,13 @@ def test_rows_are_dealt_once_each_and_evenly(model):
         assert ph["wait"] == -1 and ph["publish"] == 0          # every phase reads its own buffer
         K = layers[ph["first"]].K
         # rows of 96 groups (K = 3072) are streamed in pairs; a phase too short to give
-        # every wave 16 chunks deals its rows in larger units to fewer waves
+        # every wave 12 chunks deals its rows in larger units to fewer waves
         assert ph["pair_stream"] == (2 if K == 3072 else 0)
         u, gpl = ph["row_unit"], (K // 32 + 63) // 64
         chunks_per_row = 1.5 if K == 3072 else gpl
         step = max(ph["pair_stream"], 1)
         want = step
-        while want * chunks_per_row < 16:
+        while want * chunks_per_row < 12:
             want += step
         assert u == (want if ph["rows"] < want * waves else step)
         assert ph["rows_base"] * waves + ph["rows_extra"] == -(-ph["rows"] // u)
@@ -81,9 +81,10 @@ def test_rows_are_dealt_once_each_and_evenly(model):
             load[j] += count * (K // 32) * 18
         assert covered.min() == 1 and covered.max() == 1         # every row exactly once
         biggest_unit = max(biggest_unit, u * (K // 32) * 18)
-    # the heaviest wave carries at most 4 % more than the average, the lightest at most 8 % less
+    # the heaviest wave (it ends the step) carries at most 3 % more than the average, the
+    # lightest at most 12 % less
     assert biggest_unit > 0
-    assert load.max() <= 1.04 * load.mean() and load.min() >= 0.92 * load.mean()
+    assert load.max() <= 1.03 * load.mean() and load.min() >= 0.88 * load.mean()
 
 
 def test_image_regions_never_overwrite_an_image_that_may_still_be_read():
