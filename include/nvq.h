@@ -231,7 +231,9 @@ int nvq_decode_linears(const nvq_linear *layers, int n, int M, int act_group,
  *   nvq_plan_trace   diagnostic: give a device buffer of phases * 8 uint64
  *                    (or NULL to stop); later runs of the persistent kernel
  *                    store workgroup 0's timestamps per phase in it (100 MHz
- *                    wall clock), taken by its first wave: [0] phase entered,
+ *                    wall clock), taken by its first wave (phases in which
+ *                    that wave has no rows and no barrier keep what was there):
+ *                    [0] phase entered,
  *                    [1] dependency satisfied, [2] input staged, [3] all
  *                    waves done (published phases only), [4] published,
  *                    [5] input seen, [6] activations ready, [7] own rows done

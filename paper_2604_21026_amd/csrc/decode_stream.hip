@@ -10,9 +10,13 @@
 //
 // Structure.  One workgroup per compute unit, all co-resident: kStreamWaves
 // streaming waves (three per SIMD) and one loader wave.  Each streaming wave
-// owns a contiguous range of rows in every phase and sees its work as one flat
-// sequence of 1 KiB chunks (64 groups x 16 B of one weight row) across all
-// phases.  Chunks are fetched with non-temporal global->LDS loads into a
+// owns a contiguous range of rows in every phase (possibly none: a phase too
+// short to give every wave a dozen chunks deals its rows in larger units to
+// fewer waves, and a wave passes the phases that give it nothing without a
+// look, by a skip table the host prepares; a wave issues one instruction per
+// 6-10 cycles, and taking part in a phase costs it some 250 of them) and sees
+// its work as one flat sequence of 1 KiB chunks (64 groups x 16 B of one
+// weight row) across all phases.  Chunks are fetched with non-temporal global->LDS loads into a
 // per-wave ring of kSlots slots and consumed in order; a slot is refilled as
 // soon as its chunk has been taken out, independent of phase boundaries, and
 // the ring is first filled before anything else happens in the kernel.  The
