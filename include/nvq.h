@@ -270,6 +270,17 @@ int nvq_plan_trace(nvq_plan *plan, uint64_t *buf, size_t bytes);
 int nvq_plan_describe(const nvq_linear *layers, int n, int M, int act_group, int flags,
                       int workgroups, int32_t *out, int out_words);
 /*
+ * nvq_plan_describe_skips -- likewise the skip table of the persistent batch-1
+ * kernel: out (host) receives workgroups * 12 rows (workgroup * 12 + streaming
+ * wave) of *stride bytes; byte p of a row = the number of phases from p on (at
+ * most 255) that the wave passes without a look: it has no rows in them, they
+ * wait for nobody and nobody waits for them.  *stride = 0 and nothing written if
+ * the list does not qualify for that kernel; NVQ_ERR_WORKSPACE if out is too
+ * small (out_bytes < rows * stride, stride = phases + 4 rounded up to 4).
+ */
+int nvq_plan_describe_skips(const nvq_linear *layers, int n, int M, int act_group, int flags,
+                            int workgroups, uint8_t *out, size_t out_bytes, int *stride);
+/*
  * nvq_plan_describe_batches -- likewise for the grouped small-batch launches
  * (M > 1): out[0] = batches of mutually independent phases (0 if the list does
  * not qualify for the matrix-core kernels), out[1] = 1 if the persistent kernel

@@ -821,6 +821,28 @@ extern "C" int nvq_plan_describe(const nvq_linear *layers, int n, int M, int act
     return NVQ_OK;
 }
 
+extern "C" int nvq_plan_describe_skips(const nvq_linear *layers, int n, int M, int act_group,
+                                       int flags, int workgroups, uint8_t *out, size_t out_bytes,
+                                       int *stride) {
+    using namespace nvq;
+    if (!out || !stride || workgroups <= 0 || (flags & ~NVQ_PLAN_ORDERED))
+        return NVQ_ERR_INVALID_ARG;
+    ListSizes ls;
+    const int rc = check_layers(layers, n, M, act_group, &ls);
+    if (rc != NVQ_OK) return rc;
+    const std::vector<Phase> phases = group_phases(layers, n);
+    int nimages = 0;
+    std::vector<uint8_t> skips;
+    const std::vector<StreamPhase> tab =
+        stream_table(layers, phases, M, act_group, workgroups, (flags & NVQ_PLAN_ORDERED) != 0,
+                     reinterpret_cast<char *>(uintptr_t(4096)) /* never followed */, &nimages,
+                     &skips);
+    *stride = tab.empty() ? 0 : stream_skip_stride((int)tab.size());
+    if (out_bytes < skips.size()) return NVQ_ERR_WORKSPACE;
+    std::copy(skips.begin(), skips.end(), out);
+    return NVQ_OK;
+}
+
 extern "C" int nvq_plan_describe_batches(const nvq_linear *layers, int n, int M, int act_group,
                                          int flags, int32_t *out, int out_words) {
     using namespace nvq;

@@ -24,6 +24,7 @@ EXPORTS = (
     "nvq_gemv_w4a16", "nvq_gemv_w4a8", "nvq_decode_workspace_bytes", "nvq_decode_linears",
     "nvq_plan_create", "nvq_plan_run", "nvq_plan_info", "nvq_plan_status", "nvq_plan_trace",
     "nvq_plan_destroy", "nvq_plan_describe", "nvq_plan_describe_batches",
+    "nvq_plan_describe_skips",
     "nvq_dequant_bf16", "nvq_gemm_w4a16", "nvq_rms_norm_bf16", "nvq_silu_mul_bf16", "nvq_precision_from_scores", "nvq_token_norms", "nvq_mcap_scores", "nvq_stream_read", "nvq_stream_copy",
 )
 
@@ -80,6 +81,7 @@ def lib() -> C.CDLL:
     L.nvq_plan_destroy.argtypes = [vp]
     L.nvq_plan_describe.argtypes = [vp, ci, ci, ci, ci, ci, vp, ci]
     L.nvq_plan_describe_batches.argtypes = [vp, ci, ci, ci, ci, vp, ci]
+    L.nvq_plan_describe_skips.argtypes = [vp, ci, ci, ci, ci, ci, vp, sz, vp]
     L.nvq_plan_destroy.restype = None
     L.nvq_precision_from_scores.argtypes = [vp, ci, C.c_double, C.c_double, vp]
     L.nvq_token_norms.argtypes = [vp, ci, vp, ci, ci, ci, vp, vp]
@@ -362,6 +364,26 @@ def plan_describe(linears: Sequence[Linear], M: int, act_group: int = 0, ordered
     k = len(DESCRIBE_FIELDS)
     return int(out[1]), [dict(zip(DESCRIBE_FIELDS, out[2 + p * k:2 + (p + 1) * k]))
                           for p in range(out[0])]
+
+
+def plan_describe_skips(linears: Sequence[Linear], M: int, act_group: int = 0,
+                        ordered: bool = False, workgroups: int = 256):
+    """The skip table of the batch-1 persistent kernel (no device needed): a uint8 array
+    [workgroups * 12][phases] (row = workgroup * 12 + streaming wave), or None."""
+    import numpy as np
+    n = len(linears)
+    arr = (Linear * max(n, 1))(*linears)
+    rows = workgroups * 12
+    cap = rows * (n + 8)
+    out = np.zeros(cap, np.uint8)
+    stride = C.c_int(0)
+    _check(lib().nvq_plan_describe_skips(C.byref(arr), n, M, act_group,
+                                         PLAN_ORDERED if ordered else 0, workgroups,
+                                         out.ctypes.data, cap, C.byref(stride)),
+           "nvq_plan_describe_skips")
+    if stride.value == 0:
+        return None
+    return out[:rows * stride.value].reshape(rows, stride.value)
 
 
 def decode_linears(entries: Sequence[dict], M: int, act_group: int = 0) -> DecodeList:

@@ -87,6 +87,45 @@ def test_rows_are_dealt_once_each_and_evenly(model):
     assert load.max() <= 1.03 * load.mean() and load.min() >= 0.88 * load.mean()
 
 
+@pytest.mark.parametrize("model,ordered", [("llama-1b", False), ("llama-3b", False),
+                                           ("llama-8b", False), ("llama-1b", True)])
+def test_skip_table_passes_exactly_the_phases_without_rows_and_barriers(model, ordered):
+    nb = synth.MODELS[model][0]
+    layers = model_list(model, synth.make_precision_map(nb, nb // 2))
+    waves, phases = nvq.plan_describe(layers, 1, ordered=ordered)
+    skips = nvq.plan_describe_skips(layers, 1, ordered=ordered)
+    P = len(phases)
+    assert skips.shape[0] == waves and skips.shape[1] >= P + 4 and skips.shape[1] % 4 == 0
+    assert not skips[:, P:].any()                       # the padding reads as "do not pass"
+    # which wave works in which phase, from the dealing alone
+    nwg = waves // 12
+    active = np.zeros((P, waves), bool)
+    for p, ph in enumerate(phases):
+        for j in range(waves):
+            _, count = rows_of_wave(ph, j, waves)
+            g = (j % nwg) * 12 + j // nwg if ph["spread"] else j
+            active[p, g] = count > 0 or ph["wait"] >= 0 or ph["publish"] == 1
+    if ordered:
+        assert not skips.any()                          # every phase has barriers
+        return
+    assert skips.any()
+    for g in range(0, waves, 37):                       # a sample of the waves
+        for p in range(P):
+            run = 0
+            while p + run < P and not active[p + run, g]:
+                run += 1
+            assert skips[g, p] == min(run, 255)
+    # a wave that follows its row of the table visits exactly the phases it works in
+    for g in (0, 1, 11, 12, 1000, waves - 1):
+        p, seen = 0, []
+        while p < P:
+            p += int(skips[g, p])
+            if p < P:
+                seen.append(p)
+                p += 1
+        assert seen == [p for p in range(P) if active[p, g]]
+
+
 def test_image_regions_never_overwrite_an_image_that_may_still_be_read():
     layers = model_list("llama-8b", synth.make_precision_map(32, 16))
     _, phases = nvq.plan_describe(layers, 1)
