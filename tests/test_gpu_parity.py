@@ -407,6 +407,36 @@ def test_streaming_plan_matches_oracle_on_repeated_runs(name, group, ordered):
     dl.close()
 
 
+def test_streaming_plan_of_many_tiny_phases():
+    """300 independent layers of 40 rows: nearly every wave has no rows in more than 255 phases
+    in a row (the skip table's cap), a few work in one phase in a hundred."""
+    say("stream plan, 300 tiny phases")
+    entries, host = [], []
+    for i in range(300):
+        N, K = 40, 2048
+        xh = act(9100 + i, 1, K)
+        _, q, s = packed(9500 + i, N, K)
+        qd, sd = to_dev_packed(q, s)
+        entries.append(dict(qweight=qd, scales=sd, x=xh.to(DEV), precision=i % 2,
+                            y=torch.zeros((1, N), dtype=torch.float32, device=DEV)))
+        host.append(dict(qweight=q, scales=s, x=u16(xh), precision=i % 2))
+    ys_ref = oracle.decode_linears(host, 1, 0)
+    dl = nvq.DecodeList(entries, 1, 0)
+    info = dl.plan_info()
+    assert info["streaming"] and info["phases"] == 300 and info["waits"] == 0
+    skips = nvq.plan_describe_skips([dl.arr[i] for i in range(dl.n)], 1,
+                                    workgroups=torch.cuda.get_device_properties(0).multi_processor_count)
+    assert skips.max() == 255
+    for rep in range(2):
+        for e in entries:
+            e["y"].zero_()
+        dl.run_plan()
+        assert not dl.plan_timed_out()
+        for e, y_r in zip(entries, ys_ref):
+            assert np_ref.rel_l2(e["y"].cpu().numpy(), y_r) < 1e-5
+    dl.close()
+
+
 def test_streaming_plan_orders_dependent_phases():
     say("stream chain")
     # four phases, each reading the bf16 output of the one before it
