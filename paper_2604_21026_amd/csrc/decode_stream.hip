@@ -450,21 +450,39 @@ __device__ __forceinline__ void image_build(const Writer &wr, CPhase &ph, Shared
     const int nxc = (K + kXChunkElems - 1) / kXChunkElems;
     const uint4 *x = reinterpret_cast<const uint4 *>(ph.x);
     const uint4 *x2 = reinterpret_cast<const uint4 *>(ph.x2);
-    uint4 xsh[kMaxXShare];
+    uint4 xsh[kMaxXShare], x2sh[kMaxXShare];
     float ss = 0.0f;
+    // All requests first (the input, then the second operand of the transform), so
+    // that they are in flight together: issued piece by piece between the uses, a
+    // wave's two or three pieces cost it two or three trips to memory in a row.
+    const bool second = in_op == NVQ_IN_SILU_MUL || (in_op == NVQ_IN_RMSNORM && x2 != nullptr);
 #pragma unroll
     for (int k = 0; k < kMaxXShare; ++k) {
         const int j = w + k * kStreamWaves;
         int idx = j * 64 + lane;
         asm volatile("" : "+v"(idx));  // computed here, not kept through the kernel
         xsh[k] = make_uint4(0, 0, 0, 0);
+        if (j < nxc && idx < K / 8) xsh[k] = x[idx];
+    }
+#pragma unroll
+    for (int k = 0; k < kMaxXShare; ++k) {
+        const int j = w + k * kStreamWaves;
+        int idx = j * 64 + lane;
+        asm volatile("" : "+v"(idx));
+        x2sh[k] = make_uint4(0, 0, 0, 0);
+        if (second && j < nxc && idx < K / 8) x2sh[k] = x2[idx];
+    }
+#pragma unroll
+    for (int k = 0; k < kMaxXShare; ++k) {
+        const int j = w + k * kStreamWaves;
+        int idx = j * 64 + lane;
+        asm volatile("" : "+v"(idx));
         if (j < nxc && idx < K / 8) {
-            xsh[k] = x[idx];
             if (in_op == NVQ_IN_SILU_MUL) {
-                xsh[k] = silu_mul_bf16x8(xsh[k], x2[idx]);
+                xsh[k] = silu_mul_bf16x8(xsh[k], x2sh[k]);
             } else if (in_op == NVQ_IN_RMSNORM) {
                 if (x2) {
-                    xsh[k] = add_bf16x8(xsh[k], x2[idx]);
+                    xsh[k] = add_bf16x8(xsh[k], x2sh[k]);
                     if (store_h && ph.h_out) reinterpret_cast<uint4 *>(ph.h_out)[idx] = xsh[k];
                 }
                 ss += sumsq_bf16x8(xsh[k]);
@@ -519,6 +537,7 @@ __device__ __forceinline__ void image_build(const Writer &wr, CPhase &ph, Shared
         if (j < nxc)
             image_put<PER_GROUP>(wr, L, w4a8, G, j * 16 + (lane >> 2), lane, xsh[k], s_tok);
     }
+
 }
 
 // ---- per-wave stream state ---------------------------------------------------------
