@@ -49,17 +49,19 @@ struct StreamPhase {
     // spread evenly over them, which a phase that others wait for needs (it ends with
     // its busiest compute unit; 18 % of the step time of a dependent chain), while
     // independent phases stream faster (5 %) with a compute unit's waves on
-    // neighbouring rows.  Wave j' = (wave - rows_rot) mod W takes rows_base rows, one more
-    // if j' < rows_extra, in order of j'.  The host chooses rows_rot per phase so
-    // that the extra rows go to the waves that have received the fewest extra
-    // bytes so far.
+    // neighbouring rows.  Wave j' = (wave - rows_rot) mod W takes rows_base units
+    // of rows, one more if j' < rows_extra, in order of j'.  The host chooses
+    // rows_rot per phase so that the extra units go to the waves that have
+    // received the fewest bytes so far, or simply to the run of waves after the
+    // previous phase's, whichever leaves the heaviest wave of the table lighter.
     int rows_base, rows_extra, rows_rot;
-    // Rows are dealt in units of row_unit neighbours (rows_base and rows_extra
-    // count units; the last unit of the phase may be short).  pair_stream = 2 with G = 96, where a row is one and a half
-    // chunks: rows 2i and 2i + 1 are streamed as three full chunks, the middle one
-    // half of each row, instead of four chunks of which two are half empty; it
-    // needs an even number of rows in every segment, per-token activation scales
-    // and an even row_unit.  Otherwise 0.
+    // A unit is row_unit neighbouring rows (the last unit of the phase may be
+    // short): 1, or more where an independent phase is too short to give every
+    // wave kStreamThinChunks chunks.  pair_stream = 2 with G = 96, where a row is
+    // one and a half chunks: rows 2i and 2i + 1 are streamed as three full chunks,
+    // the middle one half of each row, instead of four chunks of which two are
+    // half empty; it needs an even number of rows in every segment, per-token
+    // activation scales and an even row_unit.  Otherwise 0.
     int row_unit, pair_stream;
     int spread;
     int wait_phase;        // latest earlier phase this one depends on, or -1
