@@ -272,7 +272,9 @@ int nvq_plan_describe(const nvq_linear *layers, int n, int M, int act_group, int
 /*
  * nvq_plan_describe_skips -- likewise the skip table of the persistent batch-1
  * kernel: out (host) receives workgroups * 12 rows (workgroup * 12 + streaming
- * wave) of *stride bytes; byte p of a row = the number of phases from p on (at
+ * wave; the kernel counts its workgroups XCD by XCD for this: of a grid of a
+ * multiple of 8, workgroup b is number (b mod 8) * grid / 8 + b / 8) of *stride
+ * bytes; byte p of a row = the number of phases from p on (at
  * most 255) that the wave passes without a look: it has no rows in them, they
  * wait for nobody and nobody waits for them.  *stride = 0 and nothing written if
  * the list does not qualify for that kernel; NVQ_ERR_WORKSPACE if out is too

@@ -43,7 +43,9 @@ struct StreamPhase {
     int K, G, gpl;         // G = K/32 (even), gpl = ceil(G/64) <= 7
     int precision;         // NVQ_W4A8 | NVQ_W4A16
     // Rows are dealt to the W = workgroups * kStreamWaves waves as evenly as whole
-    // rows allow.  wave = workgroup * kStreamWaves + wave in the workgroup, or, with
+    // rows allow.  Workgroups count XCD by XCD here (of a grid of a multiple of 8,
+    // workgroup b is number (b mod 8) * grid / 8 + b / 8), and so do the rows of the
+    // skip table.  wave = workgroup * kStreamWaves + wave in the workgroup, or, with
     // spread = 1, wave in the workgroup * workgroups + workgroup: then neighbours sit
     // on different compute units and the waves that get a phase's extra rows are
     // spread evenly over them, which a phase that others wait for needs (it ends with

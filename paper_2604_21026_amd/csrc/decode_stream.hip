@@ -220,7 +220,7 @@ __device__ __forceinline__ void issue_next_run(Issue &c, CPhase *tab, CSkipWord 
             c.part = 1;
             int first, count;
             stream_wave_rows(ph.rows_base, ph.rows_extra, ph.rows_rot,
-                             ph.spread ? w * (int)gridDim.x + (int)blockIdx.x : gw,
+                             ph.spread ? w * (int)gridDim.x + (gw - w) / kStreamWaves : gw,
                              (int)gridDim.x * kStreamWaves, first, count);
             c.row = first * ph.row_unit;
             c.row_stop = c.row + count * ph.row_unit;  // (the last unit of a phase may be short)
@@ -598,8 +598,12 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
     const int wg = blockIdx.x;
     const int nwg = gridDim.x;
     // The wave's place in the two orders rows are dealt in (StreamPhase::spread).
-    const int gw = wg * kStreamWaves + w;
-    const int gw_spread = w * nwg + wg;
+    // For the dealing the workgroups are counted XCD by XCD (workgroup b runs on XCD
+    // b mod 8): the compute units of an XCD then stream neighbouring parts of a
+    // matrix (8B step 0.655 -> 0.645 ms).
+    const int wgd = (nwg & 7) == 0 ? (wg & 7) * (nwg >> 3) + (wg >> 3) : wg;
+    const int gw = wgd * kStreamWaves + w;
+    const int gw_spread = w * nwg + wgd;
     if (threadIdx.x == 0) lds_write4(lds_addr(&sh.abort), 0u);
     trace_mark(trace, wg, w, lane, 0, 5);  // kernel entered
 #ifdef NVQ_TRACE_ENDS
