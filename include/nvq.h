@@ -276,9 +276,11 @@ int nvq_plan_describe(const nvq_linear *layers, int n, int M, int act_group, int
  * multiple of 8, workgroup b is number (b mod 8) * grid / 8 + b / 8) of *stride
  * bytes; byte p of a row = the number of phases from p on (at
  * most 255) that the wave passes without a look: it has no rows in them, they
- * wait for nobody and nobody waits for them.  *stride = 0 and nothing written if
+ * wait for nobody and nobody waits for them.  One row per workgroup follows:
+ * byte p = 1 if all its waves pass phase p (its loader wave then leaves that
+ * phase's activations where they are), else 0.  *stride = 0 and nothing written if
  * the list does not qualify for that kernel; NVQ_ERR_WORKSPACE if out is too
- * small (out_bytes < rows * stride, stride = phases + 4 rounded up to 4).
+ * small (out_bytes < workgroups * 13 * stride, stride = phases + 4 rounded up to 4).
  */
 int nvq_plan_describe_skips(const nvq_linear *layers, int n, int M, int act_group, int flags,
                             int workgroups, uint8_t *out, size_t out_bytes, int *stride);

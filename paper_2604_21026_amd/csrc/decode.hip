@@ -93,7 +93,7 @@ Workspace carve(void *base, int M, int n, const ListSizes &ls) {
     w.dummy = take(1024);
     w.images = take(image_bytes);
     w.skips = reinterpret_cast<uint8_t *>(
-        take(M == 1 ? (size_t)kStreamMaxWg * kStreamWaves * (size_t)stream_skip_stride(n) : 0));
+        take(M == 1 ? (size_t)kStreamMaxWg * (kStreamWaves + 1) * (size_t)stream_skip_stride(n) : 0));
     const size_t nn = (size_t)(n > 0 ? n : 1);
     w.gtab = reinterpret_cast<GroupPhase *>(take(M > 1 ? nn * sizeof(GroupPhase) : 0));
     w.gjobs = reinterpret_cast<uint16_t *>(take(M > 1 ? nn * 2 : 0));
@@ -543,7 +543,7 @@ std::vector<StreamPhase> stream_table(const nvq_linear *L, const std::vector<Pha
     // no rows and have no barrier (nobody waits for them, they wait for nobody).
     if (skips) {
         const int stride = stream_skip_stride((int)P);
-        skips->assign((size_t)waves * stride, 0);
+        skips->assign((size_t)(waves + nwg) * stride, 0);
         std::vector<uint8_t> active((size_t)waves);
         for (size_t pp = P; pp-- > 0;) {
             const StreamPhase &sp = tab[pp];
@@ -563,6 +563,12 @@ std::vector<StreamPhase> stream_table(const nvq_linear *L, const std::vector<Pha
                     const int next = pp + 1 < P ? row[pp + 1] : 0;
                     row[pp] = (uint8_t)(next >= 255 ? 255 : next + 1);
                 }
+            }
+            for (int wgi = 0; wgi < nwg; ++wgi) {
+                bool any = false;
+                for (int k = 0; k < kStreamWaves; ++k)
+                    any = any || active[(size_t)wgi * kStreamWaves + k];
+                (*skips)[(size_t)(waves + wgi) * stride + pp] = any ? 0 : 1;
             }
         }
     }

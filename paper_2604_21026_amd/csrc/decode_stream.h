@@ -17,6 +17,8 @@ constexpr int kStreamImageFlags = kStreamMaxWg + 64;
 // Skip table: one row of skip_stride(phases) bytes per streaming wave (workgroup *
 // kStreamWaves + wave); byte p = how many phases from p on the wave may pass
 // without a look (it has no rows in them and they have no barriers), at most 255.
+// Then one row per workgroup: byte p = 1 if all its waves pass phase p (the loader
+// wave does not fetch that phase's image), else 0.
 constexpr int stream_skip_stride(int nphase) { return (nphase + 4 + 3) / 4 * 4; }
 constexpr int kStreamPairG = 96;  // groups per row for which rows are streamed in pairs
 // Chunks a wave should at least get from a phase it works on (measured on 1B-, 3B-
@@ -106,7 +108,7 @@ static inline int stream_image_bytes(int K, int precision, int act_group) {
 // image (0 skips the prologue).  `dummy` is any valid
 // 1 KiB of device memory.  `trace` is nullptr or nphase * 8 words that
 // receive workgroup 0's per-phase timestamps (of the phases its first wave does
-// not pass).  `skips`: the skip table, nwg * kStreamWaves rows.  `pairs` says that some phase of
+// not pass).  `skips`: the skip table, nwg * (kStreamWaves + 1) rows.  `pairs` says that some phase of
 // the table streams its rows in pairs (pair_stream): the kernel variant that has
 // that path is launched.
 int launch_decode_stream(const StreamPhase *tab_dev, const uint8_t *skips, int nphase, int nimages,

@@ -615,6 +615,10 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
     // this wave's row of the skip table (the loader wave has none and looks at every phase)
     CSkipWord *skips = (CSkipWord *)(skips_generic + (size_t)(w < kStreamWaves ? gw : 0) *
                                                          (size_t)stream_skip_stride(nphase));
+    // the workgroup's row behind the waves' rows: byte p != 0 = no wave of it works in phase p
+    CSkipWord *wg_passes =
+        (CSkipWord *)(skips_generic + ((size_t)nwg * kStreamWaves + (size_t)wgd) *
+                                          (size_t)stream_skip_stride(nphase));
     Stream st;
     st.ic.p = 0;
     st.ic.part = 0;
@@ -769,9 +773,14 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
             // Run ahead of the streaming waves.  Only regions that free up
             // without a barrier of phase p or later may be waited for here:
             // the streaming waves may need this wave at such a barrier first.
-            while (live && q < nphase && q <= p + kLookahead && tab[q].wait_phase < 0 &&
-                   tab[q].img_need < p)
+            for (;;) {
+                // images of phases in which no wave of this workgroup works are not loaded
+                while (q < nphase && phase_skip(wg_passes, q) != 0) ++q;
+                if (!(live && q < nphase && q <= p + kLookahead && tab[q].wait_phase < 0 &&
+                      tab[q].img_need < p))
+                    break;
                 live = load_image();
+            }
             if (ph.publish && live) {
                 flush();
                 lds_barrier();

@@ -369,11 +369,12 @@ def plan_describe(linears: Sequence[Linear], M: int, act_group: int = 0, ordered
 def plan_describe_skips(linears: Sequence[Linear], M: int, act_group: int = 0,
                         ordered: bool = False, workgroups: int = 256):
     """The skip table of the batch-1 persistent kernel (no device needed): a uint8 array
-    [workgroups * 12][phases] (row = workgroup * 12 + streaming wave), or None."""
+    [workgroups * 13][phases + padding]: rows workgroup * 12 + streaming wave, then one row per
+    workgroup; or None."""
     import numpy as np
     n = len(linears)
     arr = (Linear * max(n, 1))(*linears)
-    rows = workgroups * 12
+    rows = workgroups * 13
     cap = rows * (n + 8)
     out = np.zeros(cap, np.uint8)
     stride = C.c_int(0)

@@ -93,9 +93,10 @@ def test_skip_table_passes_exactly_the_phases_without_rows_and_barriers(model, o
     nb = synth.MODELS[model][0]
     layers = model_list(model, synth.make_precision_map(nb, nb // 2))
     waves, phases = nvq.plan_describe(layers, 1, ordered=ordered)
-    skips = nvq.plan_describe_skips(layers, 1, ordered=ordered)
+    table = nvq.plan_describe_skips(layers, 1, ordered=ordered)
     P = len(phases)
-    assert skips.shape[0] == waves and skips.shape[1] >= P + 4 and skips.shape[1] % 4 == 0
+    assert table.shape[0] == waves + waves // 12 and table.shape[1] >= P + 4 and table.shape[1] % 4 == 0
+    skips, wg_passes = table[:waves], table[waves:]
     assert not skips[:, P:].any()                       # the padding reads as "do not pass"
     # which wave works in which phase, from the dealing alone
     nwg = waves // 12
@@ -105,8 +106,11 @@ def test_skip_table_passes_exactly_the_phases_without_rows_and_barriers(model, o
             _, count = rows_of_wave(ph, j, waves)
             g = (j % nwg) * 12 + j // nwg if ph["spread"] else j
             active[p, g] = count > 0 or ph["wait"] >= 0 or ph["publish"] == 1
+    # a workgroup leaves a phase's image alone exactly if none of its 12 waves works in it
+    assert np.array_equal(wg_passes[:, :P].T, ~active.reshape(P, nwg, 12).any(axis=2))
+    assert not wg_passes[:, P:].any()
     if ordered:
-        assert not skips.any()                          # every phase has barriers
+        assert not skips.any() and not wg_passes.any()  # every phase has barriers
         return
     assert skips.any()
     for g in range(0, waves, 37):                       # a sample of the waves
