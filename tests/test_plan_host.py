@@ -130,6 +130,56 @@ def test_skip_table_passes_exactly_the_phases_without_rows_and_barriers(model, o
         assert seen == [p for p in range(P) if active[p, g]]
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_random_lists_deal_every_row_once_and_skip_only_idle_phases(seed):
+    """Random shapes (rows from 1 to 40000, K any multiple of 32 the kernel takes, several
+    layers per phase, chained and independent phases, 64 to 304 workgroups)."""
+    rng = np.random.default_rng(4200 + seed)
+    a = Arena()
+    layers, prev_y, prev_n = [], None, 0
+    for _ in range(int(rng.integers(3, 40))):
+        K = int(rng.choice([32, 96, 1024, 2048, 2112, 3072, 4096, 8192, 14336]))
+        chained = prev_y is not None and prev_n == K and rng.random() < 0.5
+        x = prev_y if chained else a.take(K * 2)
+        for _ in range(int(rng.integers(1, 4))):          # layers sharing the input: one phase
+            N = int(rng.choice([1, 2, 7, 40, 96, 511, 1024, 3072, 4097, 40000]))
+            y_bf16 = chained is False and rng.random() < 0.3
+            y = a.take(N * 4)
+            layers.append(linear(a, N, K, x, y=y, prec=int(rng.integers(0, 2)), y_f32=not y_bf16))
+            prev_y, prev_n = (y, N) if y_bf16 else (None, 0)   # only bf16 outputs can feed a layer
+    nwg = int(rng.choice([64, 256, 304]))
+    ordered = bool(rng.random() < 0.25)
+    waves, phases = nvq.plan_describe(layers, 1, ordered=ordered, workgroups=nwg)
+    assert waves == nwg * 12
+    table = nvq.plan_describe_skips(layers, 1, ordered=ordered, workgroups=nwg)
+    P = len(phases)
+    skips, wg_passes = table[:waves], table[waves:]
+    active = np.zeros((P, waves), bool)
+    for p, ph in enumerate(phases):
+        covered = np.zeros(ph["rows"], np.int32)
+        barrier = ph["wait"] >= 0 or ph["publish"] == 1
+        assert ph["spread"] == int(barrier)
+        if barrier:
+            assert ph["row_unit"] == max(ph["pair_stream"], 1)
+        for j in range(waves):
+            first, count = rows_of_wave(ph, j, waves)
+            covered[first:first + count] += 1
+            g = (j % nwg) * 12 + j // nwg if ph["spread"] else j
+            active[p, g] = count > 0 or barrier
+        assert covered.min() == 1 and covered.max() == 1
+    for g in range(0, waves, 53):
+        p, seen = 0, []
+        while p < P:
+            p += int(skips[g, p])
+            if p < P:
+                seen.append(p)
+                p += 1
+        # a visited phase is one the wave works in, or where a run of 255 passes ended
+        assert set(p for p in range(P) if active[p, g]) <= set(seen)
+        assert all(active[p, g] or skips[g, max(p - 255, 0)] == 255 for p in seen)
+    assert np.array_equal(wg_passes[:, :P].T, ~active.reshape(P, nwg, 12).any(axis=2))
+
+
 def test_image_regions_never_overwrite_an_image_that_may_still_be_read():
     layers = model_list("llama-8b", synth.make_precision_map(32, 16))
     _, phases = nvq.plan_describe(layers, 1)
