@@ -407,6 +407,41 @@ def test_streaming_plan_matches_oracle_on_repeated_runs(name, group, ordered):
     dl.close()
 
 
+@pytest.mark.parametrize("seed", range(4))
+def test_streaming_plan_of_random_lists_matches_oracle(seed):
+    """Random phases (1 to 3 layers on one input; rows from 1 to 9000; K with whole, ragged and
+    one-and-a-half-chunk rows), both precisions, with and without forced ordering."""
+    rng = np.random.default_rng(7300 + seed)
+    entries, host = [], []
+    for ph in range(int(rng.integers(4, 14))):
+        K = int(rng.choice([96, 1024, 2048, 2112, 3072, 4096, 8192]))
+        xh = act(7400 + 100 * seed + ph, 1, K)
+        xd = xh.to(DEV)
+        bit = int(rng.integers(0, 2))
+        for k in range(int(rng.integers(1, 4))):
+            N = int(rng.choice([1, 2, 7, 40, 96, 511, 1024, 3072, 4097, 9000]))
+            _, q, s = packed(7500 + 1000 * seed + 10 * ph + k, N, K)
+            qd, sd = to_dev_packed(q, s)
+            entries.append(dict(qweight=qd, scales=sd, x=xd, precision=bit,
+                                y=torch.zeros((1, N), dtype=torch.float32, device=DEV)))
+            host.append(dict(qweight=q, scales=s, x=u16(xh), precision=bit))
+    ordered = bool(seed & 1)
+    say("stream plan, random list", seed, len(entries), "layers, ordered", ordered)
+    ys_ref = oracle.decode_linears(host, 1, 0)
+    dl = nvq.DecodeList(entries, 1, 0, ordered=ordered)
+    assert dl.plan_info()["streaming"]
+    for rep in range(2):
+        for e in entries:
+            e["y"].zero_()
+        dl.run_plan()
+        assert not dl.plan_timed_out()
+        for i, (e, y_r) in enumerate(zip(entries, ys_ref)):
+            err = np_ref.rel_l2(e["y"].cpu().numpy(), y_r)
+            # (a handful of outputs can be small against their terms: the bar only)
+            assert err < (1e-5 if y_r.size >= 96 else TOL), (rep, i, err)
+    dl.close()
+
+
 def test_streaming_plan_of_many_tiny_phases():
     """300 independent layers of 40 rows: nearly every wave has no rows in more than 255 phases
     in a row (the skip table's cap), a few work in one phase in a hundred."""
