@@ -94,7 +94,7 @@ __global__ __launch_bounds__(256) void gemv_w4a16_m1_kernel(GemvSegs S, int G,
             const RowRef r = locate_row(S, t * U + u, G);
 #pragma unroll
             for (int i = 0; i < GPL; ++i) {
-                w[u][i] = r.qw[gc[i]];
+                w[u][i] = stream_load16(r.qw + gc[i]);  // read once: non-temporal, whole lines
                 s[u][i] = r.sc[gc[i]];
             }
         }
@@ -179,7 +179,7 @@ template <int GPL, int LPR>
 static int launch_m1(const GemvSegs &S, int G, const uint16_t *x, hipStream_t st) {
     constexpr int U = tile_rows(GPL);
     const int tiles = (S.total_rows + U - 1) / U;
-    const dim3 grid(gemv_grid(tiles, 256 / LPR, 2)), block(256);
+    const dim3 grid(gemv_grid(tiles, 256 / LPR, kM1WgPerCu)), block(256);
     hipLaunchKernelGGL((gemv_w4a16_m1_kernel<GPL, LPR>), grid, block, 0, st, S, G,
                        reinterpret_cast<const uint4 *>(x));
     NVQ_HIP_TRY(hipGetLastError());

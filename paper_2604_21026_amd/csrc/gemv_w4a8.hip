@@ -71,7 +71,7 @@ __global__ __launch_bounds__(256) void gemv_w4a8_m1_kernel(GemvSegs S, int G,
             const RowRef r = locate_row(S, t * U + u, G);
 #pragma unroll
             for (int i = 0; i < GPL; ++i) {
-                w[u][i] = r.qw[gc[i]];
+                w[u][i] = stream_load16(r.qw + gc[i]);  // read once: non-temporal, whole lines
                 s[u][i] = r.sc[gc[i]];
             }
         }
@@ -162,7 +162,7 @@ static int launch_m1(const GemvSegs &S, int G, const int8_t *xq, const float *xs
                      const int32_t *xgsum, bool per_group, bool debug, hipStream_t st) {
     constexpr int U = tile_rows(GPL);
     const int tiles = (S.total_rows + U - 1) / U;
-    const dim3 grid(gemv_grid(tiles, 256 / LPR, 2)), block(256);
+    const dim3 grid(gemv_grid(tiles, 256 / LPR, kM1WgPerCu)), block(256);
     const uint4 *x4 = reinterpret_cast<const uint4 *>(xq);
 #define NVQ_GO(PG, DBG)                                                                        \
     hipLaunchKernelGGL((gemv_w4a8_m1_kernel<GPL, LPR, PG, DBG>), grid, block, 0, st, S, G, x4, \
