@@ -196,8 +196,11 @@ typedef struct nvq_linear {
  * K a multiple of 128, phases that do not depend on each other share two or
  * three launches on the matrix cores.  Otherwise one or two launches per phase
  * are enqueued.  All give the same results (up to the fp32 summation order).
- * nvq_decode_linears copies its phase table to the device on every call
- * (a blocking copy of a few KiB); a plan does that once.
+ * nvq_decode_linears copies its tables to the device on every call (blocking
+ * copies: the phase table, a few KiB, and at M = 1 one byte per streaming wave
+ * and phase, ~0.4 MB for 129 phases); a plan does that once.  At M = 1 the
+ * workspace also reserves that table for the largest grid (13312 bytes per
+ * phase).
  * nvq_decode_workspace_bytes returns 0 for invalid arguments.
  */
 size_t nvq_decode_workspace_bytes(const nvq_linear *layers, int n, int M, int act_group);
