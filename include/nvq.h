@@ -153,8 +153,7 @@ int nvq_silu_mul_bf16(const uint16_t *g, const uint16_t *u, int M, int K, uint16
  *   NVQ_IN_PLAIN     the layer reads x_bf16
  *   NVQ_IN_RMSNORM   the layer reads nvq_rms_norm_bf16(x_bf16, x2_bf16, gamma_bf16, eps)
  *                    (x2_bf16 may be NULL; with x2_bf16 the sum x + x2 goes to
- *                    h_out_bf16 if that is not NULL: the updated residual stream;
- *                    h_out_bf16 must not be x_bf16 or x2_bf16)
+ *                    h_out_bf16 if that is not NULL: the updated residual stream)
  *   NVQ_IN_SILU_MUL  the layer reads nvq_silu_mul_bf16(x_bf16, x2_bf16)
  */
 enum { NVQ_IN_PLAIN = 0, NVQ_IN_RMSNORM = 1, NVQ_IN_SILU_MUL = 2 };
@@ -188,6 +187,10 @@ typedef struct nvq_linear {
  *   other: a phase whose input overlaps an earlier phase's output, or whose
  *   output overlaps an earlier phase's input or output, starts only after
  *   that phase has completed; phases that share no buffer may overlap.
+ *   Inside a phase nothing is ordered: no output of a phase (y of each of its
+ *   layers, h_out_bf16) may overlap what the phase reads (x_bf16, x2_bf16,
+ *   gamma_bf16) or another of its outputs; such a list is refused with
+ *   NVQ_ERR_INVALID_ARG.
  *   workspace  device buffer of at least nvq_decode_workspace_bytes(...)
  *              bytes, 256-byte aligned; its contents are scratch.
  * At M = 1 the whole list runs as ONE persistent kernel that keeps streaming
@@ -202,10 +205,19 @@ typedef struct nvq_linear {
  * workspace also reserves that table for the largest grid (13312 bytes per
  * phase).
  * nvq_decode_workspace_bytes returns 0 for invalid arguments.
+ * The persistent kernels wait for each other with bounded spins; a wait that
+ * gives up (the grid was not co-resident, say because another stream held
+ * compute units) sets a status word in the workspace and leaves the outputs
+ * invalid.  nvq_decode_linears itself does not look at it (it does not
+ * synchronise): nvq_decode_status synchronises `stream` and reports the word of
+ * the last walk that used `workspace` (the uint32 at byte
+ * NVQ_WORKSPACE_STATUS_OFFSET; plan creation clears it).
  */
+#define NVQ_WORKSPACE_STATUS_OFFSET 4096
 size_t nvq_decode_workspace_bytes(const nvq_linear *layers, int n, int M, int act_group);
 int nvq_decode_linears(const nvq_linear *layers, int n, int M, int act_group,
                        void *workspace, size_t workspace_bytes, void *stream);
+int nvq_decode_status(const void *workspace, void *stream, int *timed_out);
 
 /*
  * Plans: the same walk, prepared once and run many times (the role graph

@@ -14,6 +14,7 @@
 // tokens of shapes the matrix-core kernel takes, as two launches per batch of
 // mutually independent phases (one grid quantises, one multiplies).
 #include <algorithm>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -70,6 +71,8 @@ size_t quant_bytes(int M, int K) {
            round_up((size_t)M * (K / 32) * 4, 256);
 }
 
+static_assert(kStreamMaxWg * 4 == NVQ_WORKSPACE_STATUS_OFFSET, "the header states the offset");
+
 Workspace carve(void *base, int M, int n, const ListSizes &ls) {
     const int maxK = ls.maxK;
     const size_t image_bytes = ls.image_bytes;
@@ -82,14 +85,15 @@ Workspace carve(void *base, int M, int n, const ListSizes &ls) {
         off += round_up(bytes, 256);
         return p;
     };
+    // the flag block comes first: the status word has a fixed place in every workspace
+    w.flags = reinterpret_cast<uint32_t *>(take(kStreamMaxWg * 4));
+    w.status = reinterpret_cast<uint32_t *>(take(256));
+    w.imgflags = reinterpret_cast<uint32_t *>(take((size_t)(n > 0 ? n : 1) * 4));
     w.xt = reinterpret_cast<uint16_t *>(take(ls.transforms ? (size_t)M * maxK * 2 : 0));
     w.xq = reinterpret_cast<int8_t *>(take((size_t)M * maxK));
     w.xscale = reinterpret_cast<float *>(take((size_t)M * G * 4));
     w.xgsum = reinterpret_cast<int32_t *>(take((size_t)M * G * 4));
     w.tab = reinterpret_cast<StreamPhase *>(take((size_t)(n > 0 ? n : 1) * sizeof(StreamPhase)));
-    w.flags = reinterpret_cast<uint32_t *>(take(kStreamMaxWg * 4));
-    w.status = reinterpret_cast<uint32_t *>(take(256));
-    w.imgflags = reinterpret_cast<uint32_t *>(take((size_t)(n > 0 ? n : 1) * 4));
     w.dummy = take(1024);
     w.images = take(image_bytes);
     w.skips = reinterpret_cast<uint8_t *>(
@@ -126,10 +130,6 @@ int check_layers(const nvq_linear *L, int n, int M, int act_group, ListSizes *si
         if (e.in_op != NVQ_IN_PLAIN &&
             (!aligned(e.x2_bf16, 16) || !aligned(e.gamma_bf16, 16) || !aligned(e.h_out_bf16, 16)))
             return NVQ_ERR_ALIGN;
-        // the sum is stored while the inputs are still being read
-        if (e.in_op == NVQ_IN_RMSNORM && e.h_out_bf16 &&
-            (e.h_out_bf16 == e.x_bf16 || e.h_out_bf16 == e.x2_bf16))
-            return NVQ_ERR_INVALID_ARG;
         tr = tr || e.in_op != NVQ_IN_PLAIN;
         if (e.y_dtype != NVQ_F32 && e.y_dtype != NVQ_BF16) return NVQ_ERR_INVALID_ARG;
         if (e.N <= 0 || e.K <= 0 || (e.K % 32) != 0 || e.K > NVQ_MAX_K) return NVQ_ERR_SHAPE;
@@ -247,6 +247,44 @@ struct Range {
 };
 bool overlap(const Range &a, const Range &b) { return a.lo < b.hi && b.lo < a.hi; }
 
+// What a phase reads (input, second operand and norm weights) and what it
+// writes (every layer's output, the residual sum).
+void phase_ranges(const nvq_linear *L, const Phase &ph, int M, std::vector<Range> *in,
+                  std::vector<Range> *out) {
+    const nvq_linear &e0 = L[ph.first];
+    const size_t xbytes = (size_t)M * e0.K * 2;
+    in->push_back({(uintptr_t)e0.x_bf16, (uintptr_t)e0.x_bf16 + xbytes});
+    if (e0.in_op != NVQ_IN_PLAIN) {
+        if (e0.x2_bf16) in->push_back({(uintptr_t)e0.x2_bf16, (uintptr_t)e0.x2_bf16 + xbytes});
+        if (e0.gamma_bf16)
+            in->push_back({(uintptr_t)e0.gamma_bf16, (uintptr_t)e0.gamma_bf16 + (size_t)e0.K * 2});
+        if (e0.in_op == NVQ_IN_RMSNORM && e0.x2_bf16 && e0.h_out_bf16)
+            out->push_back({(uintptr_t)e0.h_out_bf16, (uintptr_t)e0.h_out_bf16 + xbytes});
+    }
+    for (int k = 0; k < ph.count; ++k) {
+        const nvq_linear &e = L[ph.first + k];
+        const size_t bytes = (size_t)M * e.N * (e.y_dtype == NVQ_F32 ? 4 : 2);
+        out->push_back({(uintptr_t)e.y, (uintptr_t)e.y + bytes});
+    }
+}
+
+// The layers of a phase run concurrently and read their input while outputs
+// are already being stored: no output of a phase may overlap anything the phase
+// reads, or another of its outputs.
+int check_phase_hazards(const nvq_linear *L, const std::vector<Phase> &phases, int M) {
+    for (const Phase &ph : phases) {
+        std::vector<Range> in, out;
+        phase_ranges(L, ph, M, &in, &out);
+        for (size_t a = 0; a < out.size(); ++a) {
+            for (const Range &r : in)
+                if (overlap(out[a], r)) return NVQ_ERR_INVALID_ARG;
+            for (size_t b = a + 1; b < out.size(); ++b)
+                if (overlap(out[a], out[b])) return NVQ_ERR_INVALID_ARG;
+        }
+    }
+    return NVQ_OK;
+}
+
 // Per phase the latest earlier phase it conflicts with (it reads what that
 // phase wrote, or writes what that phase read or wrote), or -1; with `ordered`
 // every phase depends on its predecessor.
@@ -255,24 +293,7 @@ std::vector<int> phase_deps(const nvq_linear *L, const std::vector<Phase> &phase
     const size_t P = phases.size();
     std::vector<int> deps(P, -1);
     std::vector<std::vector<Range>> xin(P), yout(P);  // what a phase reads and writes
-    for (size_t p = 0; p < P; ++p) {
-        const nvq_linear &e0 = L[phases[p].first];
-        const size_t xbytes = (size_t)M * e0.K * 2;
-        xin[p].push_back({(uintptr_t)e0.x_bf16, (uintptr_t)e0.x_bf16 + xbytes});
-        if (e0.in_op != NVQ_IN_PLAIN) {
-            if (e0.x2_bf16) xin[p].push_back({(uintptr_t)e0.x2_bf16, (uintptr_t)e0.x2_bf16 + xbytes});
-            if (e0.gamma_bf16)
-                xin[p].push_back({(uintptr_t)e0.gamma_bf16,
-                                  (uintptr_t)e0.gamma_bf16 + (size_t)e0.K * 2});
-            if (e0.in_op == NVQ_IN_RMSNORM && e0.x2_bf16 && e0.h_out_bf16)
-                yout[p].push_back({(uintptr_t)e0.h_out_bf16, (uintptr_t)e0.h_out_bf16 + xbytes});
-        }
-        for (int k = 0; k < phases[p].count; ++k) {
-            const nvq_linear &e = L[phases[p].first + k];
-            const size_t bytes = (size_t)M * e.N * (e.y_dtype == NVQ_F32 ? 4 : 2);
-            yout[p].push_back({(uintptr_t)e.y, (uintptr_t)e.y + bytes});
-        }
-    }
+    for (size_t p = 0; p < P; ++p) phase_ranges(L, phases[p], M, &xin[p], &yout[p]);
     for (size_t p = 1; p < P; ++p) {
         int dep = ordered ? (int)p - 1 : -1;
         for (size_t q = 0; q < p && !ordered; ++q) {
@@ -667,6 +688,10 @@ extern "C" int nvq_plan_create(const nvq_linear *layers, int n, int M, int act_g
     if (!pl) return NVQ_ERR_UNSUPPORTED;
     pl->layers.assign(layers, layers + n);
     pl->phases = group_phases(pl->layers.data(), n);
+    if (check_phase_hazards(pl->layers.data(), pl->phases, M) != NVQ_OK) {
+        delete pl;
+        return NVQ_ERR_INVALID_ARG;
+    }
     pl->ws = ws;
     pl->M = M;
     pl->act_group = act_group;
@@ -792,6 +817,7 @@ extern "C" int nvq_plan_describe(const nvq_linear *layers, int n, int M, int act
     const int rc = check_layers(layers, n, M, act_group, &ls);
     if (rc != NVQ_OK) return rc;
     const std::vector<Phase> phases = group_phases(layers, n);
+    if (check_phase_hazards(layers, phases, M) != NVQ_OK) return NVQ_ERR_INVALID_ARG;
     const bool ordered = (flags & NVQ_PLAN_ORDERED) != 0;
     int nimages = 0;
     const std::vector<StreamPhase> tab =
@@ -837,6 +863,7 @@ extern "C" int nvq_plan_describe_skips(const nvq_linear *layers, int n, int M, i
     const int rc = check_layers(layers, n, M, act_group, &ls);
     if (rc != NVQ_OK) return rc;
     const std::vector<Phase> phases = group_phases(layers, n);
+    if (check_phase_hazards(layers, phases, M) != NVQ_OK) return NVQ_ERR_INVALID_ARG;
     int nimages = 0;
     std::vector<uint8_t> skips;
     const std::vector<StreamPhase> tab =
@@ -857,6 +884,7 @@ extern "C" int nvq_plan_describe_batches(const nvq_linear *layers, int n, int M,
     const int rc = check_layers(layers, n, M, act_group, &ls);
     if (rc != NVQ_OK) return rc;
     const std::vector<Phase> phases = group_phases(layers, n);
+    if (check_phase_hazards(layers, phases, M) != NVQ_OK) return NVQ_ERR_INVALID_ARG;
     Workspace none = {};  // pointers into it are computed, never followed
     const GroupPlan gp = group_plan(layers, phases, M, act_group, (flags & NVQ_PLAN_ORDERED) != 0,
                                     none);
@@ -885,11 +913,7 @@ extern "C" int nvq_plan_describe_batches(const nvq_linear *layers, int n, int M,
 
 extern "C" int nvq_plan_trace(nvq_plan *pl, uint64_t *buf, size_t bytes) {
     if (!pl) return NVQ_ERR_INVALID_ARG;
-    size_t need = (size_t)pl->nphase * nvq::kStreamTraceSlots * 8;
-#ifdef NVQ_TRACE_ENDS
-    // working builds with per-wave entry and end times: 16 words per workgroup, twice
-    need += (size_t)32 * (pl->nwg > 0 ? pl->nwg : 0) * 8;
-#endif
+    const size_t need = (size_t)pl->nphase * nvq::kStreamTraceSlots * 8;
     if (buf && (bytes < need || !nvq::aligned(buf, 8))) return NVQ_ERR_WORKSPACE;
     pl->trace = reinterpret_cast<unsigned long long *>(buf);
     return NVQ_OK;
@@ -921,4 +945,14 @@ extern "C" int nvq_decode_linears(const nvq_linear *layers, int n, int M, int ac
     rc = nvq_plan_run(pl, stream);
     nvq_plan_destroy(pl);
     return rc;
+}
+
+extern "C" int nvq_decode_status(const void *workspace, void *stream, int *timed_out) {
+    if (!workspace || !timed_out || !nvq::aligned(workspace, 256)) return NVQ_ERR_INVALID_ARG;
+    uint32_t v = 0;
+    NVQ_HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
+    NVQ_HIP_TRY(hipMemcpy(&v, static_cast<const char *>(workspace) + NVQ_WORKSPACE_STATUS_OFFSET, 4,
+                          hipMemcpyDeviceToHost));
+    *timed_out = (int)v;
+    return NVQ_OK;
 }

@@ -42,7 +42,7 @@ struct StreamPhase {
     int in_op;
     float eps;
     int nseg, total_rows;
-    int K, G, gpl;         // G = K/32 (even), gpl = ceil(G/64) <= 7
+    int K, G, gpl;         // G = K/32, gpl = ceil(G/64) <= 7
     int precision;         // NVQ_W4A8 | NVQ_W4A16
     // Rows are dealt to the W = workgroups * kStreamWaves waves as evenly as whole
     // rows allow.  Workgroups count XCD by XCD here (of a grid of a multiple of 8,

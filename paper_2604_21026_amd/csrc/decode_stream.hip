@@ -606,9 +606,6 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
     const int gw_spread = w * nwg + wgd;
     if (threadIdx.x == 0) lds_write4(lds_addr(&sh.abort), 0u);
     trace_mark(trace, wg, w, lane, 0, 5);  // kernel entered
-#ifdef NVQ_TRACE_ENDS
-    if (trace && lane == 0) trace[nphase * kTraceSlots + 16 * (nwg + wg) + w] = wall_clock64();
-#endif
 
     // The streaming waves request their first chunks at once: weights depend on
     // nothing, so the ring fills while the prologue below prepares the images.
@@ -729,6 +726,7 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
                 if (lds_read4_uniform(abort_a)) return false;
                 if (++spins > kSpinLimit) {
                     lds_write4(abort_a, 1u);
+                    __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     return false;
                 }
                 __builtin_amdgcn_s_sleep(2);
@@ -1139,11 +1137,6 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
             }
         }
     }
-#ifdef NVQ_TRACE_ENDS
-    if (trace && lane == 0) {
-        trace[nphase * kTraceSlots + 16 * wg + w] = wall_clock64();
-    }
-#endif
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // no load may outlive the wave
 }
 
@@ -1152,11 +1145,16 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
 int stream_grid_limit() {
     static int cached = -1;
     if (cached < 0) {
-        int per_cu = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_stream_kernel<false, false>,
-                                                         kStreamThreads, 0) != hipSuccess)
-            per_cu = 0;
-        cached = per_cu >= 1 ? device_cu_count() : 0;
+        // every instantiation that may be launched must fit a compute unit
+        int a = 0, b = 0, c = 0;
+        const bool ok =
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&a, decode_stream_kernel<false, false>,
+                                                         kStreamThreads, 0) == hipSuccess &&
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&b, decode_stream_kernel<true, false>,
+                                                         kStreamThreads, 0) == hipSuccess &&
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&c, decode_stream_kernel<false, true>,
+                                                         kStreamThreads, 0) == hipSuccess;
+        cached = ok && a >= 1 && b >= 1 && c >= 1 ? device_cu_count() : 0;
     }
     return cached;
 }

@@ -77,6 +77,42 @@ def test_decode_list_validation_and_workspace_size():
     assert L.nvq_decode_linears(C.byref(arr), 0, 1, 0, None, 0, None) == 0
 
 
+def test_outputs_that_overlap_their_own_phase_are_refused():
+    """Inside a phase nothing is ordered: an output over the phase's input, second operand,
+    norm weights or a sibling's output is rejected before anything touches a device."""
+    L = nvq.lib()
+    q, s, x, y0, y1 = 0x10000, 0x20000, 0x30000, 0x40000, 0x50000
+    out = (C.c_int32 * 64)()
+
+    def describe(entries):
+        arr = (nvq.Linear * len(entries))(*entries)
+        return L.nvq_plan_describe(C.byref(arr), len(entries), 1, 0, 0, 256, out, 64)
+
+    lin = lambda y, **kw: nvq.Linear(q, s, 64, 64, kw.get("x", x), y, kw.get("dt", 1), 0,
+                                     kw.get("op", 0), 1e-5, kw.get("x2"), kw.get("gamma"),
+                                     kw.get("h"))
+    assert describe([lin(y0), lin(y1)]) == 0
+    assert describe([lin(x)]) == 1                       # y in place over x
+    assert describe([lin(x + 64)]) == 1                  # y over the second half of x (bf16 x 64)
+    assert describe([lin(x + 128)]) == 0                 # just behind x
+    assert describe([lin(y0), lin(y0 + 64)]) == 1        # sibling outputs overlap (bf16 y x 64)
+    assert describe([lin(y0), lin(y0 + 128)]) == 0
+    assert describe([lin(y0, dt=0), lin(y0 + 128)]) == 1  # the fp32 output is twice as long
+    g, x2, h = 0x60000, 0x70000, 0x80000
+    assert describe([lin(y0, op=1, x2=x2, gamma=g, h=h)]) == 0
+    assert describe([lin(g, op=1, x2=x2, gamma=g, h=h)]) == 1   # y over the norm weights
+    assert describe([lin(y0, op=1, x2=x2, gamma=g, h=x2)]) == 1  # residual sum over x2
+    assert describe([lin(y0, op=1, x2=x2, gamma=g, h=y0)]) == 1  # residual sum over y
+    assert describe([lin(x2, op=2, x2=x2)]) == 1                  # y over the SiLU operand
+    # a later phase may of course overwrite an earlier phase's input: that is ordered
+    assert describe([lin(y0), lin(x, x=y0)]) == 0
+    ws = 0x100000
+    arr = (nvq.Linear * 1)(lin(x))
+    assert L.nvq_decode_linears(C.byref(arr), 1, 1, 0, ws, 1 << 24, None) == 1
+    assert L.nvq_decode_status(None, None, C.byref(C.c_int())) == 1
+    assert L.nvq_decode_status(ws, None, None) == 1
+
+
 def test_precision_from_scores_follows_the_papers_table():
     from tests.test_oracle_act_gemv import _golden
     scores, l1, counts = _golden()

@@ -242,7 +242,7 @@ def test_lists_the_persistent_kernel_does_not_take():
     big = [linear(a, 8, 16384, a.take(16384 * 2))]           # wider than an image holds
     waves, phases = nvq.plan_describe(big, 1)
     assert waves == 0 and len(phases) == 1 and phases[0]["wait"] == -1
-    waves, _ = nvq.plan_describe(model_list("llama-1b", [0] * 16), 4)   # batch 4: not batch 1
+    waves, _ = nvq.plan_describe(model_list_m("llama-1b", [0] * 16, 4), 4)   # batch 4: not batch 1
     assert waves == 0
 
 
