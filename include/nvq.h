@@ -220,6 +220,27 @@ int nvq_decode_linears(const nvq_linear *layers, int n, int M, int act_group,
 int nvq_decode_status(const void *workspace, void *stream, int *timed_out);
 
 /*
+ * nvq_decode_linears_static -- the same walk for callers that cannot allocate
+ * device memory or pass a workspace: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  It only enqueues kernels
+ * (one or two launches per phase plus one per input transform; no copies, no
+ * hipMalloc / hipFree, no allocating library call), so it is slower than the
+ * persistent kernel of nvq_decode_linears but can be captured.  The
+ * activation codes, scales and code sums of the phase being run (and its
+ * transformed input) live in a device array inside the library, one copy of
+ * NVQ_STATIC_SCRATCH_BYTES per GPU held until the process ends; a list that
+ * needs more (M * maxK * 3 bytes with input transforms, M * maxK without, plus
+ * M * maxK / 4) is refused with NVQ_ERR_WORKSPACE.  Results equal those of
+ * nvq_decode_linears up to the fp32 summation order.  Every call on a GPU
+ * uses that GPU's one array: calls that overlap on one GPU (two streams, two
+ * threads) race; issue them on one stream.  Nothing has to be cleared between
+ * calls (a phase writes what it reads there before reading it).
+ */
+#define NVQ_STATIC_SCRATCH_BYTES (2u << 20)
+int nvq_decode_linears_static(const nvq_linear *layers, int n, int M, int act_group,
+                              void *stream);
+
+/*
  * Plans: the same walk, prepared once and run many times (the role graph
  * capture plays in the paper's decode loop).  A plan is a small host object
  * (the only thing the library allocates, with new/delete); it keeps a copy of

@@ -956,3 +956,65 @@ extern "C" int nvq_decode_status(const void *workspace, void *stream, int *timed
     *timed_out = (int)v;
     return NVQ_OK;
 }
+
+// ---- the walk for callers that cannot allocate ------------------------------
+namespace nvq {
+namespace {
+
+// Activation codes, scales and code sums of the phase being run (and its
+// transformed input): the scratch memory of the per-phase launches.  One copy
+// per GPU, held until the process ends; its address on a device is looked up
+// once, with that device current.
+static __device__ __align__(256) unsigned char scratch[NVQ_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices];  // per device, nullptr until looked up
+std::mutex g_scratch_mutex;
+
+int scratch_for_current_device(void **out) {
+    int dev = 0;
+    NVQ_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return NVQ_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        NVQ_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p || !aligned(p, 256)) return NVQ_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return NVQ_OK;
+}
+
+}  // namespace
+}  // namespace nvq
+
+extern "C" int nvq_decode_linears_static(const nvq_linear *layers, int n, int M, int act_group,
+                                         void *stream) {
+    using namespace nvq;
+    ListSizes ls;
+    const int rc = check_layers(layers, n, M, act_group, &ls);
+    if (rc != NVQ_OK) return rc;
+    if (n == 0) return NVQ_OK;
+    const std::vector<Phase> phases = group_phases(layers, n);
+    if (check_phase_hazards(layers, phases, M) != NVQ_OK) return NVQ_ERR_INVALID_ARG;
+    // the part of the workspace that launches per phase use
+    const size_t G = (size_t)ls.maxK / 32;
+    const size_t xt_bytes = round_up(ls.transforms ? (size_t)M * ls.maxK * 2 : 0, 256);
+    const size_t xq_bytes = round_up((size_t)M * ls.maxK, 256);
+    const size_t gs_bytes = round_up((size_t)M * G * 4, 256);
+    if (xt_bytes + xq_bytes + 2 * gs_bytes > (size_t)NVQ_STATIC_SCRATCH_BYTES)
+        return NVQ_ERR_WORKSPACE;
+    void *base = nullptr;
+    const int sc = scratch_for_current_device(&base);
+    if (sc != NVQ_OK) return sc;
+    Workspace ws = {};
+    char *b = static_cast<char *>(base);
+    ws.xt = reinterpret_cast<uint16_t *>(b);
+    ws.xq = reinterpret_cast<int8_t *>(b + xt_bytes);
+    ws.xscale = reinterpret_cast<float *>(b + xt_bytes + xq_bytes);
+    ws.xgsum = reinterpret_cast<int32_t *>(b + xt_bytes + xq_bytes + gs_bytes);
+    // every phase writes what it reads from the scratch before reading it
+    // (transform, quantisation), so nothing has to be cleared between calls
+    return walk_per_phase(layers, phases, M, act_group, ws, (hipStream_t)stream);
+}

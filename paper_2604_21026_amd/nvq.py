@@ -22,7 +22,7 @@ IN_PLAIN, IN_RMSNORM, IN_SILU_MUL = 0, 1, 2
 EXPORTS = (
     "nvq_status_string", "nvq_last_hip_error", "nvq_pack_int4", "nvq_quant_act_i8",
     "nvq_gemv_w4a16", "nvq_gemv_w4a8", "nvq_decode_workspace_bytes", "nvq_decode_linears",
-    "nvq_decode_status",
+    "nvq_decode_status", "nvq_decode_linears_static",
     "nvq_plan_create", "nvq_plan_run", "nvq_plan_info", "nvq_plan_status", "nvq_plan_trace",
     "nvq_plan_destroy", "nvq_plan_describe", "nvq_plan_describe_batches",
     "nvq_plan_describe_skips",
@@ -75,6 +75,7 @@ def lib() -> C.CDLL:
     L.nvq_decode_workspace_bytes.argtypes = [vp, ci, ci, ci]
     L.nvq_decode_linears.argtypes = [vp, ci, ci, ci, vp, sz, vp]
     L.nvq_decode_status.argtypes = [vp, vp, C.POINTER(ci)]
+    L.nvq_decode_linears_static.argtypes = [vp, ci, ci, ci, vp]
     L.nvq_plan_create.argtypes = [vp, ci, ci, ci, ci, vp, sz, vp, C.POINTER(vp)]
     L.nvq_plan_run.argtypes = [vp, vp]
     L.nvq_plan_info.argtypes = [vp, C.POINTER(ci), C.POINTER(ci), C.POINTER(ci)]
@@ -91,7 +92,8 @@ def lib() -> C.CDLL:
     L.nvq_stream_read.argtypes = [vp, sz, vp, vp]
     L.nvq_stream_copy.argtypes = [vp, vp, sz, vp]
     for f in ("nvq_pack_int4", "nvq_quant_act_i8", "nvq_gemv_w4a16", "nvq_gemv_w4a8",
-              "nvq_decode_linears", "nvq_decode_status", "nvq_precision_from_scores", "nvq_stream_read",
+              "nvq_decode_linears", "nvq_decode_status", "nvq_decode_linears_static",
+              "nvq_precision_from_scores", "nvq_stream_read",
               "nvq_stream_copy", "nvq_plan_create", "nvq_plan_run", "nvq_plan_info",
               "nvq_plan_status", "nvq_plan_trace"):
         getattr(L, f).restype = ci
@@ -283,6 +285,11 @@ class DecodeList:
         _check(lib().nvq_decode_linears(C.byref(self.arr), self.n, self.M, self.act_group,
                                         self.workspace.data_ptr(), self.workspace.numel(),
                                         _stream()), "nvq_decode_linears")
+
+    def run_static(self):
+        """One walk through nvq_decode_linears_static (no workspace, launches only)."""
+        _check(lib().nvq_decode_linears_static(C.byref(self.arr), self.n, self.M, self.act_group,
+                                               _stream()), "nvq_decode_linears_static")
 
     def timed_out(self) -> bool:
         """Synchronises; True if a wait inside the last walk on this workspace gave up."""
