@@ -195,7 +195,16 @@ typedef struct nvq_linear {
  *              bytes, 256-byte aligned; its contents are scratch.
  * At M = 1 the whole list runs as ONE persistent kernel that keeps streaming
  * the weights of coming phases while a phase is being set up (needs every
- * K <= 14336).  At 2 <= M <= 32 with per-token activation scales and every
+ * K <= 14336).  In that kernel an input operand (x_bf16, or x2_bf16 of an input
+ * transform) that is exactly the bf16 output y of one earlier layer (same
+ * address, N of that layer = K of this one), or exactly the h_out_bf16 of an
+ * earlier phase, and has not been written since, is handed over "by mail": the
+ * producing waves post each value a second time, tagged, in the workspace, and
+ * the consumers poll those words instead of waiting for flags and reading the
+ * caller's buffer (which still receives every output).  This is the fast way
+ * for the links of a real decode step (output projection -> next norm, gate
+ * and up -> SiLU-multiply, down projection -> next block); all other
+ * dependencies wait through per-workgroup flags.  At 2 <= M <= 32 with per-token activation scales and every
  * K a multiple of 128, phases that do not depend on each other share two or
  * three launches on the matrix cores.  Otherwise one or two launches per phase
  * are enqueued.  All give the same results (up to the fp32 summation order).
@@ -258,21 +267,32 @@ int nvq_decode_linears_static(const nvq_linear *layers, int n, int M, int act_gr
  *                    a persistent grid fed through LDS rings, which needs
  *                    every K a multiple of 512 and 16-byte aligned scale
  *                    rows), 0 for launches per phase;
- *                    waits = number of phases that wait for an earlier phase
- *                    (grouped launches: number of batch boundaries)
+ *                    waits = number of phases that wait for an earlier phase,
+ *                    through flags or for mail (grouped launches: number of
+ *                    batch boundaries)
  *   nvq_plan_status  synchronises `stream` and reports whether a wait inside
  *                    a persistent kernel gave up (its spins are bounded so
  *                    that a grid that cannot be co-resident ends with an
- *                    error instead of a hang); outputs are invalid then
+ *                    error instead of a hang); outputs are invalid then.
+ *                    *timed_out = 0, or a code: low byte = which wait (1 flags
+ *                    of an earlier phase, 2 a prepared input, 3 room for an
+ *                    input in local memory, 4 its announcement, 5 mail; the
+ *                    small-batch kernel: 1), the bits above it = the phase
+ *                    (mail: 2 * phase + 0 for x, + 1 for x2)
  *   nvq_plan_trace   diagnostic: give a device buffer of phases * 8 uint64
  *                    (or NULL to stop); later runs of the persistent kernel
  *                    store workgroup 0's timestamps per phase in it (100 MHz
  *                    wall clock), taken by its first wave (phases in which
- *                    that wave has no rows and no barrier keep what was there):
- *                    [0] phase entered,
- *                    [1] dependency satisfied, [2] input staged, [3] all
- *                    waves done (published phases only), [4] published,
- *                    [5] input seen, [6] activations ready, [7] own rows done
+ *                    that wave has no rows and no barrier keep what was there).
+ *                    A buffer of workgroups * phases * 8 words (workgroups =
+ *                    compute units of the device) makes every workgroup
+ *                    record, workgroup after workgroup.  Per phase:
+ *                    [0] phase entered, [1] flags seen (phases that wait),
+ *                    [2] input staged, [3] the workgroup's share of the
+ *                    operands has arrived (phases that wait; phases that
+ *                    publish through flags: all waves done), [4] published,
+ *                    [5] this wave's share of the operands has arrived,
+ *                    [6] activations ready, [7] own rows done
  */
 typedef struct nvq_plan nvq_plan;
 enum { NVQ_PLAN_DEFAULT = 0, NVQ_PLAN_ORDERED = 1 };
@@ -288,9 +308,11 @@ int nvq_plan_trace(nvq_plan *plan, uint64_t *buf, size_t bytes);
  * and checked for alignment, never followed).  `workgroups` = compute units the
  * persistent kernel would use.  out (host, out_words int32): [0] phases,
  * [1] the number of streaming waves the rows are dealt to if the list
- * qualifies for the persistent kernel, else 0; then 15 words per
+ * qualifies for the persistent kernel, else 0; then 16 words per
  * phase: first entry, entries, the latest earlier phase it must wait for (-1:
- * none), and for the persistent kernel: published (someone waits for it),
+ * none; in the persistent kernel: through the flags, operands that arrive by
+ * mail do not count), and for the persistent kernel: published (someone waits
+ * for it through the flags),
  * rows, rows per wave, waves with one more row, the wave that gets the first
  * of those, offset of the activation image in the LDS image area, the latest
  * phase whose image it overwrites there (-1: none), image bytes, 1 if the
@@ -300,7 +322,10 @@ int nvq_plan_trace(nvq_plan *plan, uint64_t *buf, size_t bytes);
  * few KiB), and 2 if neighbouring rows are streamed in pairs (K = 3072 with an
  * even number of rows in every layer of the phase), else 0, and 1 if the order
  * the waves are dealt rows in runs over the workgroups first (phases that wait
- * or are waited for), 0 if over the waves of a workgroup first.
+ * or are waited for), 0 if over the waves of a workgroup first, and which
+ * operands the phase takes from a mailbox instead of the caller's buffer (bit 0:
+ * x, bit 1: x2; see nvq_decode_linears), bit 2: it posts an output or its
+ * residual sum as mail.
  * NVQ_ERR_WORKSPACE if out is too small.
  */
 int nvq_plan_describe(const nvq_linear *layers, int n, int M, int act_group, int flags,

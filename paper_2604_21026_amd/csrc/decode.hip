@@ -47,6 +47,7 @@ struct Workspace {
     uint32_t *gteams;   // [n][2][kRingMaxParts + 1]  per batch: the parts of the ring kernel's XCDs
     uint16_t *gimgs;    // [group_images]      phase of every operand image unit, batch after batch
     char *gquant;       // per-phase activation codes, scales and code sums
+    uint32_t *mail;     // mailboxes of the streaming kernel (M = 1): tagged copies of outputs
     size_t bytes;
 };
 
@@ -58,6 +59,7 @@ struct ListSizes {
     size_t group_quant;  // codes + scales + code sums of all W4A8 entries (M > 1)
     size_t group_images; // operand image units of all entries (M > 1)
     bool transforms;     // some entry has an input transform
+    size_t mail_words;   // mailboxes for every output and residual sum (M = 1)
 };
 
 // Activations of a phase in the order the persistent small-batch kernel loads
@@ -105,6 +107,8 @@ Workspace carve(void *base, int M, int n, const ListSizes &ls) {
     w.gteams = reinterpret_cast<uint32_t *>(take(M > 1 ? nn * 2 * (kRingMaxParts + 1) * 4 : 0));
     w.gimgs = reinterpret_cast<uint16_t *>(take(M > 1 ? ls.group_images * 2 : 0));
     w.gquant = take(M > 1 ? ls.group_quant : 0);
+    w.mail = reinterpret_cast<uint32_t *>(
+        take(M == 1 ? stream_mail_stride(ls.mail_words) * kMailReplicas * 4 : 0));
     w.bytes = off;
     return w;
 }
@@ -114,7 +118,7 @@ int check_layers(const nvq_linear *L, int n, int M, int act_group, ListSizes *si
     if (act_group != 0 && act_group != 32) return NVQ_ERR_INVALID_ARG;
     if (M <= 0 || M > NVQ_MAX_M) return NVQ_ERR_SHAPE;
     int mk = 32;
-    size_t ib = 0, gu = 0, gq = 0, gi = 0;
+    size_t ib = 0, gu = 0, gq = 0, gi = 0, mw = 0;
     bool tr = false;
     for (int i = 0; i < n; ++i) {
         const nvq_linear &e = L[i];
@@ -146,6 +150,9 @@ int check_layers(const nvq_linear *L, int n, int M, int act_group, ListSizes *si
         const size_t plain = e.precision == NVQ_W4A8 ? quant_bytes(M, e.K) : 0;
         gq += image > plain ? image : plain;
         gi += (size_t)image_units(M, e.K);
+        // upper bound: every bf16 output and every residual sum has a mailbox
+        if (e.y_dtype == NVQ_BF16) mw += stream_mail_words(e.N);
+        if (e.in_op == NVQ_IN_RMSNORM && e.x2_bf16 && e.h_out_bf16) mw += stream_mail_words(e.K);
     }
     sizes->maxK = mk;
     sizes->image_bytes = ib;
@@ -153,6 +160,7 @@ int check_layers(const nvq_linear *L, int n, int M, int act_group, ListSizes *si
     sizes->group_quant = gq;
     sizes->group_images = gi;
     sizes->transforms = tr;
+    sizes->mail_words = mw;
     return NVQ_OK;
 }
 
@@ -285,15 +293,87 @@ int check_phase_hazards(const nvq_linear *L, const std::vector<Phase> &phases, i
     return NVQ_OK;
 }
 
+// Mail links (batch 1, persistent kernel).  An input operand (x, or x2 of a
+// transform) of phase p is linked if the latest earlier phase that writes any
+// of its bytes writes exactly that vector as one bf16 output (y of one of its
+// layers with N = K of p, or its residual sum): then p takes the operand from
+// the mailbox that phase posts it in, never from the caller's buffer.
+struct OperandLink {
+    int phase;  // producing phase, or -1: not linked
+    int seg;    // its layer (segment of the phase), or kMaxSeg: its residual sum
+};
+struct PhaseLinks {
+    OperandLink x, x2;
+};
+
+OperandLink find_link(const nvq_linear *L, const std::vector<Phase> &phases, size_t p,
+                      const uint16_t *operand) {
+    const OperandLink none = {-1, 0};
+    if (!operand) return none;
+    const nvq_linear &e0 = L[phases[p].first];
+    const Range r = {(uintptr_t)operand, (uintptr_t)operand + (size_t)e0.K * 2};
+    for (size_t q = p; q-- > 0;) {
+        const Phase &pq = phases[q];
+        const nvq_linear &q0 = L[pq.first];
+        OperandLink hit = none;
+        int overlaps = 0;
+        for (int k = 0; k < pq.count; ++k) {
+            const nvq_linear &e = L[pq.first + k];
+            const Range y = {(uintptr_t)e.y,
+                             (uintptr_t)e.y + (size_t)e.N * (e.y_dtype == NVQ_F32 ? 4 : 2)};
+            if (!overlap(y, r)) continue;
+            ++overlaps;
+            if (y.lo == r.lo && y.hi == r.hi && e.y_dtype == NVQ_BF16) hit = {(int)q, k};
+        }
+        if (q0.in_op == NVQ_IN_RMSNORM && q0.x2_bf16 && q0.h_out_bf16) {
+            const Range h = {(uintptr_t)q0.h_out_bf16, (uintptr_t)q0.h_out_bf16 + (size_t)q0.K * 2};
+            if (overlap(h, r)) {
+                ++overlaps;
+                if (h.lo == r.lo && h.hi == r.hi) hit = {(int)q, kMaxSeg};
+            }
+        }
+        if (overlaps == 0) continue;          // an older phase may have written it
+        return overlaps == 1 ? hit : none;     // the latest writer decides
+    }
+    return none;
+}
+
+std::vector<PhaseLinks> find_links(const nvq_linear *L, const std::vector<Phase> &phases, int M,
+                                   bool ordered) {
+    std::vector<PhaseLinks> links(phases.size(), PhaseLinks{{-1, 0}, {-1, 0}});
+    if (M != 1 || ordered) return links;
+    for (size_t p = 1; p < phases.size(); ++p) {
+        const nvq_linear &e0 = L[phases[p].first];
+        links[p].x = find_link(L, phases, p, e0.x_bf16);
+        const bool second = e0.in_op == NVQ_IN_SILU_MUL || (e0.in_op == NVQ_IN_RMSNORM && e0.x2_bf16);
+        if (second) links[p].x2 = find_link(L, phases, p, e0.x2_bf16);
+    }
+    return links;
+}
+
 // Per phase the latest earlier phase it conflicts with (it reads what that
 // phase wrote, or writes what that phase read or wrote), or -1; with `ordered`
-// every phase depends on its predecessor.
+// every phase depends on its predecessor.  Operands that arrive by mail
+// (`links`) are not read from memory and take no part in this.
 std::vector<int> phase_deps(const nvq_linear *L, const std::vector<Phase> &phases, int M,
-                            bool ordered) {
+                            bool ordered, const std::vector<PhaseLinks> *links = nullptr) {
     const size_t P = phases.size();
     std::vector<int> deps(P, -1);
     std::vector<std::vector<Range>> xin(P), yout(P);  // what a phase reads and writes
-    for (size_t p = 0; p < P; ++p) phase_ranges(L, phases[p], M, &xin[p], &yout[p]);
+    for (size_t p = 0; p < P; ++p) {
+        phase_ranges(L, phases[p], M, &xin[p], &yout[p]);
+        if (!links) continue;
+        const nvq_linear &e0 = L[phases[p].first];
+        auto drop = [&](const uint16_t *operand) {
+            for (size_t i = 0; i < xin[p].size(); ++i)
+                if (xin[p][i].lo == (uintptr_t)operand) {
+                    xin[p].erase(xin[p].begin() + (long)i);
+                    return;
+                }
+        };
+        if ((*links)[p].x.phase >= 0) drop(e0.x_bf16);
+        if ((*links)[p].x2.phase >= 0) drop(e0.x2_bf16);
+    }
     for (size_t p = 1; p < P; ++p) {
         int dep = ordered ? (int)p - 1 : -1;
         for (size_t q = 0; q < p && !ordered; ++q) {
@@ -447,19 +527,29 @@ int lightest_window(const std::vector<uint64_t> &load, int len) {
 // Each phase records the latest earlier phase it conflicts with (it reads what
 // that phase wrote, or writes what that phase read or wrote); with `ordered`
 // every phase is made to depend on its predecessor.
+// `mail`: start of the mailbox area in the workspace (words are handed out from
+// it; *mail_words receives how many).
 std::vector<StreamPhase> stream_table(const nvq_linear *L, const std::vector<Phase> &phases, int M,
                                       int act_group, int nwg, bool ordered, char *images,
-                                      int *nimages, std::vector<uint8_t> *skips = nullptr) {
+                                      int *nimages, std::vector<uint8_t> *skips = nullptr,
+                                      uint32_t *mail = nullptr, size_t *mail_words = nullptr) {
     std::vector<StreamPhase> tab;
+    if (mail_words) *mail_words = 0;
     if (M != 1 || nwg <= 0 || nwg > kStreamMaxWg) return tab;
     const int waves = nwg * kStreamWaves;
     // bytes of extra rows dealt to each wave so far: the extra rows of a phase
     // go to the run of waves that has received the least
     std::vector<uint64_t> extra_bytes((size_t)waves, 0);
-    const std::vector<int> deps = phase_deps(L, phases, M, ordered);
-    std::vector<char> published(phases.size(), 0);
-    for (size_t p = 1; p < phases.size(); ++p)
+    const std::vector<PhaseLinks> links = find_links(L, phases, M, ordered);
+    const std::vector<int> deps = phase_deps(L, phases, M, ordered, &links);
+    // a phase someone waits for, through the flags or by mail; a phase that waits
+    std::vector<char> published(phases.size(), 0), waits(phases.size(), 0);
+    for (size_t p = 1; p < phases.size(); ++p) {
         if (deps[p] >= 0) published[(size_t)deps[p]] = 1;
+        if (links[p].x.phase >= 0) published[(size_t)links[p].x.phase] = 1;
+        if (links[p].x2.phase >= 0) published[(size_t)links[p].x2.phase] = 1;
+        waits[p] = deps[p] >= 0 || links[p].x.phase >= 0 || links[p].x2.phase >= 0;
+    }
     size_t pi = 0;
     for (const Phase &ph : phases) {
         const size_t p_index = pi++;
@@ -491,7 +581,7 @@ std::vector<StreamPhase> stream_table(const nvq_linear *L, const std::vector<Pha
         sp.precision = e0.precision;
         sp.row_unit = 1;
         sp.pair_stream = 0;
-        sp.spread = deps[p_index] >= 0 || published[p_index];
+        sp.spread = waits[p_index] || published[p_index];
         if (G == kStreamPairG && act_group != 32) {
             bool even = true;
             for (int k = 0; k < ph.count; ++k) even = even && L[ph.first + k].N % 2 == 0;
@@ -503,7 +593,7 @@ std::vector<StreamPhase> stream_table(const nvq_linear *L, const std::vector<Pha
         // sums) is then spent once per that many chunks, and the other waves pass.
         // Only where nobody waits for the phase and it waits for nobody: there the
         // waves are free to drift apart and the bytes even out over the phases.
-        if (deps[p_index] < 0 && !published[p_index]) {
+        if (!waits[p_index] && !published[p_index]) {
             const int half_chunks_per_row = sp.pair_stream ? 3 : 2 * sp.gpl;  // in half chunks
             int unit = sp.row_unit;
             while (unit * half_chunks_per_row < 2 * kStreamThinChunks) unit += sp.row_unit;
@@ -515,6 +605,10 @@ std::vector<StreamPhase> stream_table(const nvq_linear *L, const std::vector<Pha
         sp.rows_rot = 0;  // set below
         sp.wait_phase = -1;
         sp.publish = 0;
+        sp.dep = waits[p_index];
+        sp.mail_x = sp.mail_x2 = nullptr;
+        sp.mail_h = nullptr;
+        for (int k = 0; k < kMaxSeg; ++k) sp.mail_y[k] = nullptr;
         sp.img = nullptr;
         sp.img_chunks = 0;
         tab.push_back(sp);
@@ -560,6 +654,27 @@ std::vector<StreamPhase> stream_table(const nvq_linear *L, const std::vector<Pha
         tab[p].wait_phase = deps[p];
         if (deps[p] >= 0) tab[deps[p]].publish = 1;
     }
+    // Mailboxes: one per linked output, shared by the phases that read it.
+    {
+        size_t used = 0;
+        auto box = [&](const OperandLink &l) -> uint32_t * {
+            StreamPhase &src = tab[(size_t)l.phase];
+            uint32_t *&slot = l.seg == kMaxSeg ? src.mail_h : src.mail_y[l.seg];
+            if (!slot) {
+                // (never followed on the host; without a workspace only counted)
+                slot = (mail ? mail : reinterpret_cast<uint32_t *>(uintptr_t(4096))) + used;
+                const int n = l.seg == kMaxSeg ? src.K
+                                               : src.row_end[l.seg] - (l.seg ? src.row_end[l.seg - 1] : 0);
+                used += stream_mail_words(n);
+            }
+            return slot;
+        };
+        for (size_t p = 1; p < P; ++p) {
+            if (links[p].x.phase >= 0) tab[p].mail_x = box(links[p].x);
+            if (links[p].x2.phase >= 0) tab[p].mail_x2 = box(links[p].x2);
+        }
+        if (mail_words) *mail_words = used;
+    }
     // The skip table: a wave passes, without looking at them, the phases that give it
     // no rows and have no barrier (nobody waits for them, they wait for nobody).
     if (skips) {
@@ -568,7 +683,7 @@ std::vector<StreamPhase> stream_table(const nvq_linear *L, const std::vector<Pha
         std::vector<uint8_t> active((size_t)waves);
         for (size_t pp = P; pp-- > 0;) {
             const StreamPhase &sp = tab[pp];
-            const bool skippable = sp.wait_phase < 0 && !sp.publish;
+            const bool skippable = !sp.dep && !sp.publish;  // no barrier in the phase
             for (int j = 0; j < waves; ++j) {
                 int jj = j - sp.rows_rot;
                 jj = jj < 0 ? jj + waves : jj;
@@ -607,7 +722,7 @@ std::vector<StreamPhase> stream_table(const nvq_linear *L, const std::vector<Pha
     int cursor = 0;
     for (size_t p = 0; p < P; ++p) {
         const int bytes = stream_image_bytes(tab[p].K, tab[p].precision, act_group);
-        if (tab[p].wait_phase < 0) {
+        if (!tab[p].dep) {
             tab[p].img = reinterpret_cast<const uint4 *>(images + off);
             tab[p].img_chunks = bytes / 1024;
             off += (size_t)bytes;
@@ -646,7 +761,7 @@ __global__ void fill_u32_kernel(uint32_t *p, int n, uint32_t v) {
 }  // namespace nvq
 
 namespace nvq {
-constexpr int kDescribeWords = 15;  // words per phase written by nvq_plan_describe
+constexpr int kDescribeWords = 16;  // words per phase written by nvq_plan_describe
 }
 
 struct nvq_plan {
@@ -662,7 +777,11 @@ struct nvq_plan {
     bool ring;         // grouped launches use the persistent ring kernel
     uint32_t runs;     // walks issued so far (advances the flag base)
     bool pairs;        // some phase of the streaming table deals its rows in pairs
+    bool mail;         // some phase of the streaming table posts or reads mail
+    int nmail;         // phases that take an operand from a mailbox
+    size_t mail_stride;  // words between the replicas of a mailbox
     unsigned long long *trace;  // device buffer for per-phase timestamps, or nullptr
+    int trace_wgs;     // workgroups that record there
 };
 
 extern "C" size_t nvq_decode_workspace_bytes(const nvq_linear *layers, int n, int M,
@@ -697,7 +816,11 @@ extern "C" int nvq_plan_create(const nvq_linear *layers, int n, int M, int act_g
     pl->act_group = act_group;
     pl->runs = 0;
     pl->pairs = false;
+    pl->mail = false;
+    pl->nmail = 0;
+    pl->mail_stride = 0;
     pl->trace = nullptr;
+    pl->trace_wgs = 0;
     pl->nwg = 0;
     pl->nphase = 0;
     pl->nwaits = 0;
@@ -707,11 +830,18 @@ extern "C" int nvq_plan_create(const nvq_linear *layers, int n, int M, int act_g
     const int nwg = n > 0 ? stream_grid_limit() : 0;
     int nimages = 0;
     std::vector<uint8_t> skips;
+    size_t mail_words = 0;
     const std::vector<StreamPhase> tab =
         stream_table(pl->layers.data(), pl->phases, M, act_group, nwg,
-                     (flags & NVQ_PLAN_ORDERED) != 0, ws.images, &nimages, &skips);
+                     (flags & NVQ_PLAN_ORDERED) != 0, ws.images, &nimages, &skips, ws.mail,
+                     &mail_words);
     if (!tab.empty()) {
-        for (const StreamPhase &sp : tab) pl->pairs = pl->pairs || sp.pair_stream != 0;
+        for (const StreamPhase &sp : tab) {
+            pl->pairs = pl->pairs || sp.pair_stream != 0;
+            pl->nmail += sp.mail_x || sp.mail_x2;
+        }
+        pl->mail = mail_words > 0;
+        pl->mail_stride = stream_mail_stride(ls.mail_words);
         // pageable source: the copy has left the host buffer when the call returns
         hipError_t e = hipMemcpyAsync(ws.tab, tab.data(), tab.size() * sizeof(StreamPhase),
                                       hipMemcpyHostToDevice, st);
@@ -723,6 +853,17 @@ extern "C" int nvq_plan_create(const nvq_linear *layers, int n, int M, int act_g
                                words, 0u);
             e = hipGetLastError();
         }
+        if (e == hipSuccess && mail_words > 0) {
+            // no word of any replica carries a tag yet (tags start at 1)
+            const size_t all = pl->mail_stride * kMailReplicas;
+            if (all > 0x7fffffffu) {
+                delete pl;
+                return NVQ_ERR_UNSUPPORTED;
+            }
+            hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((all + 255) / 256)), dim3(256), 0, st,
+                               ws.mail, (int)all, 0u);
+            e = hipGetLastError();
+        }
         if (e != hipSuccess) {
             set_hip_error(e, "nvq_plan_create");
             delete pl;
@@ -731,7 +872,7 @@ extern "C" int nvq_plan_create(const nvq_linear *layers, int n, int M, int act_g
         pl->nwg = nwg;
         pl->nphase = (int)tab.size();
         pl->nimages = nimages;
-        for (const StreamPhase &sp : tab) pl->nwaits += sp.wait_phase >= 0;
+        for (const StreamPhase &sp : tab) pl->nwaits += sp.dep;
     } else if (n > 0) {
         const GroupPlan gp = group_plan(pl->layers.data(), pl->phases, M, act_group,
                                         (flags & NVQ_PLAN_ORDERED) != 0, ws);
@@ -776,11 +917,12 @@ extern "C" int nvq_plan_run(nvq_plan *pl, void *stream) {
     if (pl->layers.empty()) return NVQ_OK;
     if (pl->nwg > 0) {
         const uint32_t base = pl->runs * (uint32_t)(pl->nphase + 2);
+        const uint32_t tag = pl->runs % 65535u + 1u;  // 1..65535, never that of the walk before
         ++pl->runs;
         return launch_decode_stream(pl->ws.tab, pl->ws.skips, pl->nphase, pl->nimages, pl->act_group,
-                                    pl->pairs,
-                                    pl->ws.flags, pl->ws.status, base, pl->ws.dummy, pl->nwg,
-                                    pl->trace, st);
+                                    pl->pairs, pl->mail, tag, (uint32_t)pl->mail_stride,
+                                    pl->ws.flags, pl->ws.status, base,
+                                    pl->ws.dummy, pl->nwg, pl->trace, pl->trace_wgs, st);
     }
     if (!pl->batches.empty()) {
         for (const GroupBatch &b : pl->batches) {
@@ -832,7 +974,7 @@ extern "C" int nvq_plan_describe(const nvq_linear *layers, int n, int M, int act
         int32_t *o = out + 2 + p * kDescribeWords;
         o[0] = phases[p].first;
         o[1] = phases[p].count;
-        o[2] = deps[p];
+        o[2] = tab.empty() ? deps[p] : tab[p].wait_phase;
         for (int k = 3; k < kDescribeWords; ++k) o[k] = 0;
         if (!tab.empty()) {
             const StreamPhase &sp = tab[p];
@@ -848,6 +990,9 @@ extern "C" int nvq_plan_describe(const nvq_linear *layers, int n, int M, int act
             o[12] = sp.row_unit;
             o[13] = sp.pair_stream;
             o[14] = sp.spread;
+            bool posts = sp.mail_h != nullptr;
+            for (int k = 0; k < kMaxSeg; ++k) posts = posts || sp.mail_y[k] != nullptr;
+            o[15] = (sp.mail_x ? 1 : 0) + (sp.mail_x2 ? 2 : 0) + (posts ? 4 : 0);
         }
     }
     return NVQ_OK;
@@ -913,9 +1058,11 @@ extern "C" int nvq_plan_describe_batches(const nvq_linear *layers, int n, int M,
 
 extern "C" int nvq_plan_trace(nvq_plan *pl, uint64_t *buf, size_t bytes) {
     if (!pl) return NVQ_ERR_INVALID_ARG;
-    const size_t need = (size_t)pl->nphase * nvq::kStreamTraceSlots * 8;
-    if (buf && (bytes < need || !nvq::aligned(buf, 8))) return NVQ_ERR_WORKSPACE;
+    const size_t one = (size_t)pl->nphase * nvq::kStreamTraceSlots * 8;
+    if (buf && (bytes < one || !nvq::aligned(buf, 8))) return NVQ_ERR_WORKSPACE;
     pl->trace = reinterpret_cast<unsigned long long *>(buf);
+    // room for every workgroup: all of them record, else the first one only
+    pl->trace_wgs = buf ? (pl->nwg > 0 && bytes >= one * (size_t)pl->nwg ? pl->nwg : 1) : 0;
     return NVQ_OK;
 }
 

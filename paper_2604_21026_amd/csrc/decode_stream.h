@@ -68,8 +68,28 @@ struct StreamPhase {
     // activation scales and an even row_unit.  Otherwise 0.
     int row_unit, pair_stream;
     int spread;
-    int wait_phase;        // latest earlier phase this one depends on, or -1
-    int publish;           // 1 if a later phase depends on this one
+    int wait_phase;        // latest earlier phase this one waits for through the flags, or -1
+    int publish;           // 1 if a later phase waits for this one through the flags
+    // Mail: an input operand that is exactly the bf16 output (or residual sum) of
+    // one earlier phase is not read from the caller's buffer.  The producing waves
+    // also post every value as a 32-bit word (tag << 16 | bf16 bits) in a mailbox of
+    // the workspace, with write-through stores and without waiting for anything; the
+    // consumers poll the words themselves until all carry the tag of this walk.  A
+    // word is its own flag, so no fence, no flag and no wait on the producer's side
+    // are needed, and the consumer's first look at the data is its wait.
+    // Word order inside a mailbox: values in pieces of 512; value 8 l + e of a piece
+    // (l < 64, e < 8) is word (e / 4) * 256 + 4 l + e % 4 of the piece, so that lane l
+    // of a wave collects its eight values with two fully coalesced 16-byte loads.
+    // Every mailbox exists kMailReplicas times, stream_mail_stride words apart; the
+    // producers post to all of them, a consumer polls the replica of its XCD
+    // (workgroup number modulo 8).  All 256 workgroups polling the same lines made
+    // the few memory channels that hold them the bound of the wait; with replicas
+    // the same requests spread over eight times as many.  The pointers below name
+    // replica 0.
+    const uint32_t *mail_x, *mail_x2;  // mailboxes this phase reads x / x2 from, or nullptr
+    uint32_t *mail_y[kMaxSeg];         // where the outputs of segment i are also posted, or nullptr
+    uint32_t *mail_h;                  // where the residual sum is also posted, or nullptr
+    int dep;               // 1 if the phase builds its image itself after waiting (flags or mail)
     int img_chunks;        // KiB chunks of the prepared image (0 if built in the kernel)
     int img_lds;           // byte offset of the phase's image inside the LDS image area
     int img_need;          // latest phase whose image this one overwrites in LDS, or -1
@@ -93,6 +113,16 @@ __device__ __forceinline__ void stream_wave_rows(int rows_base, int rows_extra, 
 
 #endif
 
+// Words of a mailbox for `n` values (whole pieces of 512).
+static inline size_t stream_mail_words(int n) { return ((size_t)n + 511) / 512 * 512; }
+// Replicas of every mailbox, and the distance in words between two replicas of
+// an area that holds `words` words of mailboxes (an odd number of 256-byte units
+// on top of whole 16 KiB, so that replicas do not fall on the same memory channels).
+constexpr int kMailReplicas = 8;
+static inline size_t stream_mail_stride(size_t words) {
+    return words == 0 ? 0 : (words + 4095) / 4096 * 4096 + 33 * 64;
+}
+
 // Bytes of the activation image of a layer with K inputs, padded to whole KiB.
 static inline int stream_image_bytes(int K, int precision, int act_group) {
     const int G = K / 32;
@@ -101,20 +131,25 @@ static inline int stream_image_bytes(int K, int precision, int act_group) {
 }
 
 // Enqueue one walk.  `flags` holds one word per workgroup, the status words
-// (`status` = flags + kStreamMaxWg; word 0 is set to 1 if a wait timed out) and
+// (`status` = flags + kStreamMaxWg; word 0 is set to a code if a wait gave up) and
 // one word per phase; all persist between runs of the same table, with
 // `flag_base` advanced by nphase + 2 per run (image word = base + 1: the
 // phase's image is stored; workgroup word = base + 2 + p: phase p published).  `nimages` = phases with a prepared
 // image (0 skips the prologue).  `dummy` is any valid
-// 1 KiB of device memory.  `trace` is nullptr or nphase * 8 words that
-// receive workgroup 0's per-phase timestamps (of the phases its first wave does
-// not pass).  `skips`: the skip table, nwg * (kStreamWaves + 1) rows.  `pairs` says that some phase of
+// 1 KiB of device memory.  `trace` is nullptr or trace_wgs * nphase * 8 words
+// that receive the per-phase timestamps of the first trace_wgs workgroups (of the
+// phases their first wave does not pass).  `skips`: the skip table, nwg * (kStreamWaves + 1) rows.  `pairs` says that some phase of
 // the table streams its rows in pairs (pair_stream): the kernel variant that has
-// that path is launched.
+// that path is launched.  `mail`: some phase of the table posts or reads mail (the
+// kernel variant with that path); `mail_tag` (1..65535) is the tag of this walk:
+// it must differ from the tag of the walk before it on the same mailboxes, and a
+// mailbox is cleared to zero before its first use; `mail_stride`: words between
+// the replicas of a mailbox.
 int launch_decode_stream(const StreamPhase *tab_dev, const uint8_t *skips, int nphase, int nimages,
-                         int act_group, bool pairs, uint32_t *flags, uint32_t *status,
-                         uint32_t flag_base, const void *dummy, int nwg,
-                         unsigned long long *trace, hipStream_t st);
+                         int act_group, bool pairs, bool mail, uint32_t mail_tag,
+                         uint32_t mail_stride, uint32_t *flags,
+                         uint32_t *status, uint32_t flag_base, const void *dummy, int nwg,
+                         unsigned long long *trace, int trace_wgs, hipStream_t st);
 
 // Timestamps written per phase when a trace buffer is given (see the kernel).
 constexpr int kStreamTraceSlots = 8;

@@ -57,6 +57,21 @@
 // atomics), and its input is read after the wait instead of being streamed
 // ahead.  A bounded spin turns a stuck wait (e.g. the grid not co-resident)
 // into an error status instead of a hang.
+//
+// Mail.  Where a phase's input is exactly the bf16 output of one earlier phase
+// (the o projection into the next norm, gate and up into SiLU-multiply, down
+// into the next block: every link of a real decode step), flags are not used at
+// all.  The producing waves post each result a second time as a 32-bit word
+// that carries the tag of this walk next to the bf16 value, with write-through
+// stores and without waiting for them; the consuming waves poll those words,
+// each its share of the vector, until all of them carry the tag.  Every word is
+// its own flag, so no store has to be waited for, no fence and no workgroup
+// barrier stand on the producer's side, and the consumer's wait and its fetch
+// of the data are one and the same trip to memory.  (With flags a dependent
+// phase cost 14 us: the producer drains its loads to learn that its stores are
+// done, meets its workgroup, writes back its L2 and raises the flag; the
+// consumer polls 256 flags, invalidates its L2, meets its workgroup and only
+// then asks for the data.)
 #include <type_traits>
 
 #include "decode_stream.h"
@@ -81,6 +96,7 @@ constexpr int kXChunkElems = 512;          // bf16 values per input chunk
 constexpr int kMaxXShare = (kStreamMaxK / kXChunkElems + kStreamWaves - 1) / kStreamWaves;  // 4
 
 constexpr uint32_t kSpinLimit = 4u << 20;  // polls before a wait gives up (seconds)
+constexpr uint32_t kMailSpinLimit = 1u << 20;  // likewise for mail (a poll is a trip to memory)
 constexpr int kLookahead = 3;              // phases the loader wave may run ahead (6 and 12: no faster)
 
 // s_waitcnt immediate that waits for vmcnt <= n only (gfx9 encoding:
@@ -396,16 +412,27 @@ __device__ __forceinline__ void image_put(const Writer &wr, const ImgLayout<PER_
             s = quad_max(chunk_absmax(raw)) / 127.0f;
             if (valid && quarter == 0) wr.w4(L.xsg + g * 4, __float_as_uint(s));
         }
+        // One division per scale instead of one per value: t = x * fl(1 / s) is within
+        // 2^-15 of the correctly rounded quotient fl(x / s) (|x / s| <= 127: two
+        // roundings of 2^-24 relative, and the quotient's own), so unless t lies within
+        // 2^-14 of a half-integer, rounding t gives the integer that rounding the
+        // quotient gives; where it does (an exact tie, say) the lane divides after all.
+        // A scale too small for its reciprocal takes the division for every value.
+        const bool by_reciprocal = s >= 0x1p-100f;
+        const float inv_s = by_reciprocal ? 1.0f / s : 0.0f;
+        auto code = [&](float x) -> int {
+            float r = rintf(x * inv_s);
+            if (!by_reciprocal || fabsf(x * inv_s - r) > 0.5f - 0x1p-14f) r = rintf(x / s);
+            return (int)fminf(fmaxf(r, -127.0f), 127.0f);
+        };
         uint32_t out[2] = {0, 0};
         int qsum = 0;
 #pragma unroll
         for (int d = 0; d < 4; ++d) {
             int q0 = 0, q1 = 0;
             if (s != 0.0f) {
-                const float r0 = rintf(bf16_bits_to_float(wv[d] & 0xffffu) / s);
-                const float r1 = rintf(bf16_bits_to_float(wv[d] >> 16) / s);
-                q0 = (int)fminf(fmaxf(r0, -127.0f), 127.0f);
-                q1 = (int)fminf(fmaxf(r1, -127.0f), 127.0f);
+                q0 = code(bf16_bits_to_float(wv[d] & 0xffffu));
+                q1 = code(bf16_bits_to_float(wv[d] >> 16));
             }
             qsum += q0 + q1;
             out[d >> 1] |= ((uint32_t)(q0 & 0xff) | ((uint32_t)(q1 & 0xff) << 8)) << (16 * (d & 1));
@@ -427,22 +454,170 @@ __device__ __forceinline__ void image_put(const Writer &wr, const ImgLayout<PER_
     }
 }
 
+// Optional per-phase timestamps (100 MHz wall clock) taken by wave 0 of
+// workgroup 0; slot meanings are documented with nvq_plan_trace.
+constexpr int kTraceSlots = 8;
+struct Trace {
+    unsigned long long *buf;  // nullptr: off
+    int wgs, nphase;          // workgroups that record (the first `wgs`), phases per workgroup
+};
+__device__ __forceinline__ void trace_mark(const Trace &trace, int wg, int w, int lane, int p,
+                                           int slot) {
+    if (trace.buf && wg < trace.wgs && w == 0 && lane == 0)
+        trace.buf[((size_t)wg * trace.nphase + p) * kTraceSlots + slot] = wall_clock64();
+}
+
+// ---- mail --------------------------------------------------------------------
+// Post eight consecutive bf16 values (piece j of 512, lane's share) in every
+// replica of a mailbox.
+__device__ __forceinline__ void mail_post8(uint32_t *mail, uint32_t stride, int j, int lane,
+                                           const uint4 &v, uint32_t tag_hi) {
+    const u32x4_t a = {tag_hi | (v.x & 0xffffu), tag_hi | (v.x >> 16), tag_hi | (v.y & 0xffffu),
+                       tag_hi | (v.y >> 16)};
+    const u32x4_t b = {tag_hi | (v.z & 0xffffu), tag_hi | (v.z >> 16), tag_hi | (v.w & 0xffffu),
+                       tag_hi | (v.w >> 16)};
+    uint32_t *p = mail + (size_t)j * 512 + lane * 4;
+    for (int r = 0; r < kMailReplicas; ++r, p += stride) {
+        // (the s_nop: a store of more than 8 bytes reads its data registers a few cycles
+        // after it issues, and the compiler, which does not see into the statement, may
+        // let the next instruction overwrite them)
+        asm volatile("global_store_dwordx4 %0, %1, off sc1\n\t"
+                     "global_store_dwordx4 %0, %2, off offset:1024 sc1\n\ts_nop 3"
+                     :
+                     : "v"(p), "v"(a), "v"(b)
+                     : "memory");
+    }
+}
+
+// Word of value v in a mailbox (see StreamPhase).
+__device__ __forceinline__ int mail_word(int v) {
+    return (v & ~511) + ((v >> 2) & 1) * 256 + ((v >> 3) & 63) * 4 + (v & 3);
+}
+
+// Collect this wave's pieces (w, w + kStreamWaves, ...) of one or two K-value
+// operands from their mailboxes (mail1 may be nullptr): poll until every word
+// carries the tag.  The loads bypass the caches that other compute units do not
+// share (device scope) and a word is written whole, so a word with the right tag
+// holds this walk's value.  A lane asks again only for what it is still missing.
+// Returns false if the wait
+// was given up (abort raised, status set) or another wave raised abort; the
+// outputs are then undefined.
+__device__ __forceinline__ uint32_t mail_bad(const u32x4_t &a, const u32x4_t &b, uint32_t tag_hi) {
+    return ((a.x ^ tag_hi) | (a.y ^ tag_hi) | (a.z ^ tag_hi) | (a.w ^ tag_hi) | (b.x ^ tag_hi) |
+            (b.y ^ tag_hi) | (b.z ^ tag_hi) | (b.w ^ tag_hi)) >> 16;
+}
+// low halves of two words side by side
+__device__ __forceinline__ uint4 mail_pack(const u32x4_t &a, const u32x4_t &b) {
+    return make_uint4(__builtin_amdgcn_perm(a.y, a.x, 0x05040100u),
+                      __builtin_amdgcn_perm(a.w, a.z, 0x05040100u),
+                      __builtin_amdgcn_perm(b.y, b.x, 0x05040100u),
+                      __builtin_amdgcn_perm(b.w, b.z, 0x05040100u));
+}
+
+// NP pieces of NO operands at a time (the registers of a wave hold three
+// piece-operands in flight next to everything else, not six).
+template <int NP, int NO, int NK>
+__device__ __forceinline__ bool mail_poll(const uint32_t *mail0, const uint32_t *mail1, int K,
+                                          int nxc, int w, int lane, uint32_t tag_hi,
+                                          uint4 (&out0)[NK], uint4 (&out1)[NK], uint32_t abort_a,
+                                          uint32_t *status, int where) {
+    // bit NO * k + o of `need`: this lane's share of piece k of operand o has not come yet
+    uint32_t need = 0;
+#pragma unroll
+    for (int k = 0; k < NP; ++k) {
+        const int j = w + k * kStreamWaves;
+        int idx = j * 64 + lane;
+        asm volatile("" : "+v"(idx));
+        if (j < nxc && idx < K / 8) need |= ((1u << NO) - 1u) << (NO * k);
+    }
+    uint32_t spins = 0;
+    while (__any(need != 0)) {
+        u32x4_t a[NP][NO], b[NP][NO];
+#pragma unroll
+        for (int k = 0; k < NP; ++k) {
+#pragma unroll
+            for (int o = 0; o < NO; ++o) {
+                a[k][o] = b[k][o] = u32x4_t{0, 0, 0, 0};
+                if (need & (1u << (NO * k + o))) {
+                    const uint32_t *p =
+                        (o == 0 ? mail0 : mail1) + (size_t)(w + k * kStreamWaves) * 512 + lane * 4;
+                    asm volatile("global_load_dwordx4 %0, %2, off sc1\n\t"
+                                 "global_load_dwordx4 %1, %2, off offset:1024 sc1"
+                                 : "+v"(a[k][o]), "+v"(b[k][o])
+                                 : "v"(p)
+                                 : "memory");
+                }
+            }
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int k = 0; k < NP; ++k) {
+#pragma unroll
+            for (int o = 0; o < NO; ++o) {
+                asm volatile("" : "+v"(a[k][o]), "+v"(b[k][o]));  // nothing is used before that wait
+                const uint32_t bit = 1u << (NO * k + o);
+                if ((need & bit) && mail_bad(a[k][o], b[k][o], tag_hi) == 0) {
+                    need &= ~bit;
+                    (o == 0 ? out0[k] : out1[k]) = mail_pack(a[k][o], b[k][o]);
+                }
+            }
+        }
+        if (!__any(need != 0)) break;
+        if (lds_read4_uniform(abort_a)) return false;
+        if (++spins > kMailSpinLimit) {
+            if (lane == 0) {
+                lds_write4(abort_a, 1u);
+                __hip_atomic_store(status, 5u | ((uint32_t)where << 8), __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            }
+            return false;
+        }
+        __builtin_amdgcn_s_sleep(1);
+    }
+    return true;
+}
+
+template <int NK>
+__device__ __forceinline__ bool mail_fetch(const uint32_t *mail0, const uint32_t *mail1, int K,
+                                           int nxc, int w, int lane, uint32_t tag_hi,
+                                           uint4 (&out0)[NK], uint4 (&out1)[NK], uint32_t abort_a,
+                                           uint32_t *status, int where) {
+    if (nxc <= kStreamWaves && mail1)  // one piece per wave: both operands at once
+        return mail_poll<1, 2>(mail0, mail1, K, nxc, w, lane, tag_hi, out0, out1, abort_a, status,
+                               where);
+    if (!mail_poll<NK, 1>(mail0, nullptr, K, nxc, w, lane, tag_hi, out0, out1, abort_a, status,
+                          where))
+        return false;
+    return !mail1 || mail_poll<NK, 1>(mail1, nullptr, K, nxc, w, lane, tag_hi, out1, out0, abort_a,
+                                      status, where + 1);
+}
+
 // Build the image of phase `ph` from its raw input, all waves of the workgroup
 // together: wave w handles the 512-value pieces w, w + waves, ...  The phase's
 // input transform (RMSNorm with residual add, SiLU-multiply; paper: kernel
 // table) is applied on the way, so it costs no launch and no pass over memory;
-// `store_h` says whether this workgroup stores the residual sum.  The caller
-// guarantees that nobody still reads the destination and that sh.amax_part and
-// sh.sumsq_part are free; up to two barriers are used inside (sum of squares
-// for RMSNorm; absmax exchange for W4A8 with a per-token scale).
-template <bool PER_GROUP, class Writer>
-__device__ __forceinline__ void image_build(const Writer &wr, CPhase &ph, Shared &sh, int w,
-                                            int lane, bool store_h) {
+// `store_h` says whether this workgroup stores the residual sum.  Operands that
+// have a mailbox (MAIL) are polled out of it instead of being loaded.  With
+// `entry_barrier` (phases built after a wait) the workgroup meets once after the
+// operands have arrived: from then on every wave has left the previous phase
+// (the image region may be written) and all see the same abort word; false is
+// returned if it is set.  The caller guarantees that sh.amax_part and
+// sh.sumsq_part are free; up to two more barriers are used inside (sum of
+// squares for RMSNorm; absmax exchange for W4A8 with a per-token scale).
+template <bool PER_GROUP, bool MAIL, class Writer>
+__device__ __forceinline__ bool image_build(const Writer &wr, CPhase &ph, Shared &sh, int w,
+                                            int lane, bool store_h, bool entry_barrier,
+                                            uint32_t tag_hi, uint32_t mail_stride, uint32_t abort_a,
+                                            uint32_t *status, int p, const Trace &trace, int wg) {
     const int in_op = ph.in_op;
     if (w >= kStreamWaves) {  // the loader wave only keeps the barrier count
+        if (entry_barrier) {
+            lds_barrier();
+            if (lds_read4_uniform(abort_a)) return false;
+        }
         if (in_op == NVQ_IN_RMSNORM) lds_barrier();
         if (ph.precision == NVQ_W4A8 && !PER_GROUP) lds_barrier();
-        return;
+        return true;
     }
     const bool w4a8 = ph.precision == NVQ_W4A8;
     const int G = ph.G, K = ph.K;
@@ -456,13 +631,20 @@ __device__ __forceinline__ void image_build(const Writer &wr, CPhase &ph, Shared
     // that they are in flight together: issued piece by piece between the uses, a
     // wave's two or three pieces cost it two or three trips to memory in a row.
     const bool second = in_op == NVQ_IN_SILU_MUL || (in_op == NVQ_IN_RMSNORM && x2 != nullptr);
+    const uint32_t *mail_x = nullptr, *mail_x2 = nullptr;
+    if constexpr (MAIL) {
+        // the replica of this workgroup's XCD
+        const size_t mine = (size_t)(wg & (kMailReplicas - 1)) * mail_stride;
+        mail_x = ph.mail_x ? ph.mail_x + mine : nullptr;
+        mail_x2 = second && ph.mail_x2 ? ph.mail_x2 + mine : nullptr;
+    }
 #pragma unroll
     for (int k = 0; k < kMaxXShare; ++k) {
         const int j = w + k * kStreamWaves;
         int idx = j * 64 + lane;
         asm volatile("" : "+v"(idx));  // computed here, not kept through the kernel
         xsh[k] = make_uint4(0, 0, 0, 0);
-        if (j < nxc && idx < K / 8) xsh[k] = x[idx];
+        if (!mail_x && j < nxc && idx < K / 8) xsh[k] = x[idx];
     }
 #pragma unroll
     for (int k = 0; k < kMaxXShare; ++k) {
@@ -470,7 +652,36 @@ __device__ __forceinline__ void image_build(const Writer &wr, CPhase &ph, Shared
         int idx = j * 64 + lane;
         asm volatile("" : "+v"(idx));
         x2sh[k] = make_uint4(0, 0, 0, 0);
-        if (second && j < nxc && idx < K / 8) x2sh[k] = x2[idx];
+        if (second && !mail_x2 && j < nxc && idx < K / 8) x2sh[k] = x2[idx];
+    }
+    if constexpr (MAIL) {
+        // (both at once if both come by mail; a result of false shows in the abort word)
+        if (mail_x)
+            mail_fetch(mail_x, mail_x2, K, nxc, w, lane, tag_hi, xsh, x2sh, abort_a, status, 2 * p);
+        else if (mail_x2)
+            mail_fetch(mail_x2, nullptr, K, nxc, w, lane, tag_hi, x2sh, xsh, abort_a, status,
+                       2 * p + 1);
+    }
+    // with mail the norm weights are requested as soon as the operands have come (not
+    // before: the registers are needed for the wait), so that they arrive while the
+    // workgroup meets and adds up the squares
+    uint4 gsh[MAIL ? kMaxXShare : 1];
+    if constexpr (MAIL) {
+        const uint4 *gamma = reinterpret_cast<const uint4 *>(ph.gamma);
+#pragma unroll
+        for (int k = 0; k < kMaxXShare; ++k) {
+            const int j = w + k * kStreamWaves;
+            int idx = j * 64 + lane;
+            asm volatile("" : "+v"(idx));
+            gsh[k] = make_uint4(0, 0, 0, 0);
+            if (in_op == NVQ_IN_RMSNORM && j < nxc && idx < K / 8) gsh[k] = gamma[idx];
+        }
+    }
+    if (entry_barrier) {
+        trace_mark(trace, wg, w, lane, p, 5);  // this wave's share of the operands has arrived
+        lds_barrier();
+        if (lds_read4_uniform(abort_a)) return false;
+        trace_mark(trace, wg, w, lane, p, 3);  // ... and everybody's
     }
 #pragma unroll
     for (int k = 0; k < kMaxXShare; ++k) {
@@ -483,7 +694,11 @@ __device__ __forceinline__ void image_build(const Writer &wr, CPhase &ph, Shared
             } else if (in_op == NVQ_IN_RMSNORM) {
                 if (x2) {
                     xsh[k] = add_bf16x8(xsh[k], x2sh[k]);
-                    if (store_h && ph.h_out) reinterpret_cast<uint4 *>(ph.h_out)[idx] = xsh[k];
+                    if (store_h && ph.h_out) {
+                        reinterpret_cast<uint4 *>(ph.h_out)[idx] = xsh[k];
+                        if constexpr (MAIL)
+                            if (ph.mail_h) mail_post8(ph.mail_h, mail_stride, j, lane, xsh[k], tag_hi);
+                    }
                 }
                 ss += sumsq_bf16x8(xsh[k]);
             }
@@ -503,14 +718,15 @@ __device__ __forceinline__ void image_build(const Writer &wr, CPhase &ph, Shared
             tot += __uint_as_float(a.w);
         }
         const float r = rms_scale(tot, K, ph.eps);
-        // (requesting the norm weights together with the input instead: 16 more live
-        // registers here and no gain, they come out of the L2)
+        // (without mail, requesting the norm weights together with the input: 16 more
+        // live registers here and no gain, they come out of the L2)
         const uint4 *gamma = reinterpret_cast<const uint4 *>(ph.gamma);
 #pragma unroll
         for (int k = 0; k < kMaxXShare; ++k) {
             const int j = w + k * kStreamWaves;
             const int idx = j * 64 + lane;
-            if (j < nxc && idx < K / 8) xsh[k] = scale_bf16x8(xsh[k], r, gamma[idx]);
+            if (j < nxc && idx < K / 8)
+                xsh[k] = scale_bf16x8(xsh[k], r, MAIL ? gsh[MAIL ? k : 0] : gamma[idx]);
         }
     }
     float amax = 0.0f;
@@ -537,7 +753,7 @@ __device__ __forceinline__ void image_build(const Writer &wr, CPhase &ph, Shared
         if (j < nxc)
             image_put<PER_GROUP>(wr, L, w4a8, G, j * 16 + (lane >> 2), lane, xsh[k], s_tok);
     }
-
+    return true;
 }
 
 // ---- per-wave stream state ---------------------------------------------------------
@@ -545,14 +761,6 @@ struct Stream {
     Issue ic;
     uint32_t slot;  // ring slot of the next chunk in stream order
 };
-
-// Optional per-phase timestamps (100 MHz wall clock) taken by wave 0 of
-// workgroup 0; slot meanings are documented with nvq_plan_trace.
-constexpr int kTraceSlots = 8;
-__device__ __forceinline__ void trace_mark(unsigned long long *trace, int wg, int w, int lane,
-                                           int p, int slot) {
-    if (trace && wg == 0 && w == 0 && lane == 0) trace[p * kTraceSlots + slot] = wall_clock64();
-}
 
 // Wave 0: spin until every workgroup's flag has reached `target`.
 __device__ __forceinline__ bool wait_flags(const uint32_t *flags, int nwg, uint32_t target,
@@ -585,11 +793,14 @@ __device__ __forceinline__ bool wait_flags(const uint32_t *flags, int nwg, uint3
 // kernel of its own, because the mere presence of that path costs the others
 // some 7 % on lists of many short phases (the compiler's register assignment
 // for the code they share).
-template <bool PER_GROUP, bool PAIRS>
+// MAIL: some phase posts or reads mail; likewise a kernel of its own.
+template <bool PER_GROUP, bool PAIRS, bool MAIL>
 __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
     const StreamPhase *__restrict__ tab_generic, const uint8_t *__restrict__ skips_generic,
     int nphase, int nimages, uint32_t *__restrict__ flags, uint32_t *__restrict__ status, uint32_t flag_base,
-    const uint4 *__restrict__ dummy, unsigned long long *__restrict__ trace) {
+    const uint4 *__restrict__ dummy, unsigned long long *__restrict__ trace_buf, int trace_wgs,
+    uint32_t mail_tag_hi, uint32_t mail_stride) {
+    const Trace trace = {trace_buf, trace_wgs, nphase};
     __shared__ Shared sh;
     CPhase *tab = (CPhase *)tab_generic;
     // wave index, made provably wave-uniform; wave 0 also talks to the other workgroups
@@ -604,7 +815,8 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
     const int wgd = (nwg & 7) == 0 ? (wg & 7) * (nwg >> 3) + (wg >> 3) : wg;
     const int gw = wgd * kStreamWaves + w;
     const int gw_spread = w * nwg + wgd;
-    if (threadIdx.x == 0) lds_write4(lds_addr(&sh.abort), 0u);
+    const uint32_t abort_a = lds_addr(&sh.abort);
+    if (threadIdx.x == 0) lds_write4(abort_a, 0u);
     trace_mark(trace, wg, w, lane, 0, 5);  // kernel entered
 
     // The streaming waves request their first chunks at once: weights depend on
@@ -633,12 +845,14 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
     // ---- soon as it is stored (the loader waves wait for the images they copy,
     // ---- nobody waits for all of them)
     uint32_t *const img_flags = flags + kStreamImageFlags;
+
     if (nimages > 0) {
         for (int p = wg; p < nphase; p += nwg) {
             CPhase &ph = tab[p];
             if (ph.img) {
                 const GlobalWriter wr = {reinterpret_cast<char *>(const_cast<uint4 *>(ph.img))};
-                image_build<PER_GROUP>(wr, ph, sh, w, lane, true);
+                image_build<PER_GROUP, MAIL>(wr, ph, sh, w, lane, true, false, mail_tag_hi, mail_stride,
+                                             abort_a, status, p, trace, wg);
                 __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // this wave's image stores have completed
                 lds_barrier();                             // (and sh.amax_part may be reused)
                 if (w == 0) {
@@ -654,7 +868,6 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
     const uint32_t area_base = lds_addr(sh.area);
     const uint32_t progress_a = lds_addr(&sh.progress[0]);
     const uint32_t ready_a = lds_addr(&sh.img_ready);
-    const uint32_t abort_a = lds_addr(&sh.abort);
     if (threadIdx.x < kStreamWaves) lds_write4(progress_a + threadIdx.x * 4, 0u);
     if (threadIdx.x == 0) lds_write4(ready_a, 0u);
     lds_barrier();
@@ -697,7 +910,7 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
                 if (lds_read4_uniform(abort_a)) return false;
                 if (++spins > kSpinLimit) {
                     lds_write4(abort_a, 1u);
-                    __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store(status, 2u | ((uint32_t)i << 8), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     return false;
                 }
                 __builtin_amdgcn_s_sleep(4);
@@ -726,7 +939,7 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
                 if (lds_read4_uniform(abort_a)) return false;
                 if (++spins > kSpinLimit) {
                     lds_write4(abort_a, 1u);
-                    __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store(status, 3u | ((uint32_t)q << 8), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     return false;
                 }
                 __builtin_amdgcn_s_sleep(2);
@@ -759,12 +972,14 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
         bool live = true;
         for (int p = 0; p < nphase && live; ++p) {
             CPhase &ph = tab[p];
-            if (ph.wait_phase >= 0) {
+            if (ph.dep) {
                 flush();
-                lds_barrier();  // dependency satisfied
-                if (lds_read4_uniform(abort_a)) break;
+                if (ph.wait_phase >= 0) lds_barrier();  // flags seen
                 const LdsWriter wr = {0};
-                image_build<PER_GROUP>(wr, ph, sh, w, lane, false);  // barrier count only
+                // barrier count only; false: abort raised
+                if (!image_build<PER_GROUP, MAIL>(wr, ph, sh, w, lane, false, true, 0u, 0u, abort_a,
+                                                  status, p, trace, wg))
+                    break;
                 lds_barrier();  // image complete
                 q = p + 1;
             }
@@ -774,7 +989,7 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
             for (;;) {
                 // images of phases in which no wave of this workgroup works are not loaded
                 while (q < nphase && phase_skip(wg_passes, q) != 0) ++q;
-                if (!(live && q < nphase && q <= p + kLookahead && tab[q].wait_phase < 0 &&
+                if (!(live && q < nphase && q <= p + kLookahead && !tab[q].dep &&
                       tab[q].img_need < p))
                     break;
                 live = load_image();
@@ -811,6 +1026,12 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
         return make_uint4(v.x, v.y, v.z, v.w);
     };
 
+    // This wave has finished every phase before `done`: the loader wave may reuse the
+    // room of their images.
+    auto note_progress = [&](uint32_t done) {
+        if (lane == 0) lds_write4(progress_a + w * 4, done);
+    };
+
     bool aborted = false;
     uint32_t ready_seen = 0;     // sh.img_ready as requested on entering an independent phase
     bool ready_pending = false;  // ... and not yet looked at
@@ -821,7 +1042,7 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
             const int pass = phase_skip(skips, p);
             if (pass > 0) {
                 p += pass;
-                if (lane == 0) lds_write4(progress_a + w * 4, (uint32_t)(p < nphase ? p : nphase));
+                note_progress((uint32_t)(p < nphase ? p : nphase));
                 if (p >= nphase) break;
             }
         }
@@ -832,23 +1053,28 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
         const uint32_t img = area_base + (uint32_t)ph.img_lds;
         trace_mark(trace, wg, w, lane, p, 0);
 
-        if (ph.wait_phase >= 0) {
-            // ---- dependent phase: wait until every workgroup has published phase
-            // ---- wait_phase, then build the image from the raw input, all together
-            if (w == 0) {
-                const bool ok =
-                    wait_flags(flags, nwg, flag_base + 2u + (uint32_t)ph.wait_phase, lane);
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-                if (!ok && lane == 0) {
-                    lds_write4(abort_a, 1u);
-                    __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (ph.dep) {
+            // ---- dependent phase.  Through the flags: wait until every workgroup has
+            // ---- published phase wait_phase.  Then build the image from the raw input
+            // ---- (or from the mail, whose arrival is the wait), all together
+            if (ph.wait_phase >= 0) {
+                if (w == 0) {
+                    const bool ok =
+                        wait_flags(flags, nwg, flag_base + 2u + (uint32_t)ph.wait_phase, lane);
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+                    if (!ok && lane == 0) {
+                        lds_write4(abort_a, 1u);
+                        __hip_atomic_store(status, 1u | ((uint32_t)p << 8), __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_AGENT);
+                    }
                 }
+                lds_barrier();  // satisfied (or abort raised)
             }
-            lds_barrier();  // satisfied (or abort raised); every wave has left the previous phase
-            if (lds_read4_uniform(abort_a)) break;
             trace_mark(trace, wg, w, lane, p, 1);
             const LdsWriter wr = {img};
-            image_build<PER_GROUP>(wr, ph, sh, w, lane, wg == 0);
+            if (!image_build<PER_GROUP, MAIL>(wr, ph, sh, w, lane, wg == 0, true, mail_tag_hi,
+                                              mail_stride, abort_a, status, p, trace, wg))
+                break;
             trace_mark(trace, wg, w, lane, p, 2);
             lds_barrier();  // the image is complete
             ready_pending = false;
@@ -900,7 +1126,7 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
                     aborted = true;
                     if (lane == 0) {
                         lds_write4(abort_a, 1u);
-                        __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        __hip_atomic_store(status, 4u | ((uint32_t)p << 8), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     }
                     return true;
                 }
@@ -964,14 +1190,27 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
                     int first = 0;
                     void *y = ph.y[0];
                     int dt = ph.y_dtype[0];
+                    uint32_t *mail = nullptr;
+                    if constexpr (MAIL) mail = ph.mail_y[0];
 #pragma unroll
                     for (int sgm = 1; sgm < kMaxSeg; ++sgm)
                         if (sgm < ph.nseg && r >= ph.row_end[sgm - 1]) {
                             first = ph.row_end[sgm - 1];
                             y = ph.y[sgm];
                             dt = ph.y_dtype[sgm];
+                            if constexpr (MAIL) mail = ph.mail_y[sgm];
                         }
                     store_out(y, dt, r - first, yv);
+                    if constexpr (MAIL) {
+                        // the same bf16 value once more, tagged, for the phases that read it
+                        if (mail) {
+                            uint32_t *at = mail + mail_word(r - first);
+                            const uint32_t word = mail_tag_hi | float_to_bf16_bits(yv);
+                            for (int rep = 0; rep < kMailReplicas; ++rep, at += mail_stride)
+                                __hip_atomic_store(at, word, __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_AGENT);
+                        }
+                    }
                 }
             }
         };
@@ -1001,7 +1240,7 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
                                  : "+v"(x[i][0]), "+v"(x[i][1]), "+v"(x[i][2]), "+v"(x[i][3]),
                                    "+v"(aux[i]), "+v"(sgb[i]));
             } while (!image_ready());
-            if (ph.wait_phase < 0) trace_mark(trace, wg, w, lane, p, 2);
+            if (!ph.dep) trace_mark(trace, wg, w, lane, p, 2);
             if (aborted) return;
             for (int row = r0; row < r0 + nrows; ++row) {
                 float sum = 0.0f;
@@ -1040,7 +1279,7 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
                                  : "+v"(x[i][0]), "+v"(x[i][1]), "+v"(x[i][2]), "+v"(x[i][3]),
                                    "+v"(aux[i]), "+v"(sgb[i]));
             } while (!image_ready());
-            if (ph.wait_phase < 0) trace_mark(trace, wg, w, lane, p, 2);
+            if (!ph.dep) trace_mark(trace, wg, w, lane, p, 2);
             if (aborted) return;
             for (int row = r0; row < r1; row += 2) {
                 uint32_t sbits;
@@ -1089,7 +1328,7 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
                                      : "+v"(hx[i][0]), "+v"(hx[i][1]), "+v"(hx[i][2]),
                                        "+v"(hx[i][3]), "+v"(haux[i]), "+v"(hsgb[i]));
                 } while (!image_ready());
-                if (ph.wait_phase < 0) trace_mark(trace, wg, w, lane, p, 2);
+                if (!ph.dep) trace_mark(trace, wg, w, lane, p, 2);
                 if (aborted) break;
                 for (int row = r0; row < r1; ++row) {
                     float sum = 0.0f;
@@ -1119,7 +1358,7 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
         }
         if (aborted) break;
         // this wave no longer reads the phase's image
-        if (lane == 0) lds_write4(progress_a + w * 4, (uint32_t)(p + 1));
+        note_progress((uint32_t)(p + 1));
         trace_mark(trace, wg, w, lane, p, 7);
 
         if (ph.publish) {
@@ -1142,40 +1381,64 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
 
 }  // namespace
 
+namespace {
+// The instantiations that are launched: per-group scales never pair rows.
+template <bool PER_GROUP, bool PAIRS, bool MAIL>
+bool fits_a_compute_unit() {
+    int n = 0;
+    return hipOccupancyMaxActiveBlocksPerMultiprocessor(
+               &n, decode_stream_kernel<PER_GROUP, PAIRS, MAIL>, kStreamThreads, 0) == hipSuccess &&
+           n >= 1;
+}
+}  // namespace
+
 int stream_grid_limit() {
     static int cached = -1;
     if (cached < 0) {
         // every instantiation that may be launched must fit a compute unit
-        int a = 0, b = 0, c = 0;
-        const bool ok =
-            hipOccupancyMaxActiveBlocksPerMultiprocessor(&a, decode_stream_kernel<false, false>,
-                                                         kStreamThreads, 0) == hipSuccess &&
-            hipOccupancyMaxActiveBlocksPerMultiprocessor(&b, decode_stream_kernel<true, false>,
-                                                         kStreamThreads, 0) == hipSuccess &&
-            hipOccupancyMaxActiveBlocksPerMultiprocessor(&c, decode_stream_kernel<false, true>,
-                                                         kStreamThreads, 0) == hipSuccess;
-        cached = ok && a >= 1 && b >= 1 && c >= 1 ? device_cu_count() : 0;
+        const bool ok = fits_a_compute_unit<false, false, false>() &&
+                        fits_a_compute_unit<true, false, false>() &&
+                        fits_a_compute_unit<false, true, false>() &&
+                        fits_a_compute_unit<false, false, true>() &&
+                        fits_a_compute_unit<true, false, true>() &&
+                        fits_a_compute_unit<false, true, true>();
+        cached = ok ? device_cu_count() : 0;
     }
     return cached;
 }
 
+namespace {
+template <bool PER_GROUP, bool PAIRS, bool MAIL>
+void launch_variant(const StreamPhase *tab_dev, const uint8_t *skips, int nphase, int nimages,
+                    uint32_t *flags, uint32_t *status, uint32_t flag_base, const uint4 *dummy,
+                    int nwg, unsigned long long *trace, int trace_wgs, uint32_t mail_tag_hi,
+                    uint32_t mail_stride, hipStream_t st) {
+    hipLaunchKernelGGL((decode_stream_kernel<PER_GROUP, PAIRS, MAIL>), dim3(nwg),
+                       dim3(kStreamThreads), 0, st, tab_dev, skips, nphase, nimages, flags, status,
+                       flag_base, dummy, trace, trace_wgs, mail_tag_hi, mail_stride);
+}
+}  // namespace
+
 int launch_decode_stream(const StreamPhase *tab_dev, const uint8_t *skips, int nphase, int nimages,
-                         int act_group, bool pairs, uint32_t *flags, uint32_t *status,
-                         uint32_t flag_base, const void *dummy, int nwg,
-                         unsigned long long *trace, hipStream_t st) {
-    const dim3 grid(nwg), block(kStreamThreads);
+                         int act_group, bool pairs, bool mail, uint32_t mail_tag,
+                         uint32_t mail_stride, uint32_t *flags, uint32_t *status, uint32_t flag_base, const void *dummy, int nwg,
+                         unsigned long long *trace, int trace_wgs, hipStream_t st) {
     const uint4 *d = reinterpret_cast<const uint4 *>(dummy);
-    if (act_group == 32) {
-        if (pairs) return NVQ_ERR_INVALID_ARG;  // rows are not paired with per-group scales
-        hipLaunchKernelGGL((decode_stream_kernel<true, false>), grid, block, 0, st, tab_dev, skips,
-                           nphase, nimages, flags, status, flag_base, d, trace);
+    if (mail && (mail_tag == 0 || mail_tag > 0xffffu)) return NVQ_ERR_INVALID_ARG;
+    const uint32_t tag_hi = mail_tag << 16;
+    const bool per_group = act_group == 32;
+    if (per_group && pairs) return NVQ_ERR_INVALID_ARG;  // rows are not paired with per-group scales
+#define NVQ_LAUNCH(PG, PR, ML)                                                                   \
+    launch_variant<PG, PR, ML>(tab_dev, skips, nphase, nimages, flags, status, flag_base, d, nwg, \
+                               trace, trace_wgs, tag_hi, mail_stride, st)
+    if (per_group) {
+        if (mail) NVQ_LAUNCH(true, false, true); else NVQ_LAUNCH(true, false, false);
     } else if (pairs) {
-        hipLaunchKernelGGL((decode_stream_kernel<false, true>), grid, block, 0, st, tab_dev, skips,
-                           nphase, nimages, flags, status, flag_base, d, trace);
+        if (mail) NVQ_LAUNCH(false, true, true); else NVQ_LAUNCH(false, true, false);
     } else {
-        hipLaunchKernelGGL((decode_stream_kernel<false, false>), grid, block, 0, st, tab_dev, skips,
-                           nphase, nimages, flags, status, flag_base, d, trace);
+        if (mail) NVQ_LAUNCH(false, false, true); else NVQ_LAUNCH(false, false, false);
     }
+#undef NVQ_LAUNCH
     NVQ_HIP_TRY(hipGetLastError());
     return NVQ_OK;
 }

@@ -11,24 +11,13 @@ namespace nvq {
 
 #if defined(__HIPCC__)
 
-// a + b of two bf16 numbers, rounded to bf16 once.  The sum of two bf16 values
-// is exact in binary64; rounding it through binary32 first could round twice.
+// a + b of two bf16 numbers, rounded to bf16 once.  The sum is formed in
+// binary32 and rounded again to bf16; with an 8-bit significand that is the
+// same as rounding the exact sum once (double rounding is innocuous for sums,
+// products, quotients and roots when the wider format has at least 2 * 8 + 2
+// bits of significand: Figueroa, "When is double rounding innocuous?", 1995).
 __device__ __forceinline__ uint32_t add_bf16_bits(uint32_t a, uint32_t b) {
-    const double v = (double)bf16_bits_to_float(a) + (double)bf16_bits_to_float(b);
-    uint64_t u = (uint64_t)__double_as_longlong(v);
-    // binary64 -> the bf16 significand (7 fraction bits): 45 bits are dropped
-    const uint64_t drop = (1ull << 45) - 1, half = 1ull << 44;
-    const uint64_t rem = u & drop;
-    u >>= 45;  // sign, 11-bit exponent, 7 fraction bits
-    if (rem > half || (rem == half && (u & 1))) ++u;
-    // rebias the exponent from binary64 (1023) to bf16 (127); sums of finite bf16
-    // inputs that are not tiny stay in range, tiny or zero results flush to zero
-    const uint32_t sign = (uint32_t)(u >> 18) & 1u;
-    const int32_t exp = (int32_t)((u >> 7) & 0x7ffu) - 1023 + 127;
-    const uint32_t frac = (uint32_t)u & 0x7fu;
-    if (exp <= 0) return sign << 15;
-    if (exp >= 255) return (sign << 15) | 0x7f80u;
-    return (sign << 15) | ((uint32_t)exp << 7) | frac;
+    return float_to_bf16_bits(bf16_bits_to_float(a) + bf16_bits_to_float(b));
 }
 
 // Eight bf16 values (one uint4) at a time.
@@ -72,8 +61,14 @@ __device__ __forceinline__ uint4 scale_bf16x8(const uint4 &h, float r, const uin
     return make_uint4(o[0], o[1], o[2], o[3]);
 }
 
+// g / (1 + exp(-g)) * u with the hardware's exp2 and reciprocal (each good to
+// about one unit of binary32; the argument of exp2 adds |g| * 2^-24 relative):
+// far below the bf16 rounding that follows, a handful of instructions instead
+// of some forty.  Where this runs every workgroup evaluates the whole vector
+// before its first weight row, so the instructions are time on the critical path.
 __device__ __forceinline__ float silu_mul_one(float g, float u) {
-    return g / (1.0f + expf(-g)) * u;
+    const float e = __builtin_amdgcn_exp2f(g * -1.44269504088896341f);
+    return g * __builtin_amdgcn_rcpf(1.0f + e) * u;
 }
 
 // bf16(silu(g) * u), eight at a time.

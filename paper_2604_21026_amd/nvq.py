@@ -322,6 +322,7 @@ class DecodeList:
     def plan_timed_out(self) -> bool:
         t = C.c_int()
         _check(lib().nvq_plan_status(self.plan(), _stream(), C.byref(t)), "nvq_plan_status")
+        self.status_code = t.value      # which wait gave up, and in which phase (see nvq.h)
         return bool(t.value)
 
     def trace(self, buf: Optional[torch.Tensor]):
@@ -364,7 +365,7 @@ def plan_describe_batches(linears: Sequence[Linear], M: int, ordered: bool = Fal
 
 DESCRIBE_FIELDS = ("first", "count", "wait", "publish", "rows", "rows_base", "rows_extra",
                    "rows_rot", "img_lds", "img_need", "img_bytes", "img_prepared", "row_unit",
-                   "pair_stream", "spread")
+                   "pair_stream", "spread", "mail")
 
 
 def plan_describe(linears: Sequence[Linear], M: int, act_group: int = 0, ordered: bool = False,

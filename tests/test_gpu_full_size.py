@@ -80,3 +80,53 @@ def test_full_8b_step_sampled_rows_match_oracle(M):
         assert err < TOL, (sp.name, err)
     print("  worst per-layer relative L2 over sampled rows:", worst, flush=True)
     dl.close()
+
+
+@pytest.mark.parametrize("model", ["llama-8b", "llama-1b"])
+def test_full_decode_chain_sampled_rows_match_oracle(model):
+    """The same linears wired up as bench.py's dependent decode step (norms, residual adds and
+    SiLU-multiply fused in, bf16 between the layers; every operand that is an earlier layer's
+    output arrives by mail): sampled rows of every layer against the oracle applied to the
+    GPU's own inputs of that layer, and the residual stream to the bit."""
+    import bench
+    print("full size decode chain,", model, flush=True)
+    nb = synth.MODELS[model][0]
+    bits = synth.make_precision_map(nb, nb // 2)
+    layers = build_sampled_model(model, 1, bits)
+    entries = bench.chain_entries(layers, bits, model, torch, nvq, synth, DEV)
+    assert len(entries) == len(layers)
+    dl = nvq.DecodeList(entries, 1, 0)
+    info = dl.plan_info()
+    _, phases = nvq.plan_describe([dl.arr[i] for i in range(dl.n)], 1, 0)
+    print("  plan", info, flush=True)
+    assert info["streaming"] and info["waits"] == 3 * nb - 1 + (1 if len(layers) % 7 else 0)
+    assert all(ph["wait"] < 0 for ph in phases)             # all of it by mail, none by flags
+    for _ in range(3):
+        dl.run_plan()
+    torch.cuda.synchronize()
+    assert not dl.plan_timed_out()
+    worst32 = worst16 = 0.0
+    for L, e in zip(layers, entries):
+        sp, rows = L["spec"], L["rows"]
+        q_r, s_r = oracle.pack_int4(L["w_rows"])
+        h = dict(qweight=q_r, scales=s_r, x=u16(e["x"]), precision=e["precision"],
+                 in_op=e.get("in_op", 0))
+        if e.get("x2") is not None:
+            h["x2"] = u16(e["x2"])
+        if e.get("gamma") is not None:
+            h["gamma"], h["eps"] = u16(e["gamma"]), e["eps"]
+        y_r = oracle.decode_linears([h], 1)[0]
+        idx = torch.from_numpy(rows).to(DEV)
+        got = e["y"][:, idx].float().cpu().numpy()
+        err = np_ref.rel_l2(got, y_r)
+        if e["y"].dtype == torch.float32:
+            worst32 = max(worst32, err)
+            assert err < TOL, (sp.name, err)
+        else:
+            worst16 = max(worst16, err)
+            assert err < 4e-3, (sp.name, err)               # one bf16 rounding per value
+        if e.get("h_out") is not None and e.get("x2") is not None:
+            assert torch.equal(e["h_out"], e["x"] + e["x2"]), sp.name   # exact bf16 sum
+    print("  worst relative L2 over sampled rows: fp32 outputs %.3g, bf16 outputs %.3g"
+          % (worst32, worst16), flush=True)
+    dl.close()

@@ -105,7 +105,8 @@ def test_skip_table_passes_exactly_the_phases_without_rows_and_barriers(model, o
         for j in range(waves):
             _, count = rows_of_wave(ph, j, waves)
             g = (j % nwg) * 12 + j // nwg if ph["spread"] else j
-            active[p, g] = count > 0 or ph["wait"] >= 0 or ph["publish"] == 1
+            active[p, g] = (count > 0 or ph["wait"] >= 0 or ph["publish"] == 1 or
+                            (ph["mail"] & 3) != 0)
     # a workgroup leaves a phase's image alone exactly if none of its 12 waves works in it
     assert np.array_equal(wg_passes[:, :P].T, ~active.reshape(P, nwg, 12).any(axis=2))
     assert not wg_passes[:, P:].any()
@@ -142,8 +143,8 @@ def test_random_lists_deal_every_row_once_and_skip_only_idle_phases(seed):
         chained = prev_y is not None and prev_n == K and rng.random() < 0.5
         x = prev_y if chained else a.take(K * 2)
         for _ in range(int(rng.integers(1, 4))):          # layers sharing the input: one phase
-            N = int(rng.choice([1, 2, 7, 40, 96, 511, 1024, 3072, 4097, 40000]))
-            y_bf16 = chained is False and rng.random() < 0.3
+            N = int(rng.choice([1, 2, 7, 40, 96, 511, 1024, 2048, 3072, 4096, 4097, 40000]))
+            y_bf16 = rng.random() < 0.4
             y = a.take(N * 4)
             layers.append(linear(a, N, K, x, y=y, prec=int(rng.integers(0, 2)), y_f32=not y_bf16))
             prev_y, prev_n = (y, N) if y_bf16 else (None, 0)   # only bf16 outputs can feed a layer
@@ -157,9 +158,11 @@ def test_random_lists_deal_every_row_once_and_skip_only_idle_phases(seed):
     active = np.zeros((P, waves), bool)
     for p, ph in enumerate(phases):
         covered = np.zeros(ph["rows"], np.int32)
-        barrier = ph["wait"] >= 0 or ph["publish"] == 1
-        assert ph["spread"] == int(barrier)
-        if barrier:
+        # a barrier: the phase waits (through flags, or for mail) or publishes through flags
+        barrier = ph["wait"] >= 0 or ph["publish"] == 1 or (ph["mail"] & 3) != 0
+        waited_for = barrier or (ph["mail"] & 4) != 0      # ... or posts mail
+        assert ph["spread"] == int(waited_for)
+        if waited_for:
             assert ph["row_unit"] == max(ph["pair_stream"], 1)
         for j in range(waves):
             first, count = rows_of_wave(ph, j, waves)
@@ -212,13 +215,73 @@ def test_dependencies_follow_the_buffers():
                h_out=a.take(K * 2)),                 # 4 reads y1 through its second operand
     ]
     waves, phases = nvq.plan_describe(layers, 1)
-    assert waves and [ph["wait"] for ph in phases] == [-1, 0, -1, 1, 1]
-    assert [ph["publish"] for ph in phases] == [1, 1, 0, 0, 0]
+    # 1 and 4 take y0 / y1 by mail (exactly one earlier layer's bf16 output): no flags, and 1
+    # never reads y0's memory, so 3 only has to wait for the phase that wrote it before
+    assert waves and [ph["wait"] for ph in phases] == [-1, -1, -1, 0, -1]
+    assert [ph["mail"] & 3 for ph in phases] == [0, 1, 0, 0, 2]
+    assert [ph["mail"] >> 2 for ph in phases] == [1, 1, 0, 0, 0]      # who posts mail
+    assert [ph["publish"] for ph in phases] == [1, 0, 0, 0, 0]
     # a phase whose input must be rebuilt after a wait has no prepared image
     assert [ph["img_prepared"] for ph in phases] == [1, 0, 1, 0, 0]
-    # forced ordering: everybody waits for the one before
+    # who waits or is waited for is dealt rows across the compute units
+    assert [ph["spread"] for ph in phases] == [1, 1, 0, 1, 1]
+    # forced ordering: everybody waits for the one before, through the flags
     _, ordered = nvq.plan_describe(layers, 1, ordered=True)
     assert [ph["wait"] for ph in ordered] == [-1, 0, 1, 2, 3]
+    assert [ph["mail"] for ph in ordered] == [0] * 5
+
+
+def test_mail_needs_exactly_one_earlier_bf16_output():
+    a = Arena()
+    K = 2048
+
+    def waits_and_mail(layers):
+        _, phases = nvq.plan_describe(layers, 1)
+        return [ph["wait"] for ph in phases], [ph["mail"] & 3 for ph in phases]
+
+    x0 = a.take(K * 2)
+    # an fp32 output read back as bf16 input: bytes overlap, no link
+    yf = a.take(K * 4)
+    assert waits_and_mail([linear(a, K, K, x0, yf), linear(a, 64, K, yf)]) == ([-1, 0], [0, 0])
+    # two half-length outputs side by side make up the input: flags
+    yh = a.take(K * 2)
+    assert waits_and_mail([linear(a, K // 2, K, x0, yh, y_f32=False),
+                           linear(a, K // 2, K, x0, yh + K, y_f32=False),
+                           linear(a, 64, K, yh)]) == ([-1, 0], [0, 0])
+    # the input is part of a longer output: flags
+    yl = a.take(2 * K * 2)
+    assert waits_and_mail([linear(a, 2 * K, K, x0, yl, y_f32=False),
+                           linear(a, 64, K, yl + 64)]) == ([-1, 0], [0, 0])
+    # written twice: the later writer is the one that sends the mail (and waits for the
+    # earlier one, whose bytes it overwrites)
+    y = a.take(K * 2)
+    w, m = waits_and_mail([linear(a, K, K, x0, y, y_f32=False),
+                           linear(a, K, K, a.take(K * 2), y, y_f32=False),
+                           linear(a, 64, K, y)])
+    assert (w, m) == ([-1, 0, -1], [0, 0, 1])
+    # the latest writer only touched a part of it: flags for the reader
+    w, m = waits_and_mail([linear(a, K, K, x0, y, y_f32=False),
+                           linear(a, 8, K, a.take(K * 2), y + 32, y_f32=False),
+                           linear(a, 64, K, y)])
+    assert (w, m) == ([-1, 0, 1], [0, 0, 0])
+    # both operands of a SiLU-multiply from the two layers of one phase, and the residual sum
+    # of a norm phase into the next norm: the links of a decode block
+    xg, xu, h0, h1, o, g = (a.take(K * 2) for _ in range(6))
+    block = [linear(a, K, K, x0, o, y_f32=False),                                    # 0 "o"
+             linear(a, K, K, h0, xg, y_f32=False, in_op=nvq.IN_RMSNORM, x2=o, gamma=g,
+                    eps=1e-5, h_out=h1),                                             # 1 gate
+             linear(a, K, K, h0, xu, y_f32=False, in_op=nvq.IN_RMSNORM, x2=o, gamma=g,
+                    eps=1e-5, h_out=h1),                                             #   up
+             linear(a, K, K, xg, a.take(K * 2), y_f32=False, in_op=nvq.IN_SILU_MUL, x2=xu),  # 2 down
+             ]
+    down = block[-1].y
+    block.append(linear(a, 64, K, h1, in_op=nvq.IN_RMSNORM, x2=down, gamma=g, eps=1e-5,
+                        h_out=a.take(K * 2)))                                        # 3 next q
+    w, m = waits_and_mail(block)
+    assert (w, m) == ([-1, -1, -1, -1], [0, 2, 3, 3])
+    # at more than one token there is no persistent batch-1 kernel and no mail
+    _, phases = nvq.plan_describe([linear(a, K, K, a.take(4 * K * 2), a.take(4 * K * 2), y_f32=False, M=4)], 4)
+    assert phases[0]["mail"] == 0
 
 
 def test_grouping_needs_the_same_input_precision_and_transform():
