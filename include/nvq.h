@@ -290,9 +290,12 @@ int nvq_decode_linears_static(const nvq_linear *layers, int n, int M, int act_gr
  *                    [0] phase entered, [1] flags seen (phases that wait),
  *                    [2] input staged, [3] the workgroup's share of the
  *                    operands has arrived (phases that wait; phases that
- *                    publish through flags: all waves done), [4] published,
+ *                    publish through flags: all waves done), [4] published (or:
+ *                    the first of two mail operands has arrived),
  *                    [5] this wave's share of the operands has arrived,
- *                    [6] activations ready, [7] own rows done
+ *                    [6] rows done by the last of the workgroup's waves (clear
+ *                    the buffer before the walk: it is a running maximum),
+ *                    [7] own rows done
  */
 typedef struct nvq_plan nvq_plan;
 enum { NVQ_PLAN_DEFAULT = 0, NVQ_PLAN_ORDERED = 1 };

@@ -581,13 +581,15 @@ template <int NK>
 __device__ __forceinline__ bool mail_fetch(const uint32_t *mail0, const uint32_t *mail1, int K,
                                            int nxc, int w, int lane, uint32_t tag_hi,
                                            uint4 (&out0)[NK], uint4 (&out1)[NK], uint32_t abort_a,
-                                           uint32_t *status, int where) {
+                                           uint32_t *status, int where, const Trace &trace,
+                                           int wg) {
     if (nxc <= kStreamWaves && mail1)  // one piece per wave: both operands at once
         return mail_poll<1, 2>(mail0, mail1, K, nxc, w, lane, tag_hi, out0, out1, abort_a, status,
                                where);
     if (!mail_poll<NK, 1>(mail0, nullptr, K, nxc, w, lane, tag_hi, out0, out1, abort_a, status,
                           where))
         return false;
+    trace_mark(trace, wg, w, lane, where / 2, 4);  // (operands fetched one after the other)
     return !mail1 || mail_poll<NK, 1>(mail1, nullptr, K, nxc, w, lane, tag_hi, out1, out0, abort_a,
                                       status, where + 1);
 }
@@ -657,10 +659,11 @@ __device__ __forceinline__ bool image_build(const Writer &wr, CPhase &ph, Shared
     if constexpr (MAIL) {
         // (both at once if both come by mail; a result of false shows in the abort word)
         if (mail_x)
-            mail_fetch(mail_x, mail_x2, K, nxc, w, lane, tag_hi, xsh, x2sh, abort_a, status, 2 * p);
+            mail_fetch(mail_x, mail_x2, K, nxc, w, lane, tag_hi, xsh, x2sh, abort_a, status, 2 * p,
+                       trace, wg);
         else if (mail_x2)
             mail_fetch(mail_x2, nullptr, K, nxc, w, lane, tag_hi, x2sh, xsh, abort_a, status,
-                       2 * p + 1);
+                       2 * p + 1, trace, wg);
     }
     // with mail the norm weights are requested as soon as the operands have come (not
     // before: the registers are needed for the wait), so that they arrive while the
@@ -1087,9 +1090,10 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
             asm volatile("ds_read_b32 %0, %1" : "=v"(ready_seen) : "v"(ready_a) : "memory");
             ready_pending = true;
         }
-        trace_mark(trace, wg, w, lane, p, 6);
         // Waves w, w + 4, w + 8 share a SIMD; rotate their priorities so that none
-        // of them is favoured for long (see the header).
+        // of them is favoured for long (see the header).  (In phases that end with
+        // everybody waiting for the slowest wave: equal priorities, or the oldest wave
+        // first, cost 7 % of a dependent step; the youngest first is as good as rotating.)
         switch (((w >> 2) + p) % 3) {
             case 0: __builtin_amdgcn_s_setprio(0); break;
             case 1: __builtin_amdgcn_s_setprio(1); break;
@@ -1360,6 +1364,9 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
         // this wave no longer reads the phase's image
         note_progress((uint32_t)(p + 1));
         trace_mark(trace, wg, w, lane, p, 7);
+        if (trace.buf && wg < trace.wgs && lane == 0)  // the last of the workgroup's waves
+            __hip_atomic_fetch_max(&trace.buf[((size_t)wg * trace.nphase + p) * kTraceSlots + 6],
+                                   wall_clock64(), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
         if (ph.publish) {
             // a later phase reads or overwrites what this one touched: make the
