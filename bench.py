@@ -1,26 +1,40 @@
 #!/usr/bin/env python3
 """Benchmark of the decode-linear hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--model llama-8b]
-                    [--map mixed|w4a8|w4a16] [--leg all|step|cpu|calib|prefill] [--extra]
-                    [--batch M] [--act-group 0|32] [--prefill-tokens T]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--model llama-8b|llama-3b|llama-1b]
+                    [--map mixed|w4a8|w4a16] [--batch M] [--act-group 0|32] [--copies C]
+                    [--leg all|step|cpu|cpu-full|config1|ceiling|calib|prefill]
 
-A step is one walk (one run of a prepared nvq plan = one launch of the
-persistent streaming kernel) over every linear layer of one decode step at
-batch 1 of the named Llama-shaped model: activation quantisation for the W4A8
-layers, all GEMVs, lm_head (W4A16) where the model has one.  All weights and
-activations are resident in HBM before the timed region; every layer reads its
-own seeded input buffer.  Prints one JSON line (metric, value, roofline of the
-persistent kernel from HIP events, cpu_baseline = the CPU oracle on a bounded sample).
+A step is one walk (one run of a prepared nvq plan = one launch of the persistent streaming
+kernel at batch 1) over every linear layer of one decode step of the named Llama-shaped model:
+activation quantisation for the W4A8 layers, all GEMVs, lm_head (W4A16) where the model has one.
+All weights and activations are resident in HBM before the timed region.  One JSON line:
 
---leg prefill is a separate measurement outside the headline metric: the seven linears of one
-transformer block of the model for T tokens at once through nvq_gemm_w4a16 (dequantisation
-fused into a bf16 matrix-core GEMM), reported in TFLOP/s against the dense bf16 MFMA peak.
+  value / ms_per_step / roofline   the workload the benchmark's metric is quoted on: every layer
+                                   reads its own seeded input buffer, phases in list order
+  config.*_block_chain             the same linears wired up as a real decode step (norms,
+                                   residual adds, SiLU-multiply fused in; 3 of 4 phases per block
+                                   wait for the phase before them)
+  config.*_ordered_chain           the independent buffers with every phase forced to wait for
+                                   its predecessor
+  config.*_all_w4a8 / _all_w4a16   the two uniform precision maps
+  roofline.ceiling_gbs             a plain streaming read of 4 GiB on this machine, this run
+  cpu_baseline                     the CPU oracle on a bounded sample of the same workload
+
+Every launch of the timed region has its own pair of HIP events on the launch stream
+(roofline.avg/min/median_launch_us); before the warm-up an untimed loop runs until the launch time
+stops falling (config.clock_ramp), so a short run measures the machine at its clocks.
+
+Other legs: `config1` = BASELINE configs[0] (one 2048 x 2048 layer, both precisions, rotated
+over 512 copies, and the warm single-buffer figure); `cpu-full` = the oracle over the whole step
+on all cores and on one; `prefill` = one block's linears for T tokens through nvq_gemm_w4a16;
+`ceiling` = the streaming read alone; `calib` = a plain copy for scaling profiler byte counters.
 """
 import argparse
 import json
 import os
 import re
+import statistics
 import sys
 import time
 
@@ -29,10 +43,13 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-STREAM_KERNEL = "nvq::decode_stream_kernel"  # <per-group scales, paired rows>: one of three
+STREAM_KERNEL = "nvq::decode_stream_kernel"  # <per-group scales, paired rows, mail>
 GROUP_KERNEL = "nvq::gemv_mfma_group_kernel (+ nvq::quant_act_group_kernel)"
 RING_KERNEL = ("nvq::gemv_mfma_ring_kernel (+ nvq::token_scale_group_kernel, "
                "nvq::operand_image_group_kernel)")
+# model copies a step rotates over so that no weight byte is read out of the 256 MB
+# Infinity Cache or the L2s (at least 1 GB of distinct bytes between two uses)
+DEFAULT_COPIES = {"llama-1b": 3, "llama-3b": 2, "llama-8b": 1}
 
 
 def parse():
@@ -43,15 +60,18 @@ def parse():
     ap.add_argument("--model", default="llama-8b", choices=["llama-1b", "llama-3b", "llama-8b"])
     ap.add_argument("--map", default="mixed", choices=["mixed", "w4a8", "w4a16"])
     ap.add_argument("--prefill-tokens", type=int, default=4096)
-    ap.add_argument("--leg", default="all", choices=["all", "step", "cpu", "calib", "prefill"],
-                    help="calib: run only the plain copy kernel (1 GiB, for scaling profiler "
-                         "byte counters)")
+    ap.add_argument("--leg", default="all",
+                    choices=["all", "step", "cpu", "cpu-full", "config1", "ceiling", "calib",
+                             "prefill"])
     ap.add_argument("--act-group", type=int, default=0, choices=[0, 32])
     ap.add_argument("--batch", type=int, default=1,
                     help="tokens per step (1 = the headline workload; 2..32 = the small-batch "
-                         "variant on the matrix cores, one launch per phase)")
-    ap.add_argument("--extra", action="store_true",
-                    help="also time the all-W4A8 / all-W4A16 maps and the fully ordered chain")
+                         "variant on the matrix cores)")
+    ap.add_argument("--copies", type=int, default=0,
+                    help="model copies the timed steps rotate over (0 = enough for 1 GB of "
+                         "distinct weight bytes between two uses of a byte)")
+    ap.add_argument("--extra", action="store_true", help="(kept for older command lines: the "
+                    "chain and uniform-map figures are now part of the default line)")
     return ap.parse_args()
 
 
@@ -66,20 +86,22 @@ def block_bits(model, which, synth):
     return synth.make_precision_map(nb, n16)
 
 
-def build_model(model, M, torch, nvq, synth, dev):
-    """Generate and pack every layer on the GPU (one fp32 tensor alive at a time)."""
+def build_model(model, M, torch, nvq, synth, dev, copy=0):
+    """Generate and pack every layer on the GPU (one fp32 tensor alive at a time).  Copy c > 0
+    is another model of the same shapes (other seeds): for rotating over more bytes than the
+    caches hold."""
     specs = synth.model_linears(model)
     layers = []
     xbuf = {}
     for sp in specs:
-        seed = synth.tensor_seed(sp.block if sp.block >= 0 else 999, sp.slot)
+        seed = synth.tensor_seed(sp.block if sp.block >= 0 else 999, sp.slot) + 7_000_000 * copy
         W = synth.make_weight(seed, sp.N, sp.K, device=dev)
         q, s = nvq.pack_int4(W)
         torch.cuda.synchronize()
         del W
         if sp.phase not in xbuf:
-            xbuf[sp.phase] = synth.make_activation(synth.activation_seed(sp.phase), M, sp.K,
-                                                   True, device=dev)
+            xbuf[sp.phase] = synth.make_activation(synth.activation_seed(sp.phase) + 7_000 * copy,
+                                                   M, sp.K, True, device=dev)
         y = torch.zeros((M, sp.N), dtype=torch.float32, device=dev)
         layers.append(dict(spec=sp, qweight=q, scales=s, x=xbuf[sp.phase], y=y))
     return layers
@@ -144,26 +166,57 @@ def chain_entries(layers, bits, model, torch, nvq, synth, dev):
     return out
 
 
-def time_steps(dl, steps, warmup, torch):
-    """K walks of the prepared plan.  Returns (wall seconds per step between two device
-    synchronisations, seconds per launch from HIP events on the launch stream)."""
-    dl.plan()
-    for _ in range(warmup):
-        dl.run_plan()
+def clock_ramp(dls, torch, budget_s=0.25):
+    """Untimed: walk until the time of a launch stops falling (the clocks of an idle GPU take
+    some milliseconds of load to come up), for at most `budget_s`.  Returns what it saw."""
     st = torch.cuda.current_stream()
-    e0 = torch.cuda.Event(enable_timing=True)
-    e1 = torch.cuda.Event(enable_timing=True)
+    t_end = time.perf_counter() + budget_s
+    first = last = best = None
+    launches = 0
+    while time.perf_counter() < t_end:
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(9)]
+        for i in range(8):
+            ev[i].record(st)
+            dls[launches % len(dls)].run_plan()
+            launches += 1
+        ev[8].record(st)
+        torch.cuda.synchronize()
+        cur = min(ev[i].elapsed_time(ev[i + 1]) for i in range(8)) * 1e3
+        first = cur if first is None else first
+        if best is not None and cur > best * 0.995 and launches >= 24:
+            last = cur
+            break
+        best = cur if best is None else min(best, cur)
+        last = cur
+    return {"launches": launches, "first_us": round(first, 2), "last_us": round(last, 2)}
+
+
+def time_steps(dls, steps, warmup, torch):
+    """K walks of the prepared plans in `dls`, taken in turn (one plan: the same walk K times).
+    Returns (wall seconds per step between two device synchronisations, list of seconds per
+    launch from a HIP event pair per launch on the launch stream)."""
+    if not isinstance(dls, (list, tuple)):
+        dls = [dls]
+    for d in dls:
+        d.plan()
+    for i in range(warmup):
+        dls[i % len(dls)].run_plan()
+    st = torch.cuda.current_stream()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    e0.record(st)
-    for _ in range(steps):
-        dl.run_plan()
-    e1.record(st)
+    for i in range(steps):
+        ev[i].record(st)
+        dls[i % len(dls)].run_plan()
+    ev[steps].record(st)
     torch.cuda.synchronize()
     wall = (time.perf_counter() - t0) / steps
-    if dl.plan_timed_out():
-        raise RuntimeError("a wait inside the streaming kernel timed out; results invalid")
-    return wall, e0.elapsed_time(e1) * 1e-3 / steps
+    for d in dls:
+        if d.plan_timed_out():
+            raise RuntimeError("a wait inside the persistent kernel gave up (code %#x); results "
+                               "invalid" % d.status_code)
+    per = [ev[i].elapsed_time(ev[i + 1]) * 1e-3 for i in range(steps)]
+    return wall, per
 
 
 def traffic_from_profile(model, which, batch, kind="group"):
@@ -174,21 +227,44 @@ def traffic_from_profile(model, which, batch, kind="group"):
     path = os.path.join(ROOT, "profiles", name)
     try:
         m = re.search(r"traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read())
-        return float(m.group(1)) if m else None
+        return (float(m.group(1)) if m else None), "profiles/" + name
     except OSError:
-        return None
+        return None, None
 
 
-def cpu_leg(model, bits, M, synth, budget_s=20.0):
+def ceiling_gbs(torch, nvq, gib=4):
+    """A plain streaming read (non-temporal 128-bit loads, nvq_stream_read) of `gib` GiB: what
+    this machine's HBM delivers to a kernel that does nothing else.  Best of five launches."""
+    buf = torch.empty(gib << 30, dtype=torch.uint8, device="cuda:0")
+    buf.random_(0, 255)
+    sink = torch.zeros(1, dtype=torch.int64, device="cuda:0")
+    for _ in range(3):
+        nvq.stream_read(buf, sink)
+    best = None
+    for _ in range(5):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        nvq.stream_read(buf, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        t = e0.elapsed_time(e1) * 1e-3
+        best = t if best is None else min(best, t)
+    del buf
+    torch.cuda.empty_cache()
+    return (gib << 30) / best / 1e9
+
+
+def cpu_sample(model, bits, M, synth, budget_s=20.0):
     """The oracle's walker on a bounded sample of the same workload: the first blocks of the
-    model (as many as the time budget allows, at most four), inputs generated and packed on
-    the CPU by the oracle itself."""
+    model (at most two) and, where the model has one, the first rows of lm_head, in the
+    proportion of the whole step; inputs generated and packed on the CPU by the oracle itself."""
     import numpy as np
     import torch
     import oracle
-    specs = [s for s in synth.model_linears(model) if s.block >= 0]
+    all_specs = synth.model_linears(model)
+    specs = [s for s in all_specs if s.block >= 0]
     nb = synth.MODELS[model][0]
-    total_w = sum(s.N * s.K for s in synth.model_linears(model))
+    total_w = sum(s.N * s.K for s in all_specs)
     host, sample_w, t_gen0 = [], 0, time.perf_counter()
     blocks = 0
     for b in range(nb):
@@ -200,20 +276,77 @@ def cpu_leg(model, bits, M, synth, budget_s=20.0):
                              precision=bits[b]))
             sample_w += sp.N * sp.K
         blocks += 1
-        if time.perf_counter() - t_gen0 > budget_s * 0.4 or blocks >= 4:
+        if time.perf_counter() - t_gen0 > budget_s * 0.2 or blocks >= 2:
             break
+    head_rows = 0
+    heads = [s for s in all_specs if s.block < 0]
+    if heads:
+        sp = heads[0]
+        # lm_head rows in the proportion blocks / nb of the whole matrix
+        head_rows = max(256, sp.N * blocks // nb // 256 * 256)
+        W = synth.make_weight(synth.tensor_seed(999, sp.slot), head_rows, sp.K)
+        q, s = oracle.pack_int4(W.numpy())
+        x = synth.make_activation(synth.activation_seed(sp.phase), M, sp.K)
+        host.append(dict(qweight=q, scales=s, x=x.view(torch.int16).numpy().view(np.uint16),
+                         precision=1))
+        sample_w += head_rows * sp.K
     oracle.decode_linears(host, M)                       # warm caches and the thread pool
     reps, t0 = 0, time.perf_counter()
-    while reps < 3 or (time.perf_counter() - t0 < budget_s * 0.4 and reps < 50):
+    while reps < 3 or (time.perf_counter() - t0 < budget_s * 0.5 and reps < 50):
         oracle.decode_linears(host, M)
         reps += 1
     t = (time.perf_counter() - t0) / reps
     step_s = t * total_w / sample_w
     threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
     return {"value": round(M / step_s, 3), "unit": "tokens/s", "cores": threads, "kind": "oracle",
-            "sample": "oracle walker over the first %d of %d blocks (%d of %d weights), %d reps, "
-                      "step time scaled by weight count" % (blocks, nb, sample_w, total_w, reps),
+            "sample": "oracle walker over the first %d of %d blocks%s (%d of %d weights), %d reps, "
+                      "step time scaled by weight count" %
+                      (blocks, nb, " and the first %d rows of lm_head" % head_rows if head_rows
+                       else "", sample_w, total_w, reps),
             "gbs": round(total_w * 0.5625 / step_s / 1e9, 2)}
+
+
+def cpu_full(model, bits, M, synth):
+    """The oracle over the whole step (every linear, lm_head included): best of three on all
+    cores, and once on one core."""
+    import numpy as np
+    import torch
+    import oracle
+    host, total_w = [], 0
+    t_gen = time.perf_counter()
+    for sp in synth.model_linears(model):
+        W = synth.make_weight(synth.tensor_seed(sp.block if sp.block >= 0 else 999, sp.slot),
+                              sp.N, sp.K)
+        q, s = oracle.pack_int4(W.numpy())
+        del W
+        x = synth.make_activation(synth.activation_seed(sp.phase), M, sp.K)
+        host.append(dict(qweight=q, scales=s, x=x.view(torch.int16).numpy().view(np.uint16),
+                         precision=1 if sp.block < 0 else bits[sp.block]))
+        total_w += sp.N * sp.K
+    t_gen = time.perf_counter() - t_gen
+    threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    oracle.decode_linears(host, M)
+    best = None
+    for _ in range(3):
+        t0 = time.perf_counter()
+        oracle.decode_linears(host, M)
+        t = time.perf_counter() - t0
+        best = t if best is None else min(best, t)
+    # one core: the OpenMP runtime the oracle's library is linked against is told so
+    import ctypes
+    gomp = ctypes.CDLL("libgomp.so.1")
+    gomp.omp_set_num_threads(1)
+    t0 = time.perf_counter()
+    oracle.decode_linears(host, M)
+    single = time.perf_counter() - t0
+    gomp.omp_set_num_threads(threads)
+    return {"value": round(M / best, 3), "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": "oracle walker over all %d linears of the step (%d weights), best of 3"
+                      % (len(host), total_w),
+            "gbs": round(total_w * 0.5625 / best / 1e9, 2),
+            "single_thread": {"value": round(M / single, 4), "unit": "tokens/s", "cores": 1,
+                              "gbs": round(total_w * 0.5625 / single / 1e9, 3)},
+            "generate_and_pack_s": round(t_gen, 1)}
 
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0
@@ -268,6 +401,89 @@ def prefill_leg(a, torch, nvq, synth):
                      "avg_launch_us": round(dev_s * 1e6 / len(mats), 2)}}))
 
 
+def config1_leg(a, torch, nvq, synth):
+    """BASELINE configs[0]: one 2048 x 2048 layer at batch 1, both precisions.  Cold: 512
+    copies of the layer (1.2 GB: more than the caches hold), as single calls (a W4A8 call is the
+    activation quantisation and the GEMV: two launches) and as one list of 512 layers in one
+    launch of the persistent kernel.  Warm: the same call on one buffer over and over (2.4 MB:
+    resident in the L2 / Infinity Cache; labelled so)."""
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    N = K = 2048
+    copies = 512
+    layer_bytes = synth.weight_bytes(N, K)
+    W = synth.make_weight(synth.tensor_seed(0, 0), N, K, device=dev)
+    q0, s0 = nvq.pack_int4(W)
+    qs = torch.empty((copies,) + tuple(q0.shape), dtype=q0.dtype, device=dev)
+    ss = torch.empty((copies,) + tuple(s0.shape), dtype=s0.dtype, device=dev)
+    gen = torch.Generator(device=dev).manual_seed(synth.BASE_SEED + 31)
+    # (the copies need not be valid quantisations of anything: random nibbles, the one real
+    # layer's scales; every byte distinct memory)
+    qs.random_(0, 256, generator=gen)
+    ss[:] = s0
+    qs[0], ss[0] = q0, s0
+    x = synth.make_activation(synth.activation_seed(0), 1, K, False, device=dev)
+    y = torch.empty((1, N), dtype=torch.float32, device=dev)
+    res = {}
+
+    def timed(fn, reps):
+        for _ in range(3):
+            fn(0)
+        torch.cuda.synchronize()
+        best = None
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(reps):
+                fn(i)
+            e1.record()
+            torch.cuda.synchronize()
+            t = e0.elapsed_time(e1) * 1e-3 / reps
+            best = t if best is None else min(best, t)
+        return best
+
+    def w4a16(i):
+        nvq.gemv_w4a16(qs[i % copies], ss[i % copies], x, out=y)
+
+    codes = nvq.quant_act_i8(x)
+
+    def w4a8(i):
+        xq, xs, gs = nvq.quant_act_i8(x, out=codes)
+        nvq.gemv_w4a8(qs[i % copies], ss[i % copies], xq, xs, gs, out=y)
+
+    for name, fn in (("w4a16", w4a16), ("w4a8", w4a8)):
+        cold = timed(fn, copies)
+        warm = timed(lambda i: fn(0), copies)
+        res[name] = {
+            "single_calls_cold": {"gemv_per_s": round(1 / cold, 1), "us": round(cold * 1e6, 2),
+                                  "gbs": round(layer_bytes / cold / 1e9, 1),
+                                  "frac_of_hbm_peak": round(layer_bytes / cold / 1e9 / HBM_PEAK_GBS, 4)},
+            "single_calls_warm_cache_resident": {"gemv_per_s": round(1 / warm, 1),
+                                                 "us": round(warm * 1e6, 2),
+                                                 "gbs": round(layer_bytes / warm / 1e9, 1)}}
+    # one launch over the 512 copies (each its own output), both precisions
+    ys = torch.empty((copies, 1, N), dtype=torch.float32, device=dev)
+    for name, prec in (("w4a16", nvq.W4A16), ("w4a8", nvq.W4A8)):
+        dl = nvq.DecodeList([dict(qweight=qs[i], scales=ss[i], x=x, y=ys[i], precision=prec)
+                             for i in range(copies)], 1, a.act_group)
+        wall, per = time_steps(dl, max(a.steps // 10, 5), max(a.warmup // 10, 2), torch)
+        t = statistics.median(per) / copies
+        res[name]["one_launch_512_layers_cold"] = {
+            "gemv_per_s": round(1 / t, 1), "us_per_layer": round(t * 1e6, 3),
+            "gbs": round(layer_bytes / t / 1e9, 1),
+            "frac_of_hbm_peak": round(layer_bytes / t / 1e9 / HBM_PEAK_GBS, 4)}
+        dl.close()
+    print(json.dumps({
+        "metric": "single linear layer 2048 x 2048, batch 1: GEMV/s and HBM GB/s",
+        "value": res["w4a8"]["one_launch_512_layers_cold"]["gemv_per_s"], "unit": "GEMV/s",
+        "n_gpus": 1, "higher_is_better": True, "vs_baseline": None, "data": "synthetic",
+        "dtype": "int4 weights; int8 x int4 -> int32 (W4A8) and bf16 x int4 -> f32 (W4A16)",
+        "config": {"workload": "one 2048 x 2048 layer (%d bytes), batch 1, N(0,1) input without "
+                               "outliers; cold = rotated over %d copies (%.2f GB)" %
+                               (layer_bytes, copies, copies * layer_bytes / 1e9),
+                   "results": res}}))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -287,8 +503,17 @@ def main():
         print(json.dumps({"calib": "nvq::stream_copy_kernel", "bytes_read": 1 << 30,
                           "bytes_written": 1 << 30, "launches": 5}))
         return
+    if a.leg == "ceiling":
+        torch.cuda.set_device(0)
+        g = ceiling_gbs(torch, nvq)
+        print(json.dumps({"ceiling": "nvq::stream_read_kernel, 4 GiB, best of 5",
+                          "gbs": round(g, 1), "frac_of_hbm_peak": round(g / HBM_PEAK_GBS, 4)}))
+        return
     if a.leg == "prefill":
         prefill_leg(a, torch, nvq, synth)
+        return
+    if a.leg == "config1":
+        config1_leg(a, torch, nvq, synth)
         return
     M = a.batch
     if not 1 <= M <= 32:
@@ -297,6 +522,7 @@ def main():
     bits = block_bits(a.model, a.map, synth)
     specs = synth.model_linears(a.model)
     step_bytes = sum(synth.weight_bytes(s.N, s.K) for s in specs)
+    copies = a.copies if a.copies > 0 else DEFAULT_COPIES[a.model]
     out = {
         "metric": "decode linear-layer tokens/s + achieved HBM GB/s (%% of peak), %s shapes, "
                   "batch %d" % (a.model.split("-")[1].upper(), M),
@@ -305,12 +531,15 @@ def main():
         "dtype": "int4 weights; int8 x int4 -> int32 (W4A8) and bf16 x int4 -> f32 (W4A16)",
         "data": "synthetic",
         "config": {"workload": "%s-shaped decode step, batch %d, %d linears in %s, precision map "
-                               "%s (%d of %d blocks W4A16%s), own input buffer per layer" %
+                               "%s (%d of %d blocks W4A16%s), own input buffer per layer%s" %
                                (a.model, M, len(specs),
                                 "one launch" if M == 1 else "three launches", a.map,
                                 sum(bits), len(bits),
-                                ", lm_head W4A16" if specs[-1].block < 0 else ""),
-                   "act_group": a.act_group, "weight_bytes_per_step": step_bytes},
+                                ", lm_head W4A16" if specs[-1].block < 0 else "",
+                                ", steps rotate over %d model copies (%.2f GB)" %
+                                (copies, copies * step_bytes / 1e9) if copies > 1 else ""),
+                   "act_group": a.act_group, "weight_bytes_per_step": step_bytes,
+                   "model_copies": copies},
     }
     if a.leg in ("all", "step"):
         if not torch.cuda.is_available():
@@ -319,63 +548,79 @@ def main():
         dev = "cuda:0"
         torch.cuda.set_device(0)
         nvq.lib()
-        layers = build_model(a.model, M, torch, nvq, synth, dev)
-        dl = nvq.DecodeList(entries_for(layers, bits, nvq), M, a.act_group)
-        info = dl.plan_info()
-        wall, per_launch = time_steps(dl, a.steps, a.warmup, torch)
+        models = [build_model(a.model, M, torch, nvq, synth, dev, c) for c in range(copies)]
+        layers = models[0]
+        dls = [nvq.DecodeList(entries_for(m, bits, nvq), M, a.act_group) for m in models]
+        for d in dls:
+            d.plan()
+        info = dls[0].plan_info()
+        out["config"]["clock_ramp"] = clock_ramp(dls, torch)
+        wall, per = time_steps(dls, a.steps, a.warmup, torch)
+        per_launch = sum(per) / len(per)
         out["value"] = round(M / wall, 2)
         out["ms_per_step"] = round(wall * 1e3, 4)
         out["config"]["plan"] = info
         gbs = step_bytes / per_launch / 1e9
+        traffic, traffic_src = traffic_from_profile(
+            a.model, a.map, M, "ring" if info["persistent_grouped"] else "group")
         out["roofline"] = {
             "bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": round(gbs / HBM_PEAK_GBS, 4),
-            "traffic": traffic_from_profile(a.model, a.map, M,
-                                            "ring" if info["persistent_grouped"] else "group"),
+            "traffic": traffic, "traffic_source": traffic_src,
             "kernel": (STREAM_KERNEL if info["streaming"] else
                        RING_KERNEL if info["persistent_grouped"] else
                        GROUP_KERNEL if info["grouped"] else "per-phase launches"),
             "launches": a.steps, "avg_launch_us": round(per_launch * 1e6, 2),  # per step
+            "min_launch_us": round(min(per) * 1e6, 2),
+            "median_launch_us": round(statistics.median(per) * 1e6, 2),
             "bytes_per_launch": step_bytes}
-        dl.close()
-        if a.extra:
-            for name in ("w4a8", "w4a16"):
-                d2 = nvq.DecodeList(entries_for(layers, block_bits(a.model, name, synth), nvq), M,
-                                    a.act_group)
-                w2, _ = time_steps(d2, max(a.steps // 2, 1), max(a.warmup // 2, 1), torch)
-                out["config"]["tokens_per_s_all_" + name] = round(M / w2, 2)
-                d2.close()
-            # prefill helper: dense bf16 weights of the largest layer (reads 0.5625, writes 2 bytes
-            # per weight)
-            big = max(layers, key=lambda L: L["spec"].N * L["spec"].K)
-            dense = nvq.dequant_bf16(big["qweight"], big["scales"])
-            e0 = torch.cuda.Event(enable_timing=True)
-            e1 = torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(20):
-                nvq.dequant_bf16_into(big["qweight"], big["scales"], dense)
-            e1.record()
-            torch.cuda.synchronize()
-            nw = big["spec"].N * big["spec"].K
-            out["config"]["dequant_bf16_gbs"] = round(nw * 2.5625 * 20 / (e0.elapsed_time(e1) * 1e-3)
-                                                      / 1e9, 1)
-            del dense
+        if copies > 1:
+            # the same walk on one copy over and over: partly out of the caches
+            w1, p1 = time_steps(dls[0], a.steps, a.warmup, torch)
+            out["config"]["single_copy_cache_resident"] = {
+                "tokens_per_s": round(M / w1, 2),
+                "frac_of_hbm_peak": round(step_bytes / statistics.median(p1) / 1e9 / HBM_PEAK_GBS, 4)}
+        for d in dls[1:]:
+            d.close()
+        del dls[1:], models[1:]
+
+        def side(entries, ordered=False):
+            d = nvq.DecodeList(entries, M, a.act_group, ordered=ordered)
+            w, p = time_steps(d, a.steps, a.warmup, torch)
+            inf = d.plan_info()
+            d.close()
+            med = statistics.median(p)
+            return {"tokens_per_s": round(M / w, 2), "ms_per_step": round(w * 1e3, 4),
+                    "median_launch_us": round(med * 1e6, 2),
+                    "frac_of_hbm_peak": round(step_bytes / med / 1e9 / HBM_PEAK_GBS, 4),
+                    "waits": inf["waits"]}
+
+        if a.leg == "all":
             if M == 1:
-                # the realistic dependent step: norms, residual adds and SiLU-multiply fused in
-                d4 = nvq.DecodeList(chain_entries(layers, bits, a.model, torch, nvq, synth, dev), 1,
-                                    a.act_group)
-                w4, _ = time_steps(d4, max(a.steps // 2, 1), max(a.warmup // 2, 1), torch)
-                out["config"]["tokens_per_s_block_chain"] = round(1 / w4, 2)
-                out["config"]["block_chain_plan"] = d4.plan_info()
-                d4.close()
-            d3 = nvq.DecodeList(entries_for(layers, bits, nvq), M, a.act_group, ordered=True)
-            w3, _ = time_steps(d3, max(a.steps // 2, 1), max(a.warmup // 2, 1), torch)
-            out["config"]["tokens_per_s_ordered_chain"] = round(M / w3, 2)
-            d3.close()
-        del layers
+                r = side(chain_entries(layers, bits, a.model, torch, nvq, synth, dev))
+                out["config"]["tokens_per_s_block_chain"] = r["tokens_per_s"]
+                out["config"]["block_chain_frac"] = r["frac_of_hbm_peak"]
+                out["config"]["block_chain"] = r
+            r = side(entries_for(layers, bits, nvq), ordered=True)
+            out["config"]["tokens_per_s_ordered_chain"] = r["tokens_per_s"]
+            out["config"]["ordered_chain_frac"] = r["frac_of_hbm_peak"]
+            out["config"]["ordered_chain"] = r
+            if a.map == "mixed":
+                for name in ("w4a8", "w4a16"):
+                    r = side(entries_for(layers, block_bits(a.model, name, synth), nvq))
+                    out["config"]["tokens_per_s_all_" + name] = r["tokens_per_s"]
+                    out["config"]["all_%s_frac" % name] = r["frac_of_hbm_peak"]
+        dls[0].close()
+        del layers, models, dls
         torch.cuda.empty_cache()
+        if a.leg == "all":
+            g = ceiling_gbs(torch, nvq)
+            out["roofline"]["ceiling_gbs"] = round(g, 1)
+            out["roofline"]["frac_of_ceiling"] = round(gbs / g, 4)
     if a.leg in ("all", "cpu"):
-        out["cpu_baseline"] = cpu_leg(a.model, bits, M, synth)
+        out["cpu_baseline"] = cpu_sample(a.model, bits, M, synth)
+    if a.leg == "cpu-full":
+        out["cpu_baseline"] = cpu_full(a.model, bits, M, synth)
     print(json.dumps(out))
 
 

@@ -90,6 +90,7 @@ Workspace carve(void *base, int M, int n, const ListSizes &ls) {
     // the flag block comes first: the status word has a fixed place in every workspace
     w.flags = reinterpret_cast<uint32_t *>(take(kStreamMaxWg * 4));
     w.status = reinterpret_cast<uint32_t *>(take(256));
+    take((size_t)(kFlagReplicas - 1) * kStreamMaxWg * 4);  // the other copies of the flags
     w.imgflags = reinterpret_cast<uint32_t *>(take((size_t)(n > 0 ? n : 1) * 4));
     w.xt = reinterpret_cast<uint16_t *>(take(ls.transforms ? (size_t)M * maxK * 2 : 0));
     w.xq = reinterpret_cast<int8_t *>(take((size_t)M * maxK));

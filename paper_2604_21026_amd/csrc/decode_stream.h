@@ -12,8 +12,14 @@ constexpr int kStreamImageMax = 31744;  // largest image, padded to whole KiB (b
 constexpr int kStreamImageArea = 59392; // LDS bytes that hold the images of consecutive phases
 constexpr int kStreamMaxWg = 1024;      // flag words reserved for workgroups
 // Layout of the flag words: [0, kStreamMaxWg) one per workgroup, then 64 status
-// words, then one word per phase ("the prepared image of this phase is stored").
-constexpr int kStreamImageFlags = kStreamMaxWg + 64;
+// words, then kFlagReplicas - 1 more copies of the workgroup flags (a workgroup
+// raises its flag in every copy and polls the copy of its XCD: 256 workgroups
+// polling the same kilobyte made the memory channel that holds it the bound of
+// the wait), then one word per phase ("the prepared image of this phase is
+// stored").
+constexpr int kFlagReplicas = 8;
+constexpr int kStreamFlagCopies = kStreamMaxWg + 64;  // copies 1 .. kFlagReplicas - 1
+constexpr int kStreamImageFlags = kStreamFlagCopies + (kFlagReplicas - 1) * kStreamMaxWg;
 // Skip table: one row of skip_stride(phases) bytes per streaming wave (workgroup *
 // kStreamWaves + wave); byte p = how many phases from p on the wave may pass
 // without a look (it has no rows in them and they have no barriers), at most 255.

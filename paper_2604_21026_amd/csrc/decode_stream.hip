@@ -90,7 +90,8 @@ typedef const __attribute__((address_space(4))) StreamPhase CPhase;
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 
-constexpr int kSlots = 6;                 // ring slots per wave (1 KiB weights + 256 B scales)
+constexpr int kSlots = 6;                 // ring slots per wave (1 KiB weights + 256 B scales);
+                                          // 3, 4 or 5 stream as fast on an 8B-shaped step
 constexpr int kOpsPerChunk = 2;            // scale load + weight load
 constexpr int kXChunkElems = 512;          // bf16 values per input chunk
 constexpr int kMaxXShare = (kStreamMaxK / kXChunkElems + kStreamWaves - 1) / kStreamWaves;  // 4
@@ -848,6 +849,9 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
     // ---- soon as it is stored (the loader waves wait for the images they copy,
     // ---- nobody waits for all of them)
     uint32_t *const img_flags = flags + kStreamImageFlags;
+    auto flag_copy = [&](int r) -> uint32_t * {
+        return r == 0 ? flags : flags + kStreamFlagCopies + (r - 1) * kStreamMaxWg;
+    };
 
     if (nimages > 0) {
         for (int p = wg; p < nphase; p += nwg) {
@@ -1062,8 +1066,8 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
             // ---- (or from the mail, whose arrival is the wait), all together
             if (ph.wait_phase >= 0) {
                 if (w == 0) {
-                    const bool ok =
-                        wait_flags(flags, nwg, flag_base + 2u + (uint32_t)ph.wait_phase, lane);
+                    const bool ok = wait_flags(flag_copy(wg & (kFlagReplicas - 1)), nwg,
+                                               flag_base + 2u + (uint32_t)ph.wait_phase, lane);
                     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
                     if (!ok && lane == 0) {
                         lds_write4(abort_a, 1u);
@@ -1376,9 +1380,9 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
             if (w == 0) {
                 trace_mark(trace, wg, w, lane, p, 3);
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-                if (lane == 0)
-                    __hip_atomic_store(flags + wg, flag_base + 2u + (uint32_t)p, __ATOMIC_RELAXED,
-                                       __HIP_MEMORY_SCOPE_AGENT);
+                if (lane < kFlagReplicas)  // one store instruction, a lane per copy
+                    __hip_atomic_store(flag_copy(lane) + wg, flag_base + 2u + (uint32_t)p,
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 trace_mark(trace, wg, w, lane, p, 4);
             }
         }

@@ -183,13 +183,17 @@ def silu_mul(g: torch.Tensor, u: torch.Tensor) -> torch.Tensor:
     return out
 
 
-def quant_act_i8(x: torch.Tensor, act_group: int = 0):
-    """x bf16 [M,K] -> xq i8 [M,K], xscale f32 [M] or [M,K/32], xgsum i32 [M,K/32]."""
+def quant_act_i8(x: torch.Tensor, act_group: int = 0, out=None):
+    """x bf16 [M,K] -> xq i8 [M,K], xscale f32 [M] or [M,K/32], xgsum i32 [M,K/32]
+    (`out`: the three tensors to write into, as returned by an earlier call)."""
     M, K = x.shape
-    xq = torch.empty((M, K), dtype=torch.int8, device=x.device)
-    xs = torch.empty((M,) if act_group == 0 else (M, K // 32), dtype=torch.float32,
-                     device=x.device)
-    gs = torch.empty((M, K // 32), dtype=torch.int32, device=x.device)
+    if out is not None:
+        xq, xs, gs = out
+    else:
+        xq = torch.empty((M, K), dtype=torch.int8, device=x.device)
+        xs = torch.empty((M,) if act_group == 0 else (M, K // 32), dtype=torch.float32,
+                         device=x.device)
+        gs = torch.empty((M, K // 32), dtype=torch.int32, device=x.device)
     _check(lib().nvq_quant_act_i8(_dev(x, torch.bfloat16, "x"), M, K, act_group, xq.data_ptr(),
                                   xs.data_ptr(), gs.data_ptr(), _stream()), "nvq_quant_act_i8")
     return xq, xs, gs
