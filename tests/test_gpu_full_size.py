@@ -1,5 +1,5 @@
-"""GPU parity at the benchmark's full size: the Llama-3.1-8B-shaped decode step
-(225 linears, 7.5 G weights), built and launched exactly as bench.py does, with
+"""GPU parity at the benchmark's full sizes: the Llama-shaped decode steps (8B: 225
+linears, 7.5 G weights; 3B; 1B), built and launched exactly as bench.py does, with
 sampled output rows checked one by one against the CPU oracle.
 
 Per layer a few rows are sampled (first, last, two seeded); their fp32 weights
@@ -46,12 +46,16 @@ def build_sampled_model(model, M, bits):
     return layers
 
 
-@pytest.mark.parametrize("M", [1, 16])
-def test_full_8b_step_sampled_rows_match_oracle(M):
-    print("full size 8B step, M =", M, flush=True)
-    model = "llama-8b"
-    nb = synth.MODELS[model][0]
-    bits = synth.make_precision_map(nb, nb // 2)
+@pytest.mark.parametrize("model,M", [("llama-8b", 1), ("llama-8b", 16), ("llama-8b", 32),
+                                     ("llama-1b", 1), ("llama-3b", 1)])
+def test_full_step_sampled_rows_match_oracle(model, M):
+    """The benchmark's workloads as bench.py builds and launches them: the 8B step at 1, 16 and
+    32 tokens (one and two token tiles of the matrix-core kernel), and the whole 1B and 3B
+    steps at batch 1 (64 and 112 phases: thin phases dealt in larger units, rows of one and a
+    half chunks streamed in pairs, the skip table)."""
+    import bench
+    print("full size step,", model, "M =", M, flush=True)
+    bits = bench.block_bits(model, "mixed", synth)
     layers = build_sampled_model(model, M, bits)
     dl = nvq.DecodeList(layers, M, 0)
     dl.plan()
@@ -82,7 +86,7 @@ def test_full_8b_step_sampled_rows_match_oracle(M):
     dl.close()
 
 
-@pytest.mark.parametrize("model", ["llama-8b", "llama-1b"])
+@pytest.mark.parametrize("model", ["llama-8b", "llama-1b", "llama-3b"])
 def test_full_decode_chain_sampled_rows_match_oracle(model):
     """The same linears wired up as bench.py's dependent decode step (norms, residual adds and
     SiLU-multiply fused in, bf16 between the layers; every operand that is an earlier layer's
@@ -91,7 +95,7 @@ def test_full_decode_chain_sampled_rows_match_oracle(model):
     import bench
     print("full size decode chain,", model, flush=True)
     nb = synth.MODELS[model][0]
-    bits = synth.make_precision_map(nb, nb // 2)
+    bits = bench.block_bits(model, "mixed", synth)
     layers = build_sampled_model(model, 1, bits)
     entries = bench.chain_entries(layers, bits, model, torch, nvq, synth, DEV)
     assert len(entries) == len(layers)
