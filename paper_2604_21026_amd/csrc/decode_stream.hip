@@ -471,23 +471,27 @@ __device__ __forceinline__ void trace_mark(const Trace &trace, int wg, int w, in
 // ---- mail --------------------------------------------------------------------
 // Post eight consecutive bf16 values (piece j of 512, lane's share) in every
 // replica of a mailbox.
-__device__ __forceinline__ void mail_post8(uint32_t *mail, uint32_t stride, int j, int lane,
-                                           const uint4 &v, uint32_t tag_hi) {
+__device__ __forceinline__ void mail_post8_one(uint32_t *mail, uint32_t stride, int r, int j,
+                                               int lane, const uint4 &v, uint32_t tag_hi) {
     const u32x4_t a = {tag_hi | (v.x & 0xffffu), tag_hi | (v.x >> 16), tag_hi | (v.y & 0xffffu),
                        tag_hi | (v.y >> 16)};
     const u32x4_t b = {tag_hi | (v.z & 0xffffu), tag_hi | (v.z >> 16), tag_hi | (v.w & 0xffffu),
                        tag_hi | (v.w >> 16)};
-    uint32_t *p = mail + (size_t)j * 512 + lane * 4;
-    for (int r = 0; r < kMailReplicas; ++r, p += stride) {
-        // (the s_nop: a store of more than 8 bytes reads its data registers a few cycles
-        // after it issues, and the compiler, which does not see into the statement, may
-        // let the next instruction overwrite them)
-        asm volatile("global_store_dwordx4 %0, %1, off sc1\n\t"
-                     "global_store_dwordx4 %0, %2, off offset:1024 sc1\n\ts_nop 3"
-                     :
-                     : "v"(p), "v"(a), "v"(b)
-                     : "memory");
-    }
+    uint32_t *p = mail + (size_t)r * stride + (size_t)j * 512 + lane * 4;
+    // (the s_nop: a store of more than 8 bytes reads its data registers a few cycles after it
+    // issues, and the compiler, which does not see into the statement, may let the next
+    // instruction overwrite them)
+    asm volatile("global_store_dwordx4 %0, %1, off sc1\n\t"
+                 "global_store_dwordx4 %0, %2, off offset:1024 sc1\n\ts_nop 3"
+                 :
+                 : "v"(p), "v"(a), "v"(b)
+                 : "memory");
+}
+
+// The same in every replica.
+__device__ __forceinline__ void mail_post8(uint32_t *mail, uint32_t stride, int j, int lane,
+                                           const uint4 &v, uint32_t tag_hi) {
+    for (int r = 0; r < kMailReplicas; ++r) mail_post8_one(mail, stride, r, j, lane, v, tag_hi);
 }
 
 // Word of value v in a mailbox (see StreamPhase).
@@ -599,7 +603,8 @@ __device__ __forceinline__ bool mail_fetch(const uint32_t *mail0, const uint32_t
 // together: wave w handles the 512-value pieces w, w + waves, ...  The phase's
 // input transform (RMSNorm with residual add, SiLU-multiply; paper: kernel
 // table) is applied on the way, so it costs no launch and no pass over memory;
-// `store_h` says whether this workgroup stores the residual sum.  Operands that
+// `h_wg`: this workgroup's number for the dealing of the residual sum's stores (-1:
+// it stores all of it).  Operands that
 // have a mailbox (MAIL) are polled out of it instead of being loaded.  With
 // `entry_barrier` (phases built after a wait) the workgroup meets once after the
 // operands have arrived: from then on every wave has left the previous phase
@@ -609,7 +614,7 @@ __device__ __forceinline__ bool mail_fetch(const uint32_t *mail0, const uint32_t
 // squares for RMSNorm; absmax exchange for W4A8 with a per-token scale).
 template <bool PER_GROUP, bool MAIL, class Writer>
 __device__ __forceinline__ bool image_build(const Writer &wr, CPhase &ph, Shared &sh, int w,
-                                            int lane, bool store_h, bool entry_barrier,
+                                            int lane, int h_wg, bool entry_barrier,
                                             uint32_t tag_hi, uint32_t mail_stride, uint32_t abort_a,
                                             uint32_t *status, int p, const Trace &trace, int wg) {
     const int in_op = ph.in_op;
@@ -698,10 +703,25 @@ __device__ __forceinline__ bool image_build(const Writer &wr, CPhase &ph, Shared
             } else if (in_op == NVQ_IN_RMSNORM) {
                 if (x2) {
                     xsh[k] = add_bf16x8(xsh[k], x2sh[k]);
-                    if (store_h && ph.h_out) {
-                        reinterpret_cast<uint4 *>(ph.h_out)[idx] = xsh[k];
-                        if constexpr (MAIL)
-                            if (ph.mail_h) mail_post8(ph.mail_h, mail_stride, j, lane, xsh[k], tag_hi);
+                    if (ph.h_out) {
+                        // Who stores the sum: the one workgroup that builds the image (h_wg
+                        // < 0: prologue), else the work is dealt out, piece j to workgroup
+                        // 8 j for the caller's buffer and to workgroups 8 j + r for replica
+                        // r of the mailbox (one workgroup doing all of it finished every
+                        // such phase 2 us behind the others, which then waited for it)
+                        const int nwg = (int)gridDim.x;
+                        int r = h_wg - j * kMailReplicas % nwg;
+                        r = r < 0 ? r + nwg : r;
+                        if (h_wg < 0 || r == 0) reinterpret_cast<uint4 *>(ph.h_out)[idx] = xsh[k];
+                        if constexpr (MAIL) {
+                            if (ph.mail_h) {
+                                if (h_wg < 0)
+                                    mail_post8(ph.mail_h, mail_stride, j, lane, xsh[k], tag_hi);
+                                else if (r < kMailReplicas)
+                                    mail_post8_one(ph.mail_h, mail_stride, r, j, lane, xsh[k],
+                                                   tag_hi);
+                            }
+                        }
                     }
                 }
                 ss += sumsq_bf16x8(xsh[k]);
@@ -858,7 +878,7 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
             CPhase &ph = tab[p];
             if (ph.img) {
                 const GlobalWriter wr = {reinterpret_cast<char *>(const_cast<uint4 *>(ph.img))};
-                image_build<PER_GROUP, MAIL>(wr, ph, sh, w, lane, true, false, mail_tag_hi, mail_stride,
+                image_build<PER_GROUP, MAIL>(wr, ph, sh, w, lane, -1, false, mail_tag_hi, mail_stride,
                                              abort_a, status, p, trace, wg);
                 __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // this wave's image stores have completed
                 lds_barrier();                             // (and sh.amax_part may be reused)
@@ -984,7 +1004,7 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
                 if (ph.wait_phase >= 0) lds_barrier();  // flags seen
                 const LdsWriter wr = {0};
                 // barrier count only; false: abort raised
-                if (!image_build<PER_GROUP, MAIL>(wr, ph, sh, w, lane, false, true, 0u, 0u, abort_a,
+                if (!image_build<PER_GROUP, MAIL>(wr, ph, sh, w, lane, 0, true, 0u, 0u, abort_a,
                                                   status, p, trace, wg))
                     break;
                 lds_barrier();  // image complete
@@ -1079,7 +1099,7 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
             }
             trace_mark(trace, wg, w, lane, p, 1);
             const LdsWriter wr = {img};
-            if (!image_build<PER_GROUP, MAIL>(wr, ph, sh, w, lane, wg == 0, true, mail_tag_hi,
+            if (!image_build<PER_GROUP, MAIL>(wr, ph, sh, w, lane, wg, true, mail_tag_hi,
                                               mail_stride, abort_a, status, p, trace, wg))
                 break;
             trace_mark(trace, wg, w, lane, p, 2);
