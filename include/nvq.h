@@ -204,7 +204,13 @@ typedef struct nvq_linear {
  * caller's buffer (which still receives every output).  This is the fast way
  * for the links of a real decode step (output projection -> next norm, gate
  * and up -> SiLU-multiply, down projection -> next block); all other
- * dependencies wait through per-workgroup flags.  At 2 <= M <= 32 with per-token activation scales and every
+ * dependencies wait through per-workgroup flags.  The persistent kernel may
+ * take two neighbouring phases in the other order: where a phase reads what its
+ * predecessor writes and the phase after it shares no buffer with either, that
+ * one goes first, so that the waves have work while the results travel (a
+ * decode step whose attention runs elsewhere has one such phase per block, the
+ * output projection).  Phases that share no buffer give the same results in
+ * any order; NVQ_PLAN_ORDERED keeps the list's order.  At 2 <= M <= 32 with per-token activation scales and every
  * K a multiple of 128, phases that do not depend on each other share two or
  * three launches on the matrix cores.  Otherwise one or two launches per phase
  * are enqueued.  All give the same results (up to the fp32 summation order).
@@ -312,7 +318,8 @@ int nvq_plan_trace(nvq_plan *plan, uint64_t *buf, size_t bytes);
  * persistent kernel would use.  out (host, out_words int32): [0] phases,
  * [1] the number of streaming waves the rows are dealt to if the list
  * qualifies for the persistent kernel, else 0; then 16 words per
- * phase: first entry, entries, the latest earlier phase it must wait for (-1:
+ * phase, in the order the kernel takes them (see nvq_decode_linears): first
+ * entry, entries, the latest earlier phase it must wait for (-1:
  * none; in the persistent kernel: through the flags, operands that arrive by
  * mail do not count), and for the persistent kernel: published (someone waits
  * for it through the flags),

@@ -294,6 +294,42 @@ int check_phase_hazards(const nvq_linear *L, const std::vector<Phase> &phases, i
     return NVQ_OK;
 }
 
+// The order the persistent kernel takes the phases in (batch 1).  A phase that
+// reads what its predecessor writes starts with everybody waiting for the
+// predecessor's slowest wave and for the results to travel.  Where the phase
+// after it conflicts with neither of the two, that one goes first: the waves
+// that are done early then have work, and the wait has passed when they get
+// there.  (A decode step whose attention runs elsewhere has one such phase per
+// block, the o projection.)  Phases that do not conflict may run in any order,
+// so every result is what the list's own order gives.
+bool phases_conflict(const nvq_linear *L, const Phase &a, const Phase &b, int M) {
+    std::vector<Range> ain, aout, bin, bout;
+    phase_ranges(L, a, M, &ain, &aout);
+    phase_ranges(L, b, M, &bin, &bout);
+    for (const Range &y : aout) {
+        for (const Range &x : bin)
+            if (overlap(y, x)) return true;
+        for (const Range &z : bout)
+            if (overlap(y, z)) return true;
+    }
+    for (const Range &y : bout)
+        for (const Range &x : ain)
+            if (overlap(y, x)) return true;
+    return false;
+}
+
+void schedule_phases(const nvq_linear *L, std::vector<Phase> *phases, int M, bool ordered) {
+    if (M != 1 || ordered) return;
+    std::vector<Phase> &ph = *phases;
+    for (size_t p = 1; p + 1 < ph.size(); ++p) {
+        if (phases_conflict(L, ph[p - 1], ph[p], M) && !phases_conflict(L, ph[p], ph[p + 1], M) &&
+            !phases_conflict(L, ph[p - 1], ph[p + 1], M)) {
+            std::swap(ph[p], ph[p + 1]);
+            ++p;  // the phase that waits stays where it is now
+        }
+    }
+}
+
 // Mail links (batch 1, persistent kernel).  An input operand (x, or x2 of a
 // transform) of phase p is linked if the latest earlier phase that writes any
 // of its bytes writes exactly that vector as one bf16 output (y of one of its
@@ -808,6 +844,7 @@ extern "C" int nvq_plan_create(const nvq_linear *layers, int n, int M, int act_g
     if (!pl) return NVQ_ERR_UNSUPPORTED;
     pl->layers.assign(layers, layers + n);
     pl->phases = group_phases(pl->layers.data(), n);
+    schedule_phases(pl->layers.data(), &pl->phases, M, (flags & NVQ_PLAN_ORDERED) != 0);
     if (check_phase_hazards(pl->layers.data(), pl->phases, M) != NVQ_OK) {
         delete pl;
         return NVQ_ERR_INVALID_ARG;
@@ -959,7 +996,8 @@ extern "C" int nvq_plan_describe(const nvq_linear *layers, int n, int M, int act
     ListSizes ls;
     const int rc = check_layers(layers, n, M, act_group, &ls);
     if (rc != NVQ_OK) return rc;
-    const std::vector<Phase> phases = group_phases(layers, n);
+    std::vector<Phase> phases = group_phases(layers, n);
+    schedule_phases(layers, &phases, M, (flags & NVQ_PLAN_ORDERED) != 0);
     if (check_phase_hazards(layers, phases, M) != NVQ_OK) return NVQ_ERR_INVALID_ARG;
     const bool ordered = (flags & NVQ_PLAN_ORDERED) != 0;
     int nimages = 0;
@@ -1008,7 +1046,8 @@ extern "C" int nvq_plan_describe_skips(const nvq_linear *layers, int n, int M, i
     ListSizes ls;
     const int rc = check_layers(layers, n, M, act_group, &ls);
     if (rc != NVQ_OK) return rc;
-    const std::vector<Phase> phases = group_phases(layers, n);
+    std::vector<Phase> phases = group_phases(layers, n);
+    schedule_phases(layers, &phases, M, (flags & NVQ_PLAN_ORDERED) != 0);
     if (check_phase_hazards(layers, phases, M) != NVQ_OK) return NVQ_ERR_INVALID_ARG;
     int nimages = 0;
     std::vector<uint8_t> skips;

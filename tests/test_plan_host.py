@@ -215,20 +215,54 @@ def test_dependencies_follow_the_buffers():
                h_out=a.take(K * 2)),                 # 4 reads y1 through its second operand
     ]
     waves, phases = nvq.plan_describe(layers, 1)
+    # layer 1 reads what its predecessor writes and layer 2 conflicts with neither: 2 goes
+    # first, so that the wait has passed when the waves get to 1
+    assert [ph["first"] for ph in phases] == [0, 2, 1, 3, 4]
     # 1 and 4 take y0 / y1 by mail (exactly one earlier layer's bf16 output): no flags, and 1
     # never reads y0's memory, so 3 only has to wait for the phase that wrote it before
     assert waves and [ph["wait"] for ph in phases] == [-1, -1, -1, 0, -1]
-    assert [ph["mail"] & 3 for ph in phases] == [0, 1, 0, 0, 2]
-    assert [ph["mail"] >> 2 for ph in phases] == [1, 1, 0, 0, 0]      # who posts mail
+    assert [ph["mail"] & 3 for ph in phases] == [0, 0, 1, 0, 2]
+    assert [ph["mail"] >> 2 for ph in phases] == [1, 0, 1, 0, 0]      # who posts mail
     assert [ph["publish"] for ph in phases] == [1, 0, 0, 0, 0]
     # a phase whose input must be rebuilt after a wait has no prepared image
-    assert [ph["img_prepared"] for ph in phases] == [1, 0, 1, 0, 0]
+    assert [ph["img_prepared"] for ph in phases] == [1, 1, 0, 0, 0]
     # who waits or is waited for is dealt rows across the compute units
-    assert [ph["spread"] for ph in phases] == [1, 1, 0, 1, 1]
+    assert [ph["spread"] for ph in phases] == [1, 0, 1, 1, 1]
     # forced ordering: everybody waits for the one before, through the flags
     _, ordered = nvq.plan_describe(layers, 1, ordered=True)
+    assert [ph["first"] for ph in ordered] == [0, 1, 2, 3, 4]
     assert [ph["wait"] for ph in ordered] == [-1, 0, 1, 2, 3]
     assert [ph["mail"] for ph in ordered] == [0] * 5
+
+
+def test_an_independent_phase_goes_before_the_phase_that_waits():
+    """Where a phase reads what its predecessor writes and the phase after it conflicts with
+    neither, the two change places (the results cannot differ: they do not touch each other's
+    buffers); a forced order and batches above 1 keep the list's order."""
+    a = Arena()
+    K = 2048
+    x0, xa, xb = a.take(K * 2), a.take(K * 2), a.take(K * 2)
+    y = [a.take(K * 2) for _ in range(6)]
+    layers = [
+        linear(a, K, K, x0, y[0], y_f32=False),      # 0
+        linear(a, K, K, y[0], y[1], y_f32=False),    # 1 waits for 0
+        linear(a, K, K, xa, y[2], y_f32=False),      # 2 independent: before 1
+        linear(a, K, K, y[1], y[3], y_f32=False),    # 3 waits for 1
+        linear(a, K, K, xb, y[4], y_f32=False),      # 4 independent: before 3
+        linear(a, K, K, y[3], y[5], y_f32=False),    # 5 waits for 3, nothing behind it
+    ]
+    _, phases = nvq.plan_describe(layers, 1)
+    assert [ph["first"] for ph in phases] == [0, 2, 1, 4, 3, 5]
+    assert [ph["mail"] & 3 for ph in phases] == [0, 0, 1, 0, 1, 1]
+    _, ordered = nvq.plan_describe(layers, 1, ordered=True)
+    assert [ph["first"] for ph in ordered] == [0, 1, 2, 3, 4, 5]
+    # a phase that reads the waiting phase's output, or writes what it reads, stays behind it
+    layers[2] = linear(a, 64, K, y[1], y[2], y_f32=False)
+    _, phases = nvq.plan_describe(layers[:3], 1)
+    assert [ph["first"] for ph in phases] == [0, 1, 2]
+    layers[2] = linear(a, K, K, xa, y[0], y_f32=False)
+    _, phases = nvq.plan_describe(layers[:3], 1)
+    assert [ph["first"] for ph in phases] == [0, 1, 2]
 
 
 def test_mail_needs_exactly_one_earlier_bf16_output():
