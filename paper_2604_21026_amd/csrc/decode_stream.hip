@@ -90,8 +90,11 @@ typedef const __attribute__((address_space(4))) StreamPhase CPhase;
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 
-constexpr int kSlots = 6;                 // ring slots per wave (1 KiB weights + 256 B scales);
-                                          // 3, 4 or 5 stream as fast on an 8B-shaped step
+constexpr int kSlots = 3;                 // ring slots per wave (1 KiB weights + 256 B scales):
+                                          // 36 KiB in flight per compute unit.  4, 5 and 6 stream
+                                          // no faster on 1B-, 3B- and 8B-shaped steps (2 is 1-4 %
+                                          // slower), and a dependent chain, which computes at the
+                                          // pace of its slowest wave, is 3 % faster with 3 than 6
 constexpr int kOpsPerChunk = 2;            // scale load + weight load
 constexpr int kXChunkElems = 512;          // bf16 values per input chunk
 constexpr int kMaxXShare = (kStreamMaxK / kXChunkElems + kStreamWaves - 1) / kStreamWaves;  // 4
