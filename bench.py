@@ -3,7 +3,7 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--model llama-8b|llama-3b|llama-1b]
                     [--map mixed|w4a8|w4a16] [--batch M] [--act-group 0|32] [--copies C]
-                    [--leg all|step|cpu|cpu-full|config1|ceiling|calib|prefill]
+                    [--leg all|step|cpu|cpu-full|config1|ceiling|calib|prefill|trace]
 
 A step is one walk (one run of a prepared nvq plan = one launch of the persistent streaming
 kernel at batch 1) over every linear layer of one decode step of the named Llama-shaped model:
@@ -61,7 +61,7 @@ def parse():
     ap.add_argument("--map", default="mixed", choices=["mixed", "w4a8", "w4a16"])
     ap.add_argument("--prefill-tokens", type=int, default=4096)
     ap.add_argument("--leg", default="all",
-                    choices=["all", "step", "cpu", "cpu-full", "config1", "ceiling", "calib",
+                    choices=["all", "step", "cpu", "cpu-full", "config1", "ceiling", "calib", "trace",
                              "prefill"])
     ap.add_argument("--act-group", type=int, default=0, choices=[0, 32])
     ap.add_argument("--batch", type=int, default=1,
@@ -323,6 +323,9 @@ def cpu_full(model, bits, M, synth):
         host.append(dict(qweight=q, scales=s, x=x.view(torch.int16).numpy().view(np.uint16),
                          precision=1 if sp.block < 0 else bits[sp.block]))
         total_w += sp.N * sp.K
+        if len(host) % 14 == 0:  # (a line a minute or so: the generation takes minutes)
+            print("cpu-full: %d linears generated and packed, %.0f s" %
+                  (len(host), time.perf_counter() - t_gen), file=sys.stderr, flush=True)
     t_gen = time.perf_counter() - t_gen
     threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
     oracle.decode_linears(host, M)
@@ -350,6 +353,59 @@ def cpu_full(model, bits, M, synth):
 
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def trace_leg(a, torch, nvq, synth):
+    """Where the time of the dependent decode chain goes: the timestamps nvq_plan_trace takes in
+    every workgroup (100 MHz clock), per kind of phase, medians over the blocks."""
+    import numpy as np
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    bits = block_bits(a.model, a.map, synth)
+    layers = build_model(a.model, 1, torch, nvq, synth, dev)
+    entries = chain_entries(layers, bits, a.model, torch, nvq, synth, dev)
+    dl = nvq.DecodeList(entries, 1, a.act_group)
+    P = dl.plan_info()["phases"]
+    wall, per = time_steps(dl, a.steps, a.warmup, torch)
+    _, phases = nvq.plan_describe([dl.arr[i] for i in range(dl.n)], 1, a.act_group)
+    kinds = [layers[ph["first"]]["spec"].name.split(".")[-1] for ph in phases]
+    kinds = ["qkv" if k == "q" else "gate/up" if k == "gate" else k for k in kinds]
+    nwg = torch.cuda.get_device_properties(0).multi_processor_count
+    buf = torch.zeros(nwg * P * 8, dtype=torch.int64, device=dev)
+    dl.trace(buf)
+    dl.run_plan()
+    torch.cuda.synchronize()
+    buf.zero_()
+    dl.run_plan()
+    torch.cuda.synchronize()
+    dl.trace(None)
+    t = buf.cpu().numpy().reshape(nwg, P, 8).astype(np.float64) * 0.01      # us
+    t = np.where(t > 0, t, np.nan)
+    with np.errstate(all="ignore"):
+        import warnings
+        warnings.simplefilter("ignore")
+        here, staged, done = t[:, :, 3], t[:, :, 2], t[:, :, 6]
+        med = lambda x: np.nanmedian(x, axis=0)
+        last_done = np.nanmax(done, axis=0)
+        rows = {}
+        for p in range(2, P):
+            rows.setdefault(kinds[p], []).append((
+                med(here)[p] - last_done[p - 1],          # operands here after the last producer
+                med(staged)[p] - med(here)[p],            # image built
+                med(done)[p] - med(staged)[p],            # rows, median workgroup's last wave
+                last_done[p] - med(done)[p],              # the slowest workgroup behind the median
+                last_done[p] - last_done[p - 1]))         # the phase, end to end
+        out = {"trace": "%s-shaped dependent chain (block chain), map %s" % (a.model, a.map),
+               "ms_per_step": round(wall * 1e3, 4), "phases": P,
+               "kernel_us": round(float(np.nanmax(done[:, -1]) - np.nanmin(t[:, 0, 5])), 1),
+               "unit": "us, medians over the phases of a kind",
+               "columns": ["operands_after_last_producer", "image_build", "rows_median_workgroup",
+                           "slowest_workgroup_behind_median", "phase_end_to_end", "count"]}
+        for k, v in rows.items():
+            v = np.array(v)
+            out[k] = [None if np.isnan(x) else round(float(x), 2)
+                      for x in np.nanmedian(v, axis=0)] + [len(v)]
+    print(json.dumps(out))
 
 
 def prefill_leg(a, torch, nvq, synth):
@@ -514,6 +570,9 @@ def main():
         return
     if a.leg == "config1":
         config1_leg(a, torch, nvq, synth)
+        return
+    if a.leg == "trace":
+        trace_leg(a, torch, nvq, synth)
         return
     M = a.batch
     if not 1 <= M <= 32:
