@@ -1135,6 +1135,10 @@ __global__ __launch_bounds__(kStreamThreads, 1) void decode_stream_kernel(
         r0 *= ph.row_unit;
         nrows *= ph.row_unit;
         if (r0 + nrows > ph.total_rows) nrows = ph.total_rows - r0;  // a short last unit
+        // In a phase that somebody waits for, the waves with a unit more than the others
+        // go first on their SIMD: the phase ends when they do.
+        if (ph.spread && ph.rows_extra > 0 && nrows > ph.rows_base * ph.row_unit)
+            __builtin_amdgcn_s_setprio(3);
         const int r1 = r0 + nrows;
         uint32_t xs_bits = 0x3f800000u;  // per-token activation scale (W4A8), else 1
         const uint32_t plane = (uint32_t)G * 16u;
