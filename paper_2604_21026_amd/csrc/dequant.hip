@@ -32,8 +32,7 @@ __global__ __launch_bounds__(256) void dequant_bf16_kernel(const uint2 *__restri
     for (int j = 0; j < 4; ++j) {
         const int c0 = (int)((w[j >> 1] >> (16 * (j & 1))) & 0xffu) - 8;
         const int c1 = (int)((w[j >> 1] >> (16 * (j & 1) + 8)) & 0xffu) - 8;
-        o[j] = (uint32_t)float_to_bf16_bits((float)c0 * s) |
-               ((uint32_t)float_to_bf16_bits((float)c1 * s) << 16);
+        o[j] = pack_bf16x2((float)c0 * s, (float)c1 * s);
     }
     // written once, read later by another kernel: keep it out of the way of the weights
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));

@@ -113,11 +113,16 @@ __device__ __forceinline__ float bf16_bits_to_float(uint32_t h) {
     return __uint_as_float(h << 16);
 }
 
-// fp32 -> bf16 bits, round to nearest even (finite inputs).
+// fp32 -> bf16 bits, round to nearest even: the hardware's conversion
+// (v_cvt_pk_bf16_f32, one instruction for two values).
 __device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {
-    uint32_t u = __float_as_uint(f);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+    return __builtin_bit_cast(uint16_t, (__bf16)f);
+}
+typedef __bf16 nvq_bf16x2 __attribute__((ext_vector_type(2)));
+// ... two at a time, `lo` in the low half of the word.
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    const nvq_bf16x2 v = {(__bf16)lo, (__bf16)hi};
+    return __builtin_bit_cast(uint32_t, v);
 }
 
 __device__ __forceinline__ float half_bits_to_float(uint16_t h) {

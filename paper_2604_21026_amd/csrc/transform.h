@@ -26,8 +26,8 @@ __device__ __forceinline__ uint4 add_bf16x8(const uint4 &a, const uint4 &b) {
     uint32_t o[4];
 #pragma unroll
     for (int d = 0; d < 4; ++d)
-        o[d] = add_bf16_bits(av[d] & 0xffffu, bv[d] & 0xffffu) |
-               (add_bf16_bits(av[d] >> 16, bv[d] >> 16) << 16);
+        o[d] = pack_bf16x2(bf16_bits_to_float(av[d] & 0xffffu) + bf16_bits_to_float(bv[d] & 0xffffu),
+                           bf16_bits_to_float(av[d] >> 16) + bf16_bits_to_float(bv[d] >> 16));
     return make_uint4(o[0], o[1], o[2], o[3]);
 }
 
@@ -56,7 +56,7 @@ __device__ __forceinline__ uint4 scale_bf16x8(const uint4 &h, float r, const uin
     for (int d = 0; d < 4; ++d) {
         const float lo = bf16_bits_to_float(hv[d] & 0xffffu) * r * bf16_bits_to_float(gv[d] & 0xffffu);
         const float hi = bf16_bits_to_float(hv[d] >> 16) * r * bf16_bits_to_float(gv[d] >> 16);
-        o[d] = (uint32_t)float_to_bf16_bits(lo) | ((uint32_t)float_to_bf16_bits(hi) << 16);
+        o[d] = pack_bf16x2(lo, hi);
     }
     return make_uint4(o[0], o[1], o[2], o[3]);
 }
@@ -81,7 +81,7 @@ __device__ __forceinline__ uint4 silu_mul_bf16x8(const uint4 &g, const uint4 &u)
                                       bf16_bits_to_float(uv[d] & 0xffffu));
         const float hi = silu_mul_one(bf16_bits_to_float(gv[d] >> 16),
                                       bf16_bits_to_float(uv[d] >> 16));
-        o[d] = (uint32_t)float_to_bf16_bits(lo) | ((uint32_t)float_to_bf16_bits(hi) << 16);
+        o[d] = pack_bf16x2(lo, hi);
     }
     return make_uint4(o[0], o[1], o[2], o[3]);
 }
