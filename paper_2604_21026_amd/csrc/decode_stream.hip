@@ -424,19 +424,33 @@ __device__ __forceinline__ void image_put(const Writer &wr, const ImgLayout<PER_
         // A scale too small for its reciprocal takes the division for every value.
         const bool by_reciprocal = s >= 0x1p-100f;
         const float inv_s = by_reciprocal ? 1.0f / s : 0.0f;
-        auto code = [&](float x) -> int {
-            float r = rintf(x * inv_s);
-            if (!by_reciprocal || fabsf(x * inv_s - r) > 0.5f - 0x1p-14f) r = rintf(x / s);
-            return (int)fminf(fmaxf(r, -127.0f), 127.0f);
-        };
+        // (one test for the lane's eight values: the lanes with a value near a tie redo
+        // all eight by division, one lane in a thousand)
+        float x[8], r[8];
+        bool redo = !by_reciprocal;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            x[2 * d] = bf16_bits_to_float(wv[d] & 0xffffu);
+            x[2 * d + 1] = bf16_bits_to_float(wv[d] >> 16);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const float t = x[i] * inv_s;
+            r[i] = rintf(t);
+            redo = redo || fabsf(t - r[i]) > 0.5f - 0x1p-14f;
+        }
+        if (redo) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) r[i] = rintf(x[i] / s);
+        }
         uint32_t out[2] = {0, 0};
         int qsum = 0;
 #pragma unroll
         for (int d = 0; d < 4; ++d) {
             int q0 = 0, q1 = 0;
             if (s != 0.0f) {
-                q0 = code(bf16_bits_to_float(wv[d] & 0xffffu));
-                q1 = code(bf16_bits_to_float(wv[d] >> 16));
+                q0 = (int)fminf(fmaxf(r[2 * d], -127.0f), 127.0f);
+                q1 = (int)fminf(fmaxf(r[2 * d + 1], -127.0f), 127.0f);
             }
             qsum += q0 + q1;
             out[d >> 1] |= ((uint32_t)(q0 & 0xff) | ((uint32_t)(q1 & 0xff) << 8)) << (16 * (d & 1));
