@@ -367,11 +367,19 @@ __device__ __forceinline__ void ring_bundle_columns(const RingUnit &d, int cnt, 
             if ((int32_t)(landed - (k + 1)) < 0)
                 landed = ring_wait(landed_addr, k + 1, abort_addr, dead);
             const int slot = (int)(k % S);
-            uint4 wv[R];
+            // Dword kb of each of the column's four 16-byte groups of row n: what the MFMA's
+            // weight operand of group i wants in lane (n, kb), read as four words (one 16-byte
+            // read per lane would bring group kb's four dwords instead, and four cross-lane
+            // swaps would have to transpose them: the vector ALU is what bounds this kernel,
+            // the local memory is not).
+            uint32_t q[R][4];
             uint2 sc[R];
 #pragma unroll
             for (int r = 0; r < R; ++r) {
-                wv[r] = sh.ring[slot][r][w >> 1][n >> 3][ring_lane_of(n, 4 * (w & 1) + kb)];
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    q[r][i] = reinterpret_cast<const uint32_t *>(
+                        &sh.ring[slot][r][w >> 1][n >> 3][ring_lane_of(n, 4 * (w & 1) + i)])[kb];
                 // the wave's column is the first or second half of 16-byte piece w / 2
                 sc[r] = reinterpret_cast<const uint2 *>(
                     &sh.sring[slot][(r * 16 + n) * 2 + (w >> 1)])[w & 1];
@@ -382,15 +390,9 @@ __device__ __forceinline__ void ring_bundle_columns(const RingUnit &d, int cnt, 
             ++k;
             if (lane == 0) ring_write_word(consumed_addr, k);
 
-            uint32_t q[R][4];
             float sw[R][4];
 #pragma unroll
             for (int r = 0; r < R; ++r) {
-                q[r][0] = wv[r].x;
-                q[r][1] = wv[r].y;
-                q[r][2] = wv[r].z;
-                q[r][3] = wv[r].w;
-                transpose_rows(q[r]);
                 sw[r][0] = half_bits_to_float((uint16_t)(sc[r].x & 0xffffu));
                 sw[r][1] = half_bits_to_float((uint16_t)(sc[r].x >> 16));
                 sw[r][2] = half_bits_to_float((uint16_t)(sc[r].y & 0xffffu));
