@@ -22,10 +22,12 @@ FLAGS = [
     "-ffp-contract=off",
     # packed-fp32 instructions are kept out of the generated code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    # MFMA results go to ordinary vector registers (no accumulator-register copies)
-    "-mllvm", "-amdgpu-mfma-vgpr-form=1",
     "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
 ]
+# MFMA results go to ordinary vector registers (no accumulator-register copies), except in the
+# prefill GEMM, whose accumulators alone fill the 256 ordinary registers of a wave
+VGPR_FORM = ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]
+NO_VGPR_FORM = {"gemm_w4a16.hip"}
 
 
 def sources():
@@ -44,7 +46,8 @@ def _compile(src, force, extra):
     if (not force and os.path.exists(obj)
             and os.path.getmtime(obj) >= max(os.path.getmtime(spath), _newest_header())):
         return obj
-    subprocess.run([HIPCC] + FLAGS + list(extra) + ["-c", spath, "-o", obj], check=True)
+    form = [] if src in NO_VGPR_FORM else VGPR_FORM
+    subprocess.run([HIPCC] + FLAGS + form + list(extra) + ["-c", spath, "-o", obj], check=True)
     return obj
 
 
