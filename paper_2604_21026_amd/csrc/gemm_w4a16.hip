@@ -219,102 +219,94 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_w4a16_kernel(
 // 256 tokens x 256 weight rows per workgroup, four waves, one per SIMD with the
 // whole register file (the 8 x 2 accumulator tiles of a wave fill 256
 // registers): a wave multiplies all 256 tokens by its own 64 rows, so that a
-// weight is dequantised once per workgroup and serves eight MFMAs.  The
-// activations of a pair of groups (256 rows of 128 bytes) go from global memory
-// straight into LDS, 16 bytes per lane and 1 KiB per load instruction; three
-// buffers, loads two pairs ahead of the multiplication, one barrier per pair.
-// A row's eight 16-byte pieces are stored permuted (piece c of row r at
-// position c ^ ((r / 2) % 8)): the 16 lanes of a quarter wave, reading the same
-// piece of 16 consecutive rows, then touch every LDS bank once.
+// weight is dequantised once per workgroup and serves eight MFMAs.  K must be a
+// multiple of 256 (a pair of groups per step, blocks of four pairs below).
+//
+// Everything comes from global memory straight into LDS, 16 bytes per lane:
+//  - the activations of a pair of groups (256 tokens x 128 bytes, three buffers
+//    shared by the waves; 1 KiB = eight whole lines per load instruction);
+//  - the packed weights of a wave's 64 rows for two pairs (64 bytes per row:
+//    16 half lines per instruction, two buffers per wave) and their scales for
+//    four pairs (16 bytes per row, two buffers per wave).  Loaded by the lane
+//    that needs them (lane i = row i, 16 bytes of one group) a load instruction
+//    touches 32 lines for 1 KiB and the wave stands still while it is taken
+//    apart: with the weight loads pointed at one row the kernel ran 25-30 %
+//    faster, which is what the detour through LDS is for.
+// A row's 16-byte pieces are stored permuted so that the 16 lanes of a quarter
+// wave, reading the same piece of 16 consecutive rows, touch every LDS bank once:
+// piece c of activation row r at position c ^ ((r / 2) % 8), piece c of weight
+// row r at position c ^ ((r / 4) % 4).
 typedef __attribute__((address_space(3))) void *lds_void_ptr;
 
 constexpr int kWideTokens = 256, kWideRows = 256;
 constexpr int kWideBuf = kWideTokens * 128;  // bytes of one activation buffer
+constexpr int kWideBw = 64 * 64;             // a wave's packed weights of two pairs
+constexpr int kWideBs = 64 * 16;             // a wave's scales of four pairs
+constexpr int kWideLds = 3 * kWideBuf + 4 * 2 * (kWideBw + kWideBs);
 
 // s_waitcnt immediate that waits for vmcnt <= n only
 constexpr int wide_vmcnt(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0f70; }
 
 template <bool F32>
 __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void
-gemm_w4a16_wide_kernel(const uint4 *__restrict__ qw, const uint16_t *__restrict__ sc, int N, int G,
-                       const unsigned char *__restrict__ x, int M, void *__restrict__ y) {
-    __shared__ __attribute__((aligned(1024))) unsigned char xa[4 * kWideBuf];
-
+gemm_w4a16_wide_kernel(const unsigned char *__restrict__ qw, const unsigned char *__restrict__ sc,
+                       int N, int G, const unsigned char *__restrict__ x, int M,
+                       void *__restrict__ y) {
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[kWideLds];
+    unsigned char *const xa = lds;
     const int t = threadIdx.x, lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    unsigned char *const bw = lds + 3 * kWideBuf + wave * 2 * kWideBw;
+    unsigned char *const bs = lds + 3 * kWideBuf + 4 * 2 * kWideBw + wave * 2 * kWideBs;
     const int li = lane & 31, lb = lane >> 5;
     // Tiles in token-major order, weight rows fastest.  (Giving each XCD, with its
     // own L2, a contiguous eighth of the tiles, so that its workgroups share one or
     // two token tiles, was 7 % slower; so was starting every workgroup at a
     // different place along K.)
-    const int nx = (N + kWideRows - 1) / kWideRows, ny = (M + kWideTokens - 1) / kWideTokens;
+    const int nx = (N + kWideRows - 1) / kWideRows;
     const int tile = (int)blockIdx.x;
-    if (tile >= nx * ny) return;
     const int m0 = (tile / nx) * kWideTokens, n0 = (tile % nx) * kWideRows;
-    const int P = (G + 1) >> 1;  // pairs of groups
-    const bool odd = (G & 1) != 0;
+    const int P = G >> 1;  // pairs of groups, a multiple of 4
 
     // Activation loads: instruction j of this wave fills rows 8 (8 wave + j) ..
-    // + 7 of a buffer, lane l the position l % 8 of row l / 8 of those: piece
-    // (l % 8) ^ ((row / 2) % 8) of that token's 128 bytes (rows past the last
-    // token: the last token again; those results are not stored).  In the
-    // missing second group of an odd last pair the first group is read again
-    // (its weights count as 0).
+    // + 7 of a buffer, lane l the position l % 8 of row l / 8 of those (rows past
+    // the last token: the last token again; those results are not stored).
     const unsigned char *xg[8];
-    int tailfix[2];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         const int r = 8 * (8 * wave + j) + (lane >> 3);
         const int c = (lane & 7) ^ ((r >> 1) & 7);
         const int m = m0 + r < M ? m0 + r : M - 1;
         xg[j] = x + (size_t)m * (size_t)(G * 64) + 16 * c;
-        if (j < 2) tailfix[j] = c >= 4 ? -64 : 0;  // c depends on j through its parity only
     }
     auto issue_a1 = [&](unsigned char *buf, int p, int j) {
-        const bool fix = odd && p == P - 1;
-        const unsigned char *g = xg[j] + (size_t)p * 128 + (fix ? tailfix[j & 1] : 0);
-        __builtin_amdgcn_global_load_lds((const void *)g, (lds_void_ptr)(buf + (8 * wave + j) * 1024),
-                                         16, 0, 0);
+        __builtin_amdgcn_global_load_lds((const void *)(xg[j] + (size_t)p * 128),
+                                         (lds_void_ptr)(buf + (8 * wave + j) * 1024), 16, 0, 0);
     };
-    auto issue_a = [&](unsigned char *buf, int p) {
+    // Weight loads: instruction j fills rows 16 j .. + 15 of a weight buffer, lane l
+    // the position l % 4 of row l / 4 of those (rows past the last one: the last one
+    // again).  Scale load: lane l the 16 bytes of row l.
+    const unsigned char *qg[4];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) issue_a1(buf, p, j);
-    };
-
-    // The lane's weight rows, one per row tile (the last row again past the end).
-    const uint4 *qrow[2];
-    const uint16_t *srow[2];
-#pragma unroll
-    for (int rt = 0; rt < 2; ++rt) {
-        const int n = n0 + wave * 64 + rt * 32 + li;
-        const int nc = n < N ? n : N - 1;
-        qrow[rt] = qw + (size_t)nc * (size_t)G;
-        srow[rt] = sc + (size_t)nc * (size_t)G;
+    for (int j = 0; j < 4; ++j) {
+        const int r = 16 * j + (lane >> 2);
+        const int c = (lane & 3) ^ ((r >> 2) & 3);
+        const int n = n0 + wave * 64 + r < N ? n0 + wave * 64 + r : N - 1;
+        qg[j] = qw + (size_t)n * (size_t)(G * 16) + 16 * c;
     }
-    struct BRaw {
-        uint4v w[2];
-        uint32_t h[2];
-        uint32_t hmask;  // 0 for the missing group of an odd last pair
+    const unsigned char *sg;
+    {
+        const int n = n0 + wave * 64 + lane < N ? n0 + wave * 64 + lane : N - 1;
+        sg = sc + (size_t)n * (size_t)(G * 2);
+    }
+    // block b2 = pairs 2 b2, 2 b2 + 1 into weight buffer `sel`; block b4 = pairs 4 b4 .. + 3
+    auto issue_bw1 = [&](int b2, int sel, int j) {
+        __builtin_amdgcn_global_load_lds((const void *)(qg[j] + (size_t)b2 * 64),
+                                         (lds_void_ptr)(bw + sel * kWideBw + j * 1024), 16, 0, 0);
     };
-    // piece 0, 2: the packed weights of row tile 0, 1; piece 1, 3: their scales
-    auto request_b1 = [&](BRaw &b, int p, bool live, int piece) {
-        const int g = 2 * p + lb;
-        const int gc = g < G ? g : G - 1;
-        const int rt = piece >> 1;
-        if ((piece & 1) == 0)
-            asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(b.w[rt]) : "v"(qrow[rt] + gc));
-        else
-            // Loaded in any case (a branch here would split the loop's body) and
-            // masked when used.  Both as instructions: the compiler would wait for
-            // every load in flight where these are used (and pack the two 16-bit
-            // values into one register at the end of the loop's body, waiting for
-            // them there).  The wait before the barrier covers them.
-            asm volatile("global_load_ushort %0, %1, off" : "=v"(b.h[rt]) : "v"(srow[rt] + gc));
-        b.hmask = (g < G && live) ? 0xffffu : 0u;
-    };
-    auto request_b = [&](BRaw &b, int p, bool live) {
-#pragma unroll
-        for (int piece = 0; piece < 4; ++piece) request_b1(b, p, live, piece);
+    auto issue_bs = [&](int b4, int sel) {
+        __builtin_amdgcn_global_load_lds((const void *)(sg + (size_t)b4 * 16),
+                                         (lds_void_ptr)(bs + sel * kWideBs), 16, 0, 0);
     };
 
     floatx16 acc[8][2];
@@ -325,23 +317,32 @@ gemm_w4a16_wide_kernel(const uint4 *__restrict__ qw, const uint16_t *__restrict_
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[tt][rt][r] = 0.0f;
 
-    // the lane's position in a row of a buffer per MFMA step, and its row of tile 0
-    int apos[4];
+    // The lane's LDS positions.  Activations: row li of a token tile, piece 4 lb +
+    // st in MFMA step st.  Weights: row li of a row tile, the group lb of the first
+    // pair of a block (the second pair: the position ^ 2); scales: row li, group lb
+    // of the first pair of a block of four.
+    const uint32_t xa0 = (uint32_t)(uintptr_t)xa;
+    uint32_t apos[4];
 #pragma unroll
     for (int st = 0; st < 4; ++st) apos[st] = li * 128 + 16 * ((4 * lb + st) ^ ((li >> 1) & 7));
+    const uint32_t bwpos = (uint32_t)(uintptr_t)bw + li * 64 + 16 * (lb ^ ((li >> 2) & 3));
+    const uint32_t bspos = (uint32_t)(uintptr_t)bs + li * 16 + 2 * lb;
 
     // The loop is a chain of MFMA steps (four per pair of groups, 16 inputs per
     // lane half each).  Everything else is dealt between the sixteen MFMAs of a
     // step, a little after each, so that the matrix core never waits for more
     // than a few instructions: the eight LDS reads of the next step's inputs, the
     // conversion of the next step's sixteen weights (byte -> fp32, one FMA with
-    // the scale, every other time the rounding of two to bf16), in step 2 the
-    // unpacking of the next pair's nibbles and in step 3 the twelve global loads
-    // of the pairs ahead (a load instruction can hold up the wave for tens of
-    // cycles).  The step after step 3 is step 0 of the next pair.  Four buffers:
-    // pair q lives in buffer q % 4; when pair p + 3 is loaded (step 3 of pair p)
-    // every wave has passed the barrier of pair p and with it pair p - 1.
-    struct Nibbles {  // a pair's weights of the lane: one nibble per byte, [row tile][low, high][dword]
+    // the scale, every other time the rounding of two to bf16), in step 1 the LDS
+    // reads of the next pair's packed weights, in step 2 their unpacking and in
+    // step 3 the loads from global memory.  The step after step 3 is step 0 of the
+    // next pair.  LDS accesses are written as instructions with their own waits:
+    // before an LDS access it knows of, the compiler waits for every load in flight.
+    struct BRaw {  // the lane's packed weights and scales of a pair, per row tile
+        uint4v w[2];
+        uint32_t h[2];
+    };
+    struct Nibbles {  // one nibble per byte, [row tile][low, high][dword]
         uint32_t d[2][2][4];
         uint32_t h[2];  // fp16 scale bits
         float m8[2];    // -8 * scale
@@ -359,8 +360,8 @@ gemm_w4a16_wide_kernel(const uint4 *__restrict__ qw, const uint16_t *__restrict_
             asm("" : "+v"(nb.d[rt][1][i]));
         } else {
             const int rt = k - 8;
-            nb.h[rt] = b.h[rt] & b.hmask;
-            nb.m8[rt] = -8.0f * half_bits_to_float((uint16_t)nb.h[rt]);
+            nb.h[rt] = b.h[rt];
+            nb.m8[rt] = -8.0f * half_bits_to_float((uint16_t)b.h[rt]);
         }
     };
     // weight i (0..15) of MFMA step st: row tile i / 8, input i % 8 of the step
@@ -370,9 +371,6 @@ gemm_w4a16_wide_kernel(const uint4 *__restrict__ qw, const uint16_t *__restrict_
         return fmaf((float)((d >> (8 * (e & 3))) & 0xffu), half_bits_to_float((uint16_t)nb.h[rt]),
                     nb.m8[rt]);
     };
-    // LDS reads are written as instructions with their own wait: before an LDS
-    // read it knows of, the compiler waits for every load in flight, the loads
-    // into LDS of the pairs ahead included.
     auto read_input = [&](uint32_t addr, int tt, uint4v &a) {
         switch (tt) {
 #define NVQ_RD(t_) case t_: asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(a) : "v"(addr), "n"(t_ * 4096)); break;
@@ -380,22 +378,35 @@ gemm_w4a16_wide_kernel(const uint4 *__restrict__ qw, const uint16_t *__restrict_
 #undef NVQ_RD
         }
     };
-    auto arrived = [&](uint4v (&a)[8]) {
-        asm volatile("s_waitcnt lgkmcnt(0)"
-                     : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]),
-                       "+v"(a[6]), "+v"(a[7]));
+    // piece 0, 1: the packed weights of row tile 0, 1 (32 rows = 2 KiB further); 2, 3: the scales
+    auto read_b1 = [&](uint32_t waddr, uint32_t saddr, BRaw &b, int piece) {
+        switch (piece) {
+            case 0: asm volatile("ds_read_b128 %0, %1" : "=v"(b.w[0]) : "v"(waddr)); break;
+            case 1: asm volatile("ds_read_b128 %0, %1 offset:2048" : "=v"(b.w[1]) : "v"(waddr)); break;
+            case 2: asm volatile("ds_read_u16 %0, %1" : "=v"(b.h[0]) : "v"(saddr)); break;
+            case 3: asm volatile("ds_read_u16 %0, %1 offset:512" : "=v"(b.h[1]) : "v"(saddr)); break;
+        }
     };
     uint4v a[2][8];
     uint32_t bo[2][2][4];  // [step parity][row tile] bf16 x 8
-    BRaw bset[2];          // the packed weights of pair q wait in set q % 2 (in flight, then landed)
+    BRaw braw;             // of the next pair
     Nibbles nb, nnb;       // of the pair being multiplied and of the next one
+    auto arrived = [&](uint4v (&v)[8]) {
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]), "+v"(v[4]), "+v"(v[5]),
+                       "+v"(v[6]), "+v"(v[7]), "+v"(braw.w[0]), "+v"(braw.w[1]), "+v"(braw.h[0]),
+                       "+v"(braw.h[1]));
+    };
 
     // Step `st` of the pair in registers (a[st % 2], bo[st % 2]) while the operands
-    // of step `nst` of the pair in LDS at `nbuf` with the nibbles `wn` are made.
-    // extra = 1: also unpacks `bs` into nnb; extra = 2: also loads the weights of
-    // pair pb into `bs` and the activations of pair pa into the buffer at abuf.
-    auto step = [&](int st, uint32_t nbuf, const Nibbles &wn, int nst, int extra, BRaw &bs, int pb,
-                    bool pb_live, unsigned char *abuf, int pa) {
+    // of step `nst` of the pair at `nbuf` with the nibbles `wn` are made.  extra =
+    // 1: also reads the next pair's packed weights from LDS (at waddr / saddr);
+    // extra = 2: also unpacks them into nnb; extra = 3: also issues the loads: the
+    // activations of pair pa into abuf, with nbw the weight block b2 into buffer
+    // wsel, with nbs the scale block b4 into buffer ssel.
+    auto step = [&](int st, uint32_t nbuf, const Nibbles &wn, int nst, int extra, uint32_t waddr,
+                    uint32_t saddr, unsigned char *abuf, int pa, bool nbw, int b2, int wsel, bool nbs,
+                    int b4, int ssel) {
         const int c = st & 1, n = c ^ 1;
         const uint32_t addr = nbuf + apos[nst];
         float prev = 0.0f;
@@ -410,44 +421,43 @@ gemm_w4a16_wide_kernel(const uint4 *__restrict__ qw, const uint16_t *__restrict_
             const float w = weight(wn, nst, i);
             if (i & 1) bo[n][i >> 3][(i & 7) >> 1] = pack_bf16(prev, w);
             prev = w;
-            if (extra == 1 && i >= 4 && i < 14) unpack1(bs, nnb, i - 4);
-            if (extra == 2 && i >= 2 && i < 6) request_b1(bs, pb, pb_live, i - 2);
-            if (extra == 2 && i >= 6 && i < 14) issue_a1(abuf, pa, i - 6);
+            if (extra == 1 && i >= 8 && i < 12) read_b1(waddr, saddr, braw, i - 8);
+            if (extra == 2 && i >= 4 && i < 14) unpack1(braw, nnb, i - 4);
+            if (extra == 3) {
+                if (nbs && i == 1) issue_bs(b4, ssel);
+                if (nbw && i >= 2 && i < 6) issue_bw1(b2, wsel, i - 2);
+                if (i >= 6 && i < 14) issue_a1(abuf, pa, i - 6);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
         arrived(a[n]);
     };
 
-    // Order of the loads, kept by compiler barriers: B(0) A(0) B(1) A(1) B(2) A(2),
-    // then in step 3 of pair p: B(p + 3) A(p + 3).  Before step 2 of pair p, A(p + 1)
-    // and B(p + 1) are needed; the twelve loads of B(p + 2) and A(p + 2) are the only
-    // younger ones.  Pairs past the last one (an odd number of pairs is rounded up:
-    // the loop takes two at a time, one per set of weight registers) read the last
-    // pair again with scale 0.
 #define NVQ_PIN asm volatile("" ::: "memory")
-    const uint32_t xa0 = (uint32_t)(uintptr_t)xa;
+    // Before the loop: the activations of pairs 0..2, the weights of pairs 0..3 and
+    // their scales; pair 0 unpacked and its first operands in registers.
+    const int last2 = (P >> 1) - 1, last4 = (P >> 2) - 1;
     auto pair_or_last = [&](int q) { return q < P ? q : P - 1; };
-    request_b(bset[0], 0, true);
+    issue_bs(0, 0);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) issue_bw1(0, 0, j);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) issue_bw1(1 < last2 ? 1 : last2, 1, j);
+#pragma unroll
+    for (int q = 0; q < 3; ++q)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) issue_a1(xa + q * kWideBuf, pair_or_last(q), j);
     NVQ_PIN;
-    issue_a(xa, 0);
-    NVQ_PIN;
-    request_b(bset[1], pair_or_last(1), 1 < P);
-    NVQ_PIN;
-    issue_a(xa + kWideBuf, pair_or_last(1));
-    NVQ_PIN;
-    __builtin_amdgcn_s_waitcnt(wide_vmcnt(12));
+    __builtin_amdgcn_s_waitcnt(wide_vmcnt(0));
     __builtin_amdgcn_s_barrier();
     NVQ_PIN;
-    asm volatile("" : "+v"(bset[0].h[0]), "+v"(bset[0].h[1]), "+v"(bset[0].w[0]), "+v"(bset[0].w[1]));
 #pragma unroll
-    for (int k = 0; k < 10; ++k) unpack1(bset[0], nb, k);
-    NVQ_PIN;
-    request_b(bset[0], pair_or_last(2), 2 < P);
-    NVQ_PIN;
-    issue_a(xa + 2 * kWideBuf, pair_or_last(2));
-    NVQ_PIN;
+    for (int piece = 0; piece < 4; ++piece) read_b1(bwpos, bspos, braw, piece);
 #pragma unroll
     for (int tt = 0; tt < 8; ++tt) read_input(xa0 + apos[0], tt, a[0][tt]);
+    arrived(a[0]);
+#pragma unroll
+    for (int k = 0; k < 10; ++k) unpack1(braw, nb, k);
     {
         float prev = 0.0f;
 #pragma unroll
@@ -457,36 +467,49 @@ gemm_w4a16_wide_kernel(const uint4 *__restrict__ qw, const uint16_t *__restrict_
             prev = w;
         }
     }
-    arrived(a[0]);
 
-    int cur = 0;  // byte offset of the buffer of pair p
-    // one pair; `bs` is the set of pair p + 1 (and then of pair p + 3)
-    auto pair = [&](int p, BRaw &bs) {
-        const int nxt = (cur + kWideBuf) & (4 * kWideBuf - 1), fill = (cur + 3 * kWideBuf) & (4 * kWideBuf - 1);
-        step(0, xa0 + cur, nb, 1, 0, bs, 0, false, xa, 0);
-        step(1, xa0 + cur, nb, 2, 0, bs, 0, false, xa, 0);
-        __builtin_amdgcn_s_waitcnt(wide_vmcnt(12));
-        __builtin_amdgcn_s_barrier();
-        NVQ_PIN;
-        // the weights were loaded behind the compiler's back: no use before the wait
-        asm volatile("" : "+v"(bs.h[0]), "+v"(bs.h[1]), "+v"(bs.w[0]), "+v"(bs.w[1]));
-        step(2, xa0 + cur, nb, 3, 1, bs, 0, false, xa, 0);
-        step(3, xa0 + nxt, nnb, 0, 2, bs, pair_or_last(p + 3), p + 3 < P, xa + fill, pair_or_last(p + 3));
-        nb = nnb;
-        cur = nxt;
-    };
-    for (int p = 0; p < P; p += 2) {
-        pair(p, bset[1]);
-        pair(p + 1, bset[0]);
+    // Four pairs per turn (a block of scales, two blocks of weights).  In step 3 of
+    // pair p = 4 k + i the loads of A(p + 3), for even i of the weight block p / 2 +
+    // 2 and for i = 0 of the scale block k + 1 are issued, the activations last: 13,
+    // 8, 12, 8 load instructions for i = 0..3.  The wait before that step lets the
+    // loads of the pair before stay in flight (8, 13, 8, 12) and ends all older ones:
+    // A(p + 1), read right after it, was issued two pairs ago, and the weights and
+    // scales of pair p + 2, read from LDS in step 1 of pair p + 1, at least three.
+    int cur = 0;  // byte offset of the activation buffer of pair p
+    int ssel = 0;  // scale buffer of the pairs 4 k .. 4 k + 3
+    for (int p = 0; p < P; p += 4) {
+#define NVQ_PAIR(i_, younger_)                                                                   \
+    do {                                                                                         \
+        const int q_ = (i_) + 1; /* the next pair's place in its blocks */                       \
+        const uint32_t waddr_ = (bwpos + ((q_ >> 1) & 1) * kWideBw) ^ ((q_ & 1) * 32);           \
+        const uint32_t saddr_ = bspos + (((q_ >> 2) ? ssel ^ 1 : ssel)) * kWideBs + (q_ & 3) * 4; \
+        const int nxt_ = cur + kWideBuf == 3 * kWideBuf ? 0 : cur + kWideBuf;                    \
+        step(0, xa0 + cur, nb, 1, 0, 0, 0, xa, 0, false, 0, 0, false, 0, 0);                     \
+        step(1, xa0 + cur, nb, 2, 1, waddr_, saddr_, xa, 0, false, 0, 0, false, 0, 0);           \
+        step(2, xa0 + cur, nb, 3, 2, 0, 0, xa, 0, false, 0, 0, false, 0, 0);                     \
+        __builtin_amdgcn_s_waitcnt(wide_vmcnt(younger_));                                        \
+        __builtin_amdgcn_s_barrier();                                                            \
+        NVQ_PIN;                                                                                 \
+        {                                                                                        \
+            const int b2_ = ((p + (i_)) >> 1) + 2, b4_ = (p >> 2) + 1;                           \
+            step(3, xa0 + nxt_, nnb, 0, 3, 0, 0, xa + cur, pair_or_last(p + (i_) + 3),           \
+                 ((i_) & 1) == 0, b2_ < last2 ? b2_ : last2, ((i_) >> 1) & 1, (i_) == 0,         \
+                 b4_ < last4 ? b4_ : last4, ssel ^ 1);                                           \
+        }                                                                                        \
+        NVQ_PIN;                                                                                 \
+        nb = nnb;                                                                                \
+        cur = nxt_;                                                                              \
+    } while (0)
+        NVQ_PAIR(0, 8);
+        NVQ_PAIR(1, 13);
+        NVQ_PAIR(2, 8);
+        NVQ_PAIR(3, 12);
+#undef NVQ_PAIR
+        ssel ^= 1;
     }
 #undef NVQ_PIN
-    // No load may outlive the loop: the loads into LDS must not outlive the wave, and
-    // the registers of the last weight loads (the compiler does not know that they
-    // are still being written) stay reserved up to this wait.
-    asm volatile("s_waitcnt vmcnt(0)" ::"v"(bset[0].w[0]), "v"(bset[0].w[1]), "v"(bset[0].h[0]),
-                 "v"(bset[0].h[1]), "v"(bset[1].w[0]), "v"(bset[1].w[1]), "v"(bset[1].h[0]),
-                 "v"(bset[1].h[1])
-                 : "memory");
+    // no load into LDS may outlive the wave
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
     // result tile: lane (j, b) holds weight row j; register r holds token
     // 8 * (r / 4) + 4 * b + r % 4
@@ -525,18 +548,26 @@ extern "C" int nvq_gemm_w4a16(const uint8_t *qweight, const uint16_t *scales, in
     if (!aligned(qweight, 16) || !aligned(scales, 2) || !aligned(x_bf16, 16) ||
         !aligned(y, y_dtype == NVQ_F32 ? 4 : 2))
         return NVQ_ERR_ALIGN;
-    const bool wide = getenv("NVQ_GEMM_WIDE") != nullptr;
+    // The wide tiles need K % 256 == 0 and enough tiles to occupy the machine; the
+    // environment variable NVQ_GEMM_TILE (wide | narrow) overrides the choice where
+    // both kernels can run (used by the tests to reach both on small shapes).
+    const int64_t tiles = ((N + kWideRows - 1) / kWideRows) * ((M + kWideTokens - 1) / kWideTokens);
+    bool wide = (K % 256) == 0 && tiles >= 96;
+    if (const char *force = getenv("NVQ_GEMM_TILE")) {
+        if (force[0] == 'w' && (K % 256) == 0) wide = true;
+        if (force[0] == 'n') wide = false;
+    }
     if (wide) {
-        const int64_t tiles = ((N + kWideRows - 1) / kWideRows) * ((M + kWideTokens - 1) / kWideTokens);
-        const dim3 wgrid((unsigned)(((tiles + 7) / 8) * 8));
+        if (tiles > (int64_t)0x7fffffff) return NVQ_ERR_SHAPE;
+        const dim3 wgrid((unsigned)tiles);
         const unsigned char *xb = reinterpret_cast<const unsigned char *>(x_bf16);
-        const uint4 *qww = reinterpret_cast<const uint4 *>(qweight);
+        const unsigned char *sb = reinterpret_cast<const unsigned char *>(scales);
         if (y_dtype == NVQ_F32)
             hipLaunchKernelGGL(gemm_w4a16_wide_kernel<true>, wgrid, dim3(kGemmThreads), 0,
-                               (hipStream_t)stream, qww, scales, (int)N, (int)(K / 32), xb, (int)M, y);
+                               (hipStream_t)stream, qweight, sb, (int)N, (int)(K / 32), xb, (int)M, y);
         else
             hipLaunchKernelGGL(gemm_w4a16_wide_kernel<false>, wgrid, dim3(kGemmThreads), 0,
-                               (hipStream_t)stream, qww, scales, (int)N, (int)(K / 32), xb, (int)M, y);
+                               (hipStream_t)stream, qweight, sb, (int)N, (int)(K / 32), xb, (int)M, y);
         NVQ_HIP_TRY(hipGetLastError());
         return NVQ_OK;
     }
