@@ -264,48 +264,57 @@ gemm_w4a16_wide_kernel(const unsigned char *__restrict__ qw, const unsigned char
     // two token tiles, was 7 % slower; so was starting every workgroup at a
     // different place along K.)
     const int nx = (N + kWideRows - 1) / kWideRows;
+#ifdef NVQ_X_MAP
+    const int ntile_ = nx * ((M + kWideTokens - 1) / kWideTokens);
+    const int per_xcd_ = (ntile_ + 7) >> 3;
+    const int tile = (int)(blockIdx.x & 7u) * per_xcd_ + (int)(blockIdx.x >> 3);
+    if (tile >= ntile_) return;
+#else
     const int tile = (int)blockIdx.x;
+#endif
     const int m0 = (tile / nx) * kWideTokens, n0 = (tile % nx) * kWideRows;
     const int P = G >> 1;  // pairs of groups, a multiple of 4
 
     // Activation loads: instruction j of this wave fills rows 8 (8 wave + j) ..
     // + 7 of a buffer, lane l the position l % 8 of row l / 8 of those (rows past
     // the last token: the last token again; those results are not stored).
-    const unsigned char *xg[8];
+    // Addresses are a base common to the wave plus a 32-bit offset per lane (the
+    // form a load instruction takes without any address arithmetic in the lanes).
+    const unsigned char *const xbase = x + (size_t)m0 * (size_t)(G * 64);
+    uint32_t xo[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         const int r = 8 * (8 * wave + j) + (lane >> 3);
         const int c = (lane & 7) ^ ((r >> 1) & 7);
-        const int m = m0 + r < M ? m0 + r : M - 1;
-        xg[j] = x + (size_t)m * (size_t)(G * 64) + 16 * c;
+        const int rc = m0 + r < M ? r : M - 1 - m0;
+        xo[j] = (uint32_t)rc * (uint32_t)(G * 64) + 16u * (uint32_t)c;
     }
     auto issue_a1 = [&](unsigned char *buf, int p, int j) {
-        __builtin_amdgcn_global_load_lds((const void *)(xg[j] + (size_t)p * 128),
+        __builtin_amdgcn_global_load_lds((const void *)(xbase + (size_t)p * 128 + xo[j]),
                                          (lds_void_ptr)(buf + (8 * wave + j) * 1024), 16, 0, 0);
     };
     // Weight loads: instruction j fills rows 16 j .. + 15 of a weight buffer, lane l
     // the position l % 4 of row l / 4 of those (rows past the last one: the last one
     // again).  Scale load: lane l the 16 bytes of row l.
-    const unsigned char *qg[4];
+    const int nw = n0 + wave * 64 < N ? n0 + wave * 64 : N - 1;  // the wave's first row
+    const unsigned char *const qbase = qw + (size_t)nw * (size_t)(G * 16);
+    const unsigned char *const sbase = sc + (size_t)nw * (size_t)(G * 2);
+    uint32_t qo[4], so;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int r = 16 * j + (lane >> 2);
         const int c = (lane & 3) ^ ((r >> 2) & 3);
-        const int n = n0 + wave * 64 + r < N ? n0 + wave * 64 + r : N - 1;
-        qg[j] = qw + (size_t)n * (size_t)(G * 16) + 16 * c;
+        const int rc = nw + r < N ? r : N - 1 - nw;
+        qo[j] = (uint32_t)rc * (uint32_t)(G * 16) + 16u * (uint32_t)c;
     }
-    const unsigned char *sg;
-    {
-        const int n = n0 + wave * 64 + lane < N ? n0 + wave * 64 + lane : N - 1;
-        sg = sc + (size_t)n * (size_t)(G * 2);
-    }
+    so = (uint32_t)(nw + lane < N ? lane : N - 1 - nw) * (uint32_t)(G * 2);
     // block b2 = pairs 2 b2, 2 b2 + 1 into weight buffer `sel`; block b4 = pairs 4 b4 .. + 3
     auto issue_bw1 = [&](int b2, int sel, int j) {
-        __builtin_amdgcn_global_load_lds((const void *)(qg[j] + (size_t)b2 * 64),
+        __builtin_amdgcn_global_load_lds((const void *)(qbase + (size_t)b2 * 64 + qo[j]),
                                          (lds_void_ptr)(bw + sel * kWideBw + j * 1024), 16, 0, 0);
     };
     auto issue_bs = [&](int b4, int sel) {
-        __builtin_amdgcn_global_load_lds((const void *)(sg + (size_t)b4 * 16),
+        __builtin_amdgcn_global_load_lds((const void *)(sbase + (size_t)b4 * 16 + so),
                                          (lds_void_ptr)(bs + sel * kWideBs), 16, 0, 0);
     };
 
@@ -342,9 +351,9 @@ gemm_w4a16_wide_kernel(const unsigned char *__restrict__ qw, const unsigned char
         uint4v w[2];
         uint32_t h[2];
     };
-    struct Nibbles {  // one nibble per byte, [row tile][low, high][dword]
+    struct Nibbles {  // one nibble per byte, [row tile][low, high][dword]; the high ones times 16
         uint32_t d[2][2][4];
-        uint32_t h[2];  // fp16 scale bits
+        float s[2][2];  // scale for the low nibbles, scale / 16 for the high ones
         float m8[2];    // -8 * scale
     };
     // piece k of 10: the low and high nibbles of a dword (k < 8), the scale of a row tile
@@ -353,23 +362,23 @@ gemm_w4a16_wide_kernel(const unsigned char *__restrict__ qw, const unsigned char
             const int rt = k >> 2, i = k & 3;
             const uint32_t d = b.w[rt][i];
             nb.d[rt][0][i] = d & 0x0f0f0f0fu;
-            nb.d[rt][1][i] = (d >> 4) & 0x0f0f0f0fu;
+            nb.d[rt][1][i] = d & 0xf0f0f0f0u;
             // the bytes are converted one by one; seen through, the compiler
             // extracts each nibble from d again with an instruction of its own
             asm("" : "+v"(nb.d[rt][0][i]));
             asm("" : "+v"(nb.d[rt][1][i]));
         } else {
             const int rt = k - 8;
-            nb.h[rt] = b.h[rt];
-            nb.m8[rt] = -8.0f * half_bits_to_float((uint16_t)b.h[rt]);
+            nb.s[rt][0] = half_bits_to_float((uint16_t)b.h[rt]);
+            nb.s[rt][1] = 0.0625f * nb.s[rt][0];  // exact
+            nb.m8[rt] = -8.0f * nb.s[rt][0];
         }
     };
     // weight i (0..15) of MFMA step st: row tile i / 8, input i % 8 of the step
     auto weight = [&](const Nibbles &nb, int st, int i) -> float {
         const int rt = i >> 3, e = i & 7;
         const uint32_t d = nb.d[rt][st >> 1][2 * (st & 1) + (e >> 2)];
-        return fmaf((float)((d >> (8 * (e & 3))) & 0xffu), half_bits_to_float((uint16_t)nb.h[rt]),
-                    nb.m8[rt]);
+        return fmaf((float)((d >> (8 * (e & 3))) & 0xffu), nb.s[rt][st >> 1], nb.m8[rt]);
     };
     auto read_input = [&](uint32_t addr, int tt, uint4v &a) {
         switch (tt) {
@@ -390,7 +399,7 @@ gemm_w4a16_wide_kernel(const unsigned char *__restrict__ qw, const unsigned char
     uint4v a[2][8];
     uint32_t bo[2][2][4];  // [step parity][row tile] bf16 x 8
     BRaw braw;             // of the next pair
-    Nibbles nb, nnb;       // of the pair being multiplied and of the next one
+    Nibbles nba, nbb;      // of the pair being multiplied and of the next one, in turn
     auto arrived = [&](uint4v (&v)[8]) {
         asm volatile("s_waitcnt lgkmcnt(0)"
                      : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]), "+v"(v[4]), "+v"(v[5]),
@@ -404,7 +413,7 @@ gemm_w4a16_wide_kernel(const unsigned char *__restrict__ qw, const unsigned char
     // extra = 2: also unpacks them into nnb; extra = 3: also issues the loads: the
     // activations of pair pa into abuf, with nbw the weight block b2 into buffer
     // wsel, with nbs the scale block b4 into buffer ssel.
-    auto step = [&](int st, uint32_t nbuf, const Nibbles &wn, int nst, int extra, uint32_t waddr,
+    auto step = [&](int st, uint32_t nbuf, const Nibbles &wn, Nibbles &wnext, int nst, int extra, uint32_t waddr,
                     uint32_t saddr, unsigned char *abuf, int pa, bool nbw, int b2, int wsel, bool nbs,
                     int b4, int ssel) {
         const int c = st & 1, n = c ^ 1;
@@ -422,7 +431,7 @@ gemm_w4a16_wide_kernel(const unsigned char *__restrict__ qw, const unsigned char
             if (i & 1) bo[n][i >> 3][(i & 7) >> 1] = pack_bf16(prev, w);
             prev = w;
             if (extra == 1 && i >= 8 && i < 12) read_b1(waddr, saddr, braw, i - 8);
-            if (extra == 2 && i >= 4 && i < 14) unpack1(braw, nnb, i - 4);
+            if (extra == 2 && i >= 4 && i < 14) unpack1(braw, wnext, i - 4);
             if (extra == 3) {
                 if (nbs && i == 1) issue_bs(b4, ssel);
                 if (nbw && i >= 2 && i < 6) issue_bw1(b2, wsel, i - 2);
@@ -457,12 +466,12 @@ gemm_w4a16_wide_kernel(const unsigned char *__restrict__ qw, const unsigned char
     for (int tt = 0; tt < 8; ++tt) read_input(xa0 + apos[0], tt, a[0][tt]);
     arrived(a[0]);
 #pragma unroll
-    for (int k = 0; k < 10; ++k) unpack1(braw, nb, k);
+    for (int k = 0; k < 10; ++k) unpack1(braw, nba, k);
     {
         float prev = 0.0f;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            const float w = weight(nb, 0, i);
+            const float w = weight(nba, 0, i);
             if (i & 1) bo[0][i >> 3][(i & 7) >> 1] = pack_bf16(prev, w);
             prev = w;
         }
@@ -478,32 +487,31 @@ gemm_w4a16_wide_kernel(const unsigned char *__restrict__ qw, const unsigned char
     int cur = 0;  // byte offset of the activation buffer of pair p
     int ssel = 0;  // scale buffer of the pairs 4 k .. 4 k + 3
     for (int p = 0; p < P; p += 4) {
-#define NVQ_PAIR(i_, younger_)                                                                   \
+#define NVQ_PAIR(i_, younger_, nb, nnb)                                                                 \
     do {                                                                                         \
         const int q_ = (i_) + 1; /* the next pair's place in its blocks */                       \
         const uint32_t waddr_ = (bwpos + ((q_ >> 1) & 1) * kWideBw) ^ ((q_ & 1) * 32);           \
         const uint32_t saddr_ = bspos + (((q_ >> 2) ? ssel ^ 1 : ssel)) * kWideBs + (q_ & 3) * 4; \
         const int nxt_ = cur + kWideBuf == 3 * kWideBuf ? 0 : cur + kWideBuf;                    \
-        step(0, xa0 + cur, nb, 1, 0, 0, 0, xa, 0, false, 0, 0, false, 0, 0);                     \
-        step(1, xa0 + cur, nb, 2, 1, waddr_, saddr_, xa, 0, false, 0, 0, false, 0, 0);           \
-        step(2, xa0 + cur, nb, 3, 2, 0, 0, xa, 0, false, 0, 0, false, 0, 0);                     \
+        step(0, xa0 + cur, nb, nnb, 1, 0, 0, 0, xa, 0, false, 0, 0, false, 0, 0);                \
+        step(1, xa0 + cur, nb, nnb, 2, 1, waddr_, saddr_, xa, 0, false, 0, 0, false, 0, 0);      \
+        step(2, xa0 + cur, nb, nnb, 3, 2, 0, 0, xa, 0, false, 0, 0, false, 0, 0);                \
         __builtin_amdgcn_s_waitcnt(wide_vmcnt(younger_));                                        \
         __builtin_amdgcn_s_barrier();                                                            \
         NVQ_PIN;                                                                                 \
         {                                                                                        \
             const int b2_ = ((p + (i_)) >> 1) + 2, b4_ = (p >> 2) + 1;                           \
-            step(3, xa0 + nxt_, nnb, 0, 3, 0, 0, xa + cur, pair_or_last(p + (i_) + 3),           \
+            step(3, xa0 + nxt_, nnb, nb, 0, 3, 0, 0, xa + cur, pair_or_last(p + (i_) + 3),       \
                  ((i_) & 1) == 0, b2_ < last2 ? b2_ : last2, ((i_) >> 1) & 1, (i_) == 0,         \
                  b4_ < last4 ? b4_ : last4, ssel ^ 1);                                           \
         }                                                                                        \
         NVQ_PIN;                                                                                 \
-        nb = nnb;                                                                                \
         cur = nxt_;                                                                              \
     } while (0)
-        NVQ_PAIR(0, 8);
-        NVQ_PAIR(1, 13);
-        NVQ_PAIR(2, 8);
-        NVQ_PAIR(3, 12);
+        NVQ_PAIR(0, 8, nba, nbb);
+        NVQ_PAIR(1, 13, nbb, nba);
+        NVQ_PAIR(2, 8, nba, nbb);
+        NVQ_PAIR(3, 12, nbb, nba);
 #undef NVQ_PAIR
         ssel ^= 1;
     }
@@ -559,7 +567,11 @@ extern "C" int nvq_gemm_w4a16(const uint8_t *qweight, const uint16_t *scales, in
     }
     if (wide) {
         if (tiles > (int64_t)0x7fffffff) return NVQ_ERR_SHAPE;
+#ifdef NVQ_X_MAP
+        const dim3 wgrid((unsigned)(((tiles + 7) / 8) * 8));
+#else
         const dim3 wgrid((unsigned)tiles);
+#endif
         const unsigned char *xb = reinterpret_cast<const unsigned char *>(x_bf16);
         const unsigned char *sb = reinterpret_cast<const unsigned char *>(scales);
         if (y_dtype == NVQ_F32)
