@@ -1020,7 +1020,55 @@ def test_gemm_w4a16_matches_oracle(M, N, K):
     assert np_ref.rel_l2(yb.float().cpu().numpy(), want) < 4e-3
 
 
-def test_gemm_w4a16_takes_every_code():
+# The kernel with 256 x 256 tiles (K % 256 == 0; chosen by itself from 96 tiles on, forced here
+# so that small shapes reach it): one tile, ragged tokens and rows inside a tile and inside the
+# MFMA tiles, a single row and token, several tiles in both directions, K from one block of four
+# pairs of groups (no steady state in the loop) to many, K with an odd number of such blocks.
+@pytest.mark.parametrize("M,N,K", [(256, 256, 256), (300, 200, 512), (1, 1, 256), (33, 70, 1280),
+                                   (513, 257, 2048), (1024, 384, 4096), (700, 1000, 2304)])
+def test_gemm_w4a16_wide_tiles_match_oracle(M, N, K, monkeypatch):
+    say("gemm wide", M, N, K)
+    monkeypatch.setenv("NVQ_GEMM_TILE", "wide")
+    _, q, s = packed(9150 + M + N, N, K)
+    xh = act(9250 + K, M, K)
+    want = oracle.gemm_w4a16_dense(q, s, u16(xh))
+    qd, sd = to_dev_packed(q, s)
+    y = nvq.gemm_w4a16(qd, sd, xh.to(DEV))
+    torch.cuda.synchronize()
+    err = np_ref.rel_l2(y.cpu().numpy(), want)
+    say("  rel l2", err)
+    assert err < 1e-5
+    yb = nvq.gemm_w4a16(qd, sd, xh.to(DEV), out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    assert np_ref.rel_l2(yb.float().cpu().numpy(), want) < 4e-3
+    # both kernels add the same products in the same order
+    monkeypatch.setenv("NVQ_GEMM_TILE", "narrow")
+    yn = nvq.gemm_w4a16(qd, sd, xh.to(DEV))
+    torch.cuda.synchronize()
+    assert torch.equal(y, yn)
+
+
+def test_gemm_w4a16_full_size_sampled():
+    """A projection of the 8B block at 4096 tokens, as the benchmark launches it (the kernel with
+    wide tiles, chosen by the library): sampled tokens and rows against the oracle."""
+    say("gemm full size")
+    M, N, K = 4096, 4096, 4096
+    _, q, s = packed(9160, N, K)
+    xh = act(9260, M, K)
+    qd, sd = to_dev_packed(q, s)
+    y = nvq.gemm_w4a16(qd, sd, xh.to(DEV))
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(9161)
+    toks = np.unique(np.concatenate([[0, 255, 256, M - 1], rng.integers(0, M, 28)]))
+    rows = np.unique(np.concatenate([[0, 31, 32, 63, 64, 255, 256, N - 1], rng.integers(0, N, 56)]))
+    want = oracle.gemm_w4a16_dense(q[rows], s[rows], u16(xh)[toks])
+    got = y.cpu().numpy()[np.ix_(toks, rows)]
+    err = np_ref.rel_l2(got, want)
+    say("  rel l2", err)
+    assert err < 1e-5
+
+
+def test_gemm_w4a16_takes_every_code(monkeypatch):
     say("gemm codes")
     rng = np.random.default_rng(9300)
     M, N, K = 96, 64, 128
@@ -1029,6 +1077,17 @@ def test_gemm_w4a16_takes_every_code():
     xh = act(9301, M, K)
     want = oracle.gemm_w4a16_dense(q, s, u16(xh))
     qd, sd = to_dev_packed(q, s)
+    y = nvq.gemm_w4a16(qd, sd, xh.to(DEV))
+    torch.cuda.synchronize()
+    assert np_ref.rel_l2(y.cpu().numpy(), want) < 1e-5
+    # and with the wide tiles
+    K = 256
+    q = rng.integers(0, 256, (N, K // 2)).astype(np.uint8)
+    s = (rng.random((N, K // 32)).astype(np.float32) * 0.1 + 0.01).astype(np.float16).view(np.uint16)
+    xh = act(9302, M, K)
+    want = oracle.gemm_w4a16_dense(q, s, u16(xh))
+    qd, sd = to_dev_packed(q, s)
+    monkeypatch.setenv("NVQ_GEMM_TILE", "wide")
     y = nvq.gemm_w4a16(qd, sd, xh.to(DEV))
     torch.cuda.synchronize()
     assert np_ref.rel_l2(y.cpu().numpy(), want) < 1e-5
