@@ -519,8 +519,43 @@ gemm_w4a16_wide_kernel(const unsigned char *__restrict__ qw, const unsigned char
     // no load into LDS may outlive the wave
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
-    // result tile: lane (j, b) holds weight row j; register r holds token
-    // 8 * (r / 4) + 4 * b + r % 4
+    // Result tile: lane (j, b) holds weight row j; register r holds token
+    // 8 * (r / 4) + 4 * b + r % 4 of a 32 x 32 tile.
+    if (!F32 && (N & 7) == 0 && (reinterpret_cast<uintptr_t>(y) & 15) == 0) {
+        // bf16 results pass through LDS (free now), so that they leave as whole
+        // 128-byte lines, 16 bytes per lane, instead of 2 bytes per lane: a wave's
+        // 256 tokens x 64 rows in 32 KiB, a row of 128 bytes per token with its
+        // 16-byte pieces permuted (piece c at position c ^ ((token / 4) % 8): the two
+        // halves of the wave write tokens four apart).
+        __builtin_amdgcn_s_barrier();  // every wave has left the loop: nothing reads or fills LDS
+        unsigned char *const out = lds + wave * (kWideTokens * 128);
+#pragma unroll
+        for (int tt = 0; tt < 8; ++tt)
+#pragma unroll
+            for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int tok = tt * 32 + 8 * (r >> 2) + 4 * lb + (r & 3);
+                    const int nl = rt * 32 + li;
+                    const int pos = (nl >> 3) ^ ((tok >> 2) & 7);
+                    *reinterpret_cast<uint16_t *>(out + tok * 128 + pos * 16 + (nl & 7) * 2) =
+                        float_to_bf16_bits(acc[tt][rt][r]);
+                }
+        // the wave reads back what it wrote itself
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        const int nb0 = n0 + wave * 64;
+#pragma unroll 4
+        for (int i = 0; i < 32; ++i) {
+            const int idx = i * 64 + lane;
+            const int tok = idx >> 3, pos = idx & 7;
+            const int c = pos ^ ((tok >> 2) & 7);
+            const uint4 v = *reinterpret_cast<const uint4 *>(out + tok * 128 + pos * 16);
+            const int m = m0 + tok, n = nb0 + c * 8;
+            if (m < M && n < N)
+                *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(y) + (size_t)m * N + n) = v;
+        }
+        return;
+    }
 #pragma unroll
     for (int tt = 0; tt < 8; ++tt)
 #pragma unroll
@@ -560,7 +595,7 @@ extern "C" int nvq_gemm_w4a16(const uint8_t *qweight, const uint16_t *scales, in
     // environment variable NVQ_GEMM_TILE (wide | narrow) overrides the choice where
     // both kernels can run (used by the tests to reach both on small shapes).
     const int64_t tiles = ((N + kWideRows - 1) / kWideRows) * ((M + kWideTokens - 1) / kWideTokens);
-    bool wide = (K % 256) == 0 && tiles >= 96;
+    bool wide = (K % 256) == 0 && tiles >= 32;
     if (const char *force = getenv("NVQ_GEMM_TILE")) {
         if (force[0] == 'w' && (K % 256) == 0) wide = true;
         if (force[0] == 'n') wide = false;
