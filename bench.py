@@ -465,6 +465,33 @@ def prefill_leg(a, torch, nvq, synth):
     single = launches([[slot] for slot in slots])
     wall7, dev7 = timed(single)
     tf, tf7 = flops / dev_s / 1e12, flops / dev7 / 1e12
+    # For scale, the route of the paper's kernel table on this machine: the dequantisation kernel
+    # (nvq_dequant_bf16) and the library's dense bf16 GEMM on its output, the same four launches;
+    # with the dense weights made once beforehand (GEMM only) and made anew in every step.
+    dense = [nvq.dequant_bf16(q, s) for q, s, _, _ in fused]
+
+    def timed_fn(fn):
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / reps
+
+    def lib_only():
+        for (q, s, x, y), w in zip(fused, dense):
+            torch.matmul(x, w.t(), out=y)
+
+    def lib_with_dequant():
+        for (q, s, x, y), w in zip(fused, dense):
+            nvq.dequant_bf16_into(q, s, w)
+            torch.matmul(x, w.t(), out=y)
+
+    lib_s, libd_s = timed_fn(lib_only), timed_fn(lib_with_dequant)
     print(json.dumps({
         "metric": "prefill linear-layer throughput, one %s block, %d tokens" % (a.model, T),
         "value": round(T / wall, 1), "unit": "tokens/s (one block's linears)", "n_gpus": 1,
@@ -480,7 +507,11 @@ def prefill_leg(a, torch, nvq, synth):
                      "launches": reps * len(fused), "avg_launch_us": round(dev_s * 1e6 / len(fused), 2)},
         "one_launch_per_projection": {"launches": len(single), "ms_per_step": round(wall7 * 1e3, 4),
                                       "achieved": round(tf7, 1), "unit": "TFLOP/s",
-                                      "frac": round(tf7 / MFMA_BF16_PEAK_TFLOPS, 4)}}))
+                                      "frac": round(tf7 / MFMA_BF16_PEAK_TFLOPS, 4)},
+        "dequantise_then_library_gemm": {
+            "gemm_only_tflops": round(flops / lib_s / 1e12, 1),
+            "with_dequantisation_each_step_tflops": round(flops / libd_s / 1e12, 1),
+            "ms_per_step": [round(lib_s * 1e3, 4), round(libd_s * 1e3, 4)]}}))
 
 
 def config1_leg(a, torch, nvq, synth):

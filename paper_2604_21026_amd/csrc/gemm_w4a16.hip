@@ -407,15 +407,46 @@ gemm_w4a16_wide_kernel(const unsigned char *__restrict__ qw, const unsigned char
                        "+v"(braw.h[1]));
     };
 
+    // The loads from global memory that belong to pair p: the activations of pair p +
+    // 3 (eight instructions), for even p before them the weight block p / 2 + 2
+    // (four), for p % 4 == 0 before those the scale block p / 4 + 1 (one): a list of
+    // `kind` = 13, 8, 12 or 8 instructions.  They are dealt over four steps (step 3
+    // of pair p, where the buffer of pair p becomes free, and steps 0..2 of pair p +
+    // 1), a quarter of the list each, one every fourth MFMA: a load instruction holds
+    // up the wave that issues it while the address unit is busy, and the four waves
+    // of a workgroup issue theirs at the same time.
+    auto load_op = [&](int kind, int quarter, int m, unsigned char *abuf, int pa, int b2, int wsel,
+                       int b4, int ssel) {
+        const int first = kind == 13 ? (quarter == 0 ? 0 : 1 + 3 * quarter) : (kind / 4) * quarter;
+        const int count = kind == 13 ? (quarter == 0 ? 4 : 3) : kind / 4;
+        if (m >= count) return;
+        int k = first + m;
+        if (kind == 13) {
+            if (k == 0) {
+                issue_bs(b4, ssel);
+                return;
+            }
+            k -= 1;
+        }
+        if (kind >= 12) {
+            if (k < 4) {
+                issue_bw1(b2, wsel, k);
+                return;
+            }
+            k -= 4;
+        }
+        issue_a1(abuf, pa, k);
+    };
+
     // Step `st` of the pair in registers (a[st % 2], bo[st % 2]) while the operands
     // of step `nst` of the pair at `nbuf` with the nibbles `wn` are made.  extra =
     // 1: also reads the next pair's packed weights from LDS (at waddr / saddr);
-    // extra = 2: also unpacks them into nnb; extra = 3: also issues the loads: the
-    // activations of pair pa into abuf, with nbw the weight block b2 into buffer
-    // wsel, with nbs the scale block b4 into buffer ssel.
-    auto step = [&](int st, uint32_t nbuf, const Nibbles &wn, Nibbles &wnext, int nst, int extra, uint32_t waddr,
-                    uint32_t saddr, unsigned char *abuf, int pa, bool nbw, int b2, int wsel, bool nbs,
-                    int b4, int ssel) {
+    // extra = 2: also unpacks them into wnext.  Every step issues a quarter of a list
+    // of loads (kind, quarter): the activations of pair pa into abuf, the weight
+    // block b2 into buffer wsel, the scale block b4 into buffer ssel.
+    auto step = [&](int st, uint32_t nbuf, const Nibbles &wn, Nibbles &wnext, int nst, int extra,
+                    uint32_t waddr, uint32_t saddr, int kind, int quarter, unsigned char *abuf, int pa,
+                    int b2, int wsel, int b4, int ssel) {
         const int c = st & 1, n = c ^ 1;
         const uint32_t addr = nbuf + apos[nst];
         float prev = 0.0f;
@@ -432,19 +463,17 @@ gemm_w4a16_wide_kernel(const unsigned char *__restrict__ qw, const unsigned char
             prev = w;
             if (extra == 1 && i >= 8 && i < 12) read_b1(waddr, saddr, braw, i - 8);
             if (extra == 2 && i >= 4 && i < 14) unpack1(braw, wnext, i - 4);
-            if (extra == 3) {
-                if (nbs && i == 1) issue_bs(b4, ssel);
-                if (nbw && i >= 2 && i < 6) issue_bw1(b2, wsel, i - 2);
-                if (i >= 6 && i < 14) issue_a1(abuf, pa, i - 6);
-            }
+            if ((i & 3) == 2) load_op(kind, quarter, i >> 2, abuf, pa, b2, wsel, b4, ssel);
             __builtin_amdgcn_sched_barrier(0);
         }
         arrived(a[n]);
     };
 
 #define NVQ_PIN asm volatile("" ::: "memory")
-    // Before the loop: the activations of pairs 0..2, the weights of pairs 0..3 and
-    // their scales; pair 0 unpacked and its first operands in registers.
+    // Before the loop: the activations of pairs 0 and 1 and the first quarter of
+    // those of pair 2 (the rest follows in steps 0..2 of pair 0, as in every turn of
+    // the loop), the weights of pairs 0..3 and their scales; pair 0 unpacked and its
+    // first operands in registers.
     const int last2 = (P >> 1) - 1, last4 = (P >> 2) - 1;
     auto pair_or_last = [&](int q) { return q < P ? q : P - 1; };
     issue_bs(0, 0);
@@ -453,9 +482,11 @@ gemm_w4a16_wide_kernel(const unsigned char *__restrict__ qw, const unsigned char
 #pragma unroll
     for (int j = 0; j < 4; ++j) issue_bw1(1 < last2 ? 1 : last2, 1, j);
 #pragma unroll
-    for (int q = 0; q < 3; ++q)
+    for (int q = 0; q < 2; ++q)
 #pragma unroll
         for (int j = 0; j < 8; ++j) issue_a1(xa + q * kWideBuf, pair_or_last(q), j);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) issue_a1(xa + 2 * kWideBuf, pair_or_last(2), j);
     NVQ_PIN;
     __builtin_amdgcn_s_waitcnt(wide_vmcnt(0));
     __builtin_amdgcn_s_barrier();
@@ -477,41 +508,50 @@ gemm_w4a16_wide_kernel(const unsigned char *__restrict__ qw, const unsigned char
         }
     }
 
-    // Four pairs per turn (a block of scales, two blocks of weights).  In step 3 of
-    // pair p = 4 k + i the loads of A(p + 3), for even i of the weight block p / 2 +
-    // 2 and for i = 0 of the scale block k + 1 are issued, the activations last: 13,
-    // 8, 12, 8 load instructions for i = 0..3.  The wait before that step lets the
-    // loads of the pair before stay in flight (8, 13, 8, 12) and ends all older ones:
-    // A(p + 1), read right after it, was issued two pairs ago, and the weights and
-    // scales of pair p + 2, read from LDS in step 1 of pair p + 1, at least three.
-    int cur = 0;  // byte offset of the activation buffer of pair p
-    int ssel = 0;  // scale buffer of the pairs 4 k .. 4 k + 3
+    // Four pairs per turn (a block of scales, two blocks of weights); pair p = 4 k +
+    // i has a list of 13, 8, 12, 8 loads for i = 0..3.  The wait before step 3 of pair
+    // p lets the list of pair p - 1 (begun in step 3 of that pair, ended in step 2 of
+    // this one) stay in flight and ends all older loads: A(p + 1), read right after the
+    // barrier, is in the list of pair p - 2, and the weights and scales of pair p + 2,
+    // read from LDS in step 1 of pair p + 1, are in that of pair p - 2 or older.
+    int cur = 0, prv = 2 * kWideBuf;  // byte offsets of the activation buffers of pairs p and p - 1
+    int ssel = 0;                     // scale buffer of the pairs 4 k .. 4 k + 3
     for (int p = 0; p < P; p += 4) {
-#define NVQ_PAIR(i_, younger_, nb, nnb)                                                                 \
+        // i_: place of the pair in the turn; kprev_, kind_: the lists of pairs p - 1 and p
+#define NVQ_PAIR(i_, kprev_, kind_, nb, nnb)                                                     \
     do {                                                                                         \
         const int q_ = (i_) + 1; /* the next pair's place in its blocks */                       \
         const uint32_t waddr_ = (bwpos + ((q_ >> 1) & 1) * kWideBw) ^ ((q_ & 1) * 32);           \
         const uint32_t saddr_ = bspos + (((q_ >> 2) ? ssel ^ 1 : ssel)) * kWideBs + (q_ & 3) * 4; \
         const int nxt_ = cur + kWideBuf == 3 * kWideBuf ? 0 : cur + kWideBuf;                    \
-        step(0, xa0 + cur, nb, nnb, 1, 0, 0, 0, xa, 0, false, 0, 0, false, 0, 0);                \
-        step(1, xa0 + cur, nb, nnb, 2, 1, waddr_, saddr_, xa, 0, false, 0, 0, false, 0, 0);      \
-        step(2, xa0 + cur, nb, nnb, 3, 2, 0, 0, xa, 0, false, 0, 0, false, 0, 0);                \
-        __builtin_amdgcn_s_waitcnt(wide_vmcnt(younger_));                                        \
+        /* the list of the pair before: its activations go to that pair's buffer */             \
+        const int pp_ = p + (i_) - 1;                                                            \
+        const int pa_ = pair_or_last(pp_ + 3);                                                   \
+        const int pb2_ = (pp_ >> 1) + 2 < last2 ? (pp_ >> 1) + 2 : last2;                        \
+        const int pb4_ = (p >> 2) + 1 < last4 ? (p >> 2) + 1 : last4;                            \
+        const int pws_ = (((i_) + 3) >> 1) & 1; /* ((i - 1) / 2) % 2 for i = 1..3 */             \
+        step(0, xa0 + cur, nb, nnb, 1, 0, 0, 0, kprev_, 1, xa + prv, pa_, pb2_, pws_, pb4_,      \
+             ssel ^ 1);                                                                          \
+        step(1, xa0 + cur, nb, nnb, 2, 1, waddr_, saddr_, kprev_, 2, xa + prv, pa_, pb2_, pws_,  \
+             pb4_, ssel ^ 1);                                                                    \
+        step(2, xa0 + cur, nb, nnb, 3, 2, 0, 0, kprev_, 3, xa + prv, pa_, pb2_, pws_, pb4_,      \
+             ssel ^ 1);                                                                          \
+        __builtin_amdgcn_s_waitcnt(wide_vmcnt(kprev_));                                          \
         __builtin_amdgcn_s_barrier();                                                            \
         NVQ_PIN;                                                                                 \
         {                                                                                        \
-            const int b2_ = ((p + (i_)) >> 1) + 2, b4_ = (p >> 2) + 1;                           \
-            step(3, xa0 + nxt_, nnb, nb, 0, 3, 0, 0, xa + cur, pair_or_last(p + (i_) + 3),       \
-                 ((i_) & 1) == 0, b2_ < last2 ? b2_ : last2, ((i_) >> 1) & 1, (i_) == 0,         \
-                 b4_ < last4 ? b4_ : last4, ssel ^ 1);                                           \
+            const int b2_ = ((p + (i_)) >> 1) + 2;                                               \
+            step(3, xa0 + nxt_, nnb, nb, 0, 0, 0, 0, kind_, 0, xa + cur, pair_or_last(p + (i_) + 3), \
+                 b2_ < last2 ? b2_ : last2, ((i_) >> 1) & 1, pb4_, ssel ^ 1);                    \
         }                                                                                        \
         NVQ_PIN;                                                                                 \
+        prv = cur;                                                                               \
         cur = nxt_;                                                                              \
     } while (0)
-        NVQ_PAIR(0, 8, nba, nbb);
-        NVQ_PAIR(1, 13, nbb, nba);
-        NVQ_PAIR(2, 8, nba, nbb);
-        NVQ_PAIR(3, 12, nbb, nba);
+        NVQ_PAIR(0, 8, 13, nba, nbb);
+        NVQ_PAIR(1, 13, 8, nbb, nba);
+        NVQ_PAIR(2, 8, 12, nba, nbb);
+        NVQ_PAIR(3, 12, 8, nbb, nba);
 #undef NVQ_PAIR
         ssel ^= 1;
     }
