@@ -393,12 +393,17 @@ int nvq_dequant_bf16(const uint8_t *qweight, const uint16_t *scales, int64_t N, 
  * hundred and more (below that the batch-1 and small-batch paths read the
  * weights once and are faster).  Note that the weights are rounded to bf16
  * here, as in the paper's prefill path, and are not in nvq_gemv_w4a16.
- * On an MI355X this kernel reaches 0.8 PFLOP/s (a third of the bf16 matrix
- * peak) on 8B-shaped layers at 4096 tokens; the paper's own route, weights
- * dequantised once with nvq_dequant_bf16 and a library bf16 GEMM on them,
- * reaches 1.45-1.6 PFLOP/s there and is the faster one wherever the dense copy
- * (2 bytes per weight instead of 0.5625) fits; this kernel is for where it does
- * not.
+ * Two kernels: tiles of 256 tokens x 256 rows when K % 256 == 0 and the
+ * output has at least 32 of them, tiles of 256 x 128 otherwise (the environment
+ * variable NVQ_GEMM_TILE = wide | narrow overrides the choice where both can
+ * run; both add the same products in the same order).  On an MI355X the 8B
+ * block's projections at 4096 tokens (q+k+v, o, gate+up, down as one launch
+ * each) run at 1.1-1.2 PFLOP/s, 47 % of the bf16 matrix peak; the paper's own
+ * route, weights dequantised with nvq_dequant_bf16 and a library bf16 GEMM on
+ * them, reaches 1.3-1.45 PFLOP/s on the same machine (1.3-1.4 with the
+ * dequantisation repeated in every step) and is the faster one wherever the
+ * dense copy (2 bytes per weight instead of 0.5625) fits; this kernel is for
+ * where it does not.
  *   qweight  device, [N][K/2], layout of nvq_pack_int4, 16-byte aligned
  *   scales   device, [N][K/32] fp16 bits
  *   x_bf16   device, [M][K] bf16 bits, 16-byte aligned

@@ -19,6 +19,10 @@
 // Nibble -> fp32 (byte convert), one FMA with the group's scale ((n - 8) * s is
 // exact), round to bf16.
 //
+// Two kernels.  The one with wide tiles (256 x 256 per workgroup, second half of
+// this file) runs when K is a multiple of 256 and the output has at least 32
+// such tiles; the other one, described here, takes everything else.
+//
 // A workgroup of four waves owns 256 tokens x 128 weight rows, a wave 128 x 64
 // (4 x 2 MFMA tiles, 128 accumulator registers); a wave's dequantised operand
 // serves its four token tiles.  Activations pass through LDS (rows of 128 bytes
@@ -261,17 +265,11 @@ gemm_w4a16_wide_kernel(const unsigned char *__restrict__ qw, const unsigned char
     const int li = lane & 31, lb = lane >> 5;
     // Tiles in token-major order, weight rows fastest.  (Giving each XCD, with its
     // own L2, a contiguous eighth of the tiles, so that its workgroups share one or
-    // two token tiles, was 7 % slower; so was starting every workgroup at a
-    // different place along K.)
+    // two token tiles, changed the time by -1..+3 %; starting every workgroup at a
+    // different place along K made it 3-7 % slower; reading the inputs from LDS two
+    // steps ahead instead of one changed nothing.)
     const int nx = (N + kWideRows - 1) / kWideRows;
-#ifdef NVQ_X_MAP
-    const int ntile_ = nx * ((M + kWideTokens - 1) / kWideTokens);
-    const int per_xcd_ = (ntile_ + 7) >> 3;
-    const int tile = (int)(blockIdx.x & 7u) * per_xcd_ + (int)(blockIdx.x >> 3);
-    if (tile >= ntile_) return;
-#else
     const int tile = (int)blockIdx.x;
-#endif
     const int m0 = (tile / nx) * kWideTokens, n0 = (tile % nx) * kWideRows;
     const int P = G >> 1;  // pairs of groups, a multiple of 4
 
@@ -642,11 +640,7 @@ extern "C" int nvq_gemm_w4a16(const uint8_t *qweight, const uint16_t *scales, in
     }
     if (wide) {
         if (tiles > (int64_t)0x7fffffff) return NVQ_ERR_SHAPE;
-#ifdef NVQ_X_MAP
-        const dim3 wgrid((unsigned)(((tiles + 7) / 8) * 8));
-#else
         const dim3 wgrid((unsigned)tiles);
-#endif
         const unsigned char *xb = reinterpret_cast<const unsigned char *>(x_bf16);
         const unsigned char *sb = reinterpret_cast<const unsigned char *>(scales);
         if (y_dtype == NVQ_F32)
