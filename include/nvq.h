@@ -393,8 +393,9 @@ int nvq_dequant_bf16(const uint8_t *qweight, const uint16_t *scales, int64_t N, 
  * hundred and more (below that the batch-1 and small-batch paths read the
  * weights once and are faster).  Note that the weights are rounded to bf16
  * here, as in the paper's prefill path, and are not in nvq_gemv_w4a16.
- * Two kernels: tiles of 256 tokens x 256 rows when K % 256 == 0 and the
- * output has at least 32 of them, tiles of 256 x 128 otherwise (the environment
+ * Two kernels: tiles of 256 tokens x 256 rows when K % 256 == 0, the scales
+ * are 16-byte aligned and the output has at least 32 of them, tiles of 256 x
+ * 128 otherwise (the environment
  * variable NVQ_GEMM_TILE = wide | narrow overrides the choice where both can
  * run; both add the same products in the same order).  On an MI355X the 8B
  * block's projections at 4096 tokens (q+k+v, o, gate+up, down as one launch

@@ -633,9 +633,11 @@ extern "C" int nvq_gemm_w4a16(const uint8_t *qweight, const uint16_t *scales, in
     // environment variable NVQ_GEMM_TILE (wide | narrow) overrides the choice where
     // both kernels can run (used by the tests to reach both on small shapes).
     const int64_t tiles = ((N + kWideRows - 1) / kWideRows) * ((M + kWideTokens - 1) / kWideTokens);
-    bool wide = (K % 256) == 0 && tiles >= 32;
+    // (its loads move 16 bytes of scales at a time: the scales 16-byte aligned, too)
+    const bool can_wide = (K % 256) == 0 && aligned(scales, 16);
+    bool wide = can_wide && tiles >= 32;
     if (const char *force = getenv("NVQ_GEMM_TILE")) {
-        if (force[0] == 'w' && (K % 256) == 0) wide = true;
+        if (force[0] == 'w' && can_wide) wide = true;
         if (force[0] == 'n') wide = false;
     }
     if (wide) {
